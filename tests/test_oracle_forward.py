@@ -1,0 +1,222 @@
+"""Pins for the oracle's target-model forward pass and log-prob extraction.
+
+The paper prints no numeric example for the verification forward pass, so it is pinned to
+closed forms of degenerate models, to structural invariants of a causal decoder, and to
+an independent float64 formulation assembled from torch library routines (rms_norm,
+scaled_dot_product_attention with grouped KV heads, silu, log_softmax) with the rotary
+embedding written as a complex multiplication.
+"""
+import copy
+import math
+
+import numpy as np
+import pytest
+import torch
+import torch.nn.functional as F
+
+from oracle import atts_oracle as O
+from synth import ModelConfig, make_token_ids, make_weights
+
+CFG = ModelConfig(n_layers=2, d_model=32, n_q_heads=4, n_kv_heads=2, head_dim=8, d_ffn=48,
+                  vocab=50, dtype="fp32")
+
+
+def _weights(cfg=CFG, seed=5, **kw):
+    w = make_weights(cfg, seed, **kw)
+    return {k: ([t.numpy() for t in v] if isinstance(v, list) else v.numpy()) for k, v in w.items()}
+
+
+def _ids(cfg=CFG, P=9, K=3, T=6, seed=77):
+    p, d = make_token_ids(cfg.vocab, P, K, T, seed)
+    return p.numpy(), d.numpy()
+
+
+# ---------------------------------------------------------------- log-softmax closed forms
+def test_log_softmax_rows_sum_to_one_and_shift_invariance():
+    z = np.random.default_rng(0).normal(scale=30.0, size=(7, 1000))
+    lsm = O.log_softmax(z)
+    assert np.allclose(np.exp(lsm).sum(-1), 1.0, rtol=0, atol=1e-12)
+    assert np.all(lsm <= 0)
+    assert np.allclose(O.log_softmax(z + 1e3), lsm, rtol=0, atol=1e-9)
+    assert np.allclose(lsm, torch.log_softmax(torch.from_numpy(z), -1).numpy(), rtol=0, atol=1e-12)
+
+
+def test_zero_lm_head_gives_uniform_distribution():
+    w = _weights()
+    w["lm_head"] = np.zeros_like(w["lm_head"])
+    p, d = _ids()
+    lp = O.token_logprobs(w, CFG, p, d[0])
+    assert np.allclose(lp, -math.log(CFG.vocab), rtol=0, atol=1e-14)
+    lps, s = O.score_drafts(w, CFG, p, d)
+    assert np.allclose(s, math.log(CFG.vocab))            # mean NLL of a uniform model
+
+
+# ---------------------------------------------------------------- degenerate models
+def test_zero_output_projections_make_layers_identity():
+    w = _weights()
+    w["wo"] = [np.zeros_like(x) for x in w["wo"]]
+    w["w_down"] = [np.zeros_like(x) for x in w["w_down"]]
+    p, d = _ids()
+    seq = np.concatenate([p, d[1]])
+    h = O.decoder_hidden(w, CFG, seq)
+    assert np.array_equal(h, w["tok_embed"][seq].astype(np.float64))
+    x = torch.from_numpy(h)
+    z = F.rms_norm(x, (CFG.d_model,), torch.from_numpy(w["final_norm"]).double(), CFG.rms_eps) \
+        @ torch.from_numpy(w["lm_head"]).double().T
+    ref = torch.log_softmax(z, -1).numpy()
+    lp = O.token_logprobs(w, CFG, p, d[1])
+    P = len(p)
+    assert np.allclose(lp, ref[np.arange(P - 1, P - 1 + len(d[1])), d[1]], rtol=0, atol=1e-12)
+
+
+def test_zero_layers_model():
+    cfg = ModelConfig(0, 32, 4, 2, 8, 48, 50, "fp32")
+    w = _weights(cfg)
+    assert len(w["wqkv"]) == 0
+    p, d = _ids(cfg)
+    seq = np.concatenate([p, d[0]])
+    assert np.array_equal(O.decoder_hidden(w, cfg, seq), w["tok_embed"][seq].astype(np.float64))
+
+
+def test_uniform_attention_closed_form_and_gqa_head_mapping():
+    """Zero query projection => every softmax is uniform over the causal window, so the
+    context of query head j at position i is the running mean of V of KV head j // group."""
+    cfg = ModelConfig(1, 32, 4, 2, 8, 48, 50, "fp32")
+    w = _weights(cfg)
+    nq, nkv, hd = cfg.n_q_heads, cfg.n_kv_heads, cfg.head_dim
+    w["wqkv"][0][: nq * hd] = 0.0
+    w["w_down"][0][:] = 0.0
+    p, d = _ids(cfg)
+    seq = np.concatenate([p, d[0]])
+    n = len(seq)
+    e = torch.from_numpy(w["tok_embed"][seq]).double()
+    a = F.rms_norm(e, (cfg.d_model,), torch.from_numpy(w["attn_norm"][0]).double(), cfg.rms_eps)
+    v = (a @ torch.from_numpy(w["wqkv"][0][(nq + nkv) * hd:]).double().T).view(n, nkv, hd)
+    run_mean = torch.cumsum(v, 0) / torch.arange(1, n + 1).double()[:, None, None]
+    ctx = torch.stack([run_mean[:, j // (nq // nkv)] for j in range(nq)], 1).reshape(n, nq * hd)
+    expect = e + ctx @ torch.from_numpy(w["wo"][0]).double().T
+    got = O.decoder_hidden(w, cfg, seq)
+    assert np.allclose(got, expect.numpy(), rtol=0, atol=1e-12)
+
+
+# ---------------------------------------------------------------- structural invariants
+def test_causality_and_prefix_split_invariance():
+    w = _weights()
+    p, d = _ids(P=9, T=6)
+    lp = O.token_logprobs(w, CFG, p, d[0])
+    d2 = d[0].copy()
+    d2[-1] = (d2[-1] + 1) % CFG.vocab
+    lp2 = O.token_logprobs(w, CFG, p, d2)
+    assert np.allclose(lp[:-1], lp2[:-1], rtol=0, atol=1e-13)      # later tokens cannot leak back
+    assert abs(lp[-1] - lp2[-1]) > 1e-6
+    # moving the split point: (P, T) vs (P - j, j + T) agree on the common tokens
+    for j in (1, 4):
+        lp_shift = O.token_logprobs(w, CFG, p[:-j], np.concatenate([p[-j:], d[0]]))
+        assert np.allclose(lp_shift[j:], lp, rtol=0, atol=1e-12)
+
+
+def test_shared_prefix_tree_equals_independent_sequences():
+    """Scoring K drafts under one prefix == K independent causal sequences; in particular
+    the first draft token is predicted from the last prefix position, shared by all."""
+    w = _weights()
+    p, d = _ids(K=3)
+    lps, s = O.score_drafts(w, CFG, p, d)
+    h_prefix = O.decoder_hidden(w, CFG, p)
+    first = O.log_softmax(O.logits_from_hidden(w, CFG, h_prefix[-1:]))[0]
+    for k in range(3):
+        assert np.allclose(lps[k, 0], first[d[k, 0]], rtol=0, atol=1e-12)
+    lps_r, s_r = O.score_drafts(w, CFG, p, d[::-1])
+    assert np.allclose(s_r[::-1], s, rtol=0, atol=1e-13)
+    assert np.allclose(s, -lps.mean(1))
+    _, s_sum = O.score_drafts(w, CFG, p, d, mode=O.SUM_NLL)
+    assert np.allclose(s_sum, d.shape[1] * s)
+
+
+def test_variable_draft_lengths():
+    w = _weights()
+    p, d = _ids(K=3, T=6)
+    lens = np.array([6, 2, 4])
+    lps, s = O.score_drafts(w, CFG, p, d, draft_lens=lens)
+    for k in range(3):
+        ref = O.token_logprobs(w, CFG, p, d[k, : lens[k]])
+        assert np.allclose(lps[k, : lens[k]], ref) and np.all(lps[k, lens[k]:] == 0)
+        assert math.isclose(s[k], -ref.mean())
+
+
+# ---------------------------------------------------------------- rotary embedding
+def test_rope_textbook_properties():
+    rng = np.random.default_rng(2)
+    x = rng.normal(size=(5, 3, 8))
+    pos = np.array([0, 1, 2, 10, 500])
+    y = O.rope_rotate_half(x, pos, 10000.0)
+    assert np.array_equal(y[0], x[0])                                   # position 0: identity
+    assert np.allclose((y ** 2).sum(-1), (x ** 2).sum(-1))              # a rotation
+    # hd = 2, angle = pos * theta^0 = pos: quarter turn sends (a, b) -> (-b, a)
+    q = O.rope_rotate_half(np.array([[[3.0, 4.0]]]), np.array([1]), 10000.0)
+    assert np.allclose(q, [[[3 * math.cos(1) - 4 * math.sin(1), 4 * math.cos(1) + 3 * math.sin(1)]]])
+    # relative-position property: <R_a q, R_b k> depends on a - b only
+    qv, kv = rng.normal(size=(1, 1, 8)), rng.normal(size=(1, 1, 8))
+    def dot(a, b):
+        return float((O.rope_rotate_half(qv, np.array([a]), 1e4) * O.rope_rotate_half(kv, np.array([b]), 1e4)).sum())
+    assert math.isclose(dot(7, 3), dot(104, 100), rel_tol=1e-12)
+    assert not math.isclose(dot(7, 3), dot(3, 7), rel_tol=1e-6)
+    # complex form: (x_i + i x_{i+h}) * exp(i pos theta^(-2i/hd))
+    half = 4
+    zc = (x[..., :half] + 1j * x[..., half:]) * np.exp(
+        1j * pos[:, None, None] * (10000.0 ** (-2.0 * np.arange(half) / 8))[None, None, :])
+    assert np.allclose(y, np.concatenate([zc.real, zc.imag], -1), rtol=0, atol=1e-12)
+
+
+# ---------------------------------------------------------------- independent library formulation
+def _torch_reference_logprobs(w, cfg, prefix, draft):
+    t = lambda a: torch.from_numpy(np.asarray(a)).double()
+    ids = torch.from_numpy(np.concatenate([prefix, draft]).astype(np.int64))
+    n, nq, nkv, hd = len(ids), cfg.n_q_heads, cfg.n_kv_heads, cfg.head_dim
+    h = F.embedding(ids, t(w["tok_embed"]))
+    freqs = torch.polar(torch.ones(n, hd // 2, dtype=torch.float64),
+                        torch.arange(n).double()[:, None]
+                        * cfg.rope_theta ** (-torch.arange(0, hd, 2).double() / hd)[None, :])
+
+    def rot(x):                       # x: [n, H, hd]
+        xc = torch.complex(x[..., : hd // 2], x[..., hd // 2:]) * freqs[:, None, :]
+        return torch.cat([xc.real, xc.imag], -1)
+
+    for l in range(len(w["wqkv"])):
+        a = F.rms_norm(h, (cfg.d_model,), t(w["attn_norm"][l]), cfg.rms_eps)
+        q, k, v = F.linear(a, t(w["wqkv"][l])).split([nq * hd, nkv * hd, nkv * hd], -1)
+        q, k, v = rot(q.view(n, nq, hd)), rot(k.view(n, nkv, hd)), v.view(n, nkv, hd)
+        o = F.scaled_dot_product_attention(q.transpose(0, 1)[None], k.transpose(0, 1)[None],
+                                           v.transpose(0, 1)[None], is_causal=True, enable_gqa=True)
+        h = h + F.linear(o[0].transpose(0, 1).reshape(n, nq * hd), t(w["wo"][l]))
+        b = F.rms_norm(h, (cfg.d_model,), t(w["ffn_norm"][l]), cfg.rms_eps)
+        g, u = F.linear(b, t(w["w_gate_up"][l])).chunk(2, -1)
+        h = h + F.linear(F.silu(g) * u, t(w["w_down"][l]))
+    z = F.linear(F.rms_norm(h, (cfg.d_model,), t(w["final_norm"]), cfg.rms_eps), t(w["lm_head"]))
+    lsm = F.log_softmax(z, -1)
+    P, T = len(prefix), len(draft)
+    return lsm[torch.arange(P - 1, P - 1 + T), torch.from_numpy(draft.astype(np.int64))].numpy()
+
+
+@pytest.mark.parametrize("cfg", [CFG, ModelConfig(3, 64, 8, 8, 8, 96, 80, "fp32"),
+                                 ModelConfig(2, 48, 6, 1, 8, 64, 64, "bf16")])
+def test_forward_matches_library_formulation(cfg):
+    w = _weights(cfg, seed=13) if cfg.dtype == "fp32" else \
+        {k: ([t.float().numpy() for t in v] if isinstance(v, list) else v.float().numpy())
+         for k, v in make_weights(cfg, 13).items()}
+    p, d = _ids(cfg, P=11, K=2, T=7)
+    for k in range(2):
+        got = O.token_logprobs(w, cfg, p, d[k])
+        ref = _torch_reference_logprobs(w, cfg, p, d[k])
+        assert np.allclose(got, ref, rtol=0, atol=1e-11)
+
+
+def test_generator_is_device_independent_and_scaled():
+    w1 = make_weights(CFG, 5)
+    w2 = make_weights(CFG, 5)
+    assert torch.equal(w1["wqkv"][1], w2["wqkv"][1])
+    assert not torch.equal(w1["wqkv"][0], w1["wqkv"][1])
+    assert abs(float(w1["tok_embed"].std()) - 1.0) < 0.05
+    assert abs(float(w1["wqkv"][0].std()) - 1 / math.sqrt(CFG.d_model)) < 0.02
+    wb = make_weights(ModelConfig(2, 32, 4, 2, 8, 48, 50, "bf16"), 5)
+    assert wb["lm_head"].dtype == torch.bfloat16 and wb["final_norm"].dtype == torch.float32
+    assert torch.equal(wb["lm_head"], w1["lm_head"].to(torch.bfloat16))
