@@ -1,0 +1,409 @@
+// C ABI: error reporting, the target-model handle, workspace carving and the launch sequence of
+// atts_score_drafts, plus the stand-alone stage entry points.  Host code only; kernels live in
+// gemm.hip / attention.hip / elementwise.hip / calib.hip.
+#include "common.h"
+
+#include <stdarg.h>
+#include <stdio.h>
+#include <new>
+#include <vector>
+
+struct atts_model {
+    atts_model_desc desc;
+    const void* tok_embed;
+    const float* final_norm;
+    const void* lm_head;
+    std::vector<const float*> attn_norm, ffn_norm;
+    std::vector<const void*> wqkv, wo, w_gate_up, w_down;
+    int32_t* err_flag;   // device
+};
+
+namespace atts {
+
+static thread_local char g_error[512] = "";
+
+int32_t fail(int32_t code, const char* fmt, ...) {
+    va_list ap;
+    va_start(ap, fmt);
+    vsnprintf(g_error, sizeof(g_error), fmt, ap);
+    va_end(ap);
+    return code;
+}
+
+namespace {
+
+// ---- stage timing ---------------------------------------------------------------------------
+struct ProfRecord {
+    int32_t stage;
+    hipEvent_t start, stop;
+};
+bool g_prof_on = false;
+std::vector<ProfRecord> g_prof;
+
+void prof_clear() {
+    for (auto& r : g_prof) {
+        (void)hipEventDestroy(r.start);
+        (void)hipEventDestroy(r.stop);
+    }
+    g_prof.clear();
+}
+
+// Brackets the launches issued during its lifetime with an event pair (only while enabled).
+struct StageTimer {
+    hipStream_t st;
+    bool live = false;
+    ProfRecord rec{};
+    StageTimer(int32_t stage, hipStream_t s) : st(s) {
+        if (!g_prof_on) return;
+        rec.stage = stage;
+        if (hipEventCreate(&rec.start) != hipSuccess) return;
+        if (hipEventCreate(&rec.stop) != hipSuccess) {
+            (void)hipEventDestroy(rec.start);
+            return;
+        }
+        (void)hipEventRecord(rec.start, st);
+        live = true;
+    }
+    ~StageTimer() {
+        if (!live) return;
+        (void)hipEventRecord(rec.stop, st);
+        g_prof.push_back(rec);
+    }
+};
+
+// Sub-buffers of the scoring workspace, each 256-byte aligned.
+struct Workspace {
+    size_t h, xn, qkv, vt, ao, act, rope, xs, targets, valid, partials, zt, lp, total;
+    int64_t ldv;
+    int32_t n_part;
+};
+
+Workspace carve(const atts_model_desc& d, ScoreShape s) {
+    const size_t es = dtype_size(d.dtype);
+    const size_t R = (size_t)s.R(), B = (size_t)s.B();
+    Workspace w{};
+    size_t off = 0;
+    auto take = [&](size_t bytes) {
+        size_t at = off;
+        off += align_up(bytes, 256);
+        return at;
+    };
+    w.h = take(R * d.d_model * sizeof(float));
+    w.xn = take(R * d.d_model * es);
+    w.qkv = take(R * (size_t)(d.n_q_heads + 2 * d.n_kv_heads) * d.head_dim * es);
+    w.ldv = (int64_t)align_up(R, 64);
+    w.vt = take(attention_uses_vt(d.dtype, d.head_dim) ? (size_t)d.n_kv_heads * d.head_dim * w.ldv * es : 0);
+    w.ao = take(R * (size_t)d.n_q_heads * d.head_dim * es);
+    w.act = take(R * (size_t)d.d_ffn * es);
+    w.rope = take((size_t)(s.P + s.T) * (d.head_dim / 2) * sizeof(float2));
+    w.xs = take(B * d.d_model * es);
+    w.targets = take(B * sizeof(int32_t));
+    w.valid = take(B);
+    w.n_part = lmhead_num_partials(d.dtype, s.B(), d.vocab);
+    w.partials = take(B * (size_t)w.n_part * sizeof(float2));
+    w.zt = take(B * sizeof(float));
+    w.lp = take(B * sizeof(float));
+    w.total = off;
+    return w;
+}
+
+int32_t check_score_shape(const char* fn, int32_t P, int32_t K, int32_t T) {
+    if (P < 1 || K < 1 || T < 1) return fail(ATTS_ERR_INVALID_ARG, "%s: P = %d, K = %d, T_max = %d must all be >= 1", fn, P, K, T);
+    if ((int64_t)P + T > (1 << 20)) return fail(ATTS_ERR_INVALID_ARG, "%s: P + T_max = %lld exceeds 1048576", fn, (long long)P + T);
+    if ((int64_t)P + (int64_t)K * T > (1 << 24)) return fail(ATTS_ERR_INVALID_ARG, "%s: P + K T_max exceeds 2^24 rows", fn);
+    return ATTS_OK;
+}
+
+#define ATTS_TRY(expr)                    \
+    do {                                  \
+        int32_t rc__ = (expr);            \
+        if (rc__ != ATTS_OK) return rc__; \
+    } while (0)
+
+}  // namespace
+}  // namespace atts
+
+using namespace atts;
+
+extern "C" {
+
+const char* atts_last_error_string(void) { return g_error; }
+
+int32_t atts_model_create(const atts_model_desc* desc, const atts_weights* w, atts_model** out) {
+    if (!out) return fail(ATTS_ERR_INVALID_ARG, "atts_model_create: out is NULL");
+    *out = nullptr;
+    if (!desc || !w) return fail(ATTS_ERR_INVALID_ARG, "atts_model_create: desc / weights is NULL");
+    const atts_model_desc& d = *desc;
+    if (d.dtype != ATTS_DTYPE_F32 && d.dtype != ATTS_DTYPE_BF16)
+        return fail(ATTS_ERR_INVALID_ARG, "atts_model_create: unknown dtype %d", d.dtype);
+    if (d.n_layers < 0 || d.d_model < 1 || d.n_q_heads < 1 || d.n_kv_heads < 1 || d.head_dim < 2 || d.d_ffn < 1 || d.vocab < 1)
+        return fail(ATTS_ERR_INVALID_ARG, "atts_model_create: non-positive dimension");
+    if (d.n_q_heads % d.n_kv_heads) return fail(ATTS_ERR_SHAPE, "atts_model_create: n_kv_heads must divide n_q_heads");
+    if (d.head_dim % 2 || d.head_dim > 256) return fail(ATTS_ERR_SHAPE, "atts_model_create: head_dim must be even and <= 256");
+    const size_t es = dtype_size(d.dtype);
+    if ((d.d_model * es) % 16 || (d.d_ffn * es) % 16 || ((size_t)d.n_q_heads * d.head_dim * es) % 16 || (d.head_dim * es) % 16)
+        return fail(ATTS_ERR_SHAPE, "atts_model_create: d_model, d_ffn and head_dim rows must be multiples of 16 bytes");
+    if (!(d.rms_eps >= 0.f) || !(d.rope_theta > 0.f)) return fail(ATTS_ERR_INVALID_ARG, "atts_model_create: bad rms_eps / rope_theta");
+    if (!w->tok_embed || !w->final_norm || !w->lm_head) return fail(ATTS_ERR_INVALID_ARG, "atts_model_create: NULL embedding / final norm / LM head");
+    if (d.n_layers > 0 && (!w->attn_norm || !w->wqkv || !w->wo || !w->ffn_norm || !w->w_gate_up || !w->w_down))
+        return fail(ATTS_ERR_INVALID_ARG, "atts_model_create: NULL per-layer pointer array");
+    atts_model* m = new (std::nothrow) atts_model();
+    if (!m) return fail(ATTS_ERR_HIP, "atts_model_create: out of host memory");
+    m->desc = d;
+    m->tok_embed = w->tok_embed;
+    m->final_norm = w->final_norm;
+    m->lm_head = w->lm_head;
+    for (int l = 0; l < d.n_layers; ++l) {
+        if (!w->attn_norm[l] || !w->wqkv[l] || !w->wo[l] || !w->ffn_norm[l] || !w->w_gate_up[l] || !w->w_down[l]) {
+            delete m;
+            return fail(ATTS_ERR_INVALID_ARG, "atts_model_create: NULL weight pointer in layer %d", l);
+        }
+        if (((uintptr_t)w->wqkv[l] | (uintptr_t)w->wo[l] | (uintptr_t)w->w_gate_up[l] | (uintptr_t)w->w_down[l]) & 15) {
+            delete m;
+            return fail(ATTS_ERR_INVALID_ARG, "atts_model_create: layer %d matrices must be 16-byte aligned", l);
+        }
+        m->attn_norm.push_back(w->attn_norm[l]);
+        m->wqkv.push_back(w->wqkv[l]);
+        m->wo.push_back(w->wo[l]);
+        m->ffn_norm.push_back(w->ffn_norm[l]);
+        m->w_gate_up.push_back(w->w_gate_up[l]);
+        m->w_down.push_back(w->w_down[l]);
+    }
+    if (((uintptr_t)w->tok_embed | (uintptr_t)w->lm_head) & 15) {
+        delete m;
+        return fail(ATTS_ERR_INVALID_ARG, "atts_model_create: embedding / LM head must be 16-byte aligned");
+    }
+    hipError_t e = hipMalloc(reinterpret_cast<void**>(&m->err_flag), sizeof(int32_t));
+    if (e == hipSuccess) e = hipMemset(m->err_flag, 0, sizeof(int32_t));
+    if (e != hipSuccess) {
+        delete m;
+        return fail(ATTS_ERR_HIP, "atts_model_create: device flag allocation failed: %s", hipGetErrorString(e));
+    }
+    *out = m;
+    return ATTS_OK;
+}
+
+int32_t atts_model_destroy(atts_model* m) {
+    if (!m) return ATTS_OK;
+    (void)hipFree(m->err_flag);
+    delete m;
+    return ATTS_OK;
+}
+
+int32_t atts_workspace_bytes(const atts_model* m, int32_t P, int32_t K, int32_t T_max, size_t* out_bytes) {
+    if (!m || !out_bytes) return fail(ATTS_ERR_INVALID_ARG, "atts_workspace_bytes: NULL argument");
+    ATTS_TRY(check_score_shape("atts_workspace_bytes", P, K, T_max));
+    *out_bytes = carve(m->desc, ScoreShape{P, K, T_max}).total;
+    return ATTS_OK;
+}
+
+int32_t atts_score_drafts(const atts_model* m, const int32_t* prefix_ids, int32_t P, const int32_t* draft_ids,
+                          const int32_t* draft_lens, int32_t K, int32_t T_max, int32_t score_mode, float* token_logprobs,
+                          float* scores, void* workspace, size_t workspace_bytes, void* hip_stream) {
+    if (!m) return fail(ATTS_ERR_INVALID_ARG, "atts_score_drafts: NULL model");
+    if (!prefix_ids || !draft_ids || !scores) return fail(ATTS_ERR_INVALID_ARG, "atts_score_drafts: NULL prefix_ids / draft_ids / scores");
+    ATTS_TRY(check_score_shape("atts_score_drafts", P, K, T_max));
+    if (score_mode != ATTS_SCORE_MEAN_NLL && score_mode != ATTS_SCORE_SUM_NLL)
+        return fail(ATTS_ERR_INVALID_ARG, "atts_score_drafts: unknown score_mode %d", score_mode);
+    const atts_model_desc& d = m->desc;
+    const ScoreShape s{P, K, T_max};
+    const Workspace ws = carve(d, s);
+    if (!workspace || ((uintptr_t)workspace & 255)) return fail(ATTS_ERR_WORKSPACE, "atts_score_drafts: workspace is NULL or not 256-byte aligned");
+    if (workspace_bytes < ws.total)
+        return fail(ATTS_ERR_WORKSPACE, "atts_score_drafts: workspace has %zu bytes, %zu needed", workspace_bytes, ws.total);
+
+    hipStream_t st = static_cast<hipStream_t>(hip_stream);
+    char* base = static_cast<char*>(workspace);
+    float* h = reinterpret_cast<float*>(base + ws.h);
+    void* xn = base + ws.xn;
+    void* qkv = base + ws.qkv;
+    void* vt = attention_uses_vt(d.dtype, d.head_dim) ? base + ws.vt : nullptr;
+    void* ao = base + ws.ao;
+    void* act = base + ws.act;
+    float2* rope = reinterpret_cast<float2*>(base + ws.rope);
+    void* xs = base + ws.xs;
+    int32_t* targets = reinterpret_cast<int32_t*>(base + ws.targets);
+    uint8_t* valid = reinterpret_cast<uint8_t*>(base + ws.valid);
+    float2* partials = reinterpret_cast<float2*>(base + ws.partials);
+    float* zt = reinterpret_cast<float*>(base + ws.zt);
+    float* lp = reinterpret_cast<float*>(base + ws.lp);
+
+    const int R = s.R(), B = s.B();
+    const int qd = d.n_q_heads * d.head_dim;
+    const int qkv_out = (d.n_q_heads + 2 * d.n_kv_heads) * d.head_dim;
+
+    {
+        StageTimer t_(ATTS_STAGE_EMBED, st);
+        ATTS_TRY(launch_embed(d.dtype, m->tok_embed, d.vocab, d.d_model, prefix_ids, draft_ids, draft_lens, s, h, m->err_flag, st));
+        ATTS_TRY(launch_rope_table(rope, P + T_max, d.head_dim, d.rope_theta, st));
+    }
+    for (int l = 0; l < d.n_layers; ++l) {
+        {
+            StageTimer t_(ATTS_STAGE_NORM, st);
+            ATTS_TRY(launch_rmsnorm(d.dtype, h, m->attn_norm[l], d.rms_eps, R, d.d_model, xn, st));
+        }
+        GemmArgs g{};
+        g.a = xn; g.w = m->wqkv[l]; g.out = qkv; g.M = R; g.N = qkv_out; g.Kd = d.d_model;
+        g.lda = d.d_model; g.ldw = d.d_model; g.ldc = qkv_out;
+        {
+            StageTimer t_(ATTS_STAGE_GEMM_QKV, st);
+            ATTS_TRY(launch_gemm(d.dtype, EPI_STORE_ACT, g, st));
+        }
+        {
+            StageTimer t_(ATTS_STAGE_ROPE, st);
+            ATTS_TRY(launch_rope_split(d.dtype, qkv, rope, s, d.n_q_heads, d.n_kv_heads, d.head_dim, vt, ws.ldv, st));
+        }
+        {
+            StageTimer t_(ATTS_STAGE_ATTENTION, st);
+            ATTS_TRY(launch_attention(d.dtype, qkv, vt, ws.ldv, ao, s, d.n_q_heads, d.n_kv_heads, d.head_dim, st));
+        }
+        g = GemmArgs{};
+        g.a = ao; g.w = m->wo[l]; g.out = h; g.M = R; g.N = d.d_model; g.Kd = qd;
+        g.lda = qd; g.ldw = qd; g.ldc = d.d_model;
+        {
+            StageTimer t_(ATTS_STAGE_GEMM_O, st);
+            ATTS_TRY(launch_gemm(d.dtype, EPI_RESID_F32, g, st));
+        }
+        {
+            StageTimer t_(ATTS_STAGE_NORM, st);
+            ATTS_TRY(launch_rmsnorm(d.dtype, h, m->ffn_norm[l], d.rms_eps, R, d.d_model, xn, st));
+        }
+        g = GemmArgs{};
+        g.a = xn; g.w = m->w_gate_up[l]; g.out = act; g.M = R; g.N = d.d_ffn; g.Kd = d.d_model;
+        g.lda = d.d_model; g.ldw = d.d_model; g.ldc = d.d_ffn;
+        {
+            StageTimer t_(ATTS_STAGE_GEMM_GATE_UP, st);
+            ATTS_TRY(launch_gemm(d.dtype, EPI_SWIGLU, g, st));
+        }
+        g = GemmArgs{};
+        g.a = act; g.w = m->w_down[l]; g.out = h; g.M = R; g.N = d.d_model; g.Kd = d.d_ffn;
+        g.lda = d.d_ffn; g.ldw = d.d_ffn; g.ldc = d.d_model;
+        {
+            StageTimer t_(ATTS_STAGE_GEMM_DOWN, st);
+            ATTS_TRY(launch_gemm(d.dtype, EPI_RESID_F32, g, st));
+        }
+    }
+    {
+        StageTimer t_(ATTS_STAGE_GATHER_NORM, st);
+        ATTS_TRY(launch_gather_norm(d.dtype, h, m->final_norm, d.rms_eps, d.d_model, draft_ids, draft_lens, d.vocab, s, xs,
+                                    targets, valid, st));
+    }
+    GemmArgs g{};
+    g.a = xs; g.w = m->lm_head; g.out = nullptr; g.M = B; g.N = d.vocab; g.Kd = d.d_model;
+    g.lda = d.d_model; g.ldw = d.d_model; g.ldc = 0;
+    g.targets = targets; g.partials = partials; g.target_logit = zt; g.n_part = ws.n_part;
+    {
+        StageTimer t_(ATTS_STAGE_LMHEAD, st);
+        ATTS_TRY(launch_gemm(d.dtype, EPI_LMHEAD, g, st));
+    }
+    {
+        StageTimer t_(ATTS_STAGE_REDUCE, st);
+        ATTS_TRY(launch_lmhead_combine(partials, zt, B, ws.n_part, valid, lp, st));
+        ATTS_TRY(launch_score_reduce(lp, draft_lens, K, T_max, score_mode, token_logprobs, scores, st));
+    }
+    return ATTS_OK;
+}
+
+int32_t atts_model_check(const atts_model* m, void* hip_stream, int32_t* host_flag) {
+    if (!m || !host_flag) return fail(ATTS_ERR_INVALID_ARG, "atts_model_check: NULL argument");
+    hipStream_t st = static_cast<hipStream_t>(hip_stream);
+    ATTS_HIP_TRY(hipMemcpyAsync(host_flag, m->err_flag, sizeof(int32_t), hipMemcpyDeviceToHost, st));
+    ATTS_HIP_TRY(hipStreamSynchronize(st));
+    ATTS_HIP_TRY(hipMemsetAsync(m->err_flag, 0, sizeof(int32_t), st));
+    ATTS_HIP_TRY(hipStreamSynchronize(st));
+    return ATTS_OK;
+}
+
+// ---------------------------------------------------------------------------- stage timing
+
+int32_t atts_profile_enable(int32_t on) {
+    prof_clear();
+    g_prof_on = on != 0;
+    return ATTS_OK;
+}
+
+int32_t atts_profile_read(int32_t stage, double* total_ms, int64_t* launches) {
+    if (stage < 0 || stage >= ATTS_STAGE_COUNT) return fail(ATTS_ERR_INVALID_ARG, "atts_profile_read: unknown stage %d", stage);
+    double ms = 0.0;
+    int64_t n = 0;
+    for (const auto& r : g_prof) {
+        if (r.stage != stage) continue;
+        ATTS_HIP_TRY(hipEventSynchronize(r.stop));
+        float t = 0.f;
+        ATTS_HIP_TRY(hipEventElapsedTime(&t, r.start, r.stop));
+        ms += t;
+        ++n;
+    }
+    if (total_ms) *total_ms = ms;
+    if (launches) *launches = n;
+    return ATTS_OK;
+}
+
+// ---------------------------------------------------------------------------- stand-alone stages
+
+int32_t atts_lmhead_workspace_bytes(int32_t B, int32_t V, size_t* out_bytes) {
+    if (!out_bytes || B < 1 || V < 1) return fail(ATTS_ERR_INVALID_ARG, "atts_lmhead_workspace_bytes: bad argument");
+    // partial count does not depend on dtype
+    *out_bytes = align_up((size_t)B * lmhead_num_partials(ATTS_DTYPE_BF16, B, V) * sizeof(float2), 256) + align_up((size_t)B * sizeof(float), 256);
+    return ATTS_OK;
+}
+
+int32_t atts_lmhead_logprobs(int32_t dtype, const void* x, const void* w, const int32_t* targets, int32_t B, int32_t d, int32_t V,
+                             float* logprobs, void* workspace, size_t workspace_bytes, void* hip_stream) {
+    if (dtype != ATTS_DTYPE_F32 && dtype != ATTS_DTYPE_BF16) return fail(ATTS_ERR_INVALID_ARG, "atts_lmhead_logprobs: unknown dtype %d", dtype);
+    if (!x || !w || !targets || !logprobs) return fail(ATTS_ERR_INVALID_ARG, "atts_lmhead_logprobs: NULL argument");
+    if (B < 1 || d < 1 || V < 1) return fail(ATTS_ERR_INVALID_ARG, "atts_lmhead_logprobs: B, d, V must be >= 1");
+    size_t need = 0;
+    ATTS_TRY(atts_lmhead_workspace_bytes(B, V, &need));
+    if (!workspace || ((uintptr_t)workspace & 255) || workspace_bytes < need)
+        return fail(ATTS_ERR_WORKSPACE, "atts_lmhead_logprobs: workspace NULL, misaligned or smaller than %zu bytes", need);
+    const int n_part = lmhead_num_partials(dtype, B, V);
+    float2* partials = static_cast<float2*>(workspace);
+    float* zt = reinterpret_cast<float*>(static_cast<char*>(workspace) + align_up((size_t)B * n_part * sizeof(float2), 256));
+    GemmArgs g{};
+    g.a = x; g.w = w; g.M = B; g.N = V; g.Kd = d; g.lda = d; g.ldw = d;
+    g.targets = targets; g.partials = partials; g.target_logit = zt; g.n_part = n_part;
+    hipStream_t st = static_cast<hipStream_t>(hip_stream);
+    ATTS_TRY(launch_gemm(dtype, EPI_LMHEAD, g, st));
+    return launch_lmhead_combine(partials, zt, B, n_part, nullptr, logprobs, st);
+}
+
+int32_t atts_gemm_nt(int32_t dtype, const void* a, const void* w, float* c, int32_t M, int32_t N, int32_t Kdim, void* hip_stream) {
+    if (dtype != ATTS_DTYPE_F32 && dtype != ATTS_DTYPE_BF16) return fail(ATTS_ERR_INVALID_ARG, "atts_gemm_nt: unknown dtype %d", dtype);
+    if (!a || !w || !c) return fail(ATTS_ERR_INVALID_ARG, "atts_gemm_nt: NULL argument");
+    GemmArgs g{};
+    g.a = a; g.w = w; g.out = c; g.M = M; g.N = N; g.Kd = Kdim; g.lda = Kdim; g.ldw = Kdim; g.ldc = N;
+    return launch_gemm(dtype, EPI_STORE_F32, g, static_cast<hipStream_t>(hip_stream));
+}
+
+int32_t atts_attention_workspace_bytes(int32_t dtype, int32_t R, int32_t n_kv, int32_t hd, size_t* out_bytes) {
+    if (!out_bytes || R < 1 || n_kv < 1 || hd < 2) return fail(ATTS_ERR_INVALID_ARG, "atts_attention_workspace_bytes: bad argument");
+    *out_bytes = attention_uses_vt(dtype, hd) ? align_up((size_t)n_kv * hd * align_up(R, 64) * dtype_size(dtype), 256) : 0;
+    return ATTS_OK;
+}
+
+int32_t atts_attention_shared_prefix(int32_t dtype, const void* qkv, void* out, int32_t P, int32_t K, int32_t T, int32_t n_q,
+                                     int32_t n_kv, int32_t hd, void* workspace, size_t workspace_bytes, void* hip_stream) {
+    if (dtype != ATTS_DTYPE_F32 && dtype != ATTS_DTYPE_BF16) return fail(ATTS_ERR_INVALID_ARG, "atts_attention_shared_prefix: unknown dtype %d", dtype);
+    if (!qkv || !out) return fail(ATTS_ERR_INVALID_ARG, "atts_attention_shared_prefix: NULL argument");
+    if (P < 1 || K < 0 || T < 0 || (K > 0 && T < 1)) return fail(ATTS_ERR_INVALID_ARG, "atts_attention_shared_prefix: need P >= 1 and K = 0 or T >= 1");
+    if (n_q < 1 || n_kv < 1 || n_q % n_kv || hd < 2 || hd % 2 || hd > 256 || (hd * dtype_size(dtype)) % 16)
+        return fail(ATTS_ERR_SHAPE, "atts_attention_shared_prefix: unsupported head configuration");
+    if (K == 0) T = 1;
+    ATTS_TRY(check_score_shape("atts_attention_shared_prefix", P, K > 0 ? K : 1, T));
+    const ScoreShape s{P, K, T};
+    size_t need = 0;
+    ATTS_TRY(atts_attention_workspace_bytes(dtype, s.R(), n_kv, hd, &need));
+    void* vt = nullptr;
+    hipStream_t st = static_cast<hipStream_t>(hip_stream);
+    const int64_t ldv = (int64_t)align_up(s.R(), 64);
+    if (need) {
+        if (!workspace || ((uintptr_t)workspace & 255) || workspace_bytes < need)
+            return fail(ATTS_ERR_WORKSPACE, "atts_attention_shared_prefix: workspace NULL, misaligned or smaller than %zu bytes", need);
+        vt = workspace;
+        ATTS_TRY(launch_transpose_v(dtype, qkv, s.R(), n_q, n_kv, hd, vt, ldv, st));
+    }
+    return launch_attention(dtype, qkv, vt, ldv, out, s, n_q, n_kv, hd, st);
+}
+
+}  // extern "C"

@@ -1,0 +1,275 @@
+// Shared-prefix (token-tree) attention.
+//
+// Rows of the call are laid out [prefix (P) | draft 0 (T) | ... | draft K-1 (T)].  All K drafts
+// continue the same prompt, so the prefix keys/values exist once and every draft row attends
+// to them ("shared-prefix mechanism", Introduction); a draft row additionally attends causally
+// to the rows of its own draft.  With seg(r) = first row of r's draft (0 for a prefix row):
+//     key j visible to query r   <=>   j <= r  and  (j < P  or  j >= seg(r)).
+// This is exactly K independent causal sequences [prefix ; draft_k], evaluated without
+// recomputing or re-storing the prefix.
+//
+// Two kernels:
+//   * attn_mfma_kernel  bf16, head_dim 128: flash-style, 128 query rows of one head per
+//     workgroup, key/value tiles of 64 rows staged in LDS and shared by the 4 wavefronts.
+//     Works on transposed products so that no register transpose is needed:
+//        S^T = K Q^T   (32 keys x 32 queries per MFMA block; a lane owns ONE query column,
+//                       so the online-softmax statistics are per lane)
+//        O^T = V^T P^T (P^T is fed straight from the S^T accumulator registers; V^T tiles
+//                       come from a [n_kv, hd, rows] copy of V written after the QKV GEMM)
+//   * attn_simple_kernel any dtype / head_dim: one wavefront per (row, head); used by the
+//     fp32 model.
+#include "common.h"
+
+namespace atts {
+namespace {
+
+__device__ __forceinline__ int seg_start(int r, int P, int T) { return r < P ? 0 : P + (r - P) / T * T; }
+
+// ------------------------------------------------------------------------------------------
+// Simple kernel
+// ------------------------------------------------------------------------------------------
+template <typename T>
+__global__ __launch_bounds__(64) void attn_simple_kernel(const T* __restrict__ qkv, T* __restrict__ out, int P, int Tn,
+                                                         int nq, int nkv, int hd, float scale) {
+    extern __shared__ float sm[];           // [hd] query, then [n_keys] scores
+    float* sq = sm;
+    float* sp = sm + hd;
+    const int r = blockIdx.x, head = blockIdx.y, lane = threadIdx.x;
+    const int kvh = head / (nq / nkv);
+    const int64_t ld = (int64_t)(nq + 2 * nkv) * hd;
+    const T* q = qkv + (int64_t)r * ld + head * hd;
+    const T* kbase = qkv + (nq + kvh) * hd;
+    const T* vbase = qkv + (nq + nkv + kvh) * hd;
+    for (int c = lane; c < hd; c += 64) sq[c] = to_f32<T>(q[c]) * scale;
+    __syncthreads();
+
+    const int n1 = r < P ? r + 1 : P;                 // visible prefix keys
+    const int s0 = seg_start(r, P, Tn);
+    const int n2 = r < P ? 0 : r - s0 + 1;            // visible keys of the own draft
+    const int n = n1 + n2;
+    float mx = -INFINITY;
+    for (int i = lane; i < n; i += 64) {
+        const T* k = kbase + (int64_t)(i < n1 ? i : s0 + (i - n1)) * ld;
+        float s = 0.f;
+        for (int c = 0; c < hd; ++c) s += sq[c] * to_f32<T>(k[c]);
+        sp[i] = s;
+        mx = fmaxf(mx, s);
+    }
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) mx = fmaxf(mx, __shfl_xor(mx, o));
+    float sum = 0.f;
+    for (int i = lane; i < n; i += 64) {
+        float p = __expf(sp[i] - mx);
+        sp[i] = p;
+        sum += p;
+    }
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) sum += __shfl_xor(sum, o);
+    __syncthreads();
+    const float inv = 1.f / sum;
+    for (int c = lane; c < hd; c += 64) {
+        float acc = 0.f;
+        for (int i = 0; i < n; ++i) acc += sp[i] * to_f32<T>(vbase[(int64_t)(i < n1 ? i : s0 + (i - n1)) * ld + c]);
+        out[(int64_t)r * nq * hd + head * hd + c] = from_f32<T>(acc * inv);
+    }
+}
+
+// ------------------------------------------------------------------------------------------
+// MFMA kernel (bf16, hd = 128)
+// ------------------------------------------------------------------------------------------
+constexpr int kHd = 128;
+constexpr int kQTile = 128;   // query rows per workgroup (32 per wave)
+constexpr int kKTile = 64;    // keys per LDS tile
+
+__global__ __launch_bounds__(256) void attn_mfma_kernel(const bf16* __restrict__ qkv, const bf16* __restrict__ vt,
+                                                        int64_t ldv, bf16* __restrict__ out, int R, int P, int Tn,
+                                                        int nq, int nkv, float scale_log2e) {
+    __shared__ __attribute__((aligned(16))) char sK[kKTile * kHd * 2];    // [64 keys][256 B], 16 B chunks XOR (key & 15)
+    __shared__ __attribute__((aligned(16))) char sV[kHd * kKTile * 2];    // [128 dims][128 B], 16 B chunks XOR (dim & 7)
+
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int l32 = lane & 31, g = lane >> 5;
+    const int head = blockIdx.y, kvh = head / (nq / nkv);
+    const int r0 = blockIdx.x * kQTile;
+    const int r_last = min(r0 + kQTile, R) - 1;
+    const int64_t ld = (int64_t)(nq + 2 * nkv) * kHd;
+
+    // This lane's query row and its visibility window.
+    const int r = r0 + wave * 32 + l32;
+    const bool r_ok = r < R;
+    const int ss = seg_start(r_ok ? r : r_last, P, Tn);
+
+    // Q fragments (B operand of S^T = K Q^T): lane holds Q[r][16 s + 8 g + (0..7)], s = 0..7.
+    bf16x8 qf[8];
+    {
+        const bf16* qp = qkv + (int64_t)(r_ok ? r : 0) * ld + head * kHd + 8 * g;
+#pragma unroll
+        for (int s = 0; s < 8; ++s) {
+            if (r_ok) qf[s] = *reinterpret_cast<const bf16x8*>(qp + 16 * s);
+            else
+#pragma unroll
+                for (int e = 0; e < 8; ++e) qf[s][e] = (bf16)0.f;
+        }
+    }
+
+    // Tiles: the prefix range [0, min(P, r_last + 1)) and the range of the drafts this query
+    // tile touches, both walked in 64-key tiles aligned to multiples of 64.
+    const int pre_end = min(P, r_last + 1);
+    const int n1 = (pre_end + kKTile - 1) / kKTile;
+    const int s2 = max(n1 * kKTile, seg_start(r0, P, Tn) / kKTile * kKTile);
+    const int n2 = r_last >= s2 ? (r_last - s2) / kKTile + 1 : 0;
+    const int n_tiles = n1 + n2;
+
+    // Per-thread chunk coordinates for the tile loads.
+    const int k_row = tid >> 4, k_cc = tid & 15;       // K: rows k_row + 16 i, i < 4
+    const int v_row = tid >> 3, v_cc = tid & 7;        // V^T: dims v_row + 32 i, i < 4
+    const bf16* kg = qkv + (nq + kvh) * kHd + k_cc * 8;
+    const bf16* vg = vt + (int64_t)kvh * kHd * ldv + v_cc * 8;
+    uint4 rk[4], rv[4];
+    auto prefetch = [&](int t) __attribute__((always_inline)) {
+        const int j0 = t < n1 ? t * kKTile : s2 + (t - n1) * kKTile;
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            int j = j0 + k_row + 16 * i;
+            rk[i] = make_uint4(0, 0, 0, 0);
+            if (j < R) rk[i] = *reinterpret_cast<const uint4*>(kg + (int64_t)j * ld);
+            rv[i] = *reinterpret_cast<const uint4*>(vg + (int64_t)(v_row + 32 * i) * ldv + j0);
+        }
+    };
+    auto stage = [&]() __attribute__((always_inline)) {
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            int kr = k_row + 16 * i;
+            *reinterpret_cast<uint4*>(sK + kr * 256 + ((k_cc ^ (kr & 15)) << 4)) = rk[i];
+            int vr = v_row + 32 * i;
+            *reinterpret_cast<uint4*>(sV + vr * 128 + ((v_cc ^ (vr & 7)) << 4)) = rv[i];
+        }
+    };
+
+    f32x16 acc_o[4];
+#pragma unroll
+    for (int nb = 0; nb < 4; ++nb)
+#pragma unroll
+        for (int v = 0; v < 16; ++v) acc_o[nb][v] = 0.f;
+    float m_run = -1e30f;   // running max (scaled, log2 domain), shared by the lane pair (l, l ^ 32)
+    float l_run = 0.f;      // this lane's share of the running denominator
+
+    if (n_tiles > 0) prefetch(0);
+    for (int t = 0; t < n_tiles; ++t) {
+        const int j0 = t < n1 ? t * kKTile : s2 + (t - n1) * kKTile;
+        __syncthreads();
+        stage();
+        __syncthreads();
+        if (t + 1 < n_tiles) prefetch(t + 1);
+
+        // ---- S^T = K Q^T for two 32-key blocks
+        f32x16 acc_s[2];
+#pragma unroll
+        for (int kb = 0; kb < 2; ++kb) {
+#pragma unroll
+            for (int v = 0; v < 16; ++v) acc_s[kb][v] = 0.f;
+            const int kr = kb * 32 + l32;
+            const char* kp = sK + kr * 256;
+#pragma unroll
+            for (int s = 0; s < 8; ++s) {
+                bf16x8 kf = *reinterpret_cast<const bf16x8*>(kp + (((2 * s + g) ^ (kr & 15)) << 4));
+                acc_s[kb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, qf[s], acc_s[kb], 0, 0, 0);
+            }
+        }
+        // acc_s[kb][4 a + b] = score of key j0 + 32 kb + 8 a + 4 g + b for this lane's query.
+        float mx = m_run;
+#pragma unroll
+        for (int kb = 0; kb < 2; ++kb)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) {
+                int j = j0 + 32 * kb + 8 * (v >> 2) + 4 * g + (v & 3);
+                bool vis = r_ok && j <= r && (j < P || j >= ss);
+                float sc = vis ? acc_s[kb][v] * scale_log2e : -INFINITY;
+                acc_s[kb][v] = sc;
+                mx = fmaxf(mx, sc);
+            }
+        mx = fmaxf(mx, __shfl_xor(mx, 32));
+        const float alpha = exp2f(m_run - mx);
+        m_run = mx;
+        float psum = 0.f;
+        bf16x8 pf[4];
+#pragma unroll
+        for (int kb = 0; kb < 2; ++kb)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) {
+                float p = exp2f(acc_s[kb][v] - mx);
+                psum += p;
+                pf[kb * 2 + (v >> 3)][v & 7] = (bf16)p;
+            }
+        l_run = l_run * alpha + psum;
+#pragma unroll
+        for (int nb = 0; nb < 4; ++nb)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) acc_o[nb][v] *= alpha;
+
+        // ---- O^T += V^T P^T
+#pragma unroll
+        for (int nb = 0; nb < 4; ++nb) {
+            const int n = nb * 32 + l32;
+            const char* vp = sV + n * 128 + 8 * g;
+#pragma unroll
+            for (int s = 0; s < 4; ++s) {
+                union {
+                    uint2 u[2];
+                    bf16x8 f;
+                } vf;
+                vf.u[0] = *reinterpret_cast<const uint2*>(vp + (((2 * s) ^ (n & 7)) << 4));
+                vf.u[1] = *reinterpret_cast<const uint2*>(vp + (((2 * s + 1) ^ (n & 7)) << 4));
+                acc_o[nb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf.f, pf[s], acc_o[nb], 0, 0, 0);
+            }
+        }
+    }
+
+    // ---- normalise and store: acc_o[nb][4 a + b] = O[r][32 nb + 8 a + 4 g + b]
+    const float l_tot = l_run + __shfl_xor(l_run, 32);
+    if (r_ok) {
+        const float inv = 1.f / l_tot;
+        bf16* op = out + (int64_t)r * nq * kHd + head * kHd + 4 * g;
+#pragma unroll
+        for (int nb = 0; nb < 4; ++nb)
+#pragma unroll
+            for (int a = 0; a < 4; ++a) {
+                bf16x4 o4;
+#pragma unroll
+                for (int b = 0; b < 4; ++b) o4[b] = (bf16)(acc_o[nb][4 * a + b] * inv);
+                *reinterpret_cast<bf16x4*>(op + 32 * nb + 8 * a) = o4;
+            }
+    }
+}
+
+}  // namespace
+
+bool attention_uses_vt(int32_t dtype, int32_t hd) { return dtype == ATTS_DTYPE_BF16 && hd == kHd; }
+
+int32_t launch_attention(int32_t dtype, const void* qkv, const void* vt, int64_t ldv, void* out, ScoreShape s,
+                         int32_t nq, int32_t nkv, int32_t hd, hipStream_t stream) {
+    const int R = s.R();
+    const float scale = 1.f / sqrtf((float)hd);
+    if (attention_uses_vt(dtype, hd)) {
+        if (!vt || ldv < (int64_t)align_up(R, kKTile) || ldv % 8)
+            return fail(ATTS_ERR_WORKSPACE, "attention: transposed-V buffer missing or too narrow");
+        dim3 grid((unsigned)ceil_div(R, kQTile), nq);
+        hipLaunchKernelGGL(attn_mfma_kernel, grid, dim3(256), 0, stream, (const bf16*)qkv, (const bf16*)vt, ldv, (bf16*)out,
+                           R, s.P, s.T, nq, nkv, scale * 1.4426950408889634f);
+        ATTS_LAUNCH_CHECK("attn_mfma_kernel");
+        return ATTS_OK;
+    }
+    const size_t lds = (size_t)(hd + s.P + s.T) * sizeof(float);
+    if (lds > 60 * 1024) return fail(ATTS_ERR_SHAPE, "attention: context of %d keys is too long for this dtype/head_dim", s.P + s.T);
+    dim3 grid(R, nq);
+    if (dtype == ATTS_DTYPE_F32)
+        hipLaunchKernelGGL(attn_simple_kernel<float>, grid, dim3(64), lds, stream, (const float*)qkv, (float*)out, s.P, s.T, nq,
+                           nkv, hd, scale);
+    else
+        hipLaunchKernelGGL(attn_simple_kernel<bf16>, grid, dim3(64), lds, stream, (const bf16*)qkv, (bf16*)out, s.P, s.T, nq,
+                           nkv, hd, scale);
+    ATTS_LAUNCH_CHECK("attn_simple_kernel");
+    return ATTS_OK;
+}
+
+}  // namespace atts

@@ -1,0 +1,114 @@
+// Shared host/device helpers for the ATTS HIP library (gfx950 only).
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stddef.h>
+#include <stdint.h>
+
+#include "atts.h"
+
+namespace atts {
+
+typedef __bf16 bf16;
+
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef __bf16 bf16x4 __attribute__((ext_vector_type(4)));
+typedef float f32x16 __attribute__((ext_vector_type(16)));
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+
+constexpr int kWave = 64;
+
+// Records the calling thread's error text and returns `code`.
+int32_t fail(int32_t code, const char* fmt, ...) __attribute__((format(printf, 2, 3)));
+
+#define ATTS_HIP_TRY(expr)                                                                   \
+    do {                                                                                     \
+        hipError_t e__ = (expr);                                                             \
+        if (e__ != hipSuccess)                                                               \
+            return ::atts::fail(ATTS_ERR_HIP, "%s failed: %s", #expr, hipGetErrorString(e__)); \
+    } while (0)
+
+// After a kernel launch: report a launch-configuration error without synchronising.
+#define ATTS_LAUNCH_CHECK(name)                                                              \
+    do {                                                                                     \
+        hipError_t e__ = hipGetLastError();                                                  \
+        if (e__ != hipSuccess)                                                               \
+            return ::atts::fail(ATTS_ERR_HIP, "launch of %s failed: %s", name, hipGetErrorString(e__)); \
+    } while (0)
+
+inline size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
+inline int64_t ceil_div(int64_t a, int64_t b) { return (a + b - 1) / b; }
+inline size_t dtype_size(int32_t dtype) { return dtype == ATTS_DTYPE_F32 ? 4 : 2; }
+
+// ---- device-side conversions ------------------------------------------------------------
+template <typename T> __device__ __forceinline__ float to_f32(T v);
+template <> __device__ __forceinline__ float to_f32<float>(float v) { return v; }
+template <> __device__ __forceinline__ float to_f32<bf16>(bf16 v) { return (float)v; }
+
+template <typename T> __device__ __forceinline__ T from_f32(float v);
+template <> __device__ __forceinline__ float from_f32<float>(float v) { return v; }
+template <> __device__ __forceinline__ bf16 from_f32<bf16>(float v) { return (bf16)v; }  // RNE
+
+// ---- launch wrappers (each enqueues on `stream`, returns ATTS_OK / ATTS_ERR_HIP) ----------
+
+// Epilogues of the NT GEMM  acc[M, N] = A[M, Kd] . W[N, Kd]^T
+enum GemmEpilogue : int32_t {
+    EPI_STORE_ACT = 0,   // out (T) [M, ldc]      = acc
+    EPI_STORE_F32 = 1,   // out (float) [M, ldc]  = acc
+    EPI_RESID_F32 = 2,   // out (float) [M, ldc] += acc            (residual stream update)
+    EPI_SWIGLU = 3,      // W = [gate rows (F) ; up rows (F)], N = F: out (T) [M, ldc] = silu(gate) * up
+    EPI_LMHEAD = 4,      // per-row online-softmax partials over this tile's columns + target logit
+};
+
+struct GemmArgs {
+    const void* a;       // [M, Kd] row-major, leading dimension lda (elements)
+    const void* w;       // [N, Kd] row-major, leading dimension ldw  (EPI_SWIGLU: [2N, Kd])
+    void* out;           // see GemmEpilogue
+    int32_t M, N, Kd;
+    int64_t lda, ldw, ldc;
+    // EPI_LMHEAD only:
+    const int32_t* targets;  // [M] target column per row
+    float2* partials;        // [M, n_part] (running max, sum of exp) per column slab
+    float* target_logit;     // [M]
+    int32_t n_part;          // number of column slabs = lmhead_num_partials(N)
+};
+
+int32_t lmhead_num_partials(int32_t dtype, int32_t M, int32_t N);
+int32_t launch_gemm(int32_t dtype, GemmEpilogue epi, const GemmArgs& g, hipStream_t stream);
+
+// lp[b] = target_logit[b] - logsumexp over the n_part partials of row b; rows with valid[b] == 0
+// (or b beyond) get 0.  valid may be NULL.
+int32_t launch_lmhead_combine(const float2* partials, const float* target_logit, int32_t B, int32_t n_part,
+                              const uint8_t* valid, float* lp, hipStream_t stream);
+
+struct ScoreShape {
+    int32_t P, K, T;        // prefix length, drafts, padded draft length
+    int32_t R() const { return P + K * T; }
+    int32_t B() const { return K * T; }
+};
+
+int32_t launch_embed(int32_t dtype, const void* tok_embed, int32_t vocab, int32_t d,
+                     const int32_t* prefix_ids, const int32_t* draft_ids, const int32_t* draft_lens,
+                     ScoreShape s, float* h, int32_t* err_flag, hipStream_t stream);
+int32_t launch_rmsnorm(int32_t dtype, const float* h, const float* gain, float eps, int32_t rows, int32_t d,
+                       void* out, hipStream_t stream);
+// rope table: cs[pos][i] = (cos, sin)(pos * theta^(-2 i / hd)), pos < n_pos, i < hd / 2
+int32_t launch_rope_table(float2* cs, int32_t n_pos, int32_t hd, float theta, hipStream_t stream);
+// In-place rotate-half RoPE on the q and k columns of qkv [R, (nq + 2 nkv) hd]; writes V transposed
+// to vt [nkv, hd, ldv] (ldv >= R) when vt != NULL.
+int32_t launch_rope_split(int32_t dtype, void* qkv, const float2* cs, ScoreShape s, int32_t nq, int32_t nkv,
+                          int32_t hd, void* vt, int64_t ldv, hipStream_t stream);
+int32_t launch_transpose_v(int32_t dtype, const void* qkv, int32_t R, int32_t nq, int32_t nkv, int32_t hd,
+                           void* vt, int64_t ldv, hipStream_t stream);
+// xs[b] = rmsnorm(h[row(b)]) for the B = K T scoring rows; targets[b] / valid[b] from the draft ids.
+int32_t launch_gather_norm(int32_t dtype, const float* h, const float* gain, float eps, int32_t d,
+                           const int32_t* draft_ids, const int32_t* draft_lens, int32_t vocab, ScoreShape s,
+                           void* xs, int32_t* targets, uint8_t* valid, hipStream_t stream);
+int32_t launch_score_reduce(const float* lp, const int32_t* draft_lens, int32_t K, int32_t T, int32_t mode,
+                            float* token_logprobs, float* scores, hipStream_t stream);
+
+bool attention_uses_vt(int32_t dtype, int32_t hd);
+int32_t launch_attention(int32_t dtype, const void* qkv, const void* vt, int64_t ldv, void* out, ScoreShape s,
+                         int32_t nq, int32_t nkv, int32_t hd, hipStream_t stream);
+
+}  // namespace atts

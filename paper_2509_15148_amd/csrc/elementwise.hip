@@ -1,0 +1,252 @@
+// Memory-bound stages of the scoring path: embedding gather, RMSNorm, rotary embedding +
+// V transpose, scoring-row gather + final norm, score reduction.
+// All are HBM-bound and tiny next to the GEMMs; they are written for coalesced 16-byte
+// accesses and fixed reduction orders (no float atomics, so results are run-to-run stable).
+#include "common.h"
+
+namespace atts {
+namespace {
+
+// ---- wave / block reductions -------------------------------------------------------------
+__device__ __forceinline__ float wave_sum(float v) {
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o);
+    return v;
+}
+
+// Sum over a block of kBlock threads (kBlock multiple of 64, <= 1024); result valid in all threads.
+template <int kBlock>
+__device__ __forceinline__ float block_sum(float v, float* red /* [kBlock / 64] */) {
+    v = wave_sum(v);
+    if constexpr (kBlock == 64) return v;
+    const int wave = threadIdx.x >> 6;
+    __syncthreads();
+    if ((threadIdx.x & 63) == 0) red[wave] = v;
+    __syncthreads();
+    float t = 0.f;
+#pragma unroll
+    for (int i = 0; i < kBlock / 64; ++i) t += red[i];
+    return t;
+}
+
+// Row of the token tree -> (is it a draft row, which draft, which position in the draft)
+__device__ __forceinline__ int tree_position(int r, int P, int T) { return r < P ? r : P + (r - P) % T; }
+
+// ---- S0: embedding gather ------------------------------------------------------------------
+template <typename T>
+__global__ __launch_bounds__(256) void embed_kernel(const T* __restrict__ emb, int vocab, int d,
+                                                    const int32_t* __restrict__ prefix_ids,
+                                                    const int32_t* __restrict__ draft_ids,
+                                                    const int32_t* __restrict__ draft_lens, int P, int Tn,
+                                                    float* __restrict__ h, int32_t* __restrict__ err_flag) {
+    const int r = blockIdx.x;
+    int id;
+    bool padding = false;
+    if (r < P) {
+        id = prefix_ids[r];
+    } else {
+        int k = (r - P) / Tn, t = (r - P) % Tn;
+        id = draft_ids[(int64_t)k * Tn + t];
+        padding = draft_lens && t >= draft_lens[k];
+    }
+    if (id < 0 || id >= vocab) {
+        if (!padding && threadIdx.x == 0) *err_flag = 1;
+        id = 0;
+    }
+    const T* src = emb + (int64_t)id * d;
+    float* dst = h + (int64_t)r * d;
+    for (int c = threadIdx.x; c < d; c += blockDim.x) dst[c] = to_f32<T>(src[c]);
+}
+
+// ---- S1: RMSNorm over rows of the fp32 residual stream ---------------------------------------
+template <typename T>
+__global__ __launch_bounds__(256) void rmsnorm_kernel(const float* __restrict__ h, const float* __restrict__ gain,
+                                                      float eps, int d, T* __restrict__ out) {
+    __shared__ float red[4];
+    const float* x = h + (int64_t)blockIdx.x * d;
+    float ss = 0.f;
+    for (int c = threadIdx.x; c < d; c += 256) {
+        float v = x[c];
+        ss += v * v;
+    }
+    ss = block_sum<256>(ss, red);
+    const float inv = rsqrtf(ss / (float)d + eps);
+    T* o = out + (int64_t)blockIdx.x * d;
+    for (int c = threadIdx.x; c < d; c += 256) o[c] = from_f32<T>(x[c] * inv * gain[c]);
+}
+
+// ---- rotary table: (cos, sin)(pos * theta^(-2 i / hd)) in fp64, rounded once ------------------
+__global__ void rope_table_kernel(float2* __restrict__ cs, int n_pos, int half, double log_theta_over_half) {
+    int idx = blockIdx.x * blockDim.x + threadIdx.x;
+    if (idx >= n_pos * half) return;
+    int pos = idx / half, i = idx % half;
+    double ang = (double)pos * exp(-(double)i * log_theta_over_half);
+    double s, c;
+    sincos(ang, &s, &c);
+    cs[idx] = make_float2((float)c, (float)s);
+}
+
+// ---- S2 epilogue (unfused): rotate q and k in place -------------------------------------------
+// One thread per (row, head, pair).  Heads 0 .. nq + nkv - 1 of the qkv row are rotated.
+template <typename T>
+__global__ __launch_bounds__(256) void rope_kernel(T* __restrict__ qkv, const float2* __restrict__ cs, int R, int P,
+                                                   int Tn, int n_rot_heads, int hd, int64_t ld) {
+    const int half = hd >> 1;
+    int64_t idx = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    int64_t total = (int64_t)R * n_rot_heads * half;
+    if (idx >= total) return;
+    int i = (int)(idx % half);
+    int head = (int)((idx / half) % n_rot_heads);
+    int r = (int)(idx / ((int64_t)half * n_rot_heads));
+    float2 c_s = cs[(int64_t)tree_position(r, P, Tn) * half + i];
+    T* p = qkv + (int64_t)r * ld + head * hd + i;
+    float x1 = to_f32<T>(p[0]), x2 = to_f32<T>(p[half]);
+    p[0] = from_f32<T>(x1 * c_s.x - x2 * c_s.y);
+    p[half] = from_f32<T>(x2 * c_s.x + x1 * c_s.y);
+}
+
+// ---- V transpose: vt[kvh][c][r] = qkv[r][v_off + kvh hd + c] ------------------------------------
+// 64 x 64 tiles through LDS so both the read and the write are coalesced.  Columns r in [R, ldv)
+// are written as zero: the attention kernel loads whole 64-key tiles and multiplies the masked
+// probabilities (exact zeros) with whatever it finds there.
+template <typename T>
+__global__ __launch_bounds__(256) void transpose_v_kernel(const T* __restrict__ qkv, int R, int64_t ld, int v_off,
+                                                          int hd, T* __restrict__ vt, int64_t ldv) {
+    __shared__ T tile[64][65];
+    const int r0 = blockIdx.x * 64, c0 = blockIdx.y * 64, kvh = blockIdx.z;
+    const int tx = threadIdx.x & 63, ty = threadIdx.x >> 6;
+    for (int i = ty; i < 64; i += 4) {
+        int r = r0 + i, c = c0 + tx;
+        tile[i][tx] = (r < R && c < hd) ? qkv[(int64_t)r * ld + v_off + kvh * hd + c] : from_f32<T>(0.f);
+    }
+    __syncthreads();
+    for (int i = ty; i < 64; i += 4) {
+        int c = c0 + i, r = r0 + tx;
+        if (c < hd && r < ldv) vt[((int64_t)kvh * hd + c) * ldv + r] = tile[tx][i];
+    }
+}
+
+// ---- S6: gather the scoring rows, final RMSNorm, targets -----------------------------------------
+// Scoring row b = k T + t reads the hidden state that predicts y^k_t: the last prefix row for
+// t = 0, else the row of y^k_{t-1}.
+template <typename T>
+__global__ __launch_bounds__(256) void gather_norm_kernel(const float* __restrict__ h, const float* __restrict__ gain,
+                                                          float eps, int d, const int32_t* __restrict__ draft_ids,
+                                                          const int32_t* __restrict__ draft_lens, int vocab, int P,
+                                                          int Tn, T* __restrict__ xs, int32_t* __restrict__ targets,
+                                                          uint8_t* __restrict__ valid) {
+    __shared__ float red[4];
+    const int b = blockIdx.x;
+    const int k = b / Tn, t = b % Tn;
+    const int src_row = t == 0 ? P - 1 : P + k * Tn + t - 1;
+    const float* x = h + (int64_t)src_row * d;
+    float ss = 0.f;
+    for (int c = threadIdx.x; c < d; c += 256) {
+        float v = x[c];
+        ss += v * v;
+    }
+    ss = block_sum<256>(ss, red);
+    const float inv = rsqrtf(ss / (float)d + eps);
+    T* o = xs + (int64_t)b * d;
+    for (int c = threadIdx.x; c < d; c += 256) o[c] = from_f32<T>(x[c] * inv * gain[c]);
+    if (threadIdx.x == 0) {
+        int id = draft_ids[b];
+        bool ok = !(draft_lens && t >= draft_lens[k]);
+        if (id < 0 || id >= vocab) id = 0;   // flagged by the embedding kernel already
+        targets[b] = id;
+        valid[b] = ok ? 1 : 0;
+    }
+}
+
+// ---- S8: conformity score per draft, fixed-order tree sum ------------------------------------------
+__global__ __launch_bounds__(256) void score_reduce_kernel(const float* __restrict__ lp,
+                                                           const int32_t* __restrict__ draft_lens, int Tn, int mode,
+                                                           float* __restrict__ token_logprobs,
+                                                           float* __restrict__ scores) {
+    __shared__ float red[4];
+    const int k = blockIdx.x;
+    const int len = draft_lens ? min(max(draft_lens[k], 0), Tn) : Tn;
+    float s = 0.f;
+    for (int t = threadIdx.x; t < Tn; t += 256) {
+        float v = t < len ? lp[(int64_t)k * Tn + t] : 0.f;
+        if (token_logprobs) token_logprobs[(int64_t)k * Tn + t] = v;
+        s += v;
+    }
+    s = block_sum<256>(s, red);
+    if (threadIdx.x == 0) scores[k] = mode == ATTS_SCORE_MEAN_NLL ? -s / (float)max(len, 1) : -s;
+}
+
+}  // namespace
+
+#define DISPATCH_T(dtype, ...)                       \
+    if ((dtype) == ATTS_DTYPE_F32) {                 \
+        typedef float T;                             \
+        __VA_ARGS__                                  \
+    } else {                                         \
+        typedef bf16 T;                              \
+        __VA_ARGS__                                  \
+    }
+
+int32_t launch_embed(int32_t dtype, const void* tok_embed, int32_t vocab, int32_t d, const int32_t* prefix_ids,
+                     const int32_t* draft_ids, const int32_t* draft_lens, ScoreShape s, float* h, int32_t* err_flag,
+                     hipStream_t stream) {
+    DISPATCH_T(dtype, hipLaunchKernelGGL(embed_kernel<T>, dim3(s.R()), dim3(256), 0, stream, (const T*)tok_embed, vocab, d,
+                                         prefix_ids, draft_ids, draft_lens, s.P, s.T, h, err_flag);)
+    ATTS_LAUNCH_CHECK("embed_kernel");
+    return ATTS_OK;
+}
+
+int32_t launch_rmsnorm(int32_t dtype, const float* h, const float* gain, float eps, int32_t rows, int32_t d, void* out,
+                       hipStream_t stream) {
+    DISPATCH_T(dtype, hipLaunchKernelGGL(rmsnorm_kernel<T>, dim3(rows), dim3(256), 0, stream, h, gain, eps, d, (T*)out);)
+    ATTS_LAUNCH_CHECK("rmsnorm_kernel");
+    return ATTS_OK;
+}
+
+int32_t launch_rope_table(float2* cs, int32_t n_pos, int32_t hd, float theta, hipStream_t stream) {
+    const int half = hd / 2;
+    const int total = n_pos * half;
+    hipLaunchKernelGGL(rope_table_kernel, dim3((unsigned)ceil_div(total, 256)), dim3(256), 0, stream, cs, n_pos, half,
+                       log((double)theta) / (double)half);
+    ATTS_LAUNCH_CHECK("rope_table_kernel");
+    return ATTS_OK;
+}
+
+int32_t launch_transpose_v(int32_t dtype, const void* qkv, int32_t R, int32_t nq, int32_t nkv, int32_t hd, void* vt,
+                           int64_t ldv, hipStream_t stream) {
+    const int64_t ld = (int64_t)(nq + 2 * nkv) * hd;
+    dim3 grid((unsigned)ceil_div(R, 64), (unsigned)ceil_div(hd, 64), nkv);
+    DISPATCH_T(dtype, hipLaunchKernelGGL(transpose_v_kernel<T>, grid, dim3(256), 0, stream, (const T*)qkv, R, ld,
+                                         (nq + nkv) * hd, hd, (T*)vt, ldv);)
+    ATTS_LAUNCH_CHECK("transpose_v_kernel");
+    return ATTS_OK;
+}
+
+int32_t launch_rope_split(int32_t dtype, void* qkv, const float2* cs, ScoreShape s, int32_t nq, int32_t nkv, int32_t hd,
+                          void* vt, int64_t ldv, hipStream_t stream) {
+    const int64_t ld = (int64_t)(nq + 2 * nkv) * hd;
+    const int64_t total = (int64_t)s.R() * (nq + nkv) * (hd / 2);
+    DISPATCH_T(dtype, hipLaunchKernelGGL(rope_kernel<T>, dim3((unsigned)ceil_div(total, 256)), dim3(256), 0, stream,
+                                         (T*)qkv, cs, s.R(), s.P, s.T, nq + nkv, hd, ld);)
+    ATTS_LAUNCH_CHECK("rope_kernel");
+    if (vt) return launch_transpose_v(dtype, qkv, s.R(), nq, nkv, hd, vt, ldv, stream);
+    return ATTS_OK;
+}
+
+int32_t launch_gather_norm(int32_t dtype, const float* h, const float* gain, float eps, int32_t d,
+                           const int32_t* draft_ids, const int32_t* draft_lens, int32_t vocab, ScoreShape s, void* xs,
+                           int32_t* targets, uint8_t* valid, hipStream_t stream) {
+    DISPATCH_T(dtype, hipLaunchKernelGGL(gather_norm_kernel<T>, dim3(s.B()), dim3(256), 0, stream, h, gain, eps, d,
+                                         draft_ids, draft_lens, vocab, s.P, s.T, (T*)xs, targets, valid);)
+    ATTS_LAUNCH_CHECK("gather_norm_kernel");
+    return ATTS_OK;
+}
+
+int32_t launch_score_reduce(const float* lp, const int32_t* draft_lens, int32_t K, int32_t T, int32_t mode,
+                            float* token_logprobs, float* scores, hipStream_t stream) {
+    hipLaunchKernelGGL(score_reduce_kernel, dim3(K), dim3(256), 0, stream, lp, draft_lens, T, mode, token_logprobs, scores);
+    ATTS_LAUNCH_CHECK("score_reduce_kernel");
+    return ATTS_OK;
+}
+
+}  // namespace atts

@@ -1,0 +1,370 @@
+// NT GEMM on MFMA for gfx950:  acc[M, N] = A[M, Kd] . W[N, Kd]^T  with fused epilogues.
+//
+// Every linear map of the target model (QKV, attention output, SwiGLU feed-forward, LM head)
+// goes through this kernel; scoring the drafts is the compute-bound part of the method
+// (Sec. "Q1"), so this is where the time goes.
+//
+// Layout of one workgroup (256 threads = 4 wavefronts in a 2 x 2 grid):
+//   * output tile BM x BN, each wave owns (BM/2) x (BN/2) as MI x NI blocks of 32 x 32
+//     (v_mfma_f32_32x32x16_bf16, or v_mfma_f32_32x32x2_f32 for the fp32 model)
+//   * K is walked in slabs of 128 bytes per row (64 bf16 / 32 fp32).  Both operands are
+//     K-contiguous in memory, so A and W tiles are loaded the same way: 16-byte chunks,
+//     global -> registers -> LDS, double-buffered, one barrier per slab.
+//   * LDS rows are 128 bytes; the 16-byte chunk index is XOR-ed with (row & 7) so that the
+//     32 rows a fragment read touches spread over all banks.
+//   * workgroup ids are remapped so that the ids dispatched to one XCD (id mod 8) cover a
+//     compact block of tiles, which keeps each XCD's private L2 re-using A and W slabs.
+#include "common.h"
+
+namespace atts {
+namespace {
+
+constexpr int kThreads = 256;
+constexpr int kRowBytes = 128;  // bytes of K per LDS row per slab
+constexpr int kGroupM = 8;
+
+template <typename T> struct Mma;
+
+template <> struct Mma<bf16> {
+    static constexpr int kSteps = 4;  // 16-wide k-steps per 64-element slab
+    typedef bf16x8 Frag;
+    // lane (row = l % 32, half = l / 32) holds k = 16 step + 8 half + [0, 8)
+    static __device__ __forceinline__ Frag load(const char* row_ptr, int row, int step, int half) {
+        int chunk = step * 2 + half;
+        return *reinterpret_cast<const Frag*>(row_ptr + ((chunk ^ (row & 7)) << 4));
+    }
+    static __device__ __forceinline__ void mma(const Frag& a, const Frag& b, f32x16& c) {
+        c = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, c, 0, 0, 0);
+    }
+};
+
+template <> struct Mma<float> {
+    static constexpr int kSteps = 8;  // one 16-byte chunk (4 floats) per step, two MFMAs
+    typedef float2 Frag;
+    // half h of the wave takes floats 2h, 2h+1 of the chunk: the k-order inside a chunk is
+    // permuted identically for A and W, which leaves the dot product unchanged.
+    static __device__ __forceinline__ Frag load(const char* row_ptr, int row, int step, int half) {
+        return *reinterpret_cast<const Frag*>(row_ptr + ((step ^ (row & 7)) << 4) + half * 8);
+    }
+    static __device__ __forceinline__ void mma(const Frag& a, const Frag& b, f32x16& c) {
+        c = __builtin_amdgcn_mfma_f32_32x32x2f32(a.x, b.x, c, 0, 0, 0);
+        c = __builtin_amdgcn_mfma_f32_32x32x2f32(a.y, b.y, c, 0, 0, 0);
+    }
+};
+
+struct TileCoord {
+    int tm, tn;
+};
+
+// XCD-aware, grouped tile order.
+__device__ __forceinline__ TileCoord tile_of_block(int pid, int nt_m, int nt_n) {
+    int n = nt_m * nt_n;
+    int n8 = n & ~7;
+    int lid = pid < n8 ? (pid & 7) * (n8 >> 3) + (pid >> 3) : pid;
+    int per_group = kGroupM * nt_n;
+    int g = lid / per_group;
+    int first_m = g * kGroupM;
+    int gsz = min(kGroupM, nt_m - first_m);
+    int in_g = lid - g * per_group;
+    TileCoord t;
+    t.tm = first_m + in_g % gsz;
+    t.tn = in_g / gsz;
+    return t;
+}
+
+// Scalars of one GEMM launch (pointers are passed as direct kernel arguments so that the compiler
+// knows they are global addresses).
+struct GemmDims {
+    int32_t M, N, Kd;
+    int64_t lda, ldw, ldc;
+    int32_t n_part, nt_m, nt_n;
+};
+
+template <typename T, int BM, int BN, int EPI>
+__global__ __launch_bounds__(kThreads) void gemm_nt_kernel(const char* __restrict__ gA, const char* __restrict__ gW,
+                                                           void* __restrict__ g_out,
+                                                           const int32_t* __restrict__ g_targets,
+                                                           float2* __restrict__ g_partials,
+                                                           float* __restrict__ g_target_logit, const GemmDims g) {
+    constexpr int MI = BM / 64, NI = BN / 64;   // 32x32 blocks per wave along M / N
+    constexpr int WM = BM / 2, WN = BN / 2;     // wave tile
+    constexpr int kElemsPerChunk = 16 / (int)sizeof(T);
+    constexpr int kSlabElems = kRowBytes / (int)sizeof(T);
+    constexpr int A_CHUNKS = BM * 8 / kThreads, B_CHUNKS = BN * 8 / kThreads;
+    constexpr int N_OUT = (EPI == EPI_SWIGLU) ? BN / 2 : BN;   // output columns per tile
+
+    extern __shared__ __attribute__((aligned(16))) char smem[];
+    char* sA = smem;                           // [2][BM][128 B]
+    char* sB = smem + 2 * BM * kRowBytes;      // [2][BN][128 B]
+
+    const int tid = threadIdx.x;
+    const int lane = tid & 63, wave = tid >> 6;
+    const int wm = wave >> 1, wn = wave & 1;
+    const int l32 = lane & 31, half = lane >> 5;
+
+    const TileCoord tc = tile_of_block(blockIdx.x, g.nt_m, g.nt_n);
+    const int m0 = tc.tm * BM;
+    const int n0 = tc.tn * N_OUT;
+
+    // Per-thread chunk coordinates: chunk c = tid + 256 i -> tile row (tid / 8) + 32 i, 16-byte
+    // column tid % 8.  Row i of a thread differs from row 0 by a wave-uniform offset, so one base
+    // pointer per operand is kept and the per-row offsets stay in scalar registers.
+    const int crow = tid >> 3, ccol = tid & 7;
+    const int64_t es = (int64_t)sizeof(T);
+    const char* a_base = gA + ((int64_t)(m0 + crow) * g.lda + ccol * kElemsPerChunk) * es;
+    const char* b_base = gW + ((int64_t)(n0 + crow) * g.ldw + ccol * kElemsPerChunk) * es;
+    const int lds_off = crow * kRowBytes + ((ccol ^ (crow & 7)) << 4);  // + 32 i rows: (row & 7) unchanged
+
+    uint4 ra[A_CHUNKS], rb[B_CHUNKS];
+
+    auto load_slab = [&](int k0) __attribute__((always_inline)) {
+        const bool k_ok = k0 + ccol * kElemsPerChunk < g.Kd;
+        const int64_t koff = (int64_t)k0 * es;
+#pragma unroll
+        for (int i = 0; i < A_CHUNKS; ++i) {
+            const bool ok = k_ok && (m0 + crow + 32 * i < g.M);
+            ra[i] = make_uint4(0, 0, 0, 0);
+            if (ok) ra[i] = *reinterpret_cast<const uint4*>(a_base + koff + (int64_t)(32 * i) * g.lda * es);
+        }
+#pragma unroll
+        for (int i = 0; i < B_CHUNKS; ++i) {
+            // LDS row j = crow + 32 i of the W tile  <-  W row (n0 + crow) + row_off
+            int64_t row_off;
+            bool ok;
+            if (EPI == EPI_SWIGLU) {
+                // wave slab jw holds [gate | up] halves of WN / 2 features each
+                constexpr int H = WN / 2;
+                const int jw = (32 * i) / WN, jj = (32 * i) % WN;
+                const int up = jj / H, feat_off = jw * H + jj % H;
+                ok = n0 + crow + feat_off < g.N;
+                row_off = (int64_t)up * g.N + feat_off;
+            } else {
+                ok = n0 + crow + 32 * i < g.N;
+                row_off = 32 * i;
+            }
+            rb[i] = make_uint4(0, 0, 0, 0);
+            if (ok && k_ok) rb[i] = *reinterpret_cast<const uint4*>(b_base + koff + row_off * g.ldw * es);
+        }
+    };
+    auto store_slab = [&](int buf) __attribute__((always_inline)) {
+        char* dA = sA + buf * BM * kRowBytes + lds_off;
+        char* dB = sB + buf * BN * kRowBytes + lds_off;
+#pragma unroll
+        for (int i = 0; i < A_CHUNKS; ++i) *reinterpret_cast<uint4*>(dA + i * 32 * kRowBytes) = ra[i];
+#pragma unroll
+        for (int i = 0; i < B_CHUNKS; ++i) *reinterpret_cast<uint4*>(dB + i * 32 * kRowBytes) = rb[i];
+    };
+
+    f32x16 acc[MI][NI];
+#pragma unroll
+    for (int i = 0; i < MI; ++i)
+#pragma unroll
+        for (int j = 0; j < NI; ++j)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.f;
+
+    const int nk = (g.Kd + kSlabElems - 1) / kSlabElems;
+    load_slab(0);
+    store_slab(0);
+    __syncthreads();
+
+    for (int kt = 0; kt < nk; ++kt) {
+        const int buf = kt & 1;
+        if (kt + 1 < nk) load_slab((kt + 1) * kSlabElems);
+
+        const char* pA = sA + buf * BM * kRowBytes + (wm * WM + l32) * kRowBytes;
+        const char* pB = sB + buf * BN * kRowBytes + (wn * WN + l32) * kRowBytes;
+#pragma unroll
+        for (int s = 0; s < Mma<T>::kSteps; ++s) {
+            typename Mma<T>::Frag fa[MI], fb[NI];
+#pragma unroll
+            for (int i = 0; i < MI; ++i) fa[i] = Mma<T>::load(pA + i * 32 * kRowBytes, l32, s, half);
+#pragma unroll
+            for (int j = 0; j < NI; ++j) fb[j] = Mma<T>::load(pB + j * 32 * kRowBytes, l32, s, half);
+#pragma unroll
+            for (int i = 0; i < MI; ++i)
+#pragma unroll
+                for (int j = 0; j < NI; ++j) Mma<T>::mma(fa[i], fb[j], acc[i][j]);
+        }
+
+        if (kt + 1 < nk) store_slab(buf ^ 1);
+        __syncthreads();
+    }
+
+    // ---------------------------------------------------------------- epilogue
+    // acc[i][j][v] is element (row, col) of the tile with
+    //   row = wm WM + 32 i + 8 (v / 4) + 4 half + (v % 4),   col = wn WN + 32 j + l32.
+    const int row_base = m0 + wm * WM + 4 * half;
+
+    if (EPI == EPI_STORE_ACT || EPI == EPI_STORE_F32 || EPI == EPI_RESID_F32) {
+        const int col_base = n0 + wn * WN + l32;
+#pragma unroll
+        for (int i = 0; i < MI; ++i)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) {
+                int row = row_base + 32 * i + 8 * (v >> 2) + (v & 3);
+                if (row >= g.M) continue;
+#pragma unroll
+                for (int j = 0; j < NI; ++j) {
+                    int col = col_base + 32 * j;
+                    if (col >= g.N) continue;
+                    int64_t idx = (int64_t)row * g.ldc + col;
+                    if (EPI == EPI_STORE_ACT) reinterpret_cast<T*>(g_out)[idx] = from_f32<T>(acc[i][j][v]);
+                    if (EPI == EPI_STORE_F32) reinterpret_cast<float*>(g_out)[idx] = acc[i][j][v];
+                    if (EPI == EPI_RESID_F32) reinterpret_cast<float*>(g_out)[idx] += acc[i][j][v];
+                }
+            }
+    } else if (EPI == EPI_SWIGLU) {
+        // blocks j < NI/2 hold gate, j + NI/2 the matching up columns
+        const int col_base = n0 + wn * (WN / 2) + l32;
+#pragma unroll
+        for (int i = 0; i < MI; ++i)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) {
+                int row = row_base + 32 * i + 8 * (v >> 2) + (v & 3);
+                if (row >= g.M) continue;
+#pragma unroll
+                for (int j = 0; j < NI / 2; ++j) {
+                    int col = col_base + 32 * j;
+                    if (col >= g.N) continue;
+                    float gate = acc[i][j][v], up = acc[i][j + NI / 2][v];
+                    float y = gate / (1.f + __expf(-gate)) * up;
+                    reinterpret_cast<T*>(g_out)[(int64_t)row * g.ldc + col] = from_f32<T>(y);
+                }
+            }
+    } else if (EPI == EPI_LMHEAD) {
+        // One (max, sum exp) partial per row for this wave's WN columns, plus the target logit.
+        const int col0 = n0 + wn * WN;            // first column of this wave's slab
+        const int part = tc.tn * 2 + wn;
+        bool col_ok[NI];
+#pragma unroll
+        for (int j = 0; j < NI; ++j) col_ok[j] = col0 + 32 * j + l32 < g.N;
+#pragma unroll
+        for (int i = 0; i < MI; ++i)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) {
+                int row = row_base + 32 * i + 8 * (v >> 2) + (v & 3);
+                bool row_ok = row < g.M;          // uniform over the 32 lanes that share `half`
+                int tcol = row_ok ? g_targets[row] - col0 : -1;
+                float mx = -INFINITY;
+#pragma unroll
+                for (int j = 0; j < NI; ++j) {
+                    float z = acc[i][j][v];
+                    if (col_ok[j]) mx = fmaxf(mx, z);
+                    if (tcol == 32 * j + l32) g_target_logit[row] = z;
+                }
+#pragma unroll
+                for (int o = 1; o < 32; o <<= 1) mx = fmaxf(mx, __shfl_xor(mx, o));
+                float sum = 0.f;
+                if (mx > -INFINITY) {
+#pragma unroll
+                    for (int j = 0; j < NI; ++j)
+                        if (col_ok[j]) sum += __expf(acc[i][j][v] - mx);
+                }
+#pragma unroll
+                for (int o = 1; o < 32; o <<= 1) sum += __shfl_xor(sum, o);
+                if (row_ok && l32 == 0) g_partials[(int64_t)row * g.n_part + part] = make_float2(mx, sum);
+            }
+    }
+}
+
+template <typename T, int BM, int BN, int EPI>
+int32_t launch_cfg(const GemmArgs& g, hipStream_t stream) {
+    constexpr int n_out = (EPI == EPI_SWIGLU) ? BN / 2 : BN;
+    GemmDims d;
+    d.M = g.M; d.N = g.N; d.Kd = g.Kd;
+    d.lda = g.lda; d.ldw = g.ldw; d.ldc = g.ldc;
+    d.n_part = g.n_part;
+    d.nt_m = (int)ceil_div(g.M, BM);
+    d.nt_n = (int)ceil_div(g.N, n_out);
+    const size_t lds = 2 * (size_t)(BM + BN) * kRowBytes;
+    auto kern = gemm_nt_kernel<T, BM, BN, EPI>;
+    static bool attr_set = false;   // per instantiation
+    if (!attr_set) {
+        ATTS_HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
+                                         hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
+        attr_set = true;
+    }
+    hipLaunchKernelGGL(kern, dim3(d.nt_m * d.nt_n), dim3(kThreads), lds, stream, reinterpret_cast<const char*>(g.a),
+                       reinterpret_cast<const char*>(g.w), g.out, g.targets, g.partials, g.target_logit, d);
+    ATTS_LAUNCH_CHECK("gemm_nt_kernel");
+    return ATTS_OK;
+}
+
+// Tile choice: 256 x 256 when the problem fills the chip with such tiles, else 128 x 128.
+bool use_big_tile(int32_t M, int32_t N) {
+    return ceil_div(M, 256) * ceil_div(N, 256) >= 192;
+}
+
+template <typename T, int EPI>
+int32_t launch_epi(const GemmArgs& g, hipStream_t stream) {
+    int32_t n_cols = (EPI == EPI_SWIGLU) ? 2 * g.N : g.N;
+    if (use_big_tile(g.M, n_cols)) return launch_cfg<T, 256, 256, EPI>(g, stream);
+    return launch_cfg<T, 128, 128, EPI>(g, stream);
+}
+
+template <typename T>
+int32_t launch_t(GemmEpilogue epi, const GemmArgs& g, hipStream_t stream) {
+    switch (epi) {
+        case EPI_STORE_ACT: return launch_epi<T, EPI_STORE_ACT>(g, stream);
+        case EPI_STORE_F32: return launch_epi<T, EPI_STORE_F32>(g, stream);
+        case EPI_RESID_F32: return launch_epi<T, EPI_RESID_F32>(g, stream);
+        case EPI_SWIGLU: return launch_epi<T, EPI_SWIGLU>(g, stream);
+        case EPI_LMHEAD: return launch_epi<T, EPI_LMHEAD>(g, stream);
+    }
+    return fail(ATTS_ERR_INVALID_ARG, "unknown GEMM epilogue %d", (int)epi);
+}
+
+__global__ void lmhead_combine_kernel(const float2* __restrict__ partials, const float* __restrict__ target_logit,
+                                      int B, int n_part, const uint8_t* __restrict__ valid, float* __restrict__ lp) {
+    // one wavefront per row
+    const int row = blockIdx.x * (blockDim.x >> 6) + (threadIdx.x >> 6);
+    const int lane = threadIdx.x & 63;
+    if (row >= B) return;
+    if (valid && !valid[row]) {
+        if (lane == 0) lp[row] = 0.f;
+        return;
+    }
+    const float2* p = partials + (int64_t)row * n_part;
+    float mx = -INFINITY;
+    for (int i = lane; i < n_part; i += 64) mx = fmaxf(mx, p[i].x);
+#pragma unroll
+    for (int o = 1; o < 64; o <<= 1) mx = fmaxf(mx, __shfl_xor(mx, o));
+    float sum = 0.f;
+    for (int i = lane; i < n_part; i += 64) {
+        float2 q = p[i];
+        if (q.y > 0.f) sum += q.y * __expf(q.x - mx);
+    }
+#pragma unroll
+    for (int o = 1; o < 64; o <<= 1) sum += __shfl_xor(sum, o);
+    if (lane == 0) lp[row] = target_logit[row] - (mx + __logf(sum));
+}
+
+}  // namespace
+
+int32_t lmhead_num_partials(int32_t /*dtype*/, int32_t M, int32_t N) {
+    int bn = use_big_tile(M, N) ? 256 : 128;
+    return (int32_t)ceil_div(N, bn) * 2;
+}
+
+int32_t launch_gemm(int32_t dtype, GemmEpilogue epi, const GemmArgs& g, hipStream_t stream) {
+    const size_t es = dtype_size(dtype);
+    if (g.M <= 0 || g.N <= 0 || g.Kd <= 0) return fail(ATTS_ERR_SHAPE, "gemm: empty shape %d x %d x %d", g.M, g.N, g.Kd);
+    if ((g.Kd * es) % 16 || (g.lda * es) % 16 || (g.ldw * es) % 16)
+        return fail(ATTS_ERR_SHAPE, "gemm: K (%d) and leading dimensions must be multiples of 16 bytes", g.Kd);
+    if (((uintptr_t)g.a | (uintptr_t)g.w) & 15) return fail(ATTS_ERR_INVALID_ARG, "gemm: operands must be 16-byte aligned");
+    if (epi == EPI_LMHEAD && g.n_part != lmhead_num_partials(dtype, g.M, g.N))
+        return fail(ATTS_ERR_INVALID_ARG, "gemm: wrong partial count for the LM-head epilogue");
+    return dtype == ATTS_DTYPE_F32 ? launch_t<float>(epi, g, stream) : launch_t<bf16>(epi, g, stream);
+}
+
+int32_t launch_lmhead_combine(const float2* partials, const float* target_logit, int32_t B, int32_t n_part,
+                              const uint8_t* valid, float* lp, hipStream_t stream) {
+    const int rows_per_block = 4;
+    hipLaunchKernelGGL(lmhead_combine_kernel, dim3((unsigned)ceil_div(B, rows_per_block)), dim3(64 * rows_per_block), 0,
+                       stream, partials, target_logit, B, n_part, valid, lp);
+    ATTS_LAUNCH_CHECK("lmhead_combine_kernel");
+    return ATTS_OK;
+}
+
+}  // namespace atts

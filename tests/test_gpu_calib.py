@@ -1,0 +1,131 @@
+"""Parity of atts_calibrate_online / atts_classify_ordinal with the oracle: ranks, classes and
+thresholds bit-exact, p-values equal to the oracle's binary64 p rounded once to fp32."""
+import numpy as np
+import pytest
+import torch
+
+from oracle import atts_oracle as O
+from synth import WORKLOADS, lognormal_scores
+from util import announce, dev
+
+pytestmark = pytest.mark.gpu
+
+
+def _classify(A, calib, test, alphas, want_p=True, want_q=True):
+    M = len(test)
+    t = dev(np.asarray(test, dtype=np.float32))
+    ranks = torch.full((M,), -7, dtype=torch.int32, device="cuda")
+    cls = torch.full((M,), 99, dtype=torch.uint8, device="cuda")
+    p = torch.empty(M, dtype=torch.float32, device="cuda") if want_p else None
+    q = torch.empty(len(alphas), dtype=torch.float32, device="cuda") if want_q else None
+    A.atts_classify_ordinal(calib, t, alphas, ranks, p, cls, q)
+    torch.cuda.synchronize()
+    return (ranks.cpu().numpy(), cls.cpu().numpy(), None if p is None else p.cpu().numpy(),
+            None if q is None else q.cpu().numpy())
+
+
+def _check_against_oracle(A, calib, cal_np, test, alphas, brute=True):
+    ranks, cls, p, q = _classify(A, calib, test, alphas)
+    n = len(cal_np)
+    c = (O.rank_counts if brute else O.rank_counts_sorted)(cal_np, test)
+    r = O.reject_ranks(alphas, n)
+    assert np.array_equal(ranks.astype(np.int64), c)
+    assert np.array_equal(cls, O.classify(c, r))
+    assert np.array_equal(p, O.p_values(c, n).astype(np.float32))
+    assert np.array_equal(q, O.quantile_thresholds(cal_np, r).astype(np.float32), equal_nan=True)
+    return ranks, cls
+
+
+def test_small_with_ties_and_special_values():
+    import paper_2509_15148_amd as A
+    announce("calib small/special")
+    cal = np.array([0.5, 1.0, 1.0, 2.0, 2.0, 2.0, 3.5, 4.0, 4.0, -0.0, 0.0, np.inf, -np.inf, np.nan, 1e-45, -1e-45],
+                   dtype=np.float32)
+    test = np.array([2.0, 0.25, 5.0, 1.0, 3.75, 0.0, -0.0, np.nan, np.inf, -np.inf, 1e-45, -3.0], dtype=np.float32)
+    c = A.Calib(64)
+    A.atts_calibrate_online(c, dev(cal))
+    assert A.atts_calib_size(c) == len(cal)
+    for alphas in ([0.3], [0.3, 0.75], [0.01, 0.5, 0.5, 0.99]):
+        _check_against_oracle(A, c, cal.astype(np.float64), test, alphas)
+    out = torch.empty(len(cal), dtype=torch.float32, device="cuda")
+    A.atts_calib_export(c, out)
+    got = out.cpu().numpy()
+    assert np.isnan(got[0]) and np.array_equal(got[1:], np.sort(cal[~np.isnan(cal)]))
+    # empty test batch: only the thresholds are produced
+    ranks, cls, p, q = _classify(A, c, np.zeros(0, np.float32), [0.3])
+    assert len(ranks) == 0 and q[0] == O.quantile_thresholds(cal.astype(np.float64), O.reject_ranks([0.3], len(cal)))[0]
+
+
+@pytest.mark.parametrize("sizes", [(1,), (7, 1, 300), (8191, 8193, 5), (20000, 3, 70001), (200000, 131072 + 17)])
+def test_online_appends_span_sort_chunks_and_merge_paths(sizes):
+    """Batches below / at / above one sort chunk, the multi-way path (<= 16 runs) and the pairwise
+    path (> 16 runs); after every append the state must equal the sorted union."""
+    import paper_2509_15148_amd as A
+    announce("calib appends", sizes)
+    total = sum(sizes)
+    allv = np.round(lognormal_scores(total, seed=sum(sizes)), 3)       # rounding plants many ties
+    c = A.Calib(total)
+    test = np.concatenate([lognormal_scores(500, seed=77), allv[:50]])
+    lo = 0
+    for s in sizes:
+        A.atts_calibrate_online(c, dev(allv[lo:lo + s]))
+        lo += s
+        assert A.atts_calib_size(c) == lo
+        out = torch.empty(lo, dtype=torch.float32, device="cuda")
+        A.atts_calib_export(c, out)
+        assert np.array_equal(out.cpu().numpy(), np.sort(allv[:lo]))
+        _check_against_oracle(A, c, allv[:lo].astype(np.float64), test, [0.05, 0.2], brute=lo <= 30000)
+
+
+def test_capacity_and_argument_errors():
+    import paper_2509_15148_amd as A
+    announce("calib errors")
+    c = A.Calib(10)
+    x = dev(np.arange(8, dtype=np.float32))
+    with pytest.raises(A.AttsError) as e:                      # classify on an empty set
+        _classify(A, c, np.zeros(3, np.float32), [0.1])
+    assert e.value.code == A.ERR_INVALID_ARG
+    A.atts_calibrate_online(c, x)
+    with pytest.raises(A.AttsError) as e:
+        A.atts_calibrate_online(c, x)
+    assert e.value.code == A.ERR_CAPACITY and A.atts_calib_size(c) == 8
+    A.atts_calibrate_online(c, x[:0])                          # empty append is a no-op
+    for bad in ([], [0.0], [1.0], [0.3, 0.2], [0.1] * 9, [float("nan")]):
+        with pytest.raises(A.AttsError) as e:
+            _classify(A, c, np.zeros(3, np.float32), bad)
+        assert e.value.code == A.ERR_INVALID_ARG
+    A.atts_calib_reset(c)
+    assert A.atts_calib_size(c) == 0
+    A.atts_calibrate_online(c, x[:3])
+    _check_against_oracle(A, c, np.arange(3, dtype=np.float64), np.array([-1, 0, 1.5, 2, 9], np.float32), [0.5])
+
+
+def test_calibration_only_workload_full_size():
+    """The calibration-only workload at its published size: 2^20 lognormal scores, 16 online steps
+    of 65,536 appended + 65,536 classified at alpha = (0.05, 0.2).  Every rank and class is checked
+    against the oracle's sort-based count; 128 sampled test scores per step against the double sum."""
+    import paper_2509_15148_amd as A
+    wl = WORKLOADS["calib"]
+    announce("calib full workload", wl.n_cal, wl.n_new, wl.n_steps)
+    cal = lognormal_scores(wl.n_cal, wl.seed)
+    c = A.Calib(wl.n_cal + wl.n_steps * wl.n_new)
+    A.atts_calibrate_online(c, dev(cal))
+    rng = np.random.default_rng(1)
+    counts = np.zeros(3, dtype=np.int64)
+    for step in range(wl.n_steps):
+        new = lognormal_scores(wl.n_new, wl.seed + 1000 + step)
+        test = lognormal_scores(wl.n_test, wl.seed + 2000 + step)
+        A.atts_calibrate_online(c, dev(new))
+        cal = np.concatenate([cal, new])
+        ranks, cls, p, q = _classify(A, c, test, list(wl.alphas))
+        cal64 = cal.astype(np.float64)
+        cs = O.rank_counts_sorted(cal64, test)
+        r = O.reject_ranks(wl.alphas, len(cal))
+        assert np.array_equal(ranks.astype(np.int64), cs), step
+        assert np.array_equal(cls, O.classify(cs, r)), step
+        assert np.array_equal(q, O.quantile_thresholds(cal64, r).astype(np.float32))
+        idx = rng.choice(wl.n_test, 128, replace=False)
+        assert np.array_equal(ranks[idx].astype(np.int64), O.rank_counts(cal64, test[idx]))
+        counts += np.bincount(cls, minlength=3)
+    frac = counts / counts.sum()
+    assert abs(frac[2] - 0.05) < 0.005 and abs(frac[1] + frac[2] - 0.2) < 0.01     # take-over rate ~ alpha
