@@ -1,0 +1,248 @@
+#!/usr/bin/env python3
+"""Throughput of the ATTS hot path on one MI355X.
+
+One "step" = one pass of the whole hot path over one batch of synthetic input, inputs resident in
+HBM: atts_score_drafts (prefix + K drafts through the target model, fused LM-head log-softmax-
+gather, conformity scores) -> atts_classify_ordinal of the K fresh scores against the calibration
+set -> atts_calibrate_online appending them.  Prints ONE JSON line.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload 7b|32b|70b|tiny] [--layers L]
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import math
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+MFMA_PEAK_TFLOPS = {"bf16": 2500.0, "fp32": 157.3}     # MI355X dense peaks
+HBM_PEAK_GBS = 8000.0
+
+
+def log(*a):
+    print(*a, file=sys.stderr, flush=True)
+
+
+def algorithmic_flops(cfg, P, K, T, n_layers):
+    """Flops the method must perform (no padding, no masked-out triangle)."""
+    rows, B = P + K * T, K * T
+    d, hd, nq, nkv, F, V = cfg.d_model, cfg.head_dim, cfg.n_q_heads, cfg.n_kv_heads, cfg.d_ffn, cfg.vocab
+    per_row = {
+        "gemm_qkv": 2 * d * (nq + 2 * nkv) * hd,
+        "gemm_o": 2 * nq * hd * d,
+        "gemm_gate_up": 2 * d * 2 * F,
+        "gemm_down": 2 * F * d,
+    }
+    fl = {k: v * rows * n_layers for k, v in per_row.items()}
+    ctx = sum(i + 1 for i in range(P)) + K * sum(P + t + 1 for t in range(T))
+    fl["attention"] = 4 * hd * nq * ctx * n_layers
+    fl["lmhead"] = 2 * B * d * V
+    fl["total"] = sum(fl.values())
+    return fl
+
+
+def cpu_baseline(cfg, wl, w_dev, prefix, drafts, n_layers_full, budget_layers):
+    """The oracle, as it stands, on a bounded sample: ONE draft (P + T tokens) through the first
+    `budget_layers` layers + the LM head, extrapolated to all layers by the layer count."""
+    import numpy as np
+    import torch
+    from oracle import atts_oracle as O
+
+    sub = {k: (v[:budget_layers] if isinstance(v, list) else v) for k, v in w_dev.items()}
+    w_np = {k: ([t.float().cpu().numpy() for t in v] if isinstance(v, list) else v.float().cpu().numpy())
+            for k, v in sub.items()}
+    seq = np.concatenate([prefix, drafts[0]])
+    t0 = time.perf_counter()
+    h = O.decoder_hidden(w_np, cfg, seq)
+    t1 = time.perf_counter()
+    lsm = O.log_softmax(O.logits_from_hidden(w_np, cfg, h[wl.P - 1: wl.P - 1 + wl.T]))
+    _ = lsm[np.arange(wl.T), drafts[0]]
+    t2 = time.perf_counter()
+    t_layers, t_head = t1 - t0, t2 - t1
+    t_full = t_layers * n_layers_full / max(budget_layers, 1) + t_head
+    return {
+        "value": wl.T / t_full, "unit": "tokens/s", "cores": torch.get_num_threads(), "kind": "oracle",
+        "sample": (f"numpy fp64 oracle, 1 of {wl.K} drafts ({wl.P}+{wl.T} tokens), {budget_layers} of "
+                   f"{n_layers_full} layers timed ({t_layers:.1f} s) + LM head ({t_head:.1f} s); value = "
+                   f"{wl.T} tokens / (layer time x {n_layers_full}/{budget_layers} + head time), an extrapolation"),
+    }
+
+
+def bench_calibration(A, torch, np, steps=16):
+    """The calibration-only workload: 2^20 resident scores, then per step append 65,536 and
+    classify 65,536 at two alpha levels."""
+    from synth import WORKLOADS, lognormal_scores
+    wl = WORKLOADS["calib"]
+    calib = A.Calib(wl.n_cal + (steps + 2) * wl.n_new)
+    A.atts_calibrate_online(calib, torch.from_numpy(lognormal_scores(wl.n_cal, wl.seed)).cuda())
+    new = [torch.from_numpy(lognormal_scores(wl.n_new, wl.seed + 1000 + i)).cuda() for i in range(steps + 2)]
+    test = [torch.from_numpy(lognormal_scores(wl.n_test, wl.seed + 2000 + i)).cuda() for i in range(steps + 2)]
+    ranks = torch.empty(wl.n_test, dtype=torch.int32, device="cuda")
+    cls = torch.empty(wl.n_test, dtype=torch.uint8, device="cuda")
+
+    def step(i):
+        A.atts_calibrate_online(calib, new[i])
+        A.atts_classify_ordinal(calib, test[i], list(wl.alphas), ranks, None, cls, None)
+
+    step(0)
+    step(1)
+    torch.cuda.synchronize()
+    n0 = A.atts_calib_size(calib)
+    t0 = time.perf_counter()
+    for i in range(2, steps + 2):
+        step(i)
+    torch.cuda.synchronize()
+    dt = time.perf_counter() - t0
+    # bytes the method must move per step: read the set once, read + append the new scores,
+    # read the test scores, write ranks (4 B) and classes (1 B)
+    n_mid = n0 + wl.n_new * steps / 2
+    bytes_step = 4 * n_mid + 8 * wl.n_new + 4 * wl.n_test + 5 * wl.n_test
+    return {
+        "workload": "calib: 2^20 lognormal scores + 65536 appended and 65536 classified per step, alphas (0.05, 0.2)",
+        "steps": steps, "us_per_step": dt / steps * 1e6, "decisions_per_s": wl.n_test * steps / dt,
+        "algorithmic_bytes_per_step": bytes_step, "achieved_GBs": bytes_step * steps / dt / 1e9,
+        "hbm_frac": bytes_step * steps / dt / 1e9 / HBM_PEAK_GBS,
+        "note": "working set (4-8 MB) is cache resident and a step is a few kernel launches: launch-latency bound",
+    }
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=10)
+    ap.add_argument("--warmup", type=int, default=2)
+    ap.add_argument("--workload", default="7b", choices=["tiny", "7b", "32b", "70b"])
+    ap.add_argument("--layers", type=int, default=0, help="build only the first L layers (debug; result is labelled)")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--cpu-layers", type=int, default=2)
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build measures ONE MI355X; the path has no multi-GPU leg (run with --gpus 1)",
+              file=sys.stderr)
+        sys.exit(2)
+
+    import numpy as np
+    import torch
+
+    import paper_2509_15148_amd as A
+    from synth import WORKLOADS, make_token_ids, make_weights
+
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible; the HIP path has no CPU fallback", file=sys.stderr)
+        sys.exit(3)
+    torch.cuda.set_device(0)
+    wl = WORKLOADS[args.workload]
+    cfg = wl.model
+    L = args.layers if args.layers > 0 else cfg.n_layers
+
+    t0 = time.perf_counter()
+    w = make_weights(cfg, wl.seed, device="cuda", n_layers=L)
+    torch.cuda.synchronize()
+    log(f"[bench] weights for {wl.name} ({L} layers) built in {time.perf_counter() - t0:.1f} s")
+    model = A.Model(cfg, w)
+    ws = torch.empty(A.atts_workspace_bytes(model, wl.P, wl.K, wl.T), dtype=torch.uint8, device="cuda")
+    n_batches = args.warmup + args.steps
+    n_cal_batches = math.ceil(wl.n_cal / wl.K)
+    ids = [make_token_ids(cfg.vocab, wl.P, wl.K, wl.T, wl.seed + 17 * i, device="cuda")
+           for i in range(max(n_batches, 1))]
+    lp = torch.empty(wl.K, wl.T, dtype=torch.float32, device="cuda")
+    sc = torch.empty(wl.K, dtype=torch.float32, device="cuda")
+    ranks = torch.empty(wl.K, dtype=torch.int32, device="cuda")
+    pv = torch.empty(wl.K, dtype=torch.float32, device="cuda")
+    cls = torch.empty(wl.K, dtype=torch.uint8, device="cuda")
+    thr = torch.empty(len(wl.alphas), dtype=torch.float32, device="cuda")
+
+    # Pre-sampling pass of online calibration: n_cal scores from ceil(n_cal / K) extra batches
+    # through the same scoring path (untimed set-up).
+    calib = A.Calib(n_cal_batches * wl.K + (n_batches + args.steps) * wl.K)   # timed pass + stage-timing pass
+    t0 = time.perf_counter()
+    for i in range(n_cal_batches):
+        p, d = make_token_ids(cfg.vocab, wl.P, wl.K, wl.T, wl.seed + 100003 + i, device="cuda")
+        A.atts_score_drafts(model, p, d, None, A.SCORE_MEAN_NLL, None, sc, ws)
+        A.atts_calibrate_online(calib, sc)
+    torch.cuda.synchronize()
+    log(f"[bench] calibration pre-sampling: {n_cal_batches} batches in {time.perf_counter() - t0:.1f} s, "
+        f"N = {A.atts_calib_size(calib)}")
+
+    def step(i):
+        p, d = ids[i % len(ids)]
+        A.atts_score_drafts(model, p, d, None, A.SCORE_MEAN_NLL, lp, sc, ws)
+        A.atts_classify_ordinal(calib, sc, list(wl.alphas), ranks, pv, cls, thr)
+        A.atts_calibrate_online(calib, sc)
+
+    for i in range(args.warmup):
+        step(i)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for i in range(args.steps):
+        step(args.warmup + i)
+    torch.cuda.synchronize()
+    dt = time.perf_counter() - t0
+    ms_step = dt / args.steps * 1e3
+    assert A.atts_model_check(model) == 0
+    rej = float((cls > 0).float().mean())
+    log(f"[bench] {args.steps} steps: {ms_step:.2f} ms/step; last batch scores {sc[:4].tolist()} reject frac {rej:.2f}")
+
+    # Same steps again with per-stage HIP events on the launch stream (kernel-level durations).
+    A.atts_profile_enable(True)
+    for i in range(args.steps):
+        step(args.warmup + i)
+    torch.cuda.synchronize()
+    stage_ms = {}
+    for s, name in enumerate(A.STAGES):
+        ms, n = A.atts_profile_read(s)
+        stage_ms[name] = (ms, n)
+    A.atts_profile_enable(False)
+
+    fl = algorithmic_flops(cfg, wl.P, wl.K, wl.T, L)
+    peak = MFMA_PEAK_TFLOPS[cfg.dtype]
+    stages = {}
+    for name, (ms, n) in stage_ms.items():
+        e = {"ms_per_step": ms / args.steps, "launches_per_step": n / args.steps}
+        if name in fl and ms > 0:
+            e["tflops"] = fl[name] * args.steps / (ms * 1e-3) / 1e12
+            e["mfma_frac"] = e["tflops"] / peak
+        stages[name] = e
+    dom = "gemm_gate_up"
+    dom_ms, dom_n = stage_ms[dom]
+    dom_avg_ms = dom_ms / max(dom_n, 1)
+    dom_flops = fl[dom] / max(L, 1)                      # one launch = one layer's gate/up projection
+    achieved = dom_flops / (dom_avg_ms * 1e-3) / 1e12 if dom_avg_ms > 0 else 0.0
+
+    out = {
+        "metric": "scored draft tokens/sec (shared-prefix target scoring + online conformal calibration + ordinal "
+                  "classification), 1 MI355X",
+        "value": wl.K * wl.T * args.steps / dt,
+        "unit": "tokens/s",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_step,
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": cfg.dtype, "data": "synthetic",
+        "config": {"workload": f"{wl.name}: L={L} d={cfg.d_model} {cfg.n_q_heads}q/{cfg.n_kv_heads}kv x{cfg.head_dim} "
+                               f"F={cfg.d_ffn} V={cfg.vocab} {cfg.dtype}; P={wl.P} K={wl.K} T={wl.T}; "
+                               f"n_cal={A.atts_calib_size(calib)} alpha={list(wl.alphas)}",
+                   "scored_tokens_per_step": wl.K * wl.T, "rows_per_step": wl.P + wl.K * wl.T,
+                   "layers_built": L, "full_model": L == cfg.n_layers},
+        "conformal_decisions_per_s": wl.K * args.steps / dt,
+        "algorithmic_tflop_per_step": fl["total"] / 1e12,
+        "whole_step_mfma_frac": fl["total"] / (dt / args.steps) / 1e12 / peak,
+        "roofline": {"bound": "mfma", "kernel": f"gemm_nt_kernel<{cfg.dtype}, SwiGLU epilogue> (gate/up projection)",
+                     "achieved": achieved, "peak": peak, "unit": "TFLOP/s", "frac": achieved / peak,
+                     "avg_launch_ms": dom_avg_ms, "flops_per_launch": dom_flops, "traffic": None},
+        "stages": stages,
+    }
+    if args.workload != "tiny":
+        out["calibration_stage"] = bench_calibration(A, torch, np)
+    if not args.no_cpu_baseline:
+        p0, d0 = ids[0]
+        out["cpu_baseline"] = cpu_baseline(cfg, wl, w, p0.cpu().numpy(), d0.cpu().numpy(), L, min(args.cpu_layers, L))
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()
