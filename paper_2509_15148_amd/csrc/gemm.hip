@@ -10,8 +10,8 @@
 //   * K is walked in slabs of 128 bytes per row (64 bf16 / 32 fp32).  Both operands are
 //     K-contiguous in memory, so A and W tiles are loaded the same way: 16-byte chunks,
 //     global -> registers -> LDS, double-buffered, one barrier per slab.
-//   * LDS rows are 128 bytes; the 16-byte chunk index is XOR-ed with (row & 7) so that the
-//     32 rows a fragment read touches spread over all banks.
+//   * LDS rows are 128 bytes; the 16-byte chunk index is XOR-ed with (row >> 1) & 7 so that the
+//     rows a fragment read touches spread over all 64 banks (two rows span the 256-byte bank width).
 //   * workgroup ids are remapped so that the ids dispatched to one XCD (id mod 8) cover a
 //     compact block of tiles, which keeps each XCD's private L2 re-using A and W slabs.
 #include "common.h"
@@ -31,7 +31,7 @@ template <> struct Mma<bf16> {
     // lane (row = l % 32, half = l / 32) holds k = 16 step + 8 half + [0, 8)
     static __device__ __forceinline__ Frag load(const char* row_ptr, int row, int step, int half) {
         int chunk = step * 2 + half;
-        return *reinterpret_cast<const Frag*>(row_ptr + ((chunk ^ (row & 7)) << 4));
+        return *reinterpret_cast<const Frag*>(row_ptr + ((chunk ^ ((row >> 1) & 7)) << 4));
     }
     static __device__ __forceinline__ void mma(const Frag& a, const Frag& b, f32x16& c) {
         c = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, c, 0, 0, 0);
@@ -44,7 +44,7 @@ template <> struct Mma<float> {
     // half h of the wave takes floats 2h, 2h+1 of the chunk: the k-order inside a chunk is
     // permuted identically for A and W, which leaves the dot product unchanged.
     static __device__ __forceinline__ Frag load(const char* row_ptr, int row, int step, int half) {
-        return *reinterpret_cast<const Frag*>(row_ptr + ((step ^ (row & 7)) << 4) + half * 8);
+        return *reinterpret_cast<const Frag*>(row_ptr + ((step ^ ((row >> 1) & 7)) << 4) + half * 8);
     }
     static __device__ __forceinline__ void mma(const Frag& a, const Frag& b, f32x16& c) {
         c = __builtin_amdgcn_mfma_f32_32x32x2f32(a.x, b.x, c, 0, 0, 0);
@@ -72,6 +72,7 @@ __device__ __forceinline__ TileCoord tile_of_block(int pid, int nt_m, int nt_n) 
     return t;
 }
 
+
 // Scalars of one GEMM launch (pointers are passed as direct kernel arguments so that the compiler
 // knows they are global addresses).
 struct GemmDims {
@@ -79,6 +80,88 @@ struct GemmDims {
     int64_t lda, ldw, ldc;
     int32_t n_part, nt_m, nt_n;
 };
+
+// Epilogue shared by both kernels.  acc[i][j][v] is element (row, col) of the tile with
+//   row = wm WM + 32 i + 8 (v / 4) + 4 half + (v % 4),   col = wn WN + 32 j + l32   (WM = 32 MI, WN = 32 NI).
+template <typename T, int MI, int NI, int EPI>
+__device__ __forceinline__ void gemm_epilogue(f32x16 (&acc)[MI][NI], int m0, int n0, int wm, int wn, int l32, int half,
+                                              int tn, void* __restrict__ g_out, const int32_t* __restrict__ g_targets,
+                                              float2* __restrict__ g_partials, float* __restrict__ g_target_logit,
+                                              const GemmDims& g) {
+    constexpr int WM = 32 * MI, WN = 32 * NI;
+    const int row_base = m0 + wm * WM + 4 * half;
+
+    if (EPI == EPI_STORE_ACT || EPI == EPI_STORE_F32 || EPI == EPI_RESID_F32) {
+        const int col_base = n0 + wn * WN + l32;
+#pragma unroll
+        for (int i = 0; i < MI; ++i)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) {
+                int row = row_base + 32 * i + 8 * (v >> 2) + (v & 3);
+                if (row >= g.M) continue;
+#pragma unroll
+                for (int j = 0; j < NI; ++j) {
+                    int col = col_base + 32 * j;
+                    if (col >= g.N) continue;
+                    int64_t idx = (int64_t)row * g.ldc + col;
+                    if (EPI == EPI_STORE_ACT) reinterpret_cast<T*>(g_out)[idx] = from_f32<T>(acc[i][j][v]);
+                    if (EPI == EPI_STORE_F32) reinterpret_cast<float*>(g_out)[idx] = acc[i][j][v];
+                    if (EPI == EPI_RESID_F32) reinterpret_cast<float*>(g_out)[idx] += acc[i][j][v];
+                }
+            }
+    } else if (EPI == EPI_SWIGLU) {
+        // blocks j < NI/2 hold gate, j + NI/2 the matching up columns
+        const int col_base = n0 + wn * (WN / 2) + l32;
+#pragma unroll
+        for (int i = 0; i < MI; ++i)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) {
+                int row = row_base + 32 * i + 8 * (v >> 2) + (v & 3);
+                if (row >= g.M) continue;
+#pragma unroll
+                for (int j = 0; j < NI / 2; ++j) {
+                    int col = col_base + 32 * j;
+                    if (col >= g.N) continue;
+                    float gate = acc[i][j][v], up = acc[i][j + NI / 2][v];
+                    float y = gate / (1.f + __expf(-gate)) * up;
+                    reinterpret_cast<T*>(g_out)[(int64_t)row * g.ldc + col] = from_f32<T>(y);
+                }
+            }
+    } else if (EPI == EPI_LMHEAD) {
+        // One (max, sum exp) partial per row for this wave's WN columns, plus the target logit.
+        const int col0 = n0 + wn * WN;            // first column of this wave's slab
+        const int part = tn * 2 + wn;
+        bool col_ok[NI];
+#pragma unroll
+        for (int j = 0; j < NI; ++j) col_ok[j] = col0 + 32 * j + l32 < g.N;
+#pragma unroll
+        for (int i = 0; i < MI; ++i)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) {
+                int row = row_base + 32 * i + 8 * (v >> 2) + (v & 3);
+                bool row_ok = row < g.M;          // uniform over the 32 lanes that share `half`
+                int tcol = row_ok ? g_targets[row] - col0 : -1;
+                float mx = -INFINITY;
+#pragma unroll
+                for (int j = 0; j < NI; ++j) {
+                    float z = acc[i][j][v];
+                    if (col_ok[j]) mx = fmaxf(mx, z);
+                    if (tcol == 32 * j + l32) g_target_logit[row] = z;
+                }
+#pragma unroll
+                for (int o = 1; o < 32; o <<= 1) mx = fmaxf(mx, __shfl_xor(mx, o));
+                float sum = 0.f;
+                if (mx > -INFINITY) {
+#pragma unroll
+                    for (int j = 0; j < NI; ++j)
+                        if (col_ok[j]) sum += __expf(acc[i][j][v] - mx);
+                }
+#pragma unroll
+                for (int o = 1; o < 32; o <<= 1) sum += __shfl_xor(sum, o);
+                if (row_ok && l32 == 0) g_partials[(int64_t)row * g.n_part + part] = make_float2(mx, sum);
+            }
+    }
+}
 
 template <typename T, int BM, int BN, int EPI>
 __global__ __launch_bounds__(kThreads) void gemm_nt_kernel(const char* __restrict__ gA, const char* __restrict__ gW,
@@ -113,7 +196,7 @@ __global__ __launch_bounds__(kThreads) void gemm_nt_kernel(const char* __restric
     const int64_t es = (int64_t)sizeof(T);
     const char* a_base = gA + ((int64_t)(m0 + crow) * g.lda + ccol * kElemsPerChunk) * es;
     const char* b_base = gW + ((int64_t)(n0 + crow) * g.ldw + ccol * kElemsPerChunk) * es;
-    const int lds_off = crow * kRowBytes + ((ccol ^ (crow & 7)) << 4);  // + 32 i rows: (row & 7) unchanged
+    const int lds_off = crow * kRowBytes + ((ccol ^ ((crow >> 1) & 7)) << 4);  // + 32 i rows: swizzle term unchanged
 
     uint4 ra[A_CHUNKS], rb[B_CHUNKS];
 
@@ -191,81 +274,218 @@ __global__ __launch_bounds__(kThreads) void gemm_nt_kernel(const char* __restric
         __syncthreads();
     }
 
-    // ---------------------------------------------------------------- epilogue
-    // acc[i][j][v] is element (row, col) of the tile with
-    //   row = wm WM + 32 i + 8 (v / 4) + 4 half + (v % 4),   col = wn WN + 32 j + l32.
-    const int row_base = m0 + wm * WM + 4 * half;
+    gemm_epilogue<T, MI, NI, EPI>(acc, m0, n0, wm, wn, l32, half, tc.tn, g_out, g_targets, g_partials, g_target_logit, g);
+}
 
-    if (EPI == EPI_STORE_ACT || EPI == EPI_STORE_F32 || EPI == EPI_RESID_F32) {
-        const int col_base = n0 + wn * WN + l32;
+// ---------------------------------------------------------------------------------------------
+// Fast path: bf16, 256 x 256 tiles, every tile full (M % 256 == 0, N % tile width == 0,
+// Kd % slab == 0).  Differences from the general kernel above:
+//   * operand slabs go global -> LDS directly (global_load_lds_dwordx4, 1 KiB per wave
+//     instruction), so no staging registers and no ds_write; the XOR swizzle is applied on the
+//     global side (lane i fetches the chunk that belongs at LDS position i);
+//   * a ring of kStages slabs with kStages - 1 slabs in flight; waits are explicit
+//     (s_waitcnt vmcnt(n) + s_barrier) so that younger loads stay in flight across the barrier;
+//   * fragments of the next k-step are read from LDS while the MFMAs of the current one issue.
+// ---------------------------------------------------------------------------------------------
+#define ATTS_GPTR(p) ((const __attribute__((address_space(1))) void*)(p))
+#define ATTS_LPTR(p) ((__attribute__((address_space(3))) void*)(p))
+
+template <int N>
+__device__ __forceinline__ void wait_vmcnt() {
+    asm volatile("s_waitcnt vmcnt(%0)" ::"n"(N) : "memory");
+}
+__device__ __forceinline__ void block_barrier() {
+    // bare s_barrier (no fence): ordering against our own LDS traffic is done with the explicit
+    // waits around it; the asm statements keep the compiler from moving memory operations across.
+    asm volatile("" ::: "memory");
+    __builtin_amdgcn_s_barrier();
+    asm volatile("" ::: "memory");
+}
+
+template <int EPI, int BKB /* bytes of K per row per slab: 64 or 128 */, int kStages, int kSwzShift>
+__global__ __launch_bounds__(kThreads) void gemm_bf16_fast_kernel(const char* __restrict__ gA, const char* __restrict__ gW,
+                                                                  void* __restrict__ g_out,
+                                                                  const int32_t* __restrict__ g_targets,
+                                                                  float2* __restrict__ g_partials,
+                                                                  float* __restrict__ g_target_logit, const GemmDims g) {
+    constexpr int BM = 256, BN = 256, MI = 4, NI = 4, WM = 128, WN = 128;
+    constexpr int N_OUT = (EPI == EPI_SWIGLU) ? BN / 2 : BN;
+    constexpr int BK = BKB / 2;                    // bf16 elements per slab
+    constexpr int KSUB = BK / 16;                  // MFMA k-steps per slab
+    constexpr int CHUNKS = BKB / 16;               // 16-byte chunks per LDS row
+    constexpr int ROWS_PER_DMA = 1024 / BKB;       // tile rows filled by one wave-wide DMA instruction
+    constexpr int DMA_PER_OP = BM / ROWS_PER_DMA / 4;   // DMA instructions per wave, per operand, per slab
+    constexpr int STAGE_BYTES = (BM + BN) * BKB;
+
+    extern __shared__ __attribute__((aligned(16))) char smem[];   // [kStages][A: BM rows | B: BN rows][BKB]
+
+    const int tid = threadIdx.x;
+    const int lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);   // wave-uniform: keeps LDS/DMA bases in scalar registers
+    const int wm = wave >> 1, wn = wave & 1;
+    const int l32 = lane & 31, half = lane >> 5;
+
+    const TileCoord tc = tile_of_block(blockIdx.x, g.nt_m, g.nt_n);
+    const int m0 = tc.tm * BM;
+    const int n0 = tc.tn * N_OUT;
+
+    // ---- DMA addressing.  DMA instruction j of this wave fills LDS rows r0 = (wave DMA_PER_OP + j) ROWS_PER_DMA
+    // ... r0 + ROWS_PER_DMA - 1 of an operand tile; lane i lands at row r0 + i / CHUNKS, chunk slot i % CHUNKS,
+    // and therefore fetches logical chunk  slot ^ swz(row).
+    const int dq = lane / CHUNKS, dslot = lane % CHUNKS;
+    auto swz = [](int row) { return (row >> kSwzShift) & (CHUNKS - 1); };
+    const char* a_lane = gA + (int64_t)(m0 + wave * DMA_PER_OP * ROWS_PER_DMA + dq) * g.lda * 2;
+    const char* b_lane = gW + (int64_t)(n0 + dq) * g.ldw * 2;
+
+    auto issue_slab = [&](int kt) __attribute__((always_inline)) {
+        char* stage = smem + (kt % kStages) * STAGE_BYTES;
+        const int64_t koff = (int64_t)kt * BKB;
+#pragma unroll
+        for (int j = 0; j < DMA_PER_OP; ++j) {
+            const int r0 = (wave * DMA_PER_OP + j) * ROWS_PER_DMA;
+            const int chunk = dslot ^ swz(r0 + dq);
+            const char* src = a_lane + (int64_t)(j * ROWS_PER_DMA) * g.lda * 2 + koff + chunk * 16;
+            __builtin_amdgcn_global_load_lds(ATTS_GPTR(src), ATTS_LPTR(stage + r0 * BKB), 16, 0, 0);
+        }
+#pragma unroll
+        for (int j = 0; j < DMA_PER_OP; ++j) {
+            const int r0 = (wave * DMA_PER_OP + j) * ROWS_PER_DMA;   // LDS row of the W tile
+            int64_t wrow;                                             // W row (relative to n0 + dq) feeding LDS row r0
+            if (EPI == EPI_SWIGLU) {
+                constexpr int H = WN / 2;                             // wave slab = [gate H | up H]
+                const int jw = r0 / WN, jj = r0 % WN;
+                wrow = (int64_t)(jj / H) * g.N + jw * H + jj % H;
+            } else {
+                wrow = r0;
+            }
+            const int chunk = dslot ^ swz(r0 + dq);
+            const char* src = b_lane + wrow * g.ldw * 2 + koff + chunk * 16;
+            __builtin_amdgcn_global_load_lds(ATTS_GPTR(src), ATTS_LPTR(stage + BM * BKB + r0 * BKB), 16, 0, 0);
+        }
+    };
+
+    // ---- fragment addressing: rows wm WM + 32 i + l32 (A) / wn WN + 32 j + l32 (B); the swizzle term
+    // depends on l32 only because 32 i, WM and WN are multiples of CHUNKS << kSwzShift.
+    const int frag_xor = swz(l32);
+    const int a_row_off = (wm * WM + l32) * BKB;
+    const int b_row_off = BM * BKB + (wn * WN + l32) * BKB;
+    auto load_frags = [&](int kt, int s, bf16x8 (&fa)[MI], bf16x8 (&fb)[NI]) __attribute__((always_inline)) {
+        const char* stage = smem + (kt % kStages) * STAGE_BYTES;
+        const int coff = ((2 * s + half) ^ frag_xor) << 4;
+#pragma unroll
+        for (int i = 0; i < MI; ++i) fa[i] = *reinterpret_cast<const bf16x8*>(stage + a_row_off + i * 32 * BKB + coff);
+#pragma unroll
+        for (int j = 0; j < NI; ++j) fb[j] = *reinterpret_cast<const bf16x8*>(stage + b_row_off + j * 32 * BKB + coff);
+    };
+
+    f32x16 acc[MI][NI];
+#pragma unroll
+    for (int i = 0; i < MI; ++i)
+#pragma unroll
+        for (int j = 0; j < NI; ++j)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.f;
+    auto mma_step = [&](bf16x8 (&fa)[MI], bf16x8 (&fb)[NI]) __attribute__((always_inline)) {
 #pragma unroll
         for (int i = 0; i < MI; ++i)
 #pragma unroll
-            for (int v = 0; v < 16; ++v) {
-                int row = row_base + 32 * i + 8 * (v >> 2) + (v & 3);
-                if (row >= g.M) continue;
+            for (int j = 0; j < NI; ++j) acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[i], fb[j], acc[i][j], 0, 0, 0);
+    };
+    // Scheduling hints: spread the 8 fragment reads of the next k-step (and, after the barrier, the 8 DMA
+    // issues of a new slab) under the 16 MFMAs of the current k-step, MFMAs first so that the wait on the
+    // fragments read during the previous k-step is not merged with the new reads.
+    auto interleave_hint = [&](bool with_dma) __attribute__((always_inline)) {
+        if (with_dma) {
 #pragma unroll
-                for (int j = 0; j < NI; ++j) {
-                    int col = col_base + 32 * j;
-                    if (col >= g.N) continue;
-                    int64_t idx = (int64_t)row * g.ldc + col;
-                    if (EPI == EPI_STORE_ACT) reinterpret_cast<T*>(g_out)[idx] = from_f32<T>(acc[i][j][v]);
-                    if (EPI == EPI_STORE_F32) reinterpret_cast<float*>(g_out)[idx] = acc[i][j][v];
-                    if (EPI == EPI_RESID_F32) reinterpret_cast<float*>(g_out)[idx] += acc[i][j][v];
-                }
+            for (int r = 0; r < MI + NI; ++r) {
+                __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);   // MFMA
+                __builtin_amdgcn_sched_group_barrier(0x020, 1, 0);   // VMEM read (LDS DMA)
+                __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);   // MFMA
+                __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);   // DS read
             }
-    } else if (EPI == EPI_SWIGLU) {
-        // blocks j < NI/2 hold gate, j + NI/2 the matching up columns
-        const int col_base = n0 + wn * (WN / 2) + l32;
+        } else {
 #pragma unroll
-        for (int i = 0; i < MI; ++i)
-#pragma unroll
-            for (int v = 0; v < 16; ++v) {
-                int row = row_base + 32 * i + 8 * (v >> 2) + (v & 3);
-                if (row >= g.M) continue;
-#pragma unroll
-                for (int j = 0; j < NI / 2; ++j) {
-                    int col = col_base + 32 * j;
-                    if (col >= g.N) continue;
-                    float gate = acc[i][j][v], up = acc[i][j + NI / 2][v];
-                    float y = gate / (1.f + __expf(-gate)) * up;
-                    reinterpret_cast<T*>(g_out)[(int64_t)row * g.ldc + col] = from_f32<T>(y);
-                }
+            for (int r = 0; r < MI + NI; ++r) {
+                __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);   // MFMA
+                __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);   // DS read
             }
-    } else if (EPI == EPI_LMHEAD) {
-        // One (max, sum exp) partial per row for this wave's WN columns, plus the target logit.
-        const int col0 = n0 + wn * WN;            // first column of this wave's slab
-        const int part = tc.tn * 2 + wn;
-        bool col_ok[NI];
+            __builtin_amdgcn_sched_group_barrier(0x008, MI * NI - (MI + NI), 0);
+        }
+    };
+
+    // One k-slab = KSUB k-steps.  The barrier that publishes slab kt + 1 sits before the LAST k-step of
+    // slab kt, so the first fragments of slab kt + 1 are read under the MFMAs of that last step and no
+    // LDS latency is exposed at the slab boundary.  Ring: slabs kt and kt + 1 are being read, kt + 2 is in
+    // flight, kt + 3 is issued into the stage slab kt - 1 occupied (free once every wave passed the barrier).
+    static_assert(kStages == 4, "ring arithmetic below assumes 4 stages");
+    constexpr int kDma = 2 * DMA_PER_OP;           // DMA instructions per wave per slab
+    const int nk = g.Kd / BK;                      // >= kStages (checked on the host)
+    issue_slab(0);
+    issue_slab(1);
+    issue_slab(2);
+    wait_vmcnt<2 * kDma>();
+    block_barrier();
+    bf16x8 fa[2][MI], fb[2][NI];
+    load_frags(0, 0, fa[0], fb[0]);
+
+    auto slab = [&](int kt, auto has_next, auto has_next2, auto has_next3) __attribute__((always_inline)) {
 #pragma unroll
-        for (int j = 0; j < NI; ++j) col_ok[j] = col0 + 32 * j + l32 < g.N;
-#pragma unroll
-        for (int i = 0; i < MI; ++i)
-#pragma unroll
-            for (int v = 0; v < 16; ++v) {
-                int row = row_base + 32 * i + 8 * (v >> 2) + (v & 3);
-                bool row_ok = row < g.M;          // uniform over the 32 lanes that share `half`
-                int tcol = row_ok ? g_targets[row] - col0 : -1;
-                float mx = -INFINITY;
-#pragma unroll
-                for (int j = 0; j < NI; ++j) {
-                    float z = acc[i][j][v];
-                    if (col_ok[j]) mx = fmaxf(mx, z);
-                    if (tcol == 32 * j + l32) g_target_logit[row] = z;
-                }
-#pragma unroll
-                for (int o = 1; o < 32; o <<= 1) mx = fmaxf(mx, __shfl_xor(mx, o));
-                float sum = 0.f;
-                if (mx > -INFINITY) {
-#pragma unroll
-                    for (int j = 0; j < NI; ++j)
-                        if (col_ok[j]) sum += __expf(acc[i][j][v] - mx);
-                }
-#pragma unroll
-                for (int o = 1; o < 32; o <<= 1) sum += __shfl_xor(sum, o);
-                if (row_ok && l32 == 0) g_partials[(int64_t)row * g.n_part + part] = make_float2(mx, sum);
-            }
+        for (int s = 0; s + 1 < KSUB; ++s) {
+            load_frags(kt, s + 1, fa[(s + 1) & 1], fb[(s + 1) & 1]);
+            mma_step(fa[s & 1], fb[s & 1]);
+            interleave_hint(false);
+        }
+        if (has_next) {
+            if (has_next2) wait_vmcnt<kDma>(); else wait_vmcnt<0>();
+            block_barrier();
+            if (has_next3) issue_slab(kt + 3);
+            load_frags(kt + 1, 0, fa[KSUB & 1], fb[KSUB & 1]);
+        }
+        mma_step(fa[(KSUB - 1) & 1], fb[(KSUB - 1) & 1]);
+        if (has_next) interleave_hint(has_next3);
+    };
+    struct Yes { constexpr operator bool() const { return true; } };
+    struct No { constexpr operator bool() const { return false; } };
+    int kt = 0;
+    for (; kt + 3 < nk; ++kt) slab(kt, Yes{}, Yes{}, Yes{});
+    slab(kt, Yes{}, Yes{}, No{});       // kt = nk - 3
+    slab(kt + 1, Yes{}, No{}, No{});    // kt = nk - 2
+    slab(kt + 2, No{}, No{}, No{});     // kt = nk - 1
+
+    gemm_epilogue<bf16, MI, NI, EPI>(acc, m0, n0, wm, wn, l32, half, tc.tn, g_out, g_targets, g_partials, g_target_logit, g);
+}
+
+// 64-byte LDS rows; swizzle shift 2 (chunk ^= (row >> 2) & 3) measured free of bank conflicts on gfx950
+// (SQ_LDS_BANK_CONFLICT = 0; shifts 0 and 1 conflict on 75 % / 50 % of the LDS cycles).
+constexpr int kFastBKB = 64, kFastStages = 4, kFastSwz = 2;
+
+bool fast_path_ok(int32_t dtype, int epi, const GemmArgs& g) {
+    const int n_out = epi == EPI_SWIGLU ? 128 : 256;
+    return dtype == ATTS_DTYPE_BF16 && g.M % 256 == 0 && g.N % n_out == 0 && g.Kd % (kFastBKB / 2) == 0 &&
+           g.Kd >= kFastStages * (kFastBKB / 2);
+}
+
+template <int EPI>
+int32_t launch_fast(const GemmArgs& g, hipStream_t stream) {
+    constexpr int n_out = (EPI == EPI_SWIGLU) ? 128 : 256;
+    GemmDims d;
+    d.M = g.M; d.N = g.N; d.Kd = g.Kd;
+    d.lda = g.lda; d.ldw = g.ldw; d.ldc = g.ldc;
+    d.n_part = g.n_part;
+    d.nt_m = g.M / 256;
+    d.nt_n = g.N / n_out;
+    const size_t lds = (size_t)kFastStages * 512 * kFastBKB;
+    auto kern = gemm_bf16_fast_kernel<EPI, kFastBKB, kFastStages, kFastSwz>;
+    static bool attr_set = false;   // per instantiation
+    if (!attr_set) {
+        ATTS_HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
+                                         hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
+        attr_set = true;
     }
+    hipLaunchKernelGGL(kern, dim3(d.nt_m * d.nt_n), dim3(kThreads), lds, stream, reinterpret_cast<const char*>(g.a),
+                       reinterpret_cast<const char*>(g.w), g.out, g.targets, g.partials, g.target_logit, d);
+    ATTS_LAUNCH_CHECK("gemm_bf16_fast_kernel");
+    return ATTS_OK;
 }
 
 template <typename T, int BM, int BN, int EPI>
@@ -299,7 +519,10 @@ bool use_big_tile(int32_t M, int32_t N) {
 template <typename T, int EPI>
 int32_t launch_epi(const GemmArgs& g, hipStream_t stream) {
     int32_t n_cols = (EPI == EPI_SWIGLU) ? 2 * g.N : g.N;
-    if (use_big_tile(g.M, n_cols)) return launch_cfg<T, 256, 256, EPI>(g, stream);
+    if (use_big_tile(g.M, n_cols)) {
+        if (sizeof(T) == 2 && fast_path_ok(ATTS_DTYPE_BF16, EPI, g)) return launch_fast<EPI>(g, stream);
+        return launch_cfg<T, 256, 256, EPI>(g, stream);
+    }
     return launch_cfg<T, 128, 128, EPI>(g, stream);
 }
 
