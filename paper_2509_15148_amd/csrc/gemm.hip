@@ -302,20 +302,26 @@ __device__ __forceinline__ void block_barrier() {
     asm volatile("" ::: "memory");
 }
 
-template <int EPI, int BKB /* bytes of K per row per slab: 64 or 128 */, int kStages, int kSwzShift>
-__global__ __launch_bounds__(kThreads) void gemm_bf16_fast_kernel(const char* __restrict__ gA, const char* __restrict__ gW,
-                                                                  void* __restrict__ g_out,
-                                                                  const int32_t* __restrict__ g_targets,
-                                                                  float2* __restrict__ g_partials,
-                                                                  float* __restrict__ g_target_logit, const GemmDims g) {
-    constexpr int BM = 256, BN = 256, MI = 4, NI = 4, WM = 128, WN = 128;
+template <int EPI, int kWavesM /* 2: 4 waves of 128 x 128; 4: 8 waves of 64 x 128 */, int kStages /* 4 or 5 */>
+__global__ __launch_bounds__(128 * kWavesM) void gemm_bf16_fast_kernel(const char* __restrict__ gA,
+                                                                       const char* __restrict__ gW,
+                                                                       void* __restrict__ g_out,
+                                                                       const int32_t* __restrict__ g_targets,
+                                                                       float2* __restrict__ g_partials,
+                                                                       float* __restrict__ g_target_logit,
+                                                                       const GemmDims g) {
+    constexpr int BM = 256, BN = 256, NI = 4, WN = 128;
+    constexpr int MI = 8 / kWavesM, WM = 32 * MI;
+    constexpr int kWaves = 2 * kWavesM;
     constexpr int N_OUT = (EPI == EPI_SWIGLU) ? BN / 2 : BN;
-    constexpr int BK = BKB / 2;                    // bf16 elements per slab
-    constexpr int KSUB = BK / 16;                  // MFMA k-steps per slab
+    constexpr int BKB = 64;                        // bytes of K per row per slab
+    constexpr int BK = BKB / 2;                    // bf16 elements per slab (two MFMA k-steps)
     constexpr int CHUNKS = BKB / 16;               // 16-byte chunks per LDS row
-    constexpr int ROWS_PER_DMA = 1024 / BKB;       // tile rows filled by one wave-wide DMA instruction
-    constexpr int DMA_PER_OP = BM / ROWS_PER_DMA / 4;   // DMA instructions per wave, per operand, per slab
-    constexpr int STAGE_BYTES = (BM + BN) * BKB;
+    constexpr int kSwzShift = 2;                   // chunk ^= (row >> 2) & 3: conflict-free on the 64-bank LDS
+    constexpr int ROWS_PER_DMA = 1024 / BKB;       // tile rows filled by one wave-wide DMA instruction (16)
+    constexpr int DMA_PER_OP = BM / ROWS_PER_DMA / kWaves;   // DMA instructions per wave, per operand, per slab
+    constexpr int STAGE_BYTES = (BM + BN) * BKB;   // 32 KiB
+    constexpr int kAhead = kStages - 1;            // slab kt + kAhead is the youngest one issued during slab kt
 
     extern __shared__ __attribute__((aligned(16))) char smem[];   // [kStages][A: BM rows | B: BN rows][BKB]
 
@@ -329,39 +335,47 @@ __global__ __launch_bounds__(kThreads) void gemm_bf16_fast_kernel(const char* __
     const int m0 = tc.tm * BM;
     const int n0 = tc.tn * N_OUT;
 
-    // ---- DMA addressing.  DMA instruction j of this wave fills LDS rows r0 = (wave DMA_PER_OP + j) ROWS_PER_DMA
-    // ... r0 + ROWS_PER_DMA - 1 of an operand tile; lane i lands at row r0 + i / CHUNKS, chunk slot i % CHUNKS,
-    // and therefore fetches logical chunk  slot ^ swz(row).
+    // ---- DMA addressing.  DMA instruction j of this wave fills LDS rows r0 = (wave DMA_PER_OP + j) 16 ... r0 + 15
+    // of an operand tile; lane i lands at row r0 + i / 4, chunk slot i % 4, and therefore fetches logical chunk
+    // slot ^ swz(row).  r0 is a multiple of 16, so swz(row) = swz(i / 4): one 32-bit per-lane byte offset per
+    // operand serves every j; the row bases are wave-uniform (scalar registers).
     const int dq = lane / CHUNKS, dslot = lane % CHUNKS;
     auto swz = [](int row) { return (row >> kSwzShift) & (CHUNKS - 1); };
-    const char* a_lane = gA + (int64_t)(m0 + wave * DMA_PER_OP * ROWS_PER_DMA + dq) * g.lda * 2;
-    const char* b_lane = gW + (int64_t)(n0 + dq) * g.ldw * 2;
-
-    auto issue_slab = [&](int kt) __attribute__((always_inline)) {
+    static_assert(ROWS_PER_DMA % (CHUNKS << kSwzShift) == 0, "swizzle must not depend on the DMA instruction index");
+    uint32_t a_lane_off = (uint32_t)dq * (uint32_t)(g.lda * 2) + (uint32_t)((dslot ^ swz(dq)) * 16);
+    uint32_t b_lane_off = (uint32_t)dq * (uint32_t)(g.ldw * 2) + (uint32_t)((dslot ^ swz(dq)) * 16);
+    const char* a_base[DMA_PER_OP];
+    const char* b_base[DMA_PER_OP];
+#pragma unroll
+    for (int j = 0; j < DMA_PER_OP; ++j) {
+        const int r0 = (wave * DMA_PER_OP + j) * ROWS_PER_DMA;
+        a_base[j] = gA + (int64_t)(m0 + r0) * g.lda * 2;
+        int64_t wrow = r0;                                        // W row (relative to n0) feeding LDS row r0
+        if (EPI == EPI_SWIGLU) {
+            constexpr int H = WN / 2;                             // wave slab = [gate H | up H]
+            const int jw = r0 / WN, jj = r0 % WN;
+            wrow = (int64_t)(jj / H) * g.N + jw * H + jj % H;
+        }
+        b_base[j] = gW + (n0 + wrow) * g.ldw * 2;
+    }
+    // A slab is issued in two halves (the A rows, then the W rows); both are issued in slab order.
+    auto issue_a = [&](int kt) __attribute__((always_inline)) {
         char* stage = smem + (kt % kStages) * STAGE_BYTES;
-        const int64_t koff = (int64_t)kt * BKB;
 #pragma unroll
         for (int j = 0; j < DMA_PER_OP; ++j) {
             const int r0 = (wave * DMA_PER_OP + j) * ROWS_PER_DMA;
-            const int chunk = dslot ^ swz(r0 + dq);
-            const char* src = a_lane + (int64_t)(j * ROWS_PER_DMA) * g.lda * 2 + koff + chunk * 16;
-            __builtin_amdgcn_global_load_lds(ATTS_GPTR(src), ATTS_LPTR(stage + r0 * BKB), 16, 0, 0);
+            __builtin_amdgcn_global_load_lds(ATTS_GPTR(a_base[j] + a_lane_off), ATTS_LPTR(stage + r0 * BKB), 16, 0, 0);
         }
+        a_lane_off += BKB;
+    };
+    auto issue_b = [&](int kt) __attribute__((always_inline)) {
+        char* stage = smem + (kt % kStages) * STAGE_BYTES + BM * BKB;
 #pragma unroll
         for (int j = 0; j < DMA_PER_OP; ++j) {
-            const int r0 = (wave * DMA_PER_OP + j) * ROWS_PER_DMA;   // LDS row of the W tile
-            int64_t wrow;                                             // W row (relative to n0 + dq) feeding LDS row r0
-            if (EPI == EPI_SWIGLU) {
-                constexpr int H = WN / 2;                             // wave slab = [gate H | up H]
-                const int jw = r0 / WN, jj = r0 % WN;
-                wrow = (int64_t)(jj / H) * g.N + jw * H + jj % H;
-            } else {
-                wrow = r0;
-            }
-            const int chunk = dslot ^ swz(r0 + dq);
-            const char* src = b_lane + wrow * g.ldw * 2 + koff + chunk * 16;
-            __builtin_amdgcn_global_load_lds(ATTS_GPTR(src), ATTS_LPTR(stage + BM * BKB + r0 * BKB), 16, 0, 0);
+            const int r0 = (wave * DMA_PER_OP + j) * ROWS_PER_DMA;
+            __builtin_amdgcn_global_load_lds(ATTS_GPTR(b_base[j] + b_lane_off), ATTS_LPTR(stage + r0 * BKB), 16, 0, 0);
         }
+        b_lane_off += BKB;
     };
 
     // ---- fragment addressing: rows wm WM + 32 i + l32 (A) / wn WN + 32 j + l32 (B); the swizzle term
@@ -391,98 +405,101 @@ __global__ __launch_bounds__(kThreads) void gemm_bf16_fast_kernel(const char* __
 #pragma unroll
             for (int j = 0; j < NI; ++j) acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[i], fb[j], acc[i][j], 0, 0, 0);
     };
-    // Scheduling hints: spread the 8 fragment reads of the next k-step (and, after the barrier, the 8 DMA
-    // issues of a new slab) under the 16 MFMAs of the current k-step, MFMAs first so that the wait on the
-    // fragments read during the previous k-step is not merged with the new reads.
+    // Scheduling hint for one k-step: MFMAs with the fragment reads of the next k-step and the DMA issues of
+    // half a slab spread evenly underneath.  (The texture path accepts one 1 KiB DMA instruction per ~16
+    // cycles per CU; issued back to back they block the wave, and with it the MFMAs, for that long.)
+    constexpr int kReads = MI + NI, kMfma = MI * NI;
     auto interleave_hint = [&](bool with_dma) __attribute__((always_inline)) {
-        if (with_dma) {
 #pragma unroll
-            for (int r = 0; r < MI + NI; ++r) {
-                __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);   // MFMA
-                __builtin_amdgcn_sched_group_barrier(0x020, 1, 0);   // VMEM read (LDS DMA)
-                __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);   // MFMA
-                __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);   // DS read
-            }
-        } else {
-#pragma unroll
-            for (int r = 0; r < MI + NI; ++r) {
-                __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);   // MFMA
-                __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);   // DS read
-            }
-            __builtin_amdgcn_sched_group_barrier(0x008, MI * NI - (MI + NI), 0);
+        for (int r = 0; r < kReads; ++r) {
+            __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);                                      // MFMA
+            if (with_dma && r % (kReads / DMA_PER_OP) == 0 && r / (kReads / DMA_PER_OP) < DMA_PER_OP)
+                __builtin_amdgcn_sched_group_barrier(0x020, 1, 0);                                  // VMEM read (LDS DMA)
+            __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);                                      // DS read
         }
+        __builtin_amdgcn_sched_group_barrier(0x008, kMfma - kReads, 0);
     };
 
-    // One k-slab = KSUB k-steps.  The barrier that publishes slab kt + 1 sits before the LAST k-step of
-    // slab kt, so the first fragments of slab kt + 1 are read under the MFMAs of that last step and no
-    // LDS latency is exposed at the slab boundary.  Ring: slabs kt and kt + 1 are being read, kt + 2 is in
-    // flight, kt + 3 is issued into the stage slab kt - 1 occupied (free once every wave passed the barrier).
-    static_assert(kStages == 4, "ring arithmetic below assumes 4 stages");
-    constexpr int kDma = 2 * DMA_PER_OP;           // DMA instructions per wave per slab
-    const int nk = g.Kd / BK;                      // >= kStages (checked on the host)
-    issue_slab(0);
-    issue_slab(1);
-    issue_slab(2);
-    wait_vmcnt<2 * kDma>();
+    // Ring of kStages slabs.  During slab kt:
+    //   k-step 0   MFMAs; underneath: fragments of k-step 1, DMA of the W half of slab kt + kAhead - 1
+    //   barrier    slab kt + 1 has landed for every wave, and every wave is done with slab kt - 1
+    //   k-step 1   MFMAs; underneath: FIRST fragments of slab kt + 1 (no LDS latency is exposed at the slab
+    //              boundary), DMA of the A half of slab kt + kAhead into the stage slab kt - 1 occupied
+    // so the DMA instructions are spread one by one under the MFMAs and a slab has kStages - 3 full slab times
+    // plus one k-step to land after its last DMA instruction.
+    const int nk = g.Kd / BK;                      // >= kStages + 1 (checked on the host)
+#pragma unroll
+    for (int s = 0; s < kAhead; ++s) {
+        issue_a(s);
+        if (s + 1 < kAhead) issue_b(s);
+    }
+    // issued so far, in order: A0 B0 A1 B1 ... A(kAhead-1); slab 0 = the two oldest halves
+    wait_vmcnt<(2 * kAhead - 3) * DMA_PER_OP>();
     block_barrier();
     bf16x8 fa[2][MI], fb[2][NI];
     load_frags(0, 0, fa[0], fb[0]);
 
-    auto slab = [&](int kt, auto has_next, auto has_next2, auto has_next3) __attribute__((always_inline)) {
-#pragma unroll
-        for (int s = 0; s + 1 < KSUB; ++s) {
-            load_frags(kt, s + 1, fa[(s + 1) & 1], fb[(s + 1) & 1]);
-            mma_step(fa[s & 1], fb[s & 1]);
-            interleave_hint(false);
-        }
+    // flags: slab kt + 1 exists | W half of slab kt + kAhead - 1 still to issue | A half of slab kt + kAhead to issue
+    auto slab = [&](int kt, auto has_next, auto issue_w, auto issue_next_a, auto steady) __attribute__((always_inline)) {
+        load_frags(kt, 1, fa[1], fb[1]);
+        if (issue_w) issue_b(kt + kAhead - 1);
+        mma_step(fa[0], fb[0]);
+        interleave_hint(issue_w);
         if (has_next) {
-            if (has_next2) wait_vmcnt<kDma>(); else wait_vmcnt<0>();
+            // outstanding after slab kt + 1: slabs kt + 2 .. kt + kAhead - 1 in full
+            if (steady) wait_vmcnt<2 * (kAhead - 2) * DMA_PER_OP>(); else wait_vmcnt<0>();
             block_barrier();
-            if (has_next3) issue_slab(kt + 3);
-            load_frags(kt + 1, 0, fa[KSUB & 1], fb[KSUB & 1]);
+            load_frags(kt + 1, 0, fa[0], fb[0]);
+            if (issue_next_a) issue_a(kt + kAhead);
         }
-        mma_step(fa[(KSUB - 1) & 1], fb[(KSUB - 1) & 1]);
-        if (has_next) interleave_hint(has_next3);
+        mma_step(fa[1], fb[1]);
+        if (has_next) interleave_hint(issue_next_a);
     };
     struct Yes { constexpr operator bool() const { return true; } };
     struct No { constexpr operator bool() const { return false; } };
     int kt = 0;
-    for (; kt + 3 < nk; ++kt) slab(kt, Yes{}, Yes{}, Yes{});
-    slab(kt, Yes{}, Yes{}, No{});       // kt = nk - 3
-    slab(kt + 1, Yes{}, No{}, No{});    // kt = nk - 2
-    slab(kt + 2, No{}, No{}, No{});     // kt = nk - 1
+    for (; kt + kAhead < nk; ++kt) slab(kt, Yes{}, Yes{}, Yes{}, Yes{});
+    // kt = nk - kAhead: the W half of the last slab is still to be issued, nothing after it
+    slab(kt, Yes{}, Yes{}, No{}, No{});
+    for (++kt; kt + 1 < nk; ++kt) slab(kt, Yes{}, No{}, No{}, No{});
+    slab(kt, No{}, No{}, No{}, No{});
 
     gemm_epilogue<bf16, MI, NI, EPI>(acc, m0, n0, wm, wn, l32, half, tc.tn, g_out, g_targets, g_partials, g_target_logit, g);
 }
 
-// 64-byte LDS rows; swizzle shift 2 (chunk ^= (row >> 2) & 3) measured free of bank conflicts on gfx950
-// (SQ_LDS_BANK_CONFLICT = 0; shifts 0 and 1 conflict on 75 % / 50 % of the LDS cycles).
-constexpr int kFastBKB = 64, kFastStages = 4, kFastSwz = 2;
+constexpr int kFastBK = 32;
+#ifndef ATTS_FAST_WAVES_M
+#define ATTS_FAST_WAVES_M 4
+#endif
+#ifndef ATTS_FAST_STAGES
+#define ATTS_FAST_STAGES 5
+#endif
 
 bool fast_path_ok(int32_t dtype, int epi, const GemmArgs& g) {
     const int n_out = epi == EPI_SWIGLU ? 128 : 256;
-    return dtype == ATTS_DTYPE_BF16 && g.M % 256 == 0 && g.N % n_out == 0 && g.Kd % (kFastBKB / 2) == 0 &&
-           g.Kd >= kFastStages * (kFastBKB / 2);
+    return dtype == ATTS_DTYPE_BF16 && g.M % 256 == 0 && g.N % n_out == 0 && g.Kd % kFastBK == 0 &&
+           g.Kd >= (ATTS_FAST_STAGES + 1) * kFastBK && g.lda * 2 * 16 < (1ll << 31) && g.ldw * 2 * 16 < (1ll << 31);
 }
 
 template <int EPI>
 int32_t launch_fast(const GemmArgs& g, hipStream_t stream) {
     constexpr int n_out = (EPI == EPI_SWIGLU) ? 128 : 256;
+    constexpr int kWavesM = ATTS_FAST_WAVES_M;
     GemmDims d;
     d.M = g.M; d.N = g.N; d.Kd = g.Kd;
     d.lda = g.lda; d.ldw = g.ldw; d.ldc = g.ldc;
     d.n_part = g.n_part;
     d.nt_m = g.M / 256;
     d.nt_n = g.N / n_out;
-    const size_t lds = (size_t)kFastStages * 512 * kFastBKB;
-    auto kern = gemm_bf16_fast_kernel<EPI, kFastBKB, kFastStages, kFastSwz>;
+    const size_t lds = (size_t)ATTS_FAST_STAGES * 512 * 2 * kFastBK;
+    auto kern = gemm_bf16_fast_kernel<EPI, kWavesM, ATTS_FAST_STAGES>;
     static bool attr_set = false;   // per instantiation
     if (!attr_set) {
         ATTS_HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
                                          hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
         attr_set = true;
     }
-    hipLaunchKernelGGL(kern, dim3(d.nt_m * d.nt_n), dim3(kThreads), lds, stream, reinterpret_cast<const char*>(g.a),
+    hipLaunchKernelGGL(kern, dim3(d.nt_m * d.nt_n), dim3(128 * kWavesM), lds, stream, reinterpret_cast<const char*>(g.a),
                        reinterpret_cast<const char*>(g.w), g.out, g.targets, g.partials, g.target_logit, d);
     ATTS_LAUNCH_CHECK("gemm_bf16_fast_kernel");
     return ATTS_OK;
