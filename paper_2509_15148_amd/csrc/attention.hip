@@ -81,23 +81,29 @@ constexpr int kHd = 128;
 constexpr int kQTile = 128;   // query rows per workgroup (32 per wave)
 constexpr int kKTile = 64;    // keys per LDS tile
 
-__global__ __launch_bounds__(256) void attn_mfma_kernel(const bf16* __restrict__ qkv, const bf16* __restrict__ vt,
-                                                        int64_t ldv, bf16* __restrict__ out, int R, int P, int Tn,
-                                                        int nq, int nkv, float scale_log2e) {
-    __shared__ __attribute__((aligned(16))) char sK[kKTile * kHd * 2];    // [64 keys][256 B], 16 B chunks XOR (key & 15)
-    __shared__ __attribute__((aligned(16))) char sV[kHd * kKTile * 2];    // [128 dims][128 B], 16 B chunks XOR (dim & 7)
+__global__ __launch_bounds__(256, 2) void attn_mfma_kernel(const bf16* __restrict__ qkv, const bf16* __restrict__ vt,
+                                                           int64_t ldv, bf16* __restrict__ out, int R, int P, int Tn,
+                                                           int nq, int nkv, float scale_log2e) {
+    // Two stages of [K tile: 64 keys x 256 B | V^T tile: 128 dims x 128 B], filled by direct global -> LDS loads.
+    //   K rows are 256 B: 16-byte chunk index XOR (key & 15);  V^T rows are 128 B: chunk index XOR (dim >> 1) & 7.
+    constexpr int kKBytes = kKTile * kHd * 2, kStage = 2 * kKBytes;
+    __shared__ __attribute__((aligned(16))) char smem[2 * kStage];
 
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int l32 = lane & 31, g = lane >> 5;
     const int head = blockIdx.y, kvh = head / (nq / nkv);
     const int r0 = blockIdx.x * kQTile;
     const int r_last = min(r0 + kQTile, R) - 1;
     const int64_t ld = (int64_t)(nq + 2 * nkv) * kHd;
 
-    // This lane's query row and its visibility window.
-    const int r = r0 + wave * 32 + l32;
+    // This lane's query row and its visibility window; the wave's row range decides which tiles it can skip.
+    const int rw0 = r0 + wave * 32;                                  // first row of this wave
+    const int rw1 = min(rw0 + 31, r_last);                           // last valid row (rw1 < rw0: the wave has no rows)
+    const int r = rw0 + l32;
     const bool r_ok = r < R;
     const int ss = seg_start(r_ok ? r : r_last, P, Tn);
+    const int ss_w1 = seg_start(max(rw1, rw0 <= r_last ? rw0 : r_last), P, Tn);   // draft start of the wave's last row
 
     // Q fragments (B operand of S^T = K Q^T): lane holds Q[r][16 s + 8 g + (0..7)], s = 0..7.
     bf16x8 qf[8];
@@ -119,30 +125,33 @@ __global__ __launch_bounds__(256) void attn_mfma_kernel(const bf16* __restrict__
     const int s2 = max(n1 * kKTile, seg_start(r0, P, Tn) / kKTile * kKTile);
     const int n2 = r_last >= s2 ? (r_last - s2) / kKTile + 1 : 0;
     const int n_tiles = n1 + n2;
+    auto tile_start = [&](int t) { return t < n1 ? t * kKTile : s2 + (t - n1) * kKTile; };
 
-    // Per-thread chunk coordinates for the tile loads.
-    const int k_row = tid >> 4, k_cc = tid & 15;       // K: rows k_row + 16 i, i < 4
-    const int v_row = tid >> 3, v_cc = tid & 7;        // V^T: dims v_row + 32 i, i < 4
-    const bf16* kg = qkv + (nq + kvh) * kHd + k_cc * 8;
-    const bf16* vg = vt + (int64_t)kvh * kHd * ldv + v_cc * 8;
-    uint4 rk[4], rv[4];
-    auto prefetch = [&](int t) __attribute__((always_inline)) {
-        const int j0 = t < n1 ? t * kKTile : s2 + (t - n1) * kKTile;
+    // ---- DMA addressing (one wave-wide instruction moves 1 KiB = 4 K rows or 8 V^T rows).
+    // K: instruction j of this wave fills tile rows 16 wave + 4 j + (lane >> 4); lane lands at chunk slot lane & 15
+    //    and fetches chunk slot ^ (row & 15) = (slot ^ (lane >> 4)) ^ 4 j.  Rows past the end are clamped to row
+    //    R - 1 (their scores are masked).
+    // V^T: instruction j fills dims 32 wave + 8 j + (lane >> 3); slot lane & 7 fetches chunk
+    //    slot ^ ((dim >> 1) & 7) = slot ^ (4 (j & 1) | (lane >> 4)).  Columns past R are zero in the V^T copy.
+    const int kq = lane >> 4, kslot = lane & 15;
+    const int vq = lane >> 3, vslot = lane & 7;
+    const bf16* kg = qkv + (nq + kvh) * kHd;
+    const bf16* vg = vt + ((int64_t)kvh * kHd + 32 * wave + vq) * ldv;
+    auto issue_tile = [&](int t) __attribute__((always_inline)) {
+        const int j0 = tile_start(t);
+        char* stage = smem + (t & 1) * kStage;
 #pragma unroll
-        for (int i = 0; i < 4; ++i) {
-            int j = j0 + k_row + 16 * i;
-            rk[i] = make_uint4(0, 0, 0, 0);
-            if (j < R) rk[i] = *reinterpret_cast<const uint4*>(kg + (int64_t)j * ld);
-            rv[i] = *reinterpret_cast<const uint4*>(vg + (int64_t)(v_row + 32 * i) * ldv + j0);
+        for (int j = 0; j < 4; ++j) {
+            const int row = 16 * wave + 4 * j;                        // wave-uniform part of the tile row
+            const int key = min(j0 + row + kq, R - 1);
+            const bf16* src = kg + (int64_t)key * ld + (((kslot ^ kq) ^ (4 * j)) << 3);
+            __builtin_amdgcn_global_load_lds(ATTS_GPTR(src), ATTS_LPTR(stage + row * 256), 16, 0, 0);
         }
-    };
-    auto stage = [&]() __attribute__((always_inline)) {
 #pragma unroll
-        for (int i = 0; i < 4; ++i) {
-            int kr = k_row + 16 * i;
-            *reinterpret_cast<uint4*>(sK + kr * 256 + ((k_cc ^ (kr & 15)) << 4)) = rk[i];
-            int vr = v_row + 32 * i;
-            *reinterpret_cast<uint4*>(sV + vr * 128 + ((v_cc ^ (vr & 7)) << 4)) = rv[i];
+        for (int j = 0; j < 4; ++j) {
+            const int dim = 32 * wave + 8 * j;
+            const bf16* src = vg + (int64_t)(8 * j) * ldv + j0 + ((vslot ^ ((4 * (j & 1)) | (vq >> 1))) << 3);
+            __builtin_amdgcn_global_load_lds(ATTS_GPTR(src), ATTS_LPTR(stage + kKBytes + dim * 128), 16, 0, 0);
         }
     };
 
@@ -151,78 +160,102 @@ __global__ __launch_bounds__(256) void attn_mfma_kernel(const bf16* __restrict__
     for (int nb = 0; nb < 4; ++nb)
 #pragma unroll
         for (int v = 0; v < 16; ++v) acc_o[nb][v] = 0.f;
-    float m_run = -1e30f;   // running max (scaled, log2 domain), shared by the lane pair (l, l ^ 32)
+    float m_run = -1e30f;   // reference max (scaled, log2 domain), shared by the lane pair (l, l ^ 32)
     float l_run = 0.f;      // this lane's share of the running denominator
 
-    if (n_tiles > 0) prefetch(0);
+    if (n_tiles > 0) issue_tile(0);
     for (int t = 0; t < n_tiles; ++t) {
-        const int j0 = t < n1 ? t * kKTile : s2 + (t - n1) * kKTile;
-        __syncthreads();
-        stage();
-        __syncthreads();
-        if (t + 1 < n_tiles) prefetch(t + 1);
+        const int j0 = tile_start(t);
+        wait_vmcnt<0>();
+        block_barrier();            // tile t is in LDS for every wave; every wave is done with tile t - 1
+        if (t + 1 < n_tiles) issue_tile(t + 1);
+
+        // Wave-uniform visibility of this tile for the wave's rows rw0 .. rw1:
+        //   nothing visible: the tile starts after the last row, or lies in drafts before the wave's first row's
+        //   fully visible:   every key <= first row, and (a prefix tile or inside the draft of the last row)
+        const bool none = rw1 < rw0 || j0 > rw1 || (j0 >= P && j0 + kKTile <= seg_start(rw0, P, Tn));
+        if (none) continue;
+        const bool full = j0 + kKTile - 1 <= rw0 && (j0 + kKTile <= P || j0 >= ss_w1) && rw0 + 31 <= r_last;
+        const char* sK = smem + (t & 1) * kStage;
+        const char* sV = sK + kKBytes;
 
         // ---- S^T = K Q^T for two 32-key blocks
         f32x16 acc_s[2];
 #pragma unroll
-        for (int kb = 0; kb < 2; ++kb) {
-#pragma unroll
-            for (int v = 0; v < 16; ++v) acc_s[kb][v] = 0.f;
-            const int kr = kb * 32 + l32;
-            const char* kp = sK + kr * 256;
-#pragma unroll
-            for (int s = 0; s < 8; ++s) {
-                bf16x8 kf = *reinterpret_cast<const bf16x8*>(kp + (((2 * s + g) ^ (kr & 15)) << 4));
-                acc_s[kb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, qf[s], acc_s[kb], 0, 0, 0);
-            }
-        }
-        // acc_s[kb][4 a + b] = score of key j0 + 32 kb + 8 a + 4 g + b for this lane's query.
-        float mx = m_run;
-#pragma unroll
         for (int kb = 0; kb < 2; ++kb)
 #pragma unroll
-            for (int v = 0; v < 16; ++v) {
-                int j = j0 + 32 * kb + 8 * (v >> 2) + 4 * g + (v & 3);
-                bool vis = r_ok && j <= r && (j < P || j >= ss);
-                float sc = vis ? acc_s[kb][v] * scale_log2e : -INFINITY;
-                acc_s[kb][v] = sc;
-                mx = fmaxf(mx, sc);
+            for (int v = 0; v < 16; ++v) acc_s[kb][v] = 0.f;
+#pragma unroll
+        for (int s = 0; s < 8; ++s)
+#pragma unroll
+            for (int kb = 0; kb < 2; ++kb) {
+                const int kr = kb * 32 + l32;
+                bf16x8 kf = *reinterpret_cast<const bf16x8*>(sK + kr * 256 + (((2 * s + g) ^ (kr & 15)) << 4));
+                acc_s[kb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, qf[s], acc_s[kb], 0, 0, 0);
             }
+        // acc_s[kb][4 a + b] = score of key j0 + 32 kb + 8 a + 4 g + b for this lane's query.
+        float mx = -INFINITY;
+        if (full) {
+#pragma unroll
+            for (int kb = 0; kb < 2; ++kb)
+#pragma unroll
+                for (int v = 0; v < 16; ++v) {
+                    acc_s[kb][v] *= scale_log2e;
+                    mx = fmaxf(mx, acc_s[kb][v]);
+                }
+        } else {
+#pragma unroll
+            for (int kb = 0; kb < 2; ++kb)
+#pragma unroll
+                for (int v = 0; v < 16; ++v) {
+                    int j = j0 + 32 * kb + 8 * (v >> 2) + 4 * g + (v & 3);
+                    bool vis = r_ok && j <= r && (j < P || j >= ss);
+                    float sc = vis ? acc_s[kb][v] * scale_log2e : -INFINITY;
+                    acc_s[kb][v] = sc;
+                    mx = fmaxf(mx, sc);
+                }
+        }
         mx = fmaxf(mx, __shfl_xor(mx, 32));
-        const float alpha = exp2f(m_run - mx);
-        m_run = mx;
+        // Lazy rescaling: any reference value works in exp2(s - m) as long as it is the same for numerator and
+        // denominator, so the running reference only moves when the new maximum exceeds it by more than 2^6
+        // (p stays <= 64, far inside bf16 / fp32 range); the 64 accumulator multiplies are skipped otherwise.
+        if (__builtin_amdgcn_ballot_w64(mx > m_run + 6.f) != 0) {
+            const float m_new = fmaxf(m_run, mx);
+            const float alpha = exp2f(m_run - m_new);
+            m_run = m_new;
+            l_run *= alpha;
+#pragma unroll
+            for (int nb = 0; nb < 4; ++nb)
+#pragma unroll
+                for (int v = 0; v < 16; ++v) acc_o[nb][v] *= alpha;
+        }
         float psum = 0.f;
         bf16x8 pf[4];
 #pragma unroll
         for (int kb = 0; kb < 2; ++kb)
 #pragma unroll
             for (int v = 0; v < 16; ++v) {
-                float p = exp2f(acc_s[kb][v] - mx);
+                float p = exp2f(acc_s[kb][v] - m_run);
                 psum += p;
                 pf[kb * 2 + (v >> 3)][v & 7] = (bf16)p;
             }
-        l_run = l_run * alpha + psum;
-#pragma unroll
-        for (int nb = 0; nb < 4; ++nb)
-#pragma unroll
-            for (int v = 0; v < 16; ++v) acc_o[nb][v] *= alpha;
+        l_run += psum;
 
         // ---- O^T += V^T P^T
 #pragma unroll
-        for (int nb = 0; nb < 4; ++nb) {
-            const int n = nb * 32 + l32;
-            const char* vp = sV + n * 128 + 8 * g;
+        for (int s = 0; s < 4; ++s)
 #pragma unroll
-            for (int s = 0; s < 4; ++s) {
+            for (int nb = 0; nb < 4; ++nb) {
+                const int n = nb * 32 + l32;
+                const char* vp = sV + n * 128 + 8 * g;
                 union {
                     uint2 u[2];
                     bf16x8 f;
                 } vf;
-                vf.u[0] = *reinterpret_cast<const uint2*>(vp + (((2 * s) ^ (n & 7)) << 4));
-                vf.u[1] = *reinterpret_cast<const uint2*>(vp + (((2 * s + 1) ^ (n & 7)) << 4));
+                vf.u[0] = *reinterpret_cast<const uint2*>(vp + (((2 * s) ^ ((n >> 1) & 7)) << 4));
+                vf.u[1] = *reinterpret_cast<const uint2*>(vp + (((2 * s + 1) ^ ((n >> 1) & 7)) << 4));
                 acc_o[nb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf.f, pf[s], acc_o[nb], 0, 0, 0);
             }
-        }
     }
 
     // ---- normalise and store: acc_o[nb][4 a + b] = O[r][32 nb + 8 a + 4 g + b]

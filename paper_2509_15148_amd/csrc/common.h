@@ -49,6 +49,22 @@ template <typename T> __device__ __forceinline__ T from_f32(float v);
 template <> __device__ __forceinline__ float from_f32<float>(float v) { return v; }
 template <> __device__ __forceinline__ bf16 from_f32<bf16>(float v) { return (bf16)v; }  // RNE
 
+// ---- direct global -> LDS loads and explicit waits (device code) -------------------------------
+#define ATTS_GPTR(p) ((const __attribute__((address_space(1))) void*)(p))
+#define ATTS_LPTR(p) ((__attribute__((address_space(3))) void*)(p))
+
+template <int N>
+__device__ __forceinline__ void wait_vmcnt() {
+    asm volatile("s_waitcnt vmcnt(%0)" ::"n"(N) : "memory");
+}
+__device__ __forceinline__ void block_barrier() {
+    // bare s_barrier (no fence): ordering against our own LDS traffic is done with the explicit
+    // waits around it; the asm statements keep the compiler from moving memory operations across.
+    asm volatile("" ::: "memory");
+    __builtin_amdgcn_s_barrier();
+    asm volatile("" ::: "memory");
+}
+
 // ---- launch wrappers (each enqueues on `stream`, returns ATTS_OK / ATTS_ERR_HIP) ----------
 
 // Epilogues of the NT GEMM  acc[M, N] = A[M, Kd] . W[N, Kd]^T

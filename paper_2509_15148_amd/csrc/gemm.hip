@@ -287,21 +287,6 @@ __global__ __launch_bounds__(kThreads) void gemm_nt_kernel(const char* __restric
 //     (s_waitcnt vmcnt(n) + s_barrier) so that younger loads stay in flight across the barrier;
 //   * fragments of the next k-step are read from LDS while the MFMAs of the current one issue.
 // ---------------------------------------------------------------------------------------------
-#define ATTS_GPTR(p) ((const __attribute__((address_space(1))) void*)(p))
-#define ATTS_LPTR(p) ((__attribute__((address_space(3))) void*)(p))
-
-template <int N>
-__device__ __forceinline__ void wait_vmcnt() {
-    asm volatile("s_waitcnt vmcnt(%0)" ::"n"(N) : "memory");
-}
-__device__ __forceinline__ void block_barrier() {
-    // bare s_barrier (no fence): ordering against our own LDS traffic is done with the explicit
-    // waits around it; the asm statements keep the compiler from moving memory operations across.
-    asm volatile("" ::: "memory");
-    __builtin_amdgcn_s_barrier();
-    asm volatile("" ::: "memory");
-}
-
 template <int EPI, int kWavesM /* 2: 4 waves of 128 x 128; 4: 8 waves of 64 x 128 */, int kStages /* 4 or 5 */>
 __global__ __launch_bounds__(128 * kWavesM) void gemm_bf16_fast_kernel(const char* __restrict__ gA,
                                                                        const char* __restrict__ gW,
