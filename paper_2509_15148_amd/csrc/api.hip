@@ -95,7 +95,7 @@ Workspace carve(const atts_model_desc& d, ScoreShape s) {
     w.vt = take(attention_uses_vt(d.dtype, d.head_dim) ? (size_t)d.n_kv_heads * d.head_dim * w.ldv * es : 0);
     w.ao = take(R * (size_t)d.n_q_heads * d.head_dim * es);
     w.act = take(R * (size_t)d.d_ffn * es);
-    w.rope = take((size_t)(s.P + s.T) * (d.head_dim / 2) * sizeof(float2));
+    w.rope = take(R * (size_t)(d.head_dim / 2) * sizeof(float2));
     w.xs = take(B * d.d_model * es);
     w.targets = take(B * sizeof(int32_t));
     w.valid = take(B);
@@ -158,9 +158,10 @@ int32_t atts_model_create(const atts_model_desc* desc, const atts_weights* w, at
             delete m;
             return fail(ATTS_ERR_INVALID_ARG, "atts_model_create: NULL weight pointer in layer %d", l);
         }
-        if (((uintptr_t)w->wqkv[l] | (uintptr_t)w->wo[l] | (uintptr_t)w->w_gate_up[l] | (uintptr_t)w->w_down[l]) & 15) {
+        if (((uintptr_t)w->wqkv[l] | (uintptr_t)w->wo[l] | (uintptr_t)w->w_gate_up[l] | (uintptr_t)w->w_down[l] |
+             (uintptr_t)w->attn_norm[l] | (uintptr_t)w->ffn_norm[l]) & 15) {
             delete m;
-            return fail(ATTS_ERR_INVALID_ARG, "atts_model_create: layer %d matrices must be 16-byte aligned", l);
+            return fail(ATTS_ERR_INVALID_ARG, "atts_model_create: layer %d weights must be 16-byte aligned", l);
         }
         m->attn_norm.push_back(w->attn_norm[l]);
         m->wqkv.push_back(w->wqkv[l]);
@@ -169,9 +170,9 @@ int32_t atts_model_create(const atts_model_desc* desc, const atts_weights* w, at
         m->w_gate_up.push_back(w->w_gate_up[l]);
         m->w_down.push_back(w->w_down[l]);
     }
-    if (((uintptr_t)w->tok_embed | (uintptr_t)w->lm_head) & 15) {
+    if (((uintptr_t)w->tok_embed | (uintptr_t)w->lm_head | (uintptr_t)w->final_norm) & 15) {
         delete m;
-        return fail(ATTS_ERR_INVALID_ARG, "atts_model_create: embedding / LM head must be 16-byte aligned");
+        return fail(ATTS_ERR_INVALID_ARG, "atts_model_create: embedding / LM head / final norm must be 16-byte aligned");
     }
     hipError_t e = hipMalloc(reinterpret_cast<void**>(&m->err_flag), sizeof(int32_t));
     if (e == hipSuccess) e = hipMemset(m->err_flag, 0, sizeof(int32_t));
@@ -231,11 +232,12 @@ int32_t atts_score_drafts(const atts_model* m, const int32_t* prefix_ids, int32_
     const int R = s.R(), B = s.B();
     const int qd = d.n_q_heads * d.head_dim;
     const int qkv_out = (d.n_q_heads + 2 * d.n_kv_heads) * d.head_dim;
+    const bool fuse_rope = vt != nullptr && ws.ldv == R && qkv_rope_fusable(d.dtype, R, qkv_out, d.d_model, d.head_dim);
 
     {
         StageTimer t_(ATTS_STAGE_EMBED, st);
         ATTS_TRY(launch_embed(d.dtype, m->tok_embed, d.vocab, d.d_model, prefix_ids, draft_ids, draft_lens, s, h, m->err_flag, st));
-        ATTS_TRY(launch_rope_table(rope, P + T_max, d.head_dim, d.rope_theta, st));
+        ATTS_TRY(launch_rope_table(rope, s, d.head_dim, d.rope_theta, st));
     }
     for (int l = 0; l < d.n_layers; ++l) {
         {
@@ -245,11 +247,16 @@ int32_t atts_score_drafts(const atts_model* m, const int32_t* prefix_ids, int32_
         GemmArgs g{};
         g.a = xn; g.w = m->wqkv[l]; g.out = qkv; g.M = R; g.N = qkv_out; g.Kd = d.d_model;
         g.lda = d.d_model; g.ldw = d.d_model; g.ldc = qkv_out;
-        {
+        if (fuse_rope) {
+            // QKV projection with RoPE and the V transpose applied to the accumulators
+            g.rope = rope; g.vt = vt; g.ldv = ws.ldv; g.n_rot_heads = d.n_q_heads + d.n_kv_heads;
             StageTimer t_(ATTS_STAGE_GEMM_QKV, st);
-            ATTS_TRY(launch_gemm(d.dtype, EPI_STORE_ACT, g, st));
-        }
-        {
+            ATTS_TRY(launch_gemm(d.dtype, EPI_QKV_ROPE, g, st));
+        } else {
+            {
+                StageTimer t_(ATTS_STAGE_GEMM_QKV, st);
+                ATTS_TRY(launch_gemm(d.dtype, EPI_STORE_ACT, g, st));
+            }
             StageTimer t_(ATTS_STAGE_ROPE, st);
             ATTS_TRY(launch_rope_split(d.dtype, qkv, rope, s, d.n_q_heads, d.n_kv_heads, d.head_dim, vt, ws.ldv, st));
         }

@@ -74,6 +74,8 @@ enum GemmEpilogue : int32_t {
     EPI_RESID_F32 = 2,   // out (float) [M, ldc] += acc            (residual stream update)
     EPI_SWIGLU = 3,      // W = [gate rows (F) ; up rows (F)], N = F: out (T) [M, ldc] = silu(gate) * up
     EPI_LMHEAD = 4,      // per-row online-softmax partials over this tile's columns + target logit
+    EPI_QKV_ROPE = 5,    // QKV projection: q/k heads rotated (rotate-half RoPE) and stored to out (T) [M, ldc];
+                         // v heads stored transposed to vt [n_kv, 128, ldv].  head_dim 128, aligned bf16 shapes only.
 };
 
 struct GemmArgs {
@@ -87,10 +89,17 @@ struct GemmArgs {
     float2* partials;        // [M, n_part] (running max, sum of exp) per column slab
     float* target_logit;     // [M]
     int32_t n_part;          // number of column slabs = lmhead_num_partials(N)
+    // EPI_QKV_ROPE only:
+    const float2* rope;      // [M, 64] (cos, sin) per row and rotation pair
+    void* vt;                // [n_kv, 128, ldv] transposed V
+    int64_t ldv;
+    int32_t n_rot_heads;     // n_q + n_kv: heads (of 128 columns) that are rotated; the rest are V heads
 };
 
 int32_t lmhead_num_partials(int32_t dtype, int32_t M, int32_t N);
 int32_t launch_gemm(int32_t dtype, GemmEpilogue epi, const GemmArgs& g, hipStream_t stream);
+// true if the EPI_QKV_ROPE epilogue can serve this QKV projection (else: EPI_STORE_ACT + launch_rope_split)
+bool qkv_rope_fusable(int32_t dtype, int32_t M, int32_t N, int32_t Kd, int32_t head_dim);
 
 // lp[b] = target_logit[b] - logsumexp over the n_part partials of row b; rows with valid[b] == 0
 // (or b beyond) get 0.  valid may be NULL.
@@ -108,8 +117,8 @@ int32_t launch_embed(int32_t dtype, const void* tok_embed, int32_t vocab, int32_
                      ScoreShape s, float* h, int32_t* err_flag, hipStream_t stream);
 int32_t launch_rmsnorm(int32_t dtype, const float* h, const float* gain, float eps, int32_t rows, int32_t d,
                        void* out, hipStream_t stream);
-// rope table: cs[pos][i] = (cos, sin)(pos * theta^(-2 i / hd)), pos < n_pos, i < hd / 2
-int32_t launch_rope_table(float2* cs, int32_t n_pos, int32_t hd, float theta, hipStream_t stream);
+// rope table per row of the token tree: cs[r][i] = (cos, sin)(pos(r) * theta^(-2 i / hd)), i < hd / 2
+int32_t launch_rope_table(float2* cs, ScoreShape s, int32_t hd, float theta, hipStream_t stream);
 // In-place rotate-half RoPE on the q and k columns of qkv [R, (nq + 2 nkv) hd]; writes V transposed
 // to vt [nkv, hd, ldv] (ldv >= R) when vt != NULL.
 int32_t launch_rope_split(int32_t dtype, void* qkv, const float2* cs, ScoreShape s, int32_t nq, int32_t nkv,

@@ -59,28 +59,68 @@ __global__ __launch_bounds__(256) void embed_kernel(const T* __restrict__ emb, i
 }
 
 // ---- S1: RMSNorm over rows of the fp32 residual stream ---------------------------------------
+// One row per workgroup, 16-byte loads; up to 4 float4 per thread (d <= 4096) stay in registers between the
+// sum-of-squares pass and the scaling pass, longer rows are read again (from L2).  d % 4 == 0.
+template <typename T>
+__device__ __forceinline__ void store4(T* dst, float4 v);
+template <>
+__device__ __forceinline__ void store4<float>(float* dst, float4 v) { *reinterpret_cast<float4*>(dst) = v; }
+template <>
+__device__ __forceinline__ void store4<bf16>(bf16* dst, float4 v) {
+    bf16x4 o;
+    o[0] = (bf16)v.x; o[1] = (bf16)v.y; o[2] = (bf16)v.z; o[3] = (bf16)v.w;
+    *reinterpret_cast<bf16x4*>(dst) = o;
+}
+
+template <typename T>
+__device__ __forceinline__ void rmsnorm_row(const float* __restrict__ x, const float* __restrict__ gain, float eps, int d,
+                                            T* __restrict__ o, float* red) {
+    constexpr int kKeep = 4;
+    const int n4 = d >> 2;
+    const float4* x4 = reinterpret_cast<const float4*>(x);
+    const float4* g4 = reinterpret_cast<const float4*>(gain);
+    float4 keep[kKeep];
+    float ss = 0.f;
+#pragma unroll
+    for (int q = 0; q < kKeep; ++q) {
+        const int c = threadIdx.x + 256 * q;
+        keep[q] = c < n4 ? x4[c] : make_float4(0.f, 0.f, 0.f, 0.f);
+        ss += keep[q].x * keep[q].x + keep[q].y * keep[q].y + keep[q].z * keep[q].z + keep[q].w * keep[q].w;
+    }
+    for (int c = threadIdx.x + 256 * kKeep; c < n4; c += 256) {
+        const float4 v = x4[c];
+        ss += v.x * v.x + v.y * v.y + v.z * v.z + v.w * v.w;
+    }
+    ss = block_sum<256>(ss, red);
+    const float inv = rsqrtf(ss / (float)d + eps);
+#pragma unroll
+    for (int q = 0; q < kKeep; ++q) {
+        const int c = threadIdx.x + 256 * q;
+        if (c < n4) {
+            const float4 g = g4[c];
+            store4<T>(o + 4 * c, make_float4(keep[q].x * inv * g.x, keep[q].y * inv * g.y, keep[q].z * inv * g.z,
+                                             keep[q].w * inv * g.w));
+        }
+    }
+    for (int c = threadIdx.x + 256 * kKeep; c < n4; c += 256) {
+        const float4 v = x4[c], g = g4[c];
+        store4<T>(o + 4 * c, make_float4(v.x * inv * g.x, v.y * inv * g.y, v.z * inv * g.z, v.w * inv * g.w));
+    }
+}
+
 template <typename T>
 __global__ __launch_bounds__(256) void rmsnorm_kernel(const float* __restrict__ h, const float* __restrict__ gain,
                                                       float eps, int d, T* __restrict__ out) {
     __shared__ float red[4];
-    const float* x = h + (int64_t)blockIdx.x * d;
-    float ss = 0.f;
-    for (int c = threadIdx.x; c < d; c += 256) {
-        float v = x[c];
-        ss += v * v;
-    }
-    ss = block_sum<256>(ss, red);
-    const float inv = rsqrtf(ss / (float)d + eps);
-    T* o = out + (int64_t)blockIdx.x * d;
-    for (int c = threadIdx.x; c < d; c += 256) o[c] = from_f32<T>(x[c] * inv * gain[c]);
+    rmsnorm_row<T>(h + (int64_t)blockIdx.x * d, gain, eps, d, out + (int64_t)blockIdx.x * d, red);
 }
 
-// ---- rotary table: (cos, sin)(pos * theta^(-2 i / hd)) in fp64, rounded once ------------------
-__global__ void rope_table_kernel(float2* __restrict__ cs, int n_pos, int half, double log_theta_over_half) {
+// ---- rotary table per row: (cos, sin)(pos(r) * theta^(-2 i / hd)) in fp64, rounded once ----------
+__global__ void rope_table_kernel(float2* __restrict__ cs, int R, int P, int Tn, int half, double log_theta_over_half) {
     int idx = blockIdx.x * blockDim.x + threadIdx.x;
-    if (idx >= n_pos * half) return;
-    int pos = idx / half, i = idx % half;
-    double ang = (double)pos * exp(-(double)i * log_theta_over_half);
+    if (idx >= R * half) return;
+    int r = idx / half, i = idx % half;
+    double ang = (double)tree_position(r, P, Tn) * exp(-(double)i * log_theta_over_half);
     double s, c;
     sincos(ang, &s, &c);
     cs[idx] = make_float2((float)c, (float)s);
@@ -89,8 +129,8 @@ __global__ void rope_table_kernel(float2* __restrict__ cs, int n_pos, int half, 
 // ---- S2 epilogue (unfused): rotate q and k in place -------------------------------------------
 // One thread per (row, head, pair).  Heads 0 .. nq + nkv - 1 of the qkv row are rotated.
 template <typename T>
-__global__ __launch_bounds__(256) void rope_kernel(T* __restrict__ qkv, const float2* __restrict__ cs, int R, int P,
-                                                   int Tn, int n_rot_heads, int hd, int64_t ld) {
+__global__ __launch_bounds__(256) void rope_kernel(T* __restrict__ qkv, const float2* __restrict__ cs, int R,
+                                                   int n_rot_heads, int hd, int64_t ld) {
     const int half = hd >> 1;
     int64_t idx = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
     int64_t total = (int64_t)R * n_rot_heads * half;
@@ -98,7 +138,7 @@ __global__ __launch_bounds__(256) void rope_kernel(T* __restrict__ qkv, const fl
     int i = (int)(idx % half);
     int head = (int)((idx / half) % n_rot_heads);
     int r = (int)(idx / ((int64_t)half * n_rot_heads));
-    float2 c_s = cs[(int64_t)tree_position(r, P, Tn) * half + i];
+    float2 c_s = cs[(int64_t)r * half + i];
     T* p = qkv + (int64_t)r * ld + head * hd + i;
     float x1 = to_f32<T>(p[0]), x2 = to_f32<T>(p[half]);
     p[0] = from_f32<T>(x1 * c_s.x - x2 * c_s.y);
@@ -139,16 +179,7 @@ __global__ __launch_bounds__(256) void gather_norm_kernel(const float* __restric
     const int b = blockIdx.x;
     const int k = b / Tn, t = b % Tn;
     const int src_row = t == 0 ? P - 1 : P + k * Tn + t - 1;
-    const float* x = h + (int64_t)src_row * d;
-    float ss = 0.f;
-    for (int c = threadIdx.x; c < d; c += 256) {
-        float v = x[c];
-        ss += v * v;
-    }
-    ss = block_sum<256>(ss, red);
-    const float inv = rsqrtf(ss / (float)d + eps);
-    T* o = xs + (int64_t)b * d;
-    for (int c = threadIdx.x; c < d; c += 256) o[c] = from_f32<T>(x[c] * inv * gain[c]);
+    rmsnorm_row<T>(h + (int64_t)src_row * d, gain, eps, d, xs + (int64_t)b * d, red);
     if (threadIdx.x == 0) {
         int id = draft_ids[b];
         bool ok = !(draft_lens && t >= draft_lens[k]);
@@ -203,10 +234,10 @@ int32_t launch_rmsnorm(int32_t dtype, const float* h, const float* gain, float e
     return ATTS_OK;
 }
 
-int32_t launch_rope_table(float2* cs, int32_t n_pos, int32_t hd, float theta, hipStream_t stream) {
+int32_t launch_rope_table(float2* cs, ScoreShape s, int32_t hd, float theta, hipStream_t stream) {
     const int half = hd / 2;
-    const int total = n_pos * half;
-    hipLaunchKernelGGL(rope_table_kernel, dim3((unsigned)ceil_div(total, 256)), dim3(256), 0, stream, cs, n_pos, half,
+    const int64_t total = (int64_t)s.R() * half;
+    hipLaunchKernelGGL(rope_table_kernel, dim3((unsigned)ceil_div(total, 256)), dim3(256), 0, stream, cs, s.R(), s.P, s.T, half,
                        log((double)theta) / (double)half);
     ATTS_LAUNCH_CHECK("rope_table_kernel");
     return ATTS_OK;
@@ -227,7 +258,7 @@ int32_t launch_rope_split(int32_t dtype, void* qkv, const float2* cs, ScoreShape
     const int64_t ld = (int64_t)(nq + 2 * nkv) * hd;
     const int64_t total = (int64_t)s.R() * (nq + nkv) * (hd / 2);
     DISPATCH_T(dtype, hipLaunchKernelGGL(rope_kernel<T>, dim3((unsigned)ceil_div(total, 256)), dim3(256), 0, stream,
-                                         (T*)qkv, cs, s.R(), s.P, s.T, nq + nkv, hd, ld);)
+                                         (T*)qkv, cs, s.R(), nq + nkv, hd, ld);)
     ATTS_LAUNCH_CHECK("rope_kernel");
     if (vt) return launch_transpose_v(dtype, qkv, s.R(), nq, nkv, hd, vt, ldv, stream);
     return ATTS_OK;

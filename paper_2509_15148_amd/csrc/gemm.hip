@@ -79,6 +79,8 @@ struct GemmDims {
     int32_t M, N, Kd;
     int64_t lda, ldw, ldc;
     int32_t n_part, nt_m, nt_n;
+    int64_t ldv;            // EPI_QKV_ROPE: row pitch of the transposed V
+    int32_t n_rot_heads;    // EPI_QKV_ROPE: heads (128 columns each) that get rotated; later heads are V
 };
 
 // Epilogue shared by both kernels.  acc[i][j][v] is element (row, col) of the tile with
@@ -87,11 +89,12 @@ template <typename T, int MI, int NI, int EPI>
 __device__ __forceinline__ void gemm_epilogue(f32x16 (&acc)[MI][NI], int m0, int n0, int wm, int wn, int l32, int half,
                                               int tn, void* __restrict__ g_out, const int32_t* __restrict__ g_targets,
                                               float2* __restrict__ g_partials, float* __restrict__ g_target_logit,
+                                              const float2* __restrict__ g_rope, void* __restrict__ g_vt,
                                               const GemmDims& g) {
     constexpr int WM = 32 * MI, WN = 32 * NI;
     const int row_base = m0 + wm * WM + 4 * half;
 
-    if (EPI == EPI_STORE_ACT || EPI == EPI_STORE_F32 || EPI == EPI_RESID_F32) {
+    if constexpr (EPI == EPI_STORE_ACT || EPI == EPI_STORE_F32 || EPI == EPI_RESID_F32) {
         const int col_base = n0 + wn * WN + l32;
 #pragma unroll
         for (int i = 0; i < MI; ++i)
@@ -109,7 +112,7 @@ __device__ __forceinline__ void gemm_epilogue(f32x16 (&acc)[MI][NI], int m0, int
                     if (EPI == EPI_RESID_F32) reinterpret_cast<float*>(g_out)[idx] += acc[i][j][v];
                 }
             }
-    } else if (EPI == EPI_SWIGLU) {
+    } else if constexpr (EPI == EPI_SWIGLU) {
         // blocks j < NI/2 hold gate, j + NI/2 the matching up columns
         const int col_base = n0 + wn * (WN / 2) + l32;
 #pragma unroll
@@ -127,7 +130,47 @@ __device__ __forceinline__ void gemm_epilogue(f32x16 (&acc)[MI][NI], int m0, int
                     reinterpret_cast<T*>(g_out)[(int64_t)row * g.ldc + col] = from_f32<T>(y);
                 }
             }
-    } else if (EPI == EPI_LMHEAD) {
+    } else if constexpr (EPI == EPI_QKV_ROPE) {
+        // The wave's 128 columns are exactly one head (head_dim 128): blocks j = 0, 1 hold dims 0..63 and blocks
+        // j + 2 the partner dims 64..127 of the rotate-half pairing, in the same lane.
+        static_assert(NI == 4 && sizeof(T) == 2, "QKV epilogue needs 128-column bf16 wave tiles");
+        const int col0 = n0 + wn * WN;
+        const int head = col0 / 128;                                  // wave-uniform
+        if (head < g.n_rot_heads) {
+#pragma unroll
+            for (int i = 0; i < MI; ++i)
+#pragma unroll
+                for (int v = 0; v < 16; ++v) {
+                    const int row = row_base + 32 * i + 8 * (v >> 2) + (v & 3);
+                    T* orow = reinterpret_cast<T*>(g_out) + (int64_t)row * g.ldc + col0 + l32;
+                    const float2* crow = g_rope + (int64_t)row * 64 + l32;
+#pragma unroll
+                    for (int j = 0; j < 2; ++j) {
+                        const float2 cs = crow[32 * j];
+                        const float x1 = acc[i][j][v], x2 = acc[i][j + 2][v];
+                        orow[32 * j] = from_f32<T>(x1 * cs.x - x2 * cs.y);
+                        orow[32 * j + 64] = from_f32<T>(x2 * cs.x + x1 * cs.y);
+                    }
+                }
+        } else {
+            // V head: lane holds 4 consecutive rows (v % 4) of one head dim -> one 8-byte store into V^T
+            T* vbase = reinterpret_cast<T*>(g_vt) + (int64_t)(head - g.n_rot_heads) * 128 * g.ldv;
+#pragma unroll
+            for (int i = 0; i < MI; ++i)
+#pragma unroll
+                for (int a = 0; a < 4; ++a) {
+                    const int row0 = row_base + 32 * i + 8 * a;
+#pragma unroll
+                    for (int j = 0; j < NI; ++j) {
+                        typedef T T4 __attribute__((ext_vector_type(4)));
+                        T4 o4;
+#pragma unroll
+                        for (int b = 0; b < 4; ++b) o4[b] = from_f32<T>(acc[i][j][4 * a + b]);
+                        *reinterpret_cast<T4*>(vbase + (int64_t)(32 * j + l32) * g.ldv + row0) = o4;
+                    }
+                }
+        }
+    } else if constexpr (EPI == EPI_LMHEAD) {
         // One (max, sum exp) partial per row for this wave's WN columns, plus the target logit.
         const int col0 = n0 + wn * WN;            // first column of this wave's slab
         const int part = tn * 2 + wn;
@@ -168,7 +211,9 @@ __global__ __launch_bounds__(kThreads) void gemm_nt_kernel(const char* __restric
                                                            void* __restrict__ g_out,
                                                            const int32_t* __restrict__ g_targets,
                                                            float2* __restrict__ g_partials,
-                                                           float* __restrict__ g_target_logit, const GemmDims g) {
+                                                           float* __restrict__ g_target_logit,
+                                                           const float2* __restrict__ g_rope, void* __restrict__ g_vt,
+                                                           const GemmDims g) {
     constexpr int MI = BM / 64, NI = BN / 64;   // 32x32 blocks per wave along M / N
     constexpr int WM = BM / 2, WN = BN / 2;     // wave tile
     constexpr int kElemsPerChunk = 16 / (int)sizeof(T);
@@ -274,7 +319,7 @@ __global__ __launch_bounds__(kThreads) void gemm_nt_kernel(const char* __restric
         __syncthreads();
     }
 
-    gemm_epilogue<T, MI, NI, EPI>(acc, m0, n0, wm, wn, l32, half, tc.tn, g_out, g_targets, g_partials, g_target_logit, g);
+    gemm_epilogue<T, MI, NI, EPI>(acc, m0, n0, wm, wn, l32, half, tc.tn, g_out, g_targets, g_partials, g_target_logit, g_rope, g_vt, g);
 }
 
 // ---------------------------------------------------------------------------------------------
@@ -294,7 +339,8 @@ __global__ __launch_bounds__(128 * kWavesM) void gemm_bf16_fast_kernel(const cha
                                                                        const int32_t* __restrict__ g_targets,
                                                                        float2* __restrict__ g_partials,
                                                                        float* __restrict__ g_target_logit,
-                                                                       const GemmDims g) {
+                                                                       const float2* __restrict__ g_rope,
+                                                                       void* __restrict__ g_vt, const GemmDims g) {
     constexpr int BM = 256, BN = 256, NI = 4, WN = 128;
     constexpr int MI = 8 / kWavesM, WM = 32 * MI;
     constexpr int kWaves = 2 * kWavesM;
@@ -449,7 +495,7 @@ __global__ __launch_bounds__(128 * kWavesM) void gemm_bf16_fast_kernel(const cha
     for (++kt; kt + 1 < nk; ++kt) slab(kt, Yes{}, No{}, No{}, No{});
     slab(kt, No{}, No{}, No{}, No{});
 
-    gemm_epilogue<bf16, MI, NI, EPI>(acc, m0, n0, wm, wn, l32, half, tc.tn, g_out, g_targets, g_partials, g_target_logit, g);
+    gemm_epilogue<bf16, MI, NI, EPI>(acc, m0, n0, wm, wn, l32, half, tc.tn, g_out, g_targets, g_partials, g_target_logit, g_rope, g_vt, g);
 }
 
 constexpr int kFastBK = 32;
@@ -474,6 +520,8 @@ int32_t launch_fast(const GemmArgs& g, hipStream_t stream) {
     d.M = g.M; d.N = g.N; d.Kd = g.Kd;
     d.lda = g.lda; d.ldw = g.ldw; d.ldc = g.ldc;
     d.n_part = g.n_part;
+    d.ldv = g.ldv;
+    d.n_rot_heads = g.n_rot_heads;
     d.nt_m = g.M / 256;
     d.nt_n = g.N / n_out;
     const size_t lds = (size_t)ATTS_FAST_STAGES * 512 * 2 * kFastBK;
@@ -485,7 +533,7 @@ int32_t launch_fast(const GemmArgs& g, hipStream_t stream) {
         attr_set = true;
     }
     hipLaunchKernelGGL(kern, dim3(d.nt_m * d.nt_n), dim3(128 * kWavesM), lds, stream, reinterpret_cast<const char*>(g.a),
-                       reinterpret_cast<const char*>(g.w), g.out, g.targets, g.partials, g.target_logit, d);
+                       reinterpret_cast<const char*>(g.w), g.out, g.targets, g.partials, g.target_logit, g.rope, g.vt, d);
     ATTS_LAUNCH_CHECK("gemm_bf16_fast_kernel");
     return ATTS_OK;
 }
@@ -497,6 +545,8 @@ int32_t launch_cfg(const GemmArgs& g, hipStream_t stream) {
     d.M = g.M; d.N = g.N; d.Kd = g.Kd;
     d.lda = g.lda; d.ldw = g.ldw; d.ldc = g.ldc;
     d.n_part = g.n_part;
+    d.ldv = g.ldv;
+    d.n_rot_heads = g.n_rot_heads;
     d.nt_m = (int)ceil_div(g.M, BM);
     d.nt_n = (int)ceil_div(g.N, n_out);
     const size_t lds = 2 * (size_t)(BM + BN) * kRowBytes;
@@ -508,7 +558,7 @@ int32_t launch_cfg(const GemmArgs& g, hipStream_t stream) {
         attr_set = true;
     }
     hipLaunchKernelGGL(kern, dim3(d.nt_m * d.nt_n), dim3(kThreads), lds, stream, reinterpret_cast<const char*>(g.a),
-                       reinterpret_cast<const char*>(g.w), g.out, g.targets, g.partials, g.target_logit, d);
+                       reinterpret_cast<const char*>(g.w), g.out, g.targets, g.partials, g.target_logit, g.rope, g.vt, d);
     ATTS_LAUNCH_CHECK("gemm_nt_kernel");
     return ATTS_OK;
 }
@@ -536,6 +586,7 @@ int32_t launch_t(GemmEpilogue epi, const GemmArgs& g, hipStream_t stream) {
         case EPI_RESID_F32: return launch_epi<T, EPI_RESID_F32>(g, stream);
         case EPI_SWIGLU: return launch_epi<T, EPI_SWIGLU>(g, stream);
         case EPI_LMHEAD: return launch_epi<T, EPI_LMHEAD>(g, stream);
+        case EPI_QKV_ROPE: break;   // fast path only, dispatched by launch_gemm
     }
     return fail(ATTS_ERR_INVALID_ARG, "unknown GEMM epilogue %d", (int)epi);
 }
@@ -572,6 +623,12 @@ int32_t lmhead_num_partials(int32_t /*dtype*/, int32_t M, int32_t N) {
     return (int32_t)ceil_div(N, bn) * 2;
 }
 
+bool qkv_rope_fusable(int32_t dtype, int32_t M, int32_t N, int32_t Kd, int32_t head_dim) {
+    GemmArgs g{};
+    g.M = M; g.N = N; g.Kd = Kd; g.lda = Kd; g.ldw = Kd;
+    return head_dim == 128 && use_big_tile(M, N) && fast_path_ok(dtype, EPI_QKV_ROPE, g);
+}
+
 int32_t launch_gemm(int32_t dtype, GemmEpilogue epi, const GemmArgs& g, hipStream_t stream) {
     const size_t es = dtype_size(dtype);
     if (g.M <= 0 || g.N <= 0 || g.Kd <= 0) return fail(ATTS_ERR_SHAPE, "gemm: empty shape %d x %d x %d", g.M, g.N, g.Kd);
@@ -580,6 +637,12 @@ int32_t launch_gemm(int32_t dtype, GemmEpilogue epi, const GemmArgs& g, hipStrea
     if (((uintptr_t)g.a | (uintptr_t)g.w) & 15) return fail(ATTS_ERR_INVALID_ARG, "gemm: operands must be 16-byte aligned");
     if (epi == EPI_LMHEAD && g.n_part != lmhead_num_partials(dtype, g.M, g.N))
         return fail(ATTS_ERR_INVALID_ARG, "gemm: wrong partial count for the LM-head epilogue");
+    if (epi == EPI_QKV_ROPE) {
+        if (!qkv_rope_fusable(dtype, g.M, g.N, g.Kd, 128) || !g.rope || !g.vt || g.ldv < g.M || g.ldv % 4 ||
+            g.n_rot_heads < 1 || g.n_rot_heads * 128 >= g.N)
+            return fail(ATTS_ERR_SHAPE, "gemm: the fused QKV epilogue does not apply to this call");
+        return launch_fast<EPI_QKV_ROPE>(g, stream);
+    }
     return dtype == ATTS_DTYPE_F32 ? launch_t<float>(epi, g, stream) : launch_t<bf16>(epi, g, stream);
 }
 
