@@ -16,6 +16,8 @@
 //     compact block of tiles, which keeps each XCD's private L2 re-using A and W slabs.
 #include "common.h"
 
+#include <type_traits>
+
 namespace atts {
 namespace {
 
@@ -440,16 +442,19 @@ __global__ __launch_bounds__(128 * kWavesM) void gemm_bf16_fast_kernel(const cha
     // half a slab spread evenly underneath.  (The texture path accepts one 1 KiB DMA instruction per ~16
     // cycles per CU; issued back to back they block the wave, and with it the MFMAs, for that long.)
     constexpr int kReads = MI + NI, kMfma = MI * NI;
-    auto interleave_hint = [&](bool with_dma) __attribute__((always_inline)) {
+    auto interleave_hint = [&](bool with_dma, auto sync_id) __attribute__((always_inline)) {
+        constexpr int kId = decltype(sync_id)::value;   // std::integral_constant
 #pragma unroll
         for (int r = 0; r < kReads; ++r) {
-            __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);                                      // MFMA
+            __builtin_amdgcn_sched_group_barrier(0x008, 1, kId);                                    // MFMA
             if (with_dma && r % (kReads / DMA_PER_OP) == 0 && r / (kReads / DMA_PER_OP) < DMA_PER_OP)
-                __builtin_amdgcn_sched_group_barrier(0x020, 1, 0);                                  // VMEM read (LDS DMA)
-            __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);                                      // DS read
+                __builtin_amdgcn_sched_group_barrier(0x020, 1, kId);                                // VMEM read (LDS DMA)
+            __builtin_amdgcn_sched_group_barrier(0x100, 1, kId);                                    // DS read
         }
-        __builtin_amdgcn_sched_group_barrier(0x008, kMfma - kReads, 0);
+        __builtin_amdgcn_sched_group_barrier(0x008, kMfma - kReads, kId);
     };
+    using Id0 = std::integral_constant<int, 0>;
+    using Id1 = std::integral_constant<int, 1>;
 
     // Ring of kStages slabs.  During slab kt:
     //   k-step 0   MFMAs; underneath: fragments of k-step 1, DMA of the W half of slab kt + kAhead - 1
@@ -475,16 +480,17 @@ __global__ __launch_bounds__(128 * kWavesM) void gemm_bf16_fast_kernel(const cha
         load_frags(kt, 1, fa[1], fb[1]);
         if (issue_w) issue_b(kt + kAhead - 1);
         mma_step(fa[0], fb[0]);
-        interleave_hint(issue_w);
+        interleave_hint(issue_w, Id0{});
         if (has_next) {
             // outstanding after slab kt + 1: slabs kt + 2 .. kt + kAhead - 1 in full
             if (steady) wait_vmcnt<2 * (kAhead - 2) * DMA_PER_OP>(); else wait_vmcnt<0>();
             block_barrier();
+            __builtin_amdgcn_sched_barrier(0);     // the two k-steps are scheduled as separate regions
             load_frags(kt + 1, 0, fa[0], fb[0]);
             if (issue_next_a) issue_a(kt + kAhead);
         }
         mma_step(fa[1], fb[1]);
-        if (has_next) interleave_hint(issue_next_a);
+        if (has_next) interleave_hint(issue_next_a, Id1{});
     };
     struct Yes { constexpr operator bool() const { return true; } };
     struct No { constexpr operator bool() const { return false; } };
