@@ -131,6 +131,8 @@ def _full_width_case(name, n_layers, k_sample):
     lp, sc, flag = _run_gpu(A, cfg, w_dev, prefix, drafts)
     assert flag == 0 and np.all(np.isfinite(lp)) and np.all(lp <= 0)
     w_np = weights_to_numpy(w_dev)
+    del w_dev
+    torch.cuda.empty_cache()
     ref = O.token_logprobs(w_np, cfg, prefix, drafts[k_sample])
     err = np.abs(lp[k_sample] - ref).max()
     assert err <= TOL["bf16"], err
@@ -142,3 +144,15 @@ def _full_width_case(name, n_layers, k_sample):
 
 def test_7b_shape_two_layer_slice():
     _full_width_case("7b", n_layers=2, k_sample=5)
+
+
+def test_7b_full_model_sampled_draft():
+    """The 7B-class workload exactly as bench.py runs it (28 layers, K = 16 drafts of 256 tokens after a
+    512-token prefix); the oracle scores one sampled draft as a plain causal sequence (~1 minute of CPU)."""
+    _full_width_case("7b", n_layers=None, k_sample=11)
+
+
+@pytest.mark.parametrize("name", ["32b", "70b"])
+def test_large_models_one_layer_slice(name):
+    """Full width, full row count (34,816 / 9,216 rows: 64-bit offsets in the FFN activation), one layer."""
+    _full_width_case(name, n_layers=1, k_sample=3)
