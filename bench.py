@@ -121,6 +121,9 @@ def main():
     ap.add_argument("--layers", type=int, default=0, help="build only the first L layers (debug; result is labelled)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-layers", type=int, default=2)
+    ap.add_argument("--calib-batches", type=int, default=-1,
+                    help="scoring passes used to pre-sample the calibration set (-1: all ceil(n_cal / K) for tiny/7b, "
+                         "2 for the larger models); the rest is drawn from a normal fitted to those scores")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build measures ONE MI355X; the path has no multi-GPU leg (run with --gpus 1)",
@@ -162,12 +165,23 @@ def main():
     # through the same scoring path (untimed set-up).
     calib = A.Calib(n_cal_batches * wl.K + (n_batches + args.steps) * wl.K)   # timed pass + stage-timing pass
     t0 = time.perf_counter()
-    for i in range(n_cal_batches):
+    n_real = args.calib_batches if args.calib_batches >= 0 else (n_cal_batches if args.workload in ("tiny", "7b") else 2)
+    n_real = max(1, min(n_real, n_cal_batches))
+    seen = []
+    for i in range(n_real):
         p, d = make_token_ids(cfg.vocab, wl.P, wl.K, wl.T, wl.seed + 100003 + i, device="cuda")
         A.atts_score_drafts(model, p, d, None, A.SCORE_MEAN_NLL, None, sc, ws)
         A.atts_calibrate_online(calib, sc)
+        seen.append(sc.clone())
+    if n_real < n_cal_batches:
+        seen = torch.cat(seen)
+        g = torch.Generator(device="cuda").manual_seed(wl.seed)
+        fill = seen.mean() + seen.std() * torch.randn((n_cal_batches - n_real) * wl.K, device="cuda", generator=g)
+        A.atts_calibrate_online(calib, fill.float().contiguous())
     torch.cuda.synchronize()
-    log(f"[bench] calibration pre-sampling: {n_cal_batches} batches in {time.perf_counter() - t0:.1f} s, "
+    calib_note = (f"{n_real} scoring passes" if n_real == n_cal_batches else
+                  f"{n_real} scoring passes + {(n_cal_batches - n_real) * wl.K} scores from a normal fitted to them")
+    log(f"[bench] calibration pre-sampling: {calib_note} in {time.perf_counter() - t0:.1f} s, "
         f"N = {A.atts_calib_size(calib)}")
 
     def step(i):
@@ -227,7 +241,7 @@ def main():
                                f"F={cfg.d_ffn} V={cfg.vocab} {cfg.dtype}; P={wl.P} K={wl.K} T={wl.T}; "
                                f"n_cal={A.atts_calib_size(calib)} alpha={list(wl.alphas)}",
                    "scored_tokens_per_step": wl.K * wl.T, "rows_per_step": wl.P + wl.K * wl.T,
-                   "layers_built": L, "full_model": L == cfg.n_layers},
+                   "layers_built": L, "full_model": L == cfg.n_layers, "calibration_set": calib_note},
         "conformal_decisions_per_s": wl.K * args.steps / dt,
         "algorithmic_tflop_per_step": fl["total"] / 1e12,
         "whole_step_mfma_frac": fl["total"] / (dt / args.steps) / 1e12 / peak,
