@@ -68,31 +68,78 @@ __device__ __forceinline__ int64_t upper_bound(const uint32_t* __restrict__ a, i
     return lo;
 }
 
+// ---- merge path ------------------------------------------------------------------------------------
+// Number of elements taken from a[] among the first `diag` outputs of the stable merge (a first on ties).
+template <typename Index>
+__device__ __forceinline__ Index merge_path(const uint32_t* a, Index na, const uint32_t* b, Index nb, Index diag) {
+    Index lo = diag > nb ? diag - nb : 0, hi = diag < na ? diag : na;
+    while (lo < hi) {
+        Index mid = (lo + hi) >> 1;
+        if (a[mid] <= b[diag - 1 - mid]) lo = mid + 1; else hi = mid;
+    }
+    return lo;
+}
+
 // ---- block sort: each workgroup turns kSortChunk scores into one ascending run of keys ----------
+// 8 keys per thread: sorted in registers (odd-even transposition network), then log2(1024) rounds of pairwise
+// merges of sorted runs through two LDS buffers (each thread finds its 8 outputs by merge path and merges them
+// sequentially), one barrier per round.
+__device__ __forceinline__ void cswap(uint32_t& x, uint32_t& y) {
+    const uint32_t lo = min(x, y), hi = max(x, y);
+    x = lo;
+    y = hi;
+}
+
 __global__ __launch_bounds__(kSortThreads) void block_sort_kernel(const float* __restrict__ scores, int64_t n,
                                                                   uint32_t* __restrict__ runs) {
-    __shared__ uint32_t s[kSortChunk];
+    constexpr int VT = kSortChunk / kSortThreads;   // 8
+    static_assert(VT == 8, "register network below sorts 8 keys");
+    __shared__ uint32_t buf[2][kSortChunk];
     const int64_t base = (int64_t)blockIdx.x * kSortChunk;
-    for (int i = threadIdx.x; i < kSortChunk; i += kSortThreads)
-        s[i] = base + i < n ? score_to_key(scores[base + i]) : kPadKey;
+    const int tid = threadIdx.x;
+    for (int i = tid; i < kSortChunk; i += kSortThreads) buf[0][i] = base + i < n ? score_to_key(scores[base + i]) : kPadKey;
     __syncthreads();
-    for (int k = 2; k <= kSortChunk; k <<= 1) {
-        for (int j = k >> 1; j > 0; j >>= 1) {
-            for (int t = threadIdx.x; t < kSortChunk / 2; t += kSortThreads) {
-                int i = ((t & ~(j - 1)) << 1) | (t & (j - 1));
-                int p = i | j;
-                uint32_t a = s[i], b = s[p];
-                bool up = (i & k) == 0;
-                if ((a > b) == up) {
-                    s[i] = b;
-                    s[p] = a;
-                }
-            }
-            __syncthreads();
-        }
+    uint32_t k[VT];
+#pragma unroll
+    for (int e = 0; e < VT; ++e) k[e] = buf[0][tid * VT + e];
+#pragma unroll
+    for (int round = 0; round < VT; ++round) {
+#pragma unroll
+        for (int e = round & 1; e + 1 < VT; e += 2) cswap(k[e], k[e + 1]);
     }
-    for (int i = threadIdx.x; i < kSortChunk; i += kSortThreads)
-        if (base + i < n) runs[base + i] = s[i];
+#pragma unroll
+    for (int e = 0; e < VT; ++e) buf[0][tid * VT + e] = k[e];
+    int cur = 0;
+    for (int width = VT; width < kSortChunk; width *= 2) {
+        __syncthreads();
+        const uint32_t* src = buf[cur];
+        uint32_t* dst = buf[cur ^ 1];
+        const int o = tid * VT;
+        const int pair = o & ~(2 * width - 1);
+        const uint32_t* a = src + pair;
+        const uint32_t* b = a + width;
+        int ia = merge_path<int>(a, width, b, width, o - pair);
+        int ib = o - pair - ia;
+        uint32_t ka = ia < width ? a[ia] : kPadKey, kb = ib < width ? b[ib] : kPadKey;
+#pragma unroll
+        for (int e = 0; e < VT; ++e) {
+            const bool take_a = ib >= width || (ia < width && ka <= kb);
+            k[e] = take_a ? ka : kb;
+            if (take_a) {
+                ++ia;
+                ka = ia < width ? a[ia] : kPadKey;
+            } else {
+                ++ib;
+                kb = ib < width ? b[ib] : kPadKey;
+            }
+        }
+#pragma unroll
+        for (int e = 0; e < VT; ++e) dst[o + e] = k[e];
+        cur ^= 1;
+    }
+    __syncthreads();
+    for (int i = tid; i < kSortChunk; i += kSortThreads)
+        if (base + i < n) runs[base + i] = buf[cur][i];
 }
 
 // ---- multi-way placement: final position of every element of <= kMaxMultiwayRuns sorted runs -----
@@ -114,18 +161,7 @@ __global__ __launch_bounds__(256) void multiway_place_kernel(const uint32_t* __r
     out[pos] = x;
 }
 
-// ---- merge path ------------------------------------------------------------------------------------
-// Number of elements taken from a[] among the first `diag` outputs of the stable merge (a first on ties).
-template <typename Index>
-__device__ __forceinline__ Index merge_path(const uint32_t* a, Index na, const uint32_t* b, Index nb, Index diag) {
-    Index lo = diag > nb ? diag - nb : 0, hi = diag < na ? diag : na;
-    while (lo < hi) {
-        Index mid = (lo + hi) >> 1;
-        if (a[mid] <= b[diag - 1 - mid]) lo = mid + 1; else hi = mid;
-    }
-    return lo;
-}
-
+// ---- merging two sorted arrays --------------------------------------------------------------------
 struct MergeJob {
     const uint32_t* a;   // pair y: a + 2 y run, length min(run, n - 2 y run)   (pairwise mode: run > 0)
     int64_t na;
@@ -157,7 +193,38 @@ __global__ __launch_bounds__(kMergeThreads) void merge_kernel(MergeJob job) {
 
     __shared__ int64_t split[2];
     __shared__ uint32_t buf[kMergeSeg];
-    if (threadIdx.x < 2) split[threadIdx.x] = merge_path<int64_t>(a, na, b, nb, threadIdx.x == 0 ? o0 : o1);
+    // Merge-path split of both segment ends at once: threads 0..127 search the diagonal o0, threads 128..255 the
+    // diagonal o1.  Each round probes 128 evenly spaced candidates of the current range in parallel (one load
+    // latency per round instead of one per halving step); "a[i] <= b[diag - 1 - i]" is true below the split.
+    {
+        __shared__ int64_t s_lo[2], s_hi[2];
+        __shared__ int s_cnt[2];
+        const int h = threadIdx.x >> 7, t = threadIdx.x & 127;
+        const int64_t diag = h ? o1 : o0;
+        if (t == 0) {
+            s_lo[h] = diag > nb ? diag - nb : 0;
+            s_hi[h] = diag < na ? diag : na;
+        }
+        __syncthreads();
+        while (s_lo[0] != s_hi[0] || s_lo[1] != s_hi[1]) {      // block-uniform
+            const int64_t lo = s_lo[h], hi = s_hi[h], range = hi - lo;
+            if (t == 0) s_cnt[h] = 0;
+            __syncthreads();
+            const int64_t step = (range + 127) / 128;
+            const int64_t i = lo + t * step;
+            const bool pred = range > 0 && i < hi && a[i] <= b[diag - 1 - i];
+            const int c_wave = __popcll(__ballot(pred));
+            if ((threadIdx.x & 63) == 0 && c_wave) atomicAdd(&s_cnt[h], c_wave);
+            __syncthreads();
+            if (t == 0 && range > 0) {
+                const int64_t c = s_cnt[h], n_probe = (range + step - 1) / step;
+                s_lo[h] = c > 0 ? lo + (c - 1) * step + 1 : lo;
+                s_hi[h] = c == 0 ? lo : (c < n_probe ? lo + c * step : hi);
+            }
+            __syncthreads();
+        }
+        if (t == 0) split[h] = s_lo[h];
+    }
     __syncthreads();
     const int64_t i0 = split[0], i1 = split[1];
     const int64_t j0 = o0 - i0, j1 = o1 - i1;
@@ -183,10 +250,19 @@ struct ClassifyLevels {
     int32_t n_alpha;
 };
 
+constexpr int kTopEntries = 1024;   // LDS index: every (n / 1024 rounded up to a power of two)-th key
+
 __global__ __launch_bounds__(256) void classify_kernel(const uint32_t* __restrict__ keys, int64_t n,
                                                        const float* __restrict__ test, int64_t m, ClassifyLevels lv,
-                                                       int32_t* __restrict__ ranks, float* __restrict__ pvalues,
-                                                       uint8_t* __restrict__ classes, float* __restrict__ thresholds) {
+                                                       int top_shift, int32_t* __restrict__ ranks,
+                                                       float* __restrict__ pvalues, uint8_t* __restrict__ classes,
+                                                       float* __restrict__ thresholds) {
+    // top[i] = keys[i << top_shift]: the first ~10 steps of every binary search run in LDS, the rest touch a
+    // window of at most 2^top_shift keys.
+    __shared__ uint32_t top[kTopEntries];
+    const int n_top = (int)((n + ((int64_t)1 << top_shift) - 1) >> top_shift);
+    for (int i = threadIdx.x; i < n_top; i += 256) top[i] = keys[(int64_t)i << top_shift];
+    __syncthreads();
     const int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x;
     if (blockIdx.x == 0 && thresholds && (int)threadIdx.x < lv.n_alpha) {
         const int64_t kth = n + 1 - lv.r[threadIdx.x];     // 1-indexed order statistic
@@ -195,7 +271,21 @@ __global__ __launch_bounds__(256) void classify_kernel(const uint32_t* __restric
     if (i >= m) return;
     const float s = test[i];
     int64_t c = 0;
-    if (!score_is_nan(s)) c = n - lower_bound(keys, n, score_to_key(s));
+    if (!score_is_nan(s)) {
+        const uint32_t x = score_to_key(s);
+        int lo = 0, hi = n_top;                            // t = number of index entries < x
+        while (lo < hi) {
+            const int mid = (lo + hi) >> 1;
+            if (top[mid] < x) lo = mid + 1; else hi = mid;
+        }
+        int64_t lb = 0;
+        if (lo > 0) {                                      // keys[(lo - 1) << shift] < x <= keys[lo << shift]
+            const int64_t w0 = ((int64_t)(lo - 1) << top_shift) + 1;
+            const int64_t w1 = min(n, (int64_t)lo << top_shift);
+            lb = w0 + lower_bound(keys + w0, w1 - w0, x);
+        }
+        c = n - lb;
+    }
     ranks[i] = (int32_t)c;
     if (pvalues) pvalues[i] = (float)((double)(c + 1) / (double)(n + 1));
     int cls = 0;
@@ -332,8 +422,10 @@ int32_t atts_classify_ordinal(const atts_calib* c, const float* test_scores, int
     for (int l = 0; l < n_alpha; ++l) lv.r[l] = (int64_t)floor(alphas[l] * (double)(c->n + 1));
     if (M == 0 && !thresholds) return ATTS_OK;
     const unsigned blocks = (unsigned)(M > 0 ? ceil_div(M, 256) : 1);
+    int top_shift = 0;
+    while (((c->n + ((int64_t)1 << top_shift) - 1) >> top_shift) > kTopEntries) ++top_shift;
     hipLaunchKernelGGL(classify_kernel, dim3(blocks), dim3(256), 0, static_cast<hipStream_t>(hip_stream), c->keys[c->cur],
-                       c->n, test_scores, M, lv, ranks, pvalues, classes, thresholds);
+                       c->n, test_scores, M, lv, top_shift, ranks, pvalues, classes, thresholds);
     ATTS_LAUNCH_CHECK("classify_kernel");
     return ATTS_OK;
 }
