@@ -90,17 +90,26 @@ def cpu_baseline(cfg, wl, w_dev, prefix, drafts, n_layers_full, budget_layers):
     }
 
 
-def bench_calibration(A, torch, np, steps=16):
-    """The calibration-only workload: 2^20 resident scores, then per step append 65,536 and
-    classify 65,536 at two alpha levels."""
+def bench_calibration(A, torch, np, steps=16, scaled=False):
+    """The calibration-only workload: 2^20 resident scores, then per step append 65,536 and classify 65,536 at
+    two alpha levels.  scaled=True: the same step at an out-of-cache size (2^28 resident scores = 1 GiB of keys,
+    2^24 appended and 2^24 classified per step), where the HBM roofline is the meaningful bound; its scores are
+    drawn on the device (exp of a seeded normal)."""
     from synth import WORKLOADS, lognormal_scores
     wl = WORKLOADS["calib"]
-    calib = A.Calib(wl.n_cal + (steps + 2) * wl.n_new)
-    A.atts_calibrate_online(calib, torch.from_numpy(lognormal_scores(wl.n_cal, wl.seed)).cuda())
-    new = [torch.from_numpy(lognormal_scores(wl.n_new, wl.seed + 1000 + i)).cuda() for i in range(steps + 2)]
-    test = [torch.from_numpy(lognormal_scores(wl.n_test, wl.seed + 2000 + i)).cuda() for i in range(steps + 2)]
-    ranks = torch.empty(wl.n_test, dtype=torch.int32, device="cuda")
-    cls = torch.empty(wl.n_test, dtype=torch.uint8, device="cuda")
+    if scaled:
+        n_cal, n_new, n_test = 1 << 28, 1 << 24, 1 << 24
+        g = torch.Generator(device="cuda").manual_seed(wl.seed)
+        draw = lambda n, _seed: torch.randn(n, device="cuda", generator=g).exp_()
+    else:
+        n_cal, n_new, n_test = wl.n_cal, wl.n_new, wl.n_test
+        draw = lambda n, seed: torch.from_numpy(lognormal_scores(n, seed)).cuda()
+    calib = A.Calib(n_cal + (2 * steps + 2) * n_new)
+    A.atts_calibrate_online(calib, draw(n_cal, wl.seed))
+    new = [draw(n_new, wl.seed + 1000 + i) for i in range(steps + 2)]
+    test = [draw(n_test, wl.seed + 2000 + i) for i in range(steps + 2)]
+    ranks = torch.empty(n_test, dtype=torch.int32, device="cuda")
+    cls = torch.empty(n_test, dtype=torch.uint8, device="cuda")
 
     def step(i):
         A.atts_calibrate_online(calib, new[i])
@@ -115,17 +124,60 @@ def bench_calibration(A, torch, np, steps=16):
         step(i)
     torch.cuda.synchronize()
     dt = time.perf_counter() - t0
-    # bytes the method must move per step: read the set once, read + append the new scores,
-    # read the test scores, write ranks (4 B) and classes (1 B)
-    n_mid = n0 + wl.n_new * steps / 2
-    bytes_step = 4 * n_mid + 8 * wl.n_new + 4 * wl.n_test + 5 * wl.n_test
-    return {
-        "workload": "calib: 2^20 lognormal scores + 65536 appended and 65536 classified per step, alphas (0.05, 0.2)",
-        "steps": steps, "us_per_step": dt / steps * 1e6, "decisions_per_s": wl.n_test * steps / dt,
+    n_mid = n0 + n_new * steps / 2
+    # per-kernel-group device times of the same steps again (HIP events on the launch stream)
+    A.atts_profile_enable(True)
+    for i in range(2, steps + 2):
+        step(i)
+    torch.cuda.synchronize()
+    st = {name: A.atts_profile_read(A.STAGES.index(name))[0] / steps * 1e3 for name in ("calib_sort", "calib_merge", "classify")}
+    A.atts_profile_enable(False)
+    n_mid2 = n_mid + n_new * steps
+    # bytes the method must move per step: read the set once, read + append the new scores, read the test
+    # scores, write ranks (4 B) and classes (1 B).  Keeping the set sorted adds one more pass: the merge reads
+    # the old array and writes the new one.
+    bytes_step = 4 * n_mid + 8 * n_new + 4 * n_test + 5 * n_test
+    merge_bytes = 4 * n_mid2 + 4 * n_new + 4 * (n_mid2 + n_new) * (1 + 1 / 16 + 1 / 256)   # old + batch in, array + index out
+    out = {
+        "workload": (f"calib{' (scaled, out of cache)' if scaled else ''}: {n_cal} lognormal scores + {n_new} appended and "
+                     f"{n_test} classified per step, alphas {list(wl.alphas)}"),
+        "steps": steps, "us_per_step": dt / steps * 1e6, "decisions_per_s": n_test * steps / dt,
         "algorithmic_bytes_per_step": bytes_step, "achieved_GBs": bytes_step * steps / dt / 1e9,
         "hbm_frac": bytes_step * steps / dt / 1e9 / HBM_PEAK_GBS,
-        "note": "working set (4-8 MB) is cache resident and a step is a few kernel launches: launch-latency bound",
+        "stage_us": st,
+        "merge_kernel": {"bytes_per_launch": merge_bytes, "avg_launch_us": st["calib_merge"],
+                         "achieved_GBs": merge_bytes / (st["calib_merge"] * 1e-6) / 1e9 if st["calib_merge"] > 0 else 0.0,
+                         "hbm_frac": merge_bytes / (st["calib_merge"] * 1e-6) / 1e9 / HBM_PEAK_GBS if st["calib_merge"] > 0 else 0.0},
     }
+    if not scaled:
+        out["note"] = "working set (4-8 MB) is cache resident and a step is a few short kernels: latency bound, not HBM bound"
+    return out
+
+
+def bench_decode_shaped(A, torch, model, cfg, wl, L, P=16, K=16, T=8, steps=5):
+    """The same resident model at a decode-like shape (P + K T = 144 rows, well under the ~315 flop/byte ridge):
+    one scoring pass must stream every layer's weights and the LM head from HBM once, so it is timed against the
+    HBM roofline instead of the MFMA one.  The short prefix stands in for a prefix whose keys/values are already
+    cached."""
+    from synth import make_token_ids
+    ws = torch.empty(A.atts_workspace_bytes(model, P, K, T), dtype=torch.uint8, device="cuda")
+    sc = torch.empty(K, dtype=torch.float32, device="cuda")
+    ids = [make_token_ids(cfg.vocab, P, K, T, wl.seed + 900001 + i, device="cuda") for i in range(steps + 1)]
+    A.atts_score_drafts(model, ids[0][0], ids[0][1], None, A.SCORE_MEAN_NLL, None, sc, ws)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for i in range(1, steps + 1):
+        A.atts_score_drafts(model, ids[i][0], ids[i][1], None, A.SCORE_MEAN_NLL, None, sc, ws)
+    torch.cuda.synchronize()
+    dt = (time.perf_counter() - t0) / steps
+    esz = 2 if cfg.dtype == "bf16" else 4
+    d, hd = cfg.d_model, cfg.head_dim
+    per_layer = d * (cfg.n_q_heads + 2 * cfg.n_kv_heads) * hd + cfg.n_q_heads * hd * d + 3 * d * cfg.d_ffn
+    wbytes = esz * (per_layer * L + cfg.vocab * d)
+    return {"workload": f"{wl.name} model, P={P} K={K} T={T} ({P + K * T} rows)", "steps": steps,
+            "ms_per_pass": dt * 1e3, "scored_tokens_per_s": K * T / dt,
+            "weight_bytes_per_pass": wbytes, "achieved_GBs": wbytes / dt / 1e9,
+            "hbm_frac": wbytes / dt / 1e9 / HBM_PEAK_GBS}
 
 
 def main():
@@ -278,6 +330,8 @@ def main():
     }
     if args.workload != "tiny":
         out["calibration_stage"] = bench_calibration(A, torch, np)
+        out["calibration_stage_scaled"] = bench_calibration(A, torch, np, steps=4, scaled=True)
+        out["decode_shaped"] = bench_decode_shaped(A, torch, model, cfg, wl, L)
     if not args.no_cpu_baseline:
         p0, d0 = ids[0]
         out["cpu_baseline"] = cpu_baseline(cfg, wl, w, p0.cpu().numpy(), d0.cpu().numpy(), L, min(args.cpu_layers, L))

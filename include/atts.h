@@ -195,7 +195,10 @@ int32_t atts_attention_shared_prefix(int32_t dtype, const void* qkv, void* out,
 #define ATTS_STAGE_GATHER_NORM  8   /* scoring-row gather + final norm                      */
 #define ATTS_STAGE_LMHEAD       9   /* fused LM head log-softmax-gather GEMM                */
 #define ATTS_STAGE_REDUCE      10   /* partial combine + score reduction                    */
-#define ATTS_STAGE_COUNT       11
+#define ATTS_STAGE_CALIB_SORT  11   /* atts_calibrate_online: sorting the new batch         */
+#define ATTS_STAGE_CALIB_MERGE 12   /* atts_calibrate_online: merge into the resident array */
+#define ATTS_STAGE_CLASSIFY    13   /* atts_classify_ordinal                                */
+#define ATTS_STAGE_COUNT       14
 
 /* on != 0: start recording (clears earlier records); on == 0: stop and drop the records. */
 int32_t atts_profile_enable(int32_t on);

@@ -33,7 +33,7 @@ EXPORTS = (
 )
 
 STAGES = ("embed", "norm", "gemm_qkv", "rope", "attention", "gemm_o", "gemm_gate_up", "gemm_down", "gather_norm",
-          "lmhead", "reduce")
+          "lmhead", "reduce", "calib_sort", "calib_merge", "classify")
 
 
 class AttsError(RuntimeError):

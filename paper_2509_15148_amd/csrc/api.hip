@@ -30,15 +30,33 @@ int32_t fail(int32_t code, const char* fmt, ...) {
     return code;
 }
 
-namespace {
-
 // ---- stage timing ---------------------------------------------------------------------------
+namespace {
 struct ProfRecord {
     int32_t stage;
     hipEvent_t start, stop;
 };
 bool g_prof_on = false;
 std::vector<ProfRecord> g_prof;
+}  // namespace
+
+StageTimer::StageTimer(int32_t stage, hipStream_t s) : st_(s), stage_(stage) {
+    if (!g_prof_on) return;
+    if (hipEventCreate(&start_) != hipSuccess) return;
+    if (hipEventCreate(&stop_) != hipSuccess) {
+        (void)hipEventDestroy(start_);
+        return;
+    }
+    (void)hipEventRecord(start_, st_);
+    live_ = true;
+}
+StageTimer::~StageTimer() {
+    if (!live_) return;
+    (void)hipEventRecord(stop_, st_);
+    g_prof.push_back(ProfRecord{stage_, start_, stop_});
+}
+
+namespace {
 
 void prof_clear() {
     for (auto& r : g_prof) {
@@ -47,29 +65,6 @@ void prof_clear() {
     }
     g_prof.clear();
 }
-
-// Brackets the launches issued during its lifetime with an event pair (only while enabled).
-struct StageTimer {
-    hipStream_t st;
-    bool live = false;
-    ProfRecord rec{};
-    StageTimer(int32_t stage, hipStream_t s) : st(s) {
-        if (!g_prof_on) return;
-        rec.stage = stage;
-        if (hipEventCreate(&rec.start) != hipSuccess) return;
-        if (hipEventCreate(&rec.stop) != hipSuccess) {
-            (void)hipEventDestroy(rec.start);
-            return;
-        }
-        (void)hipEventRecord(rec.start, st);
-        live = true;
-    }
-    ~StageTimer() {
-        if (!live) return;
-        (void)hipEventRecord(rec.stop, st);
-        g_prof.push_back(rec);
-    }
-};
 
 // Sub-buffers of the scoring workspace, each 256-byte aligned.
 struct Workspace {

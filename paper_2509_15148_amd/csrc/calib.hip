@@ -4,22 +4,29 @@
 // an order-preserving image of the fp32 score (-0 folded onto +0, every NaN onto key 0, below
 // -inf), so all comparisons are unsigned-integer comparisons that reproduce the IEEE ones.
 //
-//   append (Online Calibration):  keys of the new scores are sorted (bitonic block sort in LDS,
-//       then either a one-pass multi-way placement or pairwise merge passes) and merged with the
-//       resident array by a merge-path kernel into the other half of a ping-pong buffer.
-//   classify (Eq. "p-value", Eq. "prediction_set"):  one binary search per test score gives
-//       ranks = #{cal >= s}; the class is an integer comparison of ranks + 1 with
-//       r_l = floor(alpha_l (N + 1)); the quantile thresholds of Eq. "quantile" are read straight
-//       from the sorted array.
+//   append (Online Calibration):  keys of the new scores are sorted (register + LDS block sort of
+//       8192-key runs, then either a one-pass multi-way placement or pairwise merge passes) and
+//       merged with the resident array by a merge-path kernel into the other half of a ping-pong
+//       buffer.  The same pass writes four sampled copies of its output (every 16th, 256th, 4096th,
+//       65536th key), the levels of a static 16-ary search index.
+//   classify (Eq. "p-value", Eq. "prediction_set"):  ranks = #{cal >= s} by one search per test
+//       score: the coarsest index level sits in LDS, every further level costs one aligned 64-byte
+//       line.  The class is an integer comparison of ranks + 1 with r_l = floor(alpha_l (N + 1));
+//       the quantile thresholds of Eq. "quantile" are read straight from the sorted array.
 #include "common.h"
 
 #include <math.h>
 #include <new>
 
+constexpr int kIndexLevels = 4;
+
 struct atts_calib {
-    uint32_t* keys[2];   // ping-pong sorted arrays, capacity each
-    uint32_t* runs;      // sorted runs of the batch being appended
-    uint32_t* batch;     // fully sorted batch
+    uint32_t* keys[2];                  // ping-pong sorted arrays, capacity each
+    uint32_t* index[2][kIndexLevels];   // index[side][k][j] = keys[side][j * 16^(k+1)]
+    uint32_t* runs;                     // sorted runs of the batch being appended
+    uint32_t* batch;                    // fully sorted batch
+    int32_t* splits;                    // merge-path splits of one streaming merge launch
+    int64_t splits_len;
     int64_t capacity;
     int64_t n;
     int cur;
@@ -30,9 +37,10 @@ namespace {
 
 constexpr int kSortChunk = 8192;    // keys per block-sort workgroup
 constexpr int kSortThreads = 1024;
-constexpr int kMergeSeg = 2048;     // outputs per merge workgroup
 constexpr int kMergeThreads = 256;
-constexpr int kMergePer = kMergeSeg / kMergeThreads;
+constexpr int kMergeSegSmall = 2048;   // outputs per merge workgroup: cache-resident sizes (more workgroups)
+constexpr int kMergeSegLarge = 8192;   // ... and streaming sizes (the split search is amortised over more keys)
+constexpr int64_t kMergeLargeFrom = (int64_t)1 << 22;
 constexpr int kMaxMultiwayRuns = 16;
 constexpr uint32_t kPadKey = 0xFFFFFFFFu;   // above the key of +inf (0xFF800000)
 
@@ -170,29 +178,68 @@ struct MergeJob {
     uint32_t* out;       // pair y: out + 2 y run
     int64_t run;         // 0: single job (a, na, b, nb, out) as given
     int64_t n;           // pairwise mode: total elements
+    uint32_t* index[kIndexLevels];   // EMIT only: index[k][j] = out[j * 16^(k+1)]
 };
 
-__global__ __launch_bounds__(kMergeThreads) void merge_kernel(MergeJob job) {
-    const uint32_t* a = job.a;
-    const uint32_t* b = job.b;
-    uint32_t* out = job.out;
-    int64_t na = job.na, nb = job.nb;
+// LDS position of element i: one pad word per 32, so that the accesses "thread t, element t * PER + e" fall
+// into distinct banks
+__device__ __forceinline__ int lds_pad(int i) { return i + (i >> 5); }
+
+// The operands of pair y (or of the single job).  false: nothing to do.
+__device__ __forceinline__ bool merge_operands(const MergeJob& job, int64_t y, const uint32_t*& a, int64_t& na,
+                                               const uint32_t*& b, int64_t& nb, uint32_t*& out) {
+    a = job.a;
+    b = job.b;
+    out = job.out;
+    na = job.na;
+    nb = job.nb;
     if (job.run > 0) {
-        const int64_t off = 2 * (int64_t)blockIdx.y * job.run;
-        if (off >= job.n) return;
+        const int64_t off = 2 * y * job.run;
+        if (off >= job.n) return false;
         a = job.a + off;
         na = min(job.run, job.n - off);
         b = a + na;
         nb = max((int64_t)0, min(job.run, job.n - off - job.run));
         out = job.out + off;
     }
+    return true;
+}
+
+// For a streaming merge launch of (segs, pairs) workgroups: splits[y (segs + 1) + x] = elements taken from a[]
+// among the first min(x seg, total) outputs of pair y.  One thread per entry: the searches run in parallel here
+// instead of serially in front of every workgroup's loads.
+__global__ __launch_bounds__(256) void merge_split_kernel(MergeJob job, int seg, int segs, int64_t pairs,
+                                                          int32_t* __restrict__ splits) {
+    const int64_t idx = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    const int64_t y = idx / (segs + 1), x = idx % (segs + 1);
+    if (y >= pairs) return;
+    const uint32_t *a, *b;
+    uint32_t* out;
+    int64_t na, nb;
+    if (!merge_operands(job, y, a, na, b, nb, out)) return;
+    const int64_t diag = min(x * (int64_t)seg, na + nb);
+    splits[idx] = (int32_t)merge_path<int64_t>(a, na, b, nb, diag);
+}
+
+// Each workgroup produces SEG consecutive outputs.  out + segment start must be 16-byte aligned (SEG divides
+// the run length in pairwise mode).  PRESPLIT: the segment's merge-path splits come from merge_split_kernel.
+template <int SEG, bool EMIT, bool PRESPLIT>
+__global__ __launch_bounds__(kMergeThreads) void merge_kernel(MergeJob job, const int32_t* __restrict__ splits) {
+    constexpr int PER = SEG / kMergeThreads;
+    const uint32_t *a, *b;
+    uint32_t* out;
+    int64_t na, nb;
+    if (!merge_operands(job, blockIdx.y, a, na, b, nb, out)) return;
     const int64_t total = na + nb;
-    const int64_t o0 = (int64_t)blockIdx.x * kMergeSeg;
+    const int64_t o0 = (int64_t)blockIdx.x * SEG;
     if (o0 >= total) return;
-    const int64_t o1 = min(o0 + kMergeSeg, total);
+    const int64_t o1 = min(o0 + SEG, total);
 
     __shared__ int64_t split[2];
-    __shared__ uint32_t buf[kMergeSeg];
+    __shared__ uint32_t buf[SEG + SEG / 32];
+    if constexpr (PRESPLIT) {
+        if (threadIdx.x < 2) split[threadIdx.x] = splits[(int64_t)blockIdx.y * (gridDim.x + 1) + blockIdx.x + threadIdx.x];
+    } else
     // Merge-path split of both segment ends at once: threads 0..127 search the diagonal o0, threads 128..255 the
     // diagonal o1.  Each round probes 128 evenly spaced candidates of the current range in parallel (one load
     // latency per round instead of one per halving step); "a[i] <= b[diag - 1 - i]" is true below the split.
@@ -229,18 +276,74 @@ __global__ __launch_bounds__(kMergeThreads) void merge_kernel(MergeJob job) {
     const int64_t i0 = split[0], i1 = split[1];
     const int64_t j0 = o0 - i0, j1 = o1 - i1;
     const int la = (int)(i1 - i0), lb = (int)(j1 - j0);
-    for (int i = threadIdx.x; i < la; i += kMergeThreads) buf[i] = a[i0 + i];
-    for (int i = threadIdx.x; i < lb; i += kMergeThreads) buf[la + i] = b[j0 + i];
+    const int len = la + lb;
+    uint32_t k[PER];
+    // all PER loads of a thread are issued before the first is consumed
+#pragma unroll
+    for (int e = 0; e < PER; ++e) {
+        const int i = (int)threadIdx.x + e * kMergeThreads;
+        k[e] = kPadKey;
+        if (i < la) k[e] = a[i0 + i];
+        else if (i < len) k[e] = b[j0 + (i - la)];
+    }
+#pragma unroll
+    for (int e = 0; e < PER; ++e) buf[lds_pad((int)threadIdx.x + e * kMergeThreads)] = k[e];
     __syncthreads();
 
-    const int len = la + lb;
-    const int d0 = min((int)threadIdx.x * kMergePer, len);
-    const int d1 = min(d0 + kMergePer, len);
-    int ia = merge_path<int>(buf, la, buf + la, lb, d0);
-    int ib = d0 - ia;
-    for (int d = d0; d < d1; ++d) {
-        bool take_a = ib >= lb || (ia < la && buf[ia] <= buf[la + ib]);
-        out[o0 + d] = take_a ? buf[ia++] : buf[la + ib++];
+    // every thread merges PER consecutive outputs into registers
+    const int d0 = min((int)threadIdx.x * PER, len);
+    int ia, ib;
+    {
+        int lo = d0 > lb ? d0 - lb : 0, hi = d0 < la ? d0 : la;
+        while (lo < hi) {
+            const int mid = (lo + hi) >> 1;
+            if (buf[lds_pad(mid)] <= buf[lds_pad(la + d0 - 1 - mid)]) lo = mid + 1; else hi = mid;
+        }
+        ia = lo;
+        ib = d0 - lo;
+    }
+    uint32_t ka = ia < la ? buf[lds_pad(ia)] : kPadKey, kb = ib < lb ? buf[lds_pad(la + ib)] : kPadKey;
+#pragma unroll
+    for (int e = 0; e < PER; ++e) {
+        const bool take_a = ib >= lb || (ia < la && ka <= kb);
+        k[e] = take_a ? ka : kb;
+        if (take_a) {
+            ++ia;
+            ka = ia < la ? buf[lds_pad(ia)] : kPadKey;
+        } else {
+            ++ib;
+            kb = ib < lb ? buf[lds_pad(la + ib)] : kPadKey;
+        }
+    }
+    __syncthreads();
+    // through LDS again, so that the segment leaves in whole 16-byte pieces per lane
+#pragma unroll
+    for (int e = 0; e < PER; ++e) buf[lds_pad((int)threadIdx.x * PER + e)] = k[e];
+    __syncthreads();
+    uint32_t* o = out + o0;
+    for (int i = (int)threadIdx.x * 4; i < len; i += kMergeThreads * 4) {
+        if (i + 4 <= len) {
+            uint4 v;
+            v.x = buf[lds_pad(i)];
+            v.y = buf[lds_pad(i + 1)];
+            v.z = buf[lds_pad(i + 2)];
+            v.w = buf[lds_pad(i + 3)];
+            *reinterpret_cast<uint4*>(o + i) = v;
+        } else {
+            for (int r = i; r < len; ++r) o[r] = buf[lds_pad(r)];
+        }
+    }
+    if constexpr (EMIT) {
+#pragma unroll
+        for (int lvl = 0; lvl < kIndexLevels; ++lvl) {
+            const int shift = 4 * (lvl + 1);
+            if (((int64_t)1 << shift) <= SEG) {
+                for (int t = threadIdx.x; (t << shift) < len; t += kMergeThreads)
+                    job.index[lvl][(o0 >> shift) + t] = buf[lds_pad(t << shift)];
+            } else if (threadIdx.x == 0 && (o0 & (((int64_t)1 << shift) - 1)) == 0) {
+                job.index[lvl][o0 >> shift] = buf[lds_pad(0)];
+            }
+        }
     }
 }
 
@@ -250,52 +353,104 @@ struct ClassifyLevels {
     int32_t n_alpha;
 };
 
-constexpr int kTopEntries = 1024;   // LDS index: every (n / 1024 rounded up to a power of two)-th key
+constexpr int kTopEntries = 4096;   // LDS copy of the coarsest level (or of every 2^top_shift-th entry of it)
 
-__global__ __launch_bounds__(256) void classify_kernel(const uint32_t* __restrict__ keys, int64_t n,
-                                                       const float* __restrict__ test, int64_t m, ClassifyLevels lv,
-                                                       int top_shift, int32_t* __restrict__ ranks,
+struct SearchIndex {
+    const uint32_t* lvl[kIndexLevels + 1];   // lvl[0] = the sorted keys, lvl[k][j] = keys[j * 16^k]
+    int64_t len[kIndexLevels + 1];
+    int32_t top_level;                       // the level staged in LDS
+    int32_t top_shift;
+    int32_t per_thread;                      // test scores per thread
+};
+
+// t = number of entries of the next coarser level that are < x  ->  the same count for level L: the candidates
+// are the 16 entries of one aligned 64-byte line (entries past `len` do not count).
+__device__ __forceinline__ int64_t descend(const uint32_t* __restrict__ L, int64_t len, int64_t t, uint32_t x) {
+    if (t == 0) return 0;
+    const int64_t base = (t - 1) << 4;
+    const uint4* p = reinterpret_cast<const uint4*>(L + base);
+    const uint4 q0 = p[0], q1 = p[1], q2 = p[2], q3 = p[3];
+    const int valid = (int)min((int64_t)16, len - base);
+    const uint32_t v[16] = {q0.x, q0.y, q0.z, q0.w, q1.x, q1.y, q1.z, q1.w, q2.x, q2.y, q2.z, q2.w, q3.x, q3.y, q3.z, q3.w};
+    int c = 0;
+#pragma unroll
+    for (int e = 0; e < 16; ++e) c += (e < valid && v[e] < x) ? 1 : 0;
+    return base + c;
+}
+
+__global__ __launch_bounds__(256) void classify_kernel(SearchIndex ix, const float* __restrict__ test, int64_t m,
+                                                       ClassifyLevels lv, int32_t* __restrict__ ranks,
                                                        float* __restrict__ pvalues, uint8_t* __restrict__ classes,
                                                        float* __restrict__ thresholds) {
-    // top[i] = keys[i << top_shift]: the first ~10 steps of every binary search run in LDS, the rest touch a
-    // window of at most 2^top_shift keys.
     __shared__ uint32_t top[kTopEntries];
-    const int n_top = (int)((n + ((int64_t)1 << top_shift) - 1) >> top_shift);
-    for (int i = threadIdx.x; i < n_top; i += 256) top[i] = keys[(int64_t)i << top_shift];
+    const uint32_t* __restrict__ T = ix.lvl[ix.top_level];
+    const int64_t top_len = ix.len[ix.top_level], n = ix.len[0];
+    const int s = ix.top_shift;
+    const int n_top = (int)((top_len + ((int64_t)1 << s) - 1) >> s);
+    for (int i = threadIdx.x; i < n_top; i += 256) top[i] = T[(int64_t)i << s];
     __syncthreads();
-    const int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x;
     if (blockIdx.x == 0 && thresholds && (int)threadIdx.x < lv.n_alpha) {
         const int64_t kth = n + 1 - lv.r[threadIdx.x];     // 1-indexed order statistic
-        thresholds[threadIdx.x] = kth > n ? INFINITY : (kth < 1 ? -INFINITY : key_to_score(keys[kth - 1]));
+        thresholds[threadIdx.x] = kth > n ? INFINITY : (kth < 1 ? -INFINITY : key_to_score(ix.lvl[0][kth - 1]));
     }
-    if (i >= m) return;
-    const float s = test[i];
-    int64_t c = 0;
-    if (!score_is_nan(s)) {
-        const uint32_t x = score_to_key(s);
-        int lo = 0, hi = n_top;                            // t = number of index entries < x
-        while (lo < hi) {
-            const int mid = (lo + hi) >> 1;
-            if (top[mid] < x) lo = mid + 1; else hi = mid;
+    for (int j = 0; j < ix.per_thread; ++j) {
+        const int64_t i = ((int64_t)blockIdx.x * ix.per_thread + j) * 256 + threadIdx.x;
+        if (i >= m) return;
+        const float sc = test[i];
+        int64_t c = 0;
+        if (!score_is_nan(sc)) {
+            const uint32_t x = score_to_key(sc);
+            int lo = 0, hi = n_top;                            // number of staged entries < x
+            while (lo < hi) {
+                const int mid = (lo + hi) >> 1;
+                if (top[mid] < x) lo = mid + 1; else hi = mid;
+            }
+            int64_t t = lo;                                    // -> number of top-level entries < x
+            if (s > 0 && lo > 0) {
+                const int64_t w0 = ((int64_t)(lo - 1) << s) + 1;
+                const int64_t w1 = min(top_len, (int64_t)lo << s);
+                t = w0 + lower_bound(T + w0, w1 - w0, x);
+            }
+#pragma unroll
+            for (int l = kIndexLevels - 1; l >= 0; --l)
+                if (l < ix.top_level) t = descend(ix.lvl[l], ix.len[l], t, x);
+            c = n - t;
         }
-        int64_t lb = 0;
-        if (lo > 0) {                                      // keys[(lo - 1) << shift] < x <= keys[lo << shift]
-            const int64_t w0 = ((int64_t)(lo - 1) << top_shift) + 1;
-            const int64_t w1 = min(n, (int64_t)lo << top_shift);
-            lb = w0 + lower_bound(keys + w0, w1 - w0, x);
-        }
-        c = n - lb;
+        ranks[i] = (int32_t)c;
+        if (pvalues) pvalues[i] = (float)((double)(c + 1) / (double)(n + 1));
+        int cls = 0;
+        for (int l = 0; l < lv.n_alpha; ++l) cls += (c + 1 <= lv.r[l]) ? 1 : 0;
+        classes[i] = (uint8_t)cls;
     }
-    ranks[i] = (int32_t)c;
-    if (pvalues) pvalues[i] = (float)((double)(c + 1) / (double)(n + 1));
-    int cls = 0;
-    for (int l = 0; l < lv.n_alpha; ++l) cls += (c + 1 <= lv.r[l]) ? 1 : 0;
-    classes[i] = (uint8_t)cls;
 }
 
 __global__ void export_kernel(const uint32_t* __restrict__ keys, int64_t n, float* __restrict__ out) {
     const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
     if (i < n) out[i] = key_to_score(keys[i]);
+}
+
+// One merge launch: `pairs` independent merges of at most `pair_total` outputs each.
+template <bool EMIT>
+int32_t launch_merge(atts_calib* c, const MergeJob& job, int64_t pair_total, int64_t pairs, bool streaming,
+                     hipStream_t stream) {
+    if (streaming) {
+        const int64_t segs = ceil_div(pair_total, kMergeSegLarge);
+        const int64_t n_splits = pairs * (segs + 1);
+        dim3 grid((unsigned)segs, (unsigned)pairs);
+        if (n_splits <= c->splits_len) {
+            hipLaunchKernelGGL(merge_split_kernel, dim3((unsigned)ceil_div(n_splits, 256)), dim3(256), 0, stream, job,
+                               kMergeSegLarge, (int)segs, pairs, c->splits);
+            ATTS_LAUNCH_CHECK("merge_split_kernel");
+            hipLaunchKernelGGL((merge_kernel<kMergeSegLarge, EMIT, true>), grid, dim3(kMergeThreads), 0, stream, job, c->splits);
+        } else {
+            hipLaunchKernelGGL((merge_kernel<kMergeSegLarge, EMIT, false>), grid, dim3(kMergeThreads), 0, stream, job, nullptr);
+        }
+    } else {
+        dim3 grid((unsigned)ceil_div(pair_total, kMergeSegSmall), (unsigned)pairs);
+        hipLaunchKernelGGL((merge_kernel<kMergeSegSmall, EMIT, false>), grid, dim3(kMergeThreads), 0, stream, job, nullptr);
+    }
+    ATTS_LAUNCH_CHECK("merge_kernel");
+    return ATTS_OK;
 }
 
 }  // namespace
@@ -315,18 +470,34 @@ int32_t atts_calib_create(int64_t capacity, atts_calib** out) {
     c->capacity = capacity;
     c->n = 0;
     c->cur = 0;
-    // sorted runs are padded to whole chunks only in LDS, never in memory
-    uint32_t** bufs[4] = {&c->keys[0], &c->keys[1], &c->runs, &c->batch};
-    for (int i = 0; i < 4; ++i) *bufs[i] = nullptr;
-    for (int i = 0; i < 4; ++i) {
-        hipError_t e = hipMalloc(reinterpret_cast<void**>(bufs[i]), (size_t)capacity * sizeof(uint32_t));
+    // Every array is rounded up to whole 64-byte lines plus one: the index search reads whole lines (entries
+    // past the fill are masked, not avoided).  Sorted runs are padded to whole chunks only in LDS.
+    uint32_t** bufs[4 + 2 * kIndexLevels] = {&c->keys[0], &c->keys[1], &c->runs, &c->batch};
+    int64_t sizes[4 + 2 * kIndexLevels];
+    for (int i = 0; i < 4; ++i) sizes[i] = capacity;
+    for (int side = 0; side < 2; ++side)
+        for (int k = 0; k < kIndexLevels; ++k) {
+            bufs[4 + side * kIndexLevels + k] = &c->index[side][k];
+            sizes[4 + side * kIndexLevels + k] = ceil_div(capacity, (int64_t)1 << (4 * (k + 1)));
+        }
+    constexpr int n_bufs = 4 + 2 * kIndexLevels;
+    for (int i = 0; i < n_bufs; ++i) *bufs[i] = nullptr;
+    for (int i = 0; i < n_bufs; ++i) {
+        const size_t bytes = ((size_t)ceil_div(sizes[i], 16) * 16 + 16) * sizeof(uint32_t);
+        hipError_t e = hipMalloc(reinterpret_cast<void**>(bufs[i]), bytes);
         if (e != hipSuccess) {
-            for (int j = 0; j < 4; ++j)
+            for (int j = 0; j < n_bufs; ++j)
                 if (*bufs[j]) (void)hipFree(*bufs[j]);
             delete c;
-            return fail(ATTS_ERR_HIP, "atts_calib_create: hipMalloc of %lld keys failed: %s", (long long)capacity,
-                        hipGetErrorString(e));
+            return fail(ATTS_ERR_HIP, "atts_calib_create: hipMalloc of %zu bytes failed: %s", bytes, hipGetErrorString(e));
         }
+    }
+    c->splits_len = capacity / (kMergeSegLarge / 2) + 64;
+    hipError_t e = hipMalloc(reinterpret_cast<void**>(&c->splits), (size_t)c->splits_len * sizeof(int32_t));
+    if (e != hipSuccess) {
+        for (int j = 0; j < n_bufs; ++j) (void)hipFree(*bufs[j]);
+        delete c;
+        return fail(ATTS_ERR_HIP, "atts_calib_create: hipMalloc of the split table failed: %s", hipGetErrorString(e));
     }
     *out = c;
     return ATTS_OK;
@@ -334,8 +505,11 @@ int32_t atts_calib_create(int64_t capacity, atts_calib** out) {
 
 int32_t atts_calib_destroy(atts_calib* c) {
     if (!c) return ATTS_OK;
+    (void)hipFree(c->splits);
     (void)hipFree(c->keys[0]);
     (void)hipFree(c->keys[1]);
+    for (int side = 0; side < 2; ++side)
+        for (int k = 0; k < kIndexLevels; ++k) (void)hipFree(c->index[side][k]);
     (void)hipFree(c->runs);
     (void)hipFree(c->batch);
     delete c;
@@ -366,11 +540,13 @@ int32_t atts_calibrate_online(atts_calib* c, const float* new_scores, int64_t n_
 
     // 1. keys of the new scores, sorted in runs of kSortChunk
     const int64_t n_runs = ceil_div(n_new, kSortChunk);
+    const uint32_t* sorted = c->runs;
+    {
+    StageTimer t_(ATTS_STAGE_CALIB_SORT, stream);
     hipLaunchKernelGGL(block_sort_kernel, dim3((unsigned)n_runs), dim3(kSortThreads), 0, stream, new_scores, n_new, c->runs);
     ATTS_LAUNCH_CHECK("block_sort_kernel");
 
     // 2. one sorted batch
-    const uint32_t* sorted = c->runs;
     if (n_runs > 1 && n_runs <= kMaxMultiwayRuns) {
         hipLaunchKernelGGL(multiway_place_kernel, dim3((unsigned)ceil_div(n_new, 256)), dim3(256), 0, stream, c->runs, n_new,
                            c->batch);
@@ -380,21 +556,25 @@ int32_t atts_calibrate_online(atts_calib* c, const float* new_scores, int64_t n_
         uint32_t* src = c->runs;
         uint32_t* dst = c->batch;
         for (int64_t run = kSortChunk; run < n_new; run *= 2) {
-            MergeJob job{src, 0, nullptr, 0, dst, run, n_new};
-            dim3 grid((unsigned)ceil_div(2 * run, kMergeSeg), (unsigned)ceil_div(n_new, 2 * run));
-            hipLaunchKernelGGL(merge_kernel, grid, dim3(kMergeThreads), 0, stream, job);
-            ATTS_LAUNCH_CHECK("merge_kernel (pairwise)");
+            MergeJob job{src, 0, nullptr, 0, dst, run, n_new, {}};
+            int32_t rc = launch_merge<false>(c, job, 2 * run, ceil_div(n_new, 2 * run), n_new >= kMergeLargeFrom, stream);
+            if (rc != ATTS_OK) return rc;
             uint32_t* t = src;
             src = dst;
             dst = t;
         }
         sorted = src;
     }
+    }
 
-    // 3. merge with the resident array into the other half of the ping-pong buffer
-    MergeJob job{c->keys[c->cur], c->n, sorted, n_new, c->keys[c->cur ^ 1], 0, 0};
-    hipLaunchKernelGGL(merge_kernel, dim3((unsigned)ceil_div(c->n + n_new, kMergeSeg)), dim3(kMergeThreads), 0, stream, job);
-    ATTS_LAUNCH_CHECK("merge_kernel");
+    // 3. merge with the resident array into the other half of the ping-pong buffer (+ its search index)
+    const int to = c->cur ^ 1;
+    MergeJob job{c->keys[c->cur], c->n, sorted, n_new, c->keys[to], 0, 0, {}};
+    for (int k = 0; k < kIndexLevels; ++k) job.index[k] = c->index[to][k];
+    const int64_t total = c->n + n_new;
+    StageTimer t_(ATTS_STAGE_CALIB_MERGE, stream);
+    int32_t rc = launch_merge<true>(c, job, total, 1, total >= kMergeLargeFrom, stream);
+    if (rc != ATTS_OK) return rc;
     c->cur ^= 1;
     c->n += n_new;
     return ATTS_OK;
@@ -421,11 +601,24 @@ int32_t atts_classify_ordinal(const atts_calib* c, const float* test_scores, int
     for (int l = 0; l < ATTS_MAX_ALPHAS; ++l) lv.r[l] = 0;
     for (int l = 0; l < n_alpha; ++l) lv.r[l] = (int64_t)floor(alphas[l] * (double)(c->n + 1));
     if (M == 0 && !thresholds) return ATTS_OK;
-    const unsigned blocks = (unsigned)(M > 0 ? ceil_div(M, 256) : 1);
-    int top_shift = 0;
-    while (((c->n + ((int64_t)1 << top_shift) - 1) >> top_shift) > kTopEntries) ++top_shift;
-    hipLaunchKernelGGL(classify_kernel, dim3(blocks), dim3(256), 0, static_cast<hipStream_t>(hip_stream), c->keys[c->cur],
-                       c->n, test_scores, M, lv, top_shift, ranks, pvalues, classes, thresholds);
+    SearchIndex ix;
+    ix.lvl[0] = c->keys[c->cur];
+    ix.len[0] = c->n;
+    for (int k = 1; k <= kIndexLevels; ++k) {
+        ix.lvl[k] = c->index[c->cur][k - 1];
+        ix.len[k] = ceil_div(c->n, (int64_t)1 << (4 * k));
+    }
+    ix.top_level = 0;
+    while (ix.top_level < kIndexLevels && ix.len[ix.top_level] > kTopEntries) ++ix.top_level;
+    ix.top_shift = 0;
+    while (ceil_div(ix.len[ix.top_level], (int64_t)1 << ix.top_shift) > kTopEntries) ++ix.top_shift;
+    // enough workgroups to fill the chip, few enough that staging the top level stays a small part of the work
+    int64_t per = M / ((int64_t)256 * 2048);
+    ix.per_thread = (int32_t)(per < 1 ? 1 : (per > 16 ? 16 : per));
+    const unsigned blocks = (unsigned)(M > 0 ? ceil_div(M, (int64_t)256 * ix.per_thread) : 1);
+    StageTimer t_(ATTS_STAGE_CLASSIFY, static_cast<hipStream_t>(hip_stream));
+    hipLaunchKernelGGL(classify_kernel, dim3(blocks), dim3(256), 0, static_cast<hipStream_t>(hip_stream), ix, test_scores, M,
+                       lv, ranks, pvalues, classes, thresholds);
     ATTS_LAUNCH_CHECK("classify_kernel");
     return ATTS_OK;
 }

@@ -36,6 +36,20 @@ int32_t fail(int32_t code, const char* fmt, ...) __attribute__((format(printf, 2
             return ::atts::fail(ATTS_ERR_HIP, "launch of %s failed: %s", name, hipGetErrorString(e__)); \
     } while (0)
 
+// Brackets the launches issued during its lifetime with an event pair on `stream`, while atts_profile_enable is on.
+class StageTimer {
+public:
+    StageTimer(int32_t stage, hipStream_t stream);
+    ~StageTimer();
+    StageTimer(const StageTimer&) = delete;
+    StageTimer& operator=(const StageTimer&) = delete;
+private:
+    hipStream_t st_;
+    int32_t stage_;
+    hipEvent_t start_{}, stop_{};
+    bool live_ = false;
+};
+
 inline size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
 inline int64_t ceil_div(int64_t a, int64_t b) { return (a + b - 1) / b; }
 inline size_t dtype_size(int32_t dtype) { return dtype == ATTS_DTYPE_F32 ? 4 : 2; }

@@ -129,3 +129,63 @@ def test_calibration_only_workload_full_size():
         counts += np.bincount(cls, minlength=3)
     frac = counts / counts.sum()
     assert abs(frac[2] - 0.05) < 0.005 and abs(frac[1] + frac[2] - 0.2) < 0.01     # take-over rate ~ alpha
+
+
+def test_streaming_merge_sizes():
+    """Batches and totals above 2^22 keys take the streaming merge (8192-key segments, splits found by a
+    separate kernel) in both its pairwise and its final form; smaller appends into the large set, ragged
+    lengths and ties included.  The state must equal the sorted union after every append."""
+    import paper_2509_15148_amd as A
+    sizes = ((1 << 22) + 12345, 5_000_000, 70_001, 17, 8192)
+    announce("calib streaming merge", sizes)
+    total = sum(sizes)
+    allv = np.round(lognormal_scores(total, seed=4242), 4)
+    c = A.Calib(total)
+    test = np.concatenate([lognormal_scores(4000, seed=78), allv[:96], np.array([0.0, np.inf, -1.0, np.nan], np.float32)])
+    lo = 0
+    for s in sizes:
+        A.atts_calibrate_online(c, dev(allv[lo:lo + s]))
+        lo += s
+        out = torch.empty(lo, dtype=torch.float32, device="cuda")
+        A.atts_calib_export(c, out)
+        assert np.array_equal(out.cpu().numpy(), np.sort(allv[:lo])), s
+        _check_against_oracle(A, c, allv[:lo].astype(np.float64), test, [0.05, 0.2], brute=False)
+    idx = np.arange(0, len(test), 64)
+    ranks = _classify(A, c, test[idx], [0.05, 0.2])[0]
+    assert np.array_equal(ranks.astype(np.int64), O.rank_counts(allv.astype(np.float64), test[idx]))
+
+
+def test_out_of_cache_size_sampled():
+    """2^28 resident scores + one append of 2^24 (the out-of-cache variant that bench.py times): the coarsest
+    index level no longer fits LDS whole, so the strided top level + window search is exercised.  Ranks of
+    sampled test scores against the oracle's double sum; the exported state must be ascending and keep every
+    score (sum of ranks of the extreme probes)."""
+    import paper_2509_15148_amd as A
+    n0, n1 = 1 << 28, 1 << 24
+    announce("calib out-of-cache", n0, n1)
+    g = torch.Generator(device="cuda").manual_seed(99)
+    cal0 = torch.randn(n0, device="cuda", generator=g).exp_()
+    cal1 = torch.randn(n1, device="cuda", generator=g).exp_()
+    c = A.Calib(n0 + n1)
+    A.atts_calibrate_online(c, cal0)
+    A.atts_calibrate_online(c, cal1)
+    assert A.atts_calib_size(c) == n0 + n1
+    out = torch.empty(n0 + n1, dtype=torch.float32, device="cuda")
+    A.atts_calib_export(c, out)
+    assert bool((out[1:] >= out[:-1]).all())
+    del out
+    host = np.concatenate([cal0.cpu().numpy(), cal1.cpu().numpy()])
+    del cal0, cal1
+    test = np.concatenate([lognormal_scores(60, seed=5), host[:3], np.array([0.0, 1e30], np.float32)]).astype(np.float32)
+    ranks, cls, p, q = _classify(A, c, test, [0.05, 0.2])
+    n = len(host)
+    want = O.rank_counts(host.astype(np.float64), test)
+    assert np.array_equal(ranks.astype(np.int64), want)
+    r = O.reject_ranks([0.05, 0.2], n)
+    assert np.array_equal(cls, O.classify(want, r))
+    assert np.array_equal(p, O.p_values(want, n).astype(np.float32))
+    assert ranks[-2] == n and ranks[-1] == 0
+    # thresholds: the (n + 1 - r)-th smallest, by partition instead of a full sort
+    for l in range(2):
+        kth = n + 1 - int(r[l])
+        assert q[l] == np.partition(host, kth - 1)[kth - 1]
