@@ -151,7 +151,10 @@ __global__ __launch_bounds__(kSortThreads) void block_sort_kernel(const float* _
 }
 
 // ---- multi-way placement: final position of every element of <= kMaxMultiwayRuns sorted runs -----
-// Stable: among equal keys, elements of earlier runs come first.
+// Stable: among equal keys, elements of earlier runs come first.  The searches into the other runs are taken
+// eight at a time in lock step, so that their (dependent, cache-latency bound) probes overlap.
+constexpr int kPlaceGroup = 8;
+
 __global__ __launch_bounds__(256) void multiway_place_kernel(const uint32_t* __restrict__ runs, int64_t n,
                                                              uint32_t* __restrict__ out) {
     const int64_t e = (int64_t)blockIdx.x * 256 + threadIdx.x;
@@ -159,12 +162,33 @@ __global__ __launch_bounds__(256) void multiway_place_kernel(const uint32_t* __r
     const uint32_t x = runs[e];
     const int my_run = (int)(e / kSortChunk);
     const int n_runs = (int)((n + kSortChunk - 1) / kSortChunk);
-    int64_t pos = e % kSortChunk;
-    for (int q = 0; q < n_runs; ++q) {
-        if (q == my_run) continue;
-        const int64_t off = (int64_t)q * kSortChunk;
-        const int64_t len = min((int64_t)kSortChunk, n - off);
-        pos += q < my_run ? upper_bound(runs + off, len, x) : lower_bound(runs + off, len, x);
+    const int last_len = (int)(n - (int64_t)(n_runs - 1) * kSortChunk);
+    int pos = (int)(e % kSortChunk);
+    for (int q0 = 0; q0 < n_runs; q0 += kPlaceGroup) {
+        // cnt[j] = number of keys of run q0 + j that go before x: keys <= x for an earlier run, < x for a later one
+        int cnt[kPlaceGroup] = {};
+        int len[kPlaceGroup];
+        uint32_t bias[kPlaceGroup];                                  // "key < x + bias" covers both comparisons (x < 2^32 - 1)
+#pragma unroll
+        for (int j = 0; j < kPlaceGroup; ++j) {
+            const int q = q0 + j;
+            len[j] = (q >= n_runs || q == my_run) ? 0 : (q == n_runs - 1 ? last_len : kSortChunk);
+            bias[j] = q < my_run ? 1u : 0u;
+        }
+        for (int step = kSortChunk; step > 0; step >>= 1) {
+            uint32_t v[kPlaceGroup];
+#pragma unroll
+            for (int j = 0; j < kPlaceGroup; ++j) {                   // unconditional loads (clamped), so that they overlap
+                const int probe = cnt[j] + step;
+                const int64_t at = probe <= len[j] ? (int64_t)(q0 + j) * kSortChunk + probe - 1 : e;
+                v[j] = runs[at];
+            }
+#pragma unroll
+            for (int j = 0; j < kPlaceGroup; ++j)
+                if (cnt[j] + step <= len[j] && v[j] < x + bias[j]) cnt[j] += step;
+        }
+#pragma unroll
+        for (int j = 0; j < kPlaceGroup; ++j) pos += cnt[j];
     }
     out[pos] = x;
 }
