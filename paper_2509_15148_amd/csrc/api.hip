@@ -73,9 +73,14 @@ struct Workspace {
     int32_t n_part;
 };
 
+// GEMM inputs of the bf16 path are allocated in whole 256-row tiles: the aligned kernel then serves every row
+// count (it reads the pad rows, whatever they hold, and drops their results).
+bool pads_rows(const atts_model_desc& d) { return d.dtype == ATTS_DTYPE_BF16; }
+
 Workspace carve(const atts_model_desc& d, ScoreShape s) {
     const size_t es = dtype_size(d.dtype);
     const size_t R = (size_t)s.R(), B = (size_t)s.B();
+    const size_t Ra = pads_rows(d) ? align_up(R, 256) : R, Ba = pads_rows(d) ? align_up(B, 256) : B;
     Workspace w{};
     size_t off = 0;
     auto take = [&](size_t bytes) {
@@ -84,17 +89,17 @@ Workspace carve(const atts_model_desc& d, ScoreShape s) {
         return at;
     };
     w.h = take(R * d.d_model * sizeof(float));
-    w.xn = take(R * d.d_model * es);
+    w.xn = take(Ra * d.d_model * es);
     w.qkv = take(R * (size_t)(d.n_q_heads + 2 * d.n_kv_heads) * d.head_dim * es);
     w.ldv = (int64_t)align_up(R, 64);
     w.vt = take(attention_uses_vt(d.dtype, d.head_dim) ? (size_t)d.n_kv_heads * d.head_dim * w.ldv * es : 0);
-    w.ao = take(R * (size_t)d.n_q_heads * d.head_dim * es);
-    w.act = take(R * (size_t)d.d_ffn * es);
+    w.ao = take(Ra * (size_t)d.n_q_heads * d.head_dim * es);
+    w.act = take(Ra * (size_t)d.d_ffn * es);
     w.rope = take(R * (size_t)(d.head_dim / 2) * sizeof(float2));
-    w.xs = take(B * d.d_model * es);
+    w.xs = take(Ba * d.d_model * es);
     w.targets = take(B * sizeof(int32_t));
     w.valid = take(B);
-    w.n_part = lmhead_num_partials(d.dtype, s.B(), d.vocab);
+    w.n_part = lmhead_num_partials(d.dtype, s.B(), d.vocab, d.d_model, pads_rows(d));
     w.partials = take(B * (size_t)w.n_part * sizeof(float2));
     w.zt = take(B * sizeof(float));
     w.lp = take(B * sizeof(float));
@@ -227,12 +232,15 @@ int32_t atts_score_drafts(const atts_model* m, const int32_t* prefix_ids, int32_
     const int R = s.R(), B = s.B();
     const int qd = d.n_q_heads * d.head_dim;
     const int qkv_out = (d.n_q_heads + 2 * d.n_kv_heads) * d.head_dim;
-    const bool fuse_rope = vt != nullptr && ws.ldv == R && qkv_rope_fusable(d.dtype, R, qkv_out, d.d_model, d.head_dim);
+    const bool padded = pads_rows(d);
+    const bool fuse_rope = vt != nullptr && qkv_rope_fusable(d.dtype, R, qkv_out, d.d_model, d.head_dim, padded);
 
     {
         StageTimer t_(ATTS_STAGE_EMBED, st);
         ATTS_TRY(launch_embed(d.dtype, m->tok_embed, d.vocab, d.d_model, prefix_ids, draft_ids, draft_lens, s, h, m->err_flag, st));
         ATTS_TRY(launch_rope_table(rope, s, d.head_dim, d.rope_theta, st));
+        // the fused QKV epilogue writes only the R real columns of V^T
+        if (fuse_rope) ATTS_TRY(launch_zero_vt_tail(d.dtype, vt, (int64_t)d.n_kv_heads * d.head_dim, R, ws.ldv, st));
     }
     for (int l = 0; l < d.n_layers; ++l) {
         {
@@ -241,7 +249,7 @@ int32_t atts_score_drafts(const atts_model* m, const int32_t* prefix_ids, int32_
         }
         GemmArgs g{};
         g.a = xn; g.w = m->wqkv[l]; g.out = qkv; g.M = R; g.N = qkv_out; g.Kd = d.d_model;
-        g.lda = d.d_model; g.ldw = d.d_model; g.ldc = qkv_out;
+        g.lda = d.d_model; g.ldw = d.d_model; g.ldc = qkv_out; g.a_rows_padded = padded;
         if (fuse_rope) {
             // QKV projection with RoPE and the V transpose applied to the accumulators
             g.rope = rope; g.vt = vt; g.ldv = ws.ldv; g.n_rot_heads = d.n_q_heads + d.n_kv_heads;
@@ -261,7 +269,7 @@ int32_t atts_score_drafts(const atts_model* m, const int32_t* prefix_ids, int32_
         }
         g = GemmArgs{};
         g.a = ao; g.w = m->wo[l]; g.out = h; g.M = R; g.N = d.d_model; g.Kd = qd;
-        g.lda = qd; g.ldw = qd; g.ldc = d.d_model;
+        g.lda = qd; g.ldw = qd; g.ldc = d.d_model; g.a_rows_padded = padded;
         {
             StageTimer t_(ATTS_STAGE_GEMM_O, st);
             ATTS_TRY(launch_gemm(d.dtype, EPI_RESID_F32, g, st));
@@ -272,14 +280,14 @@ int32_t atts_score_drafts(const atts_model* m, const int32_t* prefix_ids, int32_
         }
         g = GemmArgs{};
         g.a = xn; g.w = m->w_gate_up[l]; g.out = act; g.M = R; g.N = d.d_ffn; g.Kd = d.d_model;
-        g.lda = d.d_model; g.ldw = d.d_model; g.ldc = d.d_ffn;
+        g.lda = d.d_model; g.ldw = d.d_model; g.ldc = d.d_ffn; g.a_rows_padded = padded;
         {
             StageTimer t_(ATTS_STAGE_GEMM_GATE_UP, st);
             ATTS_TRY(launch_gemm(d.dtype, EPI_SWIGLU, g, st));
         }
         g = GemmArgs{};
         g.a = act; g.w = m->w_down[l]; g.out = h; g.M = R; g.N = d.d_model; g.Kd = d.d_ffn;
-        g.lda = d.d_ffn; g.ldw = d.d_ffn; g.ldc = d.d_model;
+        g.lda = d.d_ffn; g.ldw = d.d_ffn; g.ldc = d.d_model; g.a_rows_padded = padded;
         {
             StageTimer t_(ATTS_STAGE_GEMM_DOWN, st);
             ATTS_TRY(launch_gemm(d.dtype, EPI_RESID_F32, g, st));
@@ -292,7 +300,7 @@ int32_t atts_score_drafts(const atts_model* m, const int32_t* prefix_ids, int32_
     }
     GemmArgs g{};
     g.a = xs; g.w = m->lm_head; g.out = nullptr; g.M = B; g.N = d.vocab; g.Kd = d.d_model;
-    g.lda = d.d_model; g.ldw = d.d_model; g.ldc = 0;
+    g.lda = d.d_model; g.ldw = d.d_model; g.ldc = 0; g.a_rows_padded = padded;
     g.targets = targets; g.partials = partials; g.target_logit = zt; g.n_part = ws.n_part;
     {
         StageTimer t_(ATTS_STAGE_LMHEAD, st);
@@ -345,8 +353,8 @@ int32_t atts_profile_read(int32_t stage, double* total_ms, int64_t* launches) {
 
 int32_t atts_lmhead_workspace_bytes(int32_t B, int32_t V, size_t* out_bytes) {
     if (!out_bytes || B < 1 || V < 1) return fail(ATTS_ERR_INVALID_ARG, "atts_lmhead_workspace_bytes: bad argument");
-    // partial count does not depend on dtype
-    *out_bytes = align_up((size_t)B * lmhead_num_partials(ATTS_DTYPE_BF16, B, V) * sizeof(float2), 256) + align_up((size_t)B * sizeof(float), 256);
+    // sized for the finest column split any dtype / inner dimension takes
+    *out_bytes = align_up((size_t)B * lmhead_max_partials(V) * sizeof(float2), 256) + align_up((size_t)B * sizeof(float), 256);
     return ATTS_OK;
 }
 
@@ -359,9 +367,9 @@ int32_t atts_lmhead_logprobs(int32_t dtype, const void* x, const void* w, const 
     ATTS_TRY(atts_lmhead_workspace_bytes(B, V, &need));
     if (!workspace || ((uintptr_t)workspace & 255) || workspace_bytes < need)
         return fail(ATTS_ERR_WORKSPACE, "atts_lmhead_logprobs: workspace NULL, misaligned or smaller than %zu bytes", need);
-    const int n_part = lmhead_num_partials(dtype, B, V);
+    const int n_part = lmhead_num_partials(dtype, B, V, d, false);
     float2* partials = static_cast<float2*>(workspace);
-    float* zt = reinterpret_cast<float*>(static_cast<char*>(workspace) + align_up((size_t)B * n_part * sizeof(float2), 256));
+    float* zt = reinterpret_cast<float*>(static_cast<char*>(workspace) + align_up((size_t)B * lmhead_max_partials(V) * sizeof(float2), 256));
     GemmArgs g{};
     g.a = x; g.w = w; g.M = B; g.N = V; g.Kd = d; g.lda = d; g.ldw = d;
     g.targets = targets; g.partials = partials; g.target_logit = zt; g.n_part = n_part;

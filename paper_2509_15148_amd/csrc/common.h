@@ -98,11 +98,12 @@ struct GemmArgs {
     void* out;           // see GemmEpilogue
     int32_t M, N, Kd;
     int64_t lda, ldw, ldc;
+    bool a_rows_padded;  // rows M .. next multiple of 256 of `a` are readable (any values; their results are dropped)
     // EPI_LMHEAD only:
     const int32_t* targets;  // [M] target column per row
     float2* partials;        // [M, n_part] (running max, sum of exp) per column slab
     float* target_logit;     // [M]
-    int32_t n_part;          // number of column slabs = lmhead_num_partials(N)
+    int32_t n_part;          // number of column slabs = lmhead_num_partials(...) of this call
     // EPI_QKV_ROPE only:
     const float2* rope;      // [M, 64] (cos, sin) per row and rotation pair
     void* vt;                // [n_kv, 128, ldv] transposed V
@@ -110,10 +111,15 @@ struct GemmArgs {
     int32_t n_rot_heads;     // n_q + n_kv: heads (of 128 columns) that are rotated; the rest are V heads
 };
 
-int32_t lmhead_num_partials(int32_t dtype, int32_t M, int32_t N);
+// Column slabs (partials per row) the LM-head epilogue of this call writes; lmhead_max_partials bounds it for any
+// dtype / Kd / padding (workspace sizing).
+int32_t lmhead_num_partials(int32_t dtype, int32_t M, int32_t N, int32_t Kd, bool a_rows_padded);
+int32_t lmhead_max_partials(int32_t N);
 int32_t launch_gemm(int32_t dtype, GemmEpilogue epi, const GemmArgs& g, hipStream_t stream);
 // true if the EPI_QKV_ROPE epilogue can serve this QKV projection (else: EPI_STORE_ACT + launch_rope_split)
-bool qkv_rope_fusable(int32_t dtype, int32_t M, int32_t N, int32_t Kd, int32_t head_dim);
+bool qkv_rope_fusable(int32_t dtype, int32_t M, int32_t N, int32_t Kd, int32_t head_dim, bool a_rows_padded);
+// vt [rows, ldv]: zero columns [R, ldv) of every row (the attention kernel reads whole 64-key tiles of V^T).
+int32_t launch_zero_vt_tail(int32_t dtype, void* vt, int64_t rows, int32_t R, int64_t ldv, hipStream_t stream);
 
 // lp[b] = target_logit[b] - logsumexp over the n_part partials of row b; rows with valid[b] == 0
 // (or b beyond) get 0.  valid may be NULL.

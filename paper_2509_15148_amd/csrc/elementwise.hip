@@ -166,6 +166,15 @@ __global__ __launch_bounds__(256) void transpose_v_kernel(const T* __restrict__ 
     }
 }
 
+// Zero columns [R, ldv) of every row of V^T (for a producer that writes only the R real columns).
+template <typename T>
+__global__ __launch_bounds__(256) void zero_vt_tail_kernel(T* __restrict__ vt, int64_t rows, int R, int64_t ldv) {
+    const int tail = (int)(ldv - R);
+    const int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    if (i >= rows * tail) return;
+    vt[(i / tail) * ldv + R + (i % tail)] = from_f32<T>(0.f);
+}
+
 // ---- S6: gather the scoring rows, final RMSNorm, targets -----------------------------------------
 // Scoring row b = k T + t reads the hidden state that predicts y^k_t: the last prefix row for
 // t = 0, else the row of y^k_{t-1}.
@@ -250,6 +259,16 @@ int32_t launch_transpose_v(int32_t dtype, const void* qkv, int32_t R, int32_t nq
     DISPATCH_T(dtype, hipLaunchKernelGGL(transpose_v_kernel<T>, grid, dim3(256), 0, stream, (const T*)qkv, R, ld,
                                          (nq + nkv) * hd, hd, (T*)vt, ldv);)
     ATTS_LAUNCH_CHECK("transpose_v_kernel");
+    return ATTS_OK;
+}
+
+int32_t launch_zero_vt_tail(int32_t dtype, void* vt, int64_t rows, int32_t R, int64_t ldv, hipStream_t stream) {
+    const int tail = (int)(ldv - R);
+    if (tail <= 0 || rows <= 0) return ATTS_OK;
+    const int64_t total = rows * tail;
+    DISPATCH_T(dtype, hipLaunchKernelGGL(zero_vt_tail_kernel<T>, dim3((unsigned)ceil_div(total, 256)), dim3(256), 0, stream,
+                                         (T*)vt, rows, R, ldv);)
+    ATTS_LAUNCH_CHECK("zero_vt_tail_kernel");
     return ATTS_OK;
 }
 

@@ -83,6 +83,8 @@ struct GemmDims {
     int32_t n_part, nt_m, nt_n;
     int64_t ldv;            // EPI_QKV_ROPE: row pitch of the transposed V
     int32_t n_rot_heads;    // EPI_QKV_ROPE: heads (128 columns each) that get rotated; later heads are V
+    int32_t k_slices;       // fast path, EPI_RESID_F32: > 1 = the K range is split over this many workgroups per tile,
+                            // which add their partial sums to the output with atomics
 };
 
 // Epilogue shared by both kernels.  acc[i][j][v] is element (row, col) of the tile with
@@ -111,7 +113,10 @@ __device__ __forceinline__ void gemm_epilogue(f32x16 (&acc)[MI][NI], int m0, int
                     int64_t idx = (int64_t)row * g.ldc + col;
                     if (EPI == EPI_STORE_ACT) reinterpret_cast<T*>(g_out)[idx] = from_f32<T>(acc[i][j][v]);
                     if (EPI == EPI_STORE_F32) reinterpret_cast<float*>(g_out)[idx] = acc[i][j][v];
-                    if (EPI == EPI_RESID_F32) reinterpret_cast<float*>(g_out)[idx] += acc[i][j][v];
+                    if (EPI == EPI_RESID_F32) {
+                        if (g.k_slices > 1) unsafeAtomicAdd(reinterpret_cast<float*>(g_out) + idx, acc[i][j][v]);
+                        else reinterpret_cast<float*>(g_out)[idx] += acc[i][j][v];
+                    }
                 }
             }
     } else if constexpr (EPI == EPI_SWIGLU) {
@@ -144,6 +149,7 @@ __device__ __forceinline__ void gemm_epilogue(f32x16 (&acc)[MI][NI], int m0, int
 #pragma unroll
                 for (int v = 0; v < 16; ++v) {
                     const int row = row_base + 32 * i + 8 * (v >> 2) + (v & 3);
+                    if (row >= g.M) continue;
                     T* orow = reinterpret_cast<T*>(g_out) + (int64_t)row * g.ldc + col0 + l32;
                     const float2* crow = g_rope + (int64_t)row * 64 + l32;
 #pragma unroll
@@ -162,13 +168,21 @@ __device__ __forceinline__ void gemm_epilogue(f32x16 (&acc)[MI][NI], int m0, int
 #pragma unroll
                 for (int a = 0; a < 4; ++a) {
                     const int row0 = row_base + 32 * i + 8 * a;
+                    if (row0 >= g.M) continue;
 #pragma unroll
                     for (int j = 0; j < NI; ++j) {
                         typedef T T4 __attribute__((ext_vector_type(4)));
                         T4 o4;
 #pragma unroll
                         for (int b = 0; b < 4; ++b) o4[b] = from_f32<T>(acc[i][j][4 * a + b]);
-                        *reinterpret_cast<T4*>(vbase + (int64_t)(32 * j + l32) * g.ldv + row0) = o4;
+                        T* dst = vbase + (int64_t)(32 * j + l32) * g.ldv + row0;
+                        if (row0 + 4 <= g.M) {
+                            *reinterpret_cast<T4*>(dst) = o4;
+                        } else {
+#pragma unroll
+                            for (int b = 0; b < 4; ++b)
+                                if (row0 + b < g.M) dst[b] = o4[b];
+                        }
                     }
                 }
         }
@@ -364,7 +378,13 @@ __global__ __launch_bounds__(128 * kWavesM) void gemm_bf16_fast_kernel(const cha
     const int wm = wave >> 1, wn = wave & 1;
     const int l32 = lane & 31, half = lane >> 5;
 
-    const TileCoord tc = tile_of_block(blockIdx.x, g.nt_m, g.nt_n);
+    // k_slices > 1: workgroup = (tile, K slice); slice s covers slabs [s nk / S, (s + 1) nk / S)
+    const int n_tiles = g.nt_m * g.nt_n;
+    const int slice = g.k_slices > 1 ? (int)blockIdx.x / n_tiles : 0;
+    const int nk_all = g.Kd / BK;
+    const int k_first = (int)((int64_t)slice * nk_all / g.k_slices);
+    const int nk = (int)((int64_t)(slice + 1) * nk_all / g.k_slices) - k_first;   // >= kStages + 1 (checked on the host)
+    const TileCoord tc = tile_of_block((int)blockIdx.x - slice * n_tiles, g.nt_m, g.nt_n);
     const int m0 = tc.tm * BM;
     const int n0 = tc.tn * N_OUT;
 
@@ -375,8 +395,8 @@ __global__ __launch_bounds__(128 * kWavesM) void gemm_bf16_fast_kernel(const cha
     const int dq = lane / CHUNKS, dslot = lane % CHUNKS;
     auto swz = [](int row) { return (row >> kSwzShift) & (CHUNKS - 1); };
     static_assert(ROWS_PER_DMA % (CHUNKS << kSwzShift) == 0, "swizzle must not depend on the DMA instruction index");
-    uint32_t a_lane_off = (uint32_t)dq * (uint32_t)(g.lda * 2) + (uint32_t)((dslot ^ swz(dq)) * 16);
-    uint32_t b_lane_off = (uint32_t)dq * (uint32_t)(g.ldw * 2) + (uint32_t)((dslot ^ swz(dq)) * 16);
+    uint32_t a_lane_off = (uint32_t)dq * (uint32_t)(g.lda * 2) + (uint32_t)((dslot ^ swz(dq)) * 16) + (uint32_t)k_first * BKB;
+    uint32_t b_lane_off = (uint32_t)dq * (uint32_t)(g.ldw * 2) + (uint32_t)((dslot ^ swz(dq)) * 16) + (uint32_t)k_first * BKB;
     const char* a_base[DMA_PER_OP];
     const char* b_base[DMA_PER_OP];
 #pragma unroll
@@ -463,7 +483,6 @@ __global__ __launch_bounds__(128 * kWavesM) void gemm_bf16_fast_kernel(const cha
     //              boundary), DMA of the A half of slab kt + kAhead into the stage slab kt - 1 occupied
     // so the DMA instructions are spread one by one under the MFMAs and a slab has kStages - 3 full slab times
     // plus one k-step to land after its last DMA instruction.
-    const int nk = g.Kd / BK;                      // >= kStages + 1 (checked on the host)
 #pragma unroll
     for (int s = 0; s < kAhead; ++s) {
         issue_a(s);
@@ -514,8 +533,18 @@ constexpr int kFastBK = 32;
 
 bool fast_path_ok(int32_t dtype, int epi, const GemmArgs& g) {
     const int n_out = epi == EPI_SWIGLU ? 128 : 256;
-    return dtype == ATTS_DTYPE_BF16 && g.M % 256 == 0 && g.N % n_out == 0 && g.Kd % kFastBK == 0 &&
-           g.Kd >= (ATTS_FAST_STAGES + 1) * kFastBK && g.lda * 2 * 16 < (1ll << 31) && g.ldw * 2 * 16 < (1ll << 31);
+    return dtype == ATTS_DTYPE_BF16 && (g.M % 256 == 0 || g.a_rows_padded) && g.N % n_out == 0 && g.Kd % kFastBK == 0 &&
+           g.Kd >= (ATTS_FAST_STAGES + 1) * kFastBK && g.lda * 2 * 17 < (1ll << 31) && g.ldw * 2 * 17 < (1ll << 31);
+}
+
+// K slices per tile for the residual epilogue: when the tiles alone leave most of the chip idle (few rows and a
+// narrow output: the weight-streaming regime), the K range is cut so that about one workgroup per CU runs.
+int fast_k_slices(int epi, int n_tiles, int nk) {
+    if (epi != EPI_RESID_F32 || n_tiles >= 128) return 1;
+    int s = (256 + n_tiles - 1) / n_tiles;
+    const int max_s = nk / (2 * (ATTS_FAST_STAGES + 1));     // every slice keeps the DMA ring busy for a while
+    if (s > max_s) s = max_s;
+    return s < 1 ? 1 : s;
 }
 
 template <int EPI>
@@ -528,8 +557,9 @@ int32_t launch_fast(const GemmArgs& g, hipStream_t stream) {
     d.n_part = g.n_part;
     d.ldv = g.ldv;
     d.n_rot_heads = g.n_rot_heads;
-    d.nt_m = g.M / 256;
+    d.nt_m = (int)ceil_div(g.M, 256);
     d.nt_n = g.N / n_out;
+    d.k_slices = fast_k_slices(EPI, d.nt_m * d.nt_n, g.Kd / kFastBK);
     const size_t lds = (size_t)ATTS_FAST_STAGES * 512 * 2 * kFastBK;
     auto kern = gemm_bf16_fast_kernel<EPI, kWavesM, ATTS_FAST_STAGES>;
     static bool attr_set = false;   // per instantiation
@@ -538,8 +568,9 @@ int32_t launch_fast(const GemmArgs& g, hipStream_t stream) {
                                          hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
         attr_set = true;
     }
-    hipLaunchKernelGGL(kern, dim3(d.nt_m * d.nt_n), dim3(128 * kWavesM), lds, stream, reinterpret_cast<const char*>(g.a),
-                       reinterpret_cast<const char*>(g.w), g.out, g.targets, g.partials, g.target_logit, g.rope, g.vt, d);
+    hipLaunchKernelGGL(kern, dim3(d.nt_m * d.nt_n * d.k_slices), dim3(128 * kWavesM), lds, stream,
+                       reinterpret_cast<const char*>(g.a), reinterpret_cast<const char*>(g.w), g.out, g.targets, g.partials,
+                       g.target_logit, g.rope, g.vt, d);
     ATTS_LAUNCH_CHECK("gemm_bf16_fast_kernel");
     return ATTS_OK;
 }
@@ -553,6 +584,7 @@ int32_t launch_cfg(const GemmArgs& g, hipStream_t stream) {
     d.n_part = g.n_part;
     d.ldv = g.ldv;
     d.n_rot_heads = g.n_rot_heads;
+    d.k_slices = 1;
     d.nt_m = (int)ceil_div(g.M, BM);
     d.nt_n = (int)ceil_div(g.N, n_out);
     const size_t lds = 2 * (size_t)(BM + BN) * kRowBytes;
@@ -569,18 +601,18 @@ int32_t launch_cfg(const GemmArgs& g, hipStream_t stream) {
     return ATTS_OK;
 }
 
-// Tile choice: 256 x 256 when the problem fills the chip with such tiles, else 128 x 128.
+// Tile choice of the general kernel: 256 x 256 when the problem fills the chip with such tiles, else 128 x 128.
 bool use_big_tile(int32_t M, int32_t N) {
     return ceil_div(M, 256) * ceil_div(N, 256) >= 192;
 }
 
+// The aligned bf16 kernel serves every call it can (its DMA ring also streams weights well when the tiles are
+// few); everything else goes to the general kernel.
 template <typename T, int EPI>
 int32_t launch_epi(const GemmArgs& g, hipStream_t stream) {
+    if (sizeof(T) == 2 && fast_path_ok(ATTS_DTYPE_BF16, EPI, g)) return launch_fast<EPI>(g, stream);
     int32_t n_cols = (EPI == EPI_SWIGLU) ? 2 * g.N : g.N;
-    if (use_big_tile(g.M, n_cols)) {
-        if (sizeof(T) == 2 && fast_path_ok(ATTS_DTYPE_BF16, EPI, g)) return launch_fast<EPI>(g, stream);
-        return launch_cfg<T, 256, 256, EPI>(g, stream);
-    }
+    if (use_big_tile(g.M, n_cols)) return launch_cfg<T, 256, 256, EPI>(g, stream);
     return launch_cfg<T, 128, 128, EPI>(g, stream);
 }
 
@@ -624,15 +656,18 @@ __global__ void lmhead_combine_kernel(const float2* __restrict__ partials, const
 
 }  // namespace
 
-int32_t lmhead_num_partials(int32_t /*dtype*/, int32_t M, int32_t N) {
-    int bn = use_big_tile(M, N) ? 256 : 128;
+int32_t lmhead_num_partials(int32_t dtype, int32_t M, int32_t N, int32_t Kd, bool a_rows_padded) {
+    GemmArgs g{};
+    g.M = M; g.N = N; g.Kd = Kd; g.lda = Kd; g.ldw = Kd; g.a_rows_padded = a_rows_padded;
+    const int bn = (fast_path_ok(dtype, EPI_LMHEAD, g) || use_big_tile(M, N)) ? 256 : 128;
     return (int32_t)ceil_div(N, bn) * 2;
 }
+int32_t lmhead_max_partials(int32_t N) { return (int32_t)ceil_div(N, 128) * 2; }
 
-bool qkv_rope_fusable(int32_t dtype, int32_t M, int32_t N, int32_t Kd, int32_t head_dim) {
+bool qkv_rope_fusable(int32_t dtype, int32_t M, int32_t N, int32_t Kd, int32_t head_dim, bool a_rows_padded) {
     GemmArgs g{};
-    g.M = M; g.N = N; g.Kd = Kd; g.lda = Kd; g.ldw = Kd;
-    return head_dim == 128 && use_big_tile(M, N) && fast_path_ok(dtype, EPI_QKV_ROPE, g);
+    g.M = M; g.N = N; g.Kd = Kd; g.lda = Kd; g.ldw = Kd; g.a_rows_padded = a_rows_padded;
+    return head_dim == 128 && fast_path_ok(dtype, EPI_QKV_ROPE, g);
 }
 
 int32_t launch_gemm(int32_t dtype, GemmEpilogue epi, const GemmArgs& g, hipStream_t stream) {
@@ -641,10 +676,10 @@ int32_t launch_gemm(int32_t dtype, GemmEpilogue epi, const GemmArgs& g, hipStrea
     if ((g.Kd * es) % 16 || (g.lda * es) % 16 || (g.ldw * es) % 16)
         return fail(ATTS_ERR_SHAPE, "gemm: K (%d) and leading dimensions must be multiples of 16 bytes", g.Kd);
     if (((uintptr_t)g.a | (uintptr_t)g.w) & 15) return fail(ATTS_ERR_INVALID_ARG, "gemm: operands must be 16-byte aligned");
-    if (epi == EPI_LMHEAD && g.n_part != lmhead_num_partials(dtype, g.M, g.N))
+    if (epi == EPI_LMHEAD && g.n_part != lmhead_num_partials(dtype, g.M, g.N, g.Kd, g.a_rows_padded))
         return fail(ATTS_ERR_INVALID_ARG, "gemm: wrong partial count for the LM-head epilogue");
     if (epi == EPI_QKV_ROPE) {
-        if (!qkv_rope_fusable(dtype, g.M, g.N, g.Kd, 128) || !g.rope || !g.vt || g.ldv < g.M || g.ldv % 4 ||
+        if (!qkv_rope_fusable(dtype, g.M, g.N, g.Kd, 128, g.a_rows_padded) || !g.rope || !g.vt || g.ldv < g.M || g.ldv % 4 ||
             g.n_rot_heads < 1 || g.n_rot_heads * 128 >= g.N)
             return fail(ATTS_ERR_SHAPE, "gemm: the fused QKV epilogue does not apply to this call");
         return launch_fast<EPI_QKV_ROPE>(g, stream);

@@ -120,14 +120,15 @@ def test_workspace_and_argument_errors():
     assert e.value.code == A.ERR_INVALID_ARG
 
 
-def _full_width_case(name, n_layers, k_sample):
-    """GPU: the whole workload (all K drafts) in the benchmark's launch configuration.
-    Oracle: draft `k_sample` alone, as one plain causal sequence."""
+def _full_width_case(name, n_layers, k_sample, shape=None):
+    """GPU: the whole workload (all K drafts) in the benchmark's launch configuration (or the same model at
+    another (P, K, T)).  Oracle: draft `k_sample` alone, as one plain causal sequence."""
     import paper_2509_15148_amd as A
     wl = WORKLOADS[name]
     cfg = wl.model
-    announce("score full width", name, "layers", n_layers, "sample draft", k_sample)
-    w_dev, prefix, drafts = _case(cfg, wl.P, wl.K, wl.T, wl.seed, n_layers=n_layers)
+    P, K, T = shape if shape else (wl.P, wl.K, wl.T)
+    announce("score full width", name, "layers", n_layers, "shape", (P, K, T), "sample draft", k_sample)
+    w_dev, prefix, drafts = _case(cfg, P, K, T, wl.seed, n_layers=n_layers)
     lp, sc, flag = _run_gpu(A, cfg, w_dev, prefix, drafts)
     assert flag == 0 and np.all(np.isfinite(lp)) and np.all(lp <= 0)
     w_np = weights_to_numpy(w_dev)
@@ -144,6 +145,14 @@ def _full_width_case(name, n_layers, k_sample):
 
 def test_7b_shape_two_layer_slice():
     _full_width_case("7b", n_layers=2, k_sample=5)
+
+
+@pytest.mark.parametrize("shape", [(16, 16, 8), (300, 5, 67), (1, 2, 3)])
+def test_7b_width_few_and_ragged_rows(shape):
+    """Row counts that are not whole 256-row tiles, at full model width: the decode-like shape that bench.py
+    times (144 rows: projections with few tiles split their K range over several workgroups), a ragged
+    multi-tile one, and a handful of rows."""
+    _full_width_case("7b", n_layers=2, k_sample=shape[1] - 1, shape=shape)
 
 
 def test_7b_full_model_sampled_draft():
