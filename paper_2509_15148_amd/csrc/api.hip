@@ -73,14 +73,14 @@ struct Workspace {
     int32_t n_part;
 };
 
-// GEMM inputs of the bf16 path are allocated in whole 256-row tiles: the aligned kernel then serves every row
-// count (it reads the pad rows, whatever they hold, and drops their results).
+// GEMM inputs of the bf16 path are allocated in whole tiles (768 rows = a multiple of both tile heights): the
+// aligned kernel then serves every row count (it reads the pad rows, whatever they hold, and drops their results).
 bool pads_rows(const atts_model_desc& d) { return d.dtype == ATTS_DTYPE_BF16; }
 
 Workspace carve(const atts_model_desc& d, ScoreShape s) {
     const size_t es = dtype_size(d.dtype);
     const size_t R = (size_t)s.R(), B = (size_t)s.B();
-    const size_t Ra = pads_rows(d) ? align_up(R, 256) : R, Ba = pads_rows(d) ? align_up(B, 256) : B;
+    const size_t Ra = pads_rows(d) ? align_up(R, 768) : R, Ba = pads_rows(d) ? align_up(B, 768) : B;
     Workspace w{};
     size_t off = 0;
     auto take = [&](size_t bytes) {

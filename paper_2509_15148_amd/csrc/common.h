@@ -98,7 +98,7 @@ struct GemmArgs {
     void* out;           // see GemmEpilogue
     int32_t M, N, Kd;
     int64_t lda, ldw, ldc;
-    bool a_rows_padded;  // rows M .. next multiple of 256 of `a` are readable (any values; their results are dropped)
+    bool a_rows_padded;  // rows M .. next multiple of 768 of `a` are readable (any values; their results are dropped)
     // EPI_LMHEAD only:
     const int32_t* targets;  // [M] target column per row
     float2* partials;        // [M, n_part] (running max, sum of exp) per column slab

@@ -348,7 +348,7 @@ __global__ __launch_bounds__(kThreads) void gemm_nt_kernel(const char* __restric
 //     (s_waitcnt vmcnt(n) + s_barrier) so that younger loads stay in flight across the barrier;
 //   * fragments of the next k-step are read from LDS while the MFMAs of the current one issue.
 // ---------------------------------------------------------------------------------------------
-template <int EPI, int kWavesM /* 2: 4 waves of 128 x 128; 4: 8 waves of 64 x 128 */, int kStages /* 4 or 5 */>
+template <int EPI, int kWavesM /* waves along M (2 along N) */, int MI /* 32-row blocks per wave */, int kStages>
 __global__ __launch_bounds__(128 * kWavesM) void gemm_bf16_fast_kernel(const char* __restrict__ gA,
                                                                        const char* __restrict__ gW,
                                                                        void* __restrict__ g_out,
@@ -357,8 +357,8 @@ __global__ __launch_bounds__(128 * kWavesM) void gemm_bf16_fast_kernel(const cha
                                                                        float* __restrict__ g_target_logit,
                                                                        const float2* __restrict__ g_rope,
                                                                        void* __restrict__ g_vt, const GemmDims g) {
-    constexpr int BM = 256, BN = 256, NI = 4, WN = 128;
-    constexpr int MI = 8 / kWavesM, WM = 32 * MI;
+    constexpr int BN = 256, NI = 4, WN = 128;
+    constexpr int WM = 32 * MI, BM = kWavesM * WM;  // 256 or 384 rows
     constexpr int kWaves = 2 * kWavesM;
     constexpr int N_OUT = (EPI == EPI_SWIGLU) ? BN / 2 : BN;
     constexpr int BKB = 64;                        // bytes of K per row per slab
@@ -366,8 +366,10 @@ __global__ __launch_bounds__(128 * kWavesM) void gemm_bf16_fast_kernel(const cha
     constexpr int CHUNKS = BKB / 16;               // 16-byte chunks per LDS row
     constexpr int kSwzShift = 2;                   // chunk ^= (row >> 2) & 3: conflict-free on the 64-bank LDS
     constexpr int ROWS_PER_DMA = 1024 / BKB;       // tile rows filled by one wave-wide DMA instruction (16)
-    constexpr int DMA_PER_OP = BM / ROWS_PER_DMA / kWaves;   // DMA instructions per wave, per operand, per slab
-    constexpr int STAGE_BYTES = (BM + BN) * BKB;   // 32 KiB
+    constexpr int DMA_A = BM / ROWS_PER_DMA / kWaves;   // DMA instructions per wave and slab for the A rows
+    constexpr int DMA_B = BN / ROWS_PER_DMA / kWaves;   // ... and for the W rows
+    static_assert(DMA_A * ROWS_PER_DMA * kWaves == BM && DMA_B * ROWS_PER_DMA * kWaves == BN, "tile rows per wave");
+    constexpr int STAGE_BYTES = (BM + BN) * BKB;   // 32 or 40 KiB
     constexpr int kAhead = kStages - 1;            // slab kt + kAhead is the youngest one issued during slab kt
 
     extern __shared__ __attribute__((aligned(16))) char smem[];   // [kStages][A: BM rows | B: BN rows][BKB]
@@ -388,7 +390,7 @@ __global__ __launch_bounds__(128 * kWavesM) void gemm_bf16_fast_kernel(const cha
     const int m0 = tc.tm * BM;
     const int n0 = tc.tn * N_OUT;
 
-    // ---- DMA addressing.  DMA instruction j of this wave fills LDS rows r0 = (wave DMA_PER_OP + j) 16 ... r0 + 15
+    // ---- DMA addressing.  DMA instruction j of this wave fills LDS rows r0 = (wave DMA_x + j) 16 ... r0 + 15
     // of an operand tile; lane i lands at row r0 + i / 4, chunk slot i % 4, and therefore fetches logical chunk
     // slot ^ swz(row).  r0 is a multiple of 16, so swz(row) = swz(i / 4): one 32-bit per-lane byte offset per
     // operand serves every j; the row bases are wave-uniform (scalar registers).
@@ -397,12 +399,13 @@ __global__ __launch_bounds__(128 * kWavesM) void gemm_bf16_fast_kernel(const cha
     static_assert(ROWS_PER_DMA % (CHUNKS << kSwzShift) == 0, "swizzle must not depend on the DMA instruction index");
     uint32_t a_lane_off = (uint32_t)dq * (uint32_t)(g.lda * 2) + (uint32_t)((dslot ^ swz(dq)) * 16) + (uint32_t)k_first * BKB;
     uint32_t b_lane_off = (uint32_t)dq * (uint32_t)(g.ldw * 2) + (uint32_t)((dslot ^ swz(dq)) * 16) + (uint32_t)k_first * BKB;
-    const char* a_base[DMA_PER_OP];
-    const char* b_base[DMA_PER_OP];
+    const char* a_base[DMA_A];
+    const char* b_base[DMA_B];
 #pragma unroll
-    for (int j = 0; j < DMA_PER_OP; ++j) {
-        const int r0 = (wave * DMA_PER_OP + j) * ROWS_PER_DMA;
-        a_base[j] = gA + (int64_t)(m0 + r0) * g.lda * 2;
+    for (int j = 0; j < DMA_A; ++j) a_base[j] = gA + (int64_t)(m0 + (wave * DMA_A + j) * ROWS_PER_DMA) * g.lda * 2;
+#pragma unroll
+    for (int j = 0; j < DMA_B; ++j) {
+        const int r0 = (wave * DMA_B + j) * ROWS_PER_DMA;
         int64_t wrow = r0;                                        // W row (relative to n0) feeding LDS row r0
         if (EPI == EPI_SWIGLU) {
             constexpr int H = WN / 2;                             // wave slab = [gate H | up H]
@@ -415,8 +418,8 @@ __global__ __launch_bounds__(128 * kWavesM) void gemm_bf16_fast_kernel(const cha
     auto issue_a = [&](int kt) __attribute__((always_inline)) {
         char* stage = smem + (kt % kStages) * STAGE_BYTES;
 #pragma unroll
-        for (int j = 0; j < DMA_PER_OP; ++j) {
-            const int r0 = (wave * DMA_PER_OP + j) * ROWS_PER_DMA;
+        for (int j = 0; j < DMA_A; ++j) {
+            const int r0 = (wave * DMA_A + j) * ROWS_PER_DMA;
             __builtin_amdgcn_global_load_lds(ATTS_GPTR(a_base[j] + a_lane_off), ATTS_LPTR(stage + r0 * BKB), 16, 0, 0);
         }
         a_lane_off += BKB;
@@ -424,8 +427,8 @@ __global__ __launch_bounds__(128 * kWavesM) void gemm_bf16_fast_kernel(const cha
     auto issue_b = [&](int kt) __attribute__((always_inline)) {
         char* stage = smem + (kt % kStages) * STAGE_BYTES + BM * BKB;
 #pragma unroll
-        for (int j = 0; j < DMA_PER_OP; ++j) {
-            const int r0 = (wave * DMA_PER_OP + j) * ROWS_PER_DMA;
+        for (int j = 0; j < DMA_B; ++j) {
+            const int r0 = (wave * DMA_B + j) * ROWS_PER_DMA;
             __builtin_amdgcn_global_load_lds(ATTS_GPTR(b_base[j] + b_lane_off), ATTS_LPTR(stage + r0 * BKB), 16, 0, 0);
         }
         b_lane_off += BKB;
@@ -462,17 +465,23 @@ __global__ __launch_bounds__(128 * kWavesM) void gemm_bf16_fast_kernel(const cha
     // half a slab spread evenly underneath.  (The texture path accepts one 1 KiB DMA instruction per ~16
     // cycles per CU; issued back to back they block the wave, and with it the MFMAs, for that long.)
     constexpr int kReads = MI + NI, kMfma = MI * NI;
-    auto interleave_hint = [&](bool with_dma, auto sync_id) __attribute__((always_inline)) {
+    static_assert(kMfma >= kReads, "the hint pairs every fragment read with an MFMA");
+    auto interleave_hint = [&](auto n_dma_, auto sync_id) __attribute__((always_inline)) {
         constexpr int kId = decltype(sync_id)::value;   // std::integral_constant
+        constexpr int n_dma = decltype(n_dma_)::value;  // DMA instructions issued in this k-step (0: none)
+        constexpr int stride = kReads / (n_dma > 0 ? n_dma : 1) > 0 ? kReads / (n_dma > 0 ? n_dma : 1) : 1;
 #pragma unroll
         for (int r = 0; r < kReads; ++r) {
             __builtin_amdgcn_sched_group_barrier(0x008, 1, kId);                                    // MFMA
-            if (with_dma && r % (kReads / DMA_PER_OP) == 0 && r / (kReads / DMA_PER_OP) < DMA_PER_OP)
+            if (n_dma > 0 && r % stride == 0 && r / stride < n_dma)
                 __builtin_amdgcn_sched_group_barrier(0x020, 1, kId);                                // VMEM read (LDS DMA)
             __builtin_amdgcn_sched_group_barrier(0x100, 1, kId);                                    // DS read
         }
         __builtin_amdgcn_sched_group_barrier(0x008, kMfma - kReads, kId);
     };
+    using NoDma = std::integral_constant<int, 0>;
+    using DmaA = std::integral_constant<int, DMA_A>;
+    using DmaB = std::integral_constant<int, DMA_B>;
     using Id0 = std::integral_constant<int, 0>;
     using Id1 = std::integral_constant<int, 1>;
 
@@ -489,7 +498,7 @@ __global__ __launch_bounds__(128 * kWavesM) void gemm_bf16_fast_kernel(const cha
         if (s + 1 < kAhead) issue_b(s);
     }
     // issued so far, in order: A0 B0 A1 B1 ... A(kAhead-1); slab 0 = the two oldest halves
-    wait_vmcnt<(2 * kAhead - 3) * DMA_PER_OP>();
+    wait_vmcnt<(kAhead - 1) * DMA_A + (kAhead - 2) * DMA_B>();
     block_barrier();
     bf16x8 fa[2][MI], fb[2][NI];
     load_frags(0, 0, fa[0], fb[0]);
@@ -499,17 +508,19 @@ __global__ __launch_bounds__(128 * kWavesM) void gemm_bf16_fast_kernel(const cha
         load_frags(kt, 1, fa[1], fb[1]);
         if (issue_w) issue_b(kt + kAhead - 1);
         mma_step(fa[0], fb[0]);
-        interleave_hint(issue_w, Id0{});
+        if (issue_w) interleave_hint(DmaB{}, Id0{}); else interleave_hint(NoDma{}, Id0{});
         if (has_next) {
             // outstanding after slab kt + 1: slabs kt + 2 .. kt + kAhead - 1 in full
-            if (steady) wait_vmcnt<2 * (kAhead - 2) * DMA_PER_OP>(); else wait_vmcnt<0>();
+            if (steady) wait_vmcnt<(kAhead - 2) * (DMA_A + DMA_B)>(); else wait_vmcnt<0>();
             block_barrier();
             __builtin_amdgcn_sched_barrier(0);     // the two k-steps are scheduled as separate regions
             load_frags(kt + 1, 0, fa[0], fb[0]);
             if (issue_next_a) issue_a(kt + kAhead);
         }
         mma_step(fa[1], fb[1]);
-        if (has_next) interleave_hint(issue_next_a, Id1{});
+        if (has_next) {
+            if (issue_next_a) interleave_hint(DmaA{}, Id1{}); else interleave_hint(NoDma{}, Id1{});
+        }
     };
     struct Yes { constexpr operator bool() const { return true; } };
     struct No { constexpr operator bool() const { return false; } };
@@ -537,6 +548,17 @@ bool fast_path_ok(int32_t dtype, int epi, const GemmArgs& g) {
            g.Kd >= (ATTS_FAST_STAGES + 1) * kFastBK && g.lda * 2 * 17 < (1ll << 31) && g.ldw * 2 * 17 < (1ll << 31);
 }
 
+// Tile height of the aligned kernel: 384-row tiles move 1/6 fewer operand bytes per flop through L2 -> LDS than
+// 256-row ones and are taken when they do not cost whole extra rounds of workgroups over the 256 CUs.
+int fast_tile_rows(int epi, const GemmArgs& g) {
+    const int n_out = epi == EPI_SWIGLU ? 128 : 256;
+    if (!(g.M % 384 == 0 || g.a_rows_padded) || g.M <= 256) return 256;
+    const int64_t nt_n = g.N / n_out;
+    const int64_t t256 = ceil_div(g.M, 256) * nt_n, t384 = ceil_div(g.M, 384) * nt_n;
+    const int64_t cost256 = ceil_div(t256, 256) * 2, cost384 = ceil_div(t384, 256) * 3;   // rounds x tile height
+    return cost384 * 9 <= cost256 * 10 ? 384 : 256;   // a 384-row tile runs ~10 % closer to the MFMA peak
+}
+
 // K slices per tile for the residual epilogue: when the tiles alone leave most of the chip idle (few rows and a
 // narrow output: the weight-streaming regime), the K range is cut so that about one workgroup per CU runs.
 int fast_k_slices(int epi, int n_tiles, int nk) {
@@ -547,21 +569,23 @@ int fast_k_slices(int epi, int n_tiles, int nk) {
     return s < 1 ? 1 : s;
 }
 
-template <int EPI>
-int32_t launch_fast(const GemmArgs& g, hipStream_t stream) {
+template <int EPI, int MI>
+int32_t launch_fast_tile(const GemmArgs& g, hipStream_t stream) {
     constexpr int n_out = (EPI == EPI_SWIGLU) ? 128 : 256;
     constexpr int kWavesM = ATTS_FAST_WAVES_M;
+    constexpr int BM = kWavesM * MI * 32;
+    constexpr int kStages = BM > 256 ? 4 : ATTS_FAST_STAGES;          // 160 KB of LDS either way
     GemmDims d;
     d.M = g.M; d.N = g.N; d.Kd = g.Kd;
     d.lda = g.lda; d.ldw = g.ldw; d.ldc = g.ldc;
     d.n_part = g.n_part;
     d.ldv = g.ldv;
     d.n_rot_heads = g.n_rot_heads;
-    d.nt_m = (int)ceil_div(g.M, 256);
+    d.nt_m = (int)ceil_div(g.M, BM);
     d.nt_n = g.N / n_out;
     d.k_slices = fast_k_slices(EPI, d.nt_m * d.nt_n, g.Kd / kFastBK);
-    const size_t lds = (size_t)ATTS_FAST_STAGES * 512 * 2 * kFastBK;
-    auto kern = gemm_bf16_fast_kernel<EPI, kWavesM, ATTS_FAST_STAGES>;
+    const size_t lds = (size_t)kStages * (BM + 256) * 2 * kFastBK;
+    auto kern = gemm_bf16_fast_kernel<EPI, kWavesM, MI, kStages>;
     static bool attr_set = false;   // per instantiation
     if (!attr_set) {
         ATTS_HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
@@ -573,6 +597,13 @@ int32_t launch_fast(const GemmArgs& g, hipStream_t stream) {
                        g.target_logit, g.rope, g.vt, d);
     ATTS_LAUNCH_CHECK("gemm_bf16_fast_kernel");
     return ATTS_OK;
+}
+
+template <int EPI>
+int32_t launch_fast(const GemmArgs& g, hipStream_t stream) {
+    constexpr int kWavesM = ATTS_FAST_WAVES_M;
+    if (fast_tile_rows(EPI, g) == 384) return launch_fast_tile<EPI, 12 / kWavesM>(g, stream);
+    return launch_fast_tile<EPI, 8 / kWavesM>(g, stream);
 }
 
 template <typename T, int BM, int BN, int EPI>
