@@ -534,6 +534,209 @@ __global__ __launch_bounds__(128 * kWavesM) void gemm_bf16_fast_kernel(const cha
     gemm_epilogue<bf16, MI, NI, EPI>(acc, m0, n0, wm, wn, l32, half, tc.tn, g_out, g_targets, g_partials, g_target_logit, g_rope, g_vt, g);
 }
 
+// ---------------------------------------------------------------------------------------------
+// Wide-slab variant of the aligned kernel: 128 bytes of K per row and slab, so that every DMA instruction
+// asks L2 for whole 128-byte lines (8 rows x 128 B instead of 16 rows x 64 B).  L2 -> LDS delivery, which bounds
+// the 64-byte version, is ~1.4x faster that way; the price is LDS: 160 KB hold only 2.5 slabs of a 256 x 256 tile
+// (a ring of five 32 KB units A0 W0 A1 W1 A2 ...: the A rows run two slabs ahead, the W rows one) or two slabs of
+// a 384 x 256 tile.  A slab is four MFMA k-steps; the DMA of the following slabs is issued under the first two,
+// one wait + barrier per slab at its end.
+// ---------------------------------------------------------------------------------------------
+template <int EPI, int kWavesM, int MI>
+__global__ __launch_bounds__(128 * kWavesM) void gemm_bf16_wide_kernel(const char* __restrict__ gA,
+                                                                       const char* __restrict__ gW,
+                                                                       void* __restrict__ g_out,
+                                                                       const int32_t* __restrict__ g_targets,
+                                                                       float2* __restrict__ g_partials,
+                                                                       float* __restrict__ g_target_logit,
+                                                                       const float2* __restrict__ g_rope,
+                                                                       void* __restrict__ g_vt, const GemmDims g) {
+    constexpr int BN = 256, NI = 4, WN = 128;
+    constexpr int WM = 32 * MI, BM = kWavesM * WM;
+    constexpr int kWaves = 2 * kWavesM;
+    constexpr int N_OUT = (EPI == EPI_SWIGLU) ? BN / 2 : BN;
+    constexpr int BKB = 128, BK = BKB / 2, CHUNKS = BKB / 16;   // four MFMA k-steps per slab
+    constexpr int ROWS_PER_DMA = 1024 / BKB;                     // 8
+    constexpr int DMA_A = BM / ROWS_PER_DMA / kWaves, DMA_B = BN / ROWS_PER_DMA / kWaves;
+    static_assert(DMA_A % 2 == 0 && DMA_B % 2 == 0, "the swizzle parity of a DMA instruction must not depend on the wave");
+    constexpr bool kDeep = BM == 256;                            // five-unit ring, A two slabs ahead
+    constexpr int UNIT_A = BM * BKB, UNIT_B = BN * BKB;
+    static_assert(!kDeep || UNIT_A == UNIT_B, "ring units must have one size");
+
+    extern __shared__ __attribute__((aligned(16))) char smem[];
+
+    const int tid = threadIdx.x;
+    const int lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int wm = wave >> 1, wn = wave & 1;
+    const int l32 = lane & 31, half = lane >> 5;
+
+    const int n_tiles = g.nt_m * g.nt_n;
+    const int slice = g.k_slices > 1 ? (int)blockIdx.x / n_tiles : 0;
+    const int nk_all = g.Kd / BK;
+    const int k_first = (int)((int64_t)slice * nk_all / g.k_slices);
+    const int nk = (int)((int64_t)(slice + 1) * nk_all / g.k_slices) - k_first;   // >= 3 (checked on the host)
+    const TileCoord tc = tile_of_block((int)blockIdx.x - slice * n_tiles, g.nt_m, g.nt_n);
+    const int m0 = tc.tm * BM;
+    const int n0 = tc.tn * N_OUT;
+
+    // LDS offsets of the operands of slab k
+    auto a_slot = [&](int k) { return kDeep ? ((2 * k) % 5) * UNIT_A : (k & 1) * (UNIT_A + UNIT_B); };
+    auto b_slot = [&](int k) { return kDeep ? ((2 * k + 1) % 5) * UNIT_A : (k & 1) * (UNIT_A + UNIT_B) + UNIT_A; };
+
+    // ---- DMA addressing: instruction j of this wave fills LDS rows r0 = (wave DMA_x + j) 8 ... r0 + 7; lane i lands
+    // at row r0 + i / 8, chunk slot i % 8 and fetches logical chunk slot ^ swz(row), swz(row) = (row >> 1) & 7.
+    // r0 / 8 and j have the same parity, so two per-lane offsets per operand (even / odd j) serve every j.
+    const int dq = lane / CHUNKS, dslot = lane % CHUNKS;
+    uint32_t a_lane_off[2], b_lane_off[2];
+#pragma unroll
+    for (int p = 0; p < 2; ++p) {
+        const int sw = (4 * p + (dq >> 1)) & 7;
+        a_lane_off[p] = (uint32_t)dq * (uint32_t)(g.lda * 2) + (uint32_t)((dslot ^ sw) * 16) + (uint32_t)k_first * BKB;
+        b_lane_off[p] = (uint32_t)dq * (uint32_t)(g.ldw * 2) + (uint32_t)((dslot ^ sw) * 16) + (uint32_t)k_first * BKB;
+    }
+    const char* a_base[DMA_A];
+    const char* b_base[DMA_B];
+#pragma unroll
+    for (int j = 0; j < DMA_A; ++j) a_base[j] = gA + (int64_t)(m0 + (wave * DMA_A + j) * ROWS_PER_DMA) * g.lda * 2;
+#pragma unroll
+    for (int j = 0; j < DMA_B; ++j) {
+        const int r0 = (wave * DMA_B + j) * ROWS_PER_DMA;
+        int64_t wrow = r0;
+        if (EPI == EPI_SWIGLU) {
+            constexpr int H = WN / 2;                             // wave slab = [gate H | up H]
+            const int jw = r0 / WN, jj = r0 % WN;
+            wrow = (int64_t)(jj / H) * g.N + jw * H + jj % H;
+        }
+        b_base[j] = gW + (n0 + wrow) * g.ldw * 2;
+    }
+    auto issue_a = [&](int k) __attribute__((always_inline)) {
+        char* dst = smem + a_slot(k);
+#pragma unroll
+        for (int j = 0; j < DMA_A; ++j)
+            __builtin_amdgcn_global_load_lds(ATTS_GPTR(a_base[j] + a_lane_off[j & 1]),
+                                             ATTS_LPTR(dst + (wave * DMA_A + j) * 1024), 16, 0, 0);
+        a_lane_off[0] += BKB;
+        a_lane_off[1] += BKB;
+    };
+    auto issue_b = [&](int k) __attribute__((always_inline)) {
+        char* dst = smem + b_slot(k);
+#pragma unroll
+        for (int j = 0; j < DMA_B; ++j)
+            __builtin_amdgcn_global_load_lds(ATTS_GPTR(b_base[j] + b_lane_off[j & 1]),
+                                             ATTS_LPTR(dst + (wave * DMA_B + j) * 1024), 16, 0, 0);
+        b_lane_off[0] += BKB;
+        b_lane_off[1] += BKB;
+    };
+
+    // ---- fragments: rows wm WM + 32 i + l32 (A) / wn WN + 32 j + l32 (W); 32 i, WM, WN are multiples of 16, so the
+    // swizzle term depends on l32 only
+    const int frag_xor = (l32 >> 1) & 7;
+    const int a_row_off = (wm * WM + l32) * BKB;
+    const int b_row_off = (wn * WN + l32) * BKB;
+    auto load_frags = [&](int k, int s, bf16x8 (&fa)[MI], bf16x8 (&fb)[NI]) __attribute__((always_inline)) {
+        const char* pa = smem + a_slot(k) + a_row_off;
+        const char* pb = smem + b_slot(k) + b_row_off;
+        const int coff = ((2 * s + half) ^ frag_xor) << 4;
+#pragma unroll
+        for (int i = 0; i < MI; ++i) fa[i] = *reinterpret_cast<const bf16x8*>(pa + i * 32 * BKB + coff);
+#pragma unroll
+        for (int j = 0; j < NI; ++j) fb[j] = *reinterpret_cast<const bf16x8*>(pb + j * 32 * BKB + coff);
+    };
+
+    f32x16 acc[MI][NI];
+#pragma unroll
+    for (int i = 0; i < MI; ++i)
+#pragma unroll
+        for (int j = 0; j < NI; ++j)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.f;
+    auto mma_step = [&](bf16x8 (&fa)[MI], bf16x8 (&fb)[NI]) __attribute__((always_inline)) {
+#pragma unroll
+        for (int i = 0; i < MI; ++i)
+#pragma unroll
+            for (int j = 0; j < NI; ++j) acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[i], fb[j], acc[i][j], 0, 0, 0);
+    };
+    constexpr int kReads = MI + NI, kMfma = MI * NI;
+    static_assert(kMfma >= kReads, "the hint pairs every fragment read with an MFMA");
+    // one k-step: MFMAs with n_reads fragment reads (of the next k-step) and n_dma DMA issues spread underneath
+    auto interleave_hint = [&](auto n_reads_, auto n_dma_, auto sync_id) __attribute__((always_inline)) {
+        constexpr int kId = decltype(sync_id)::value;
+        constexpr int n_reads = decltype(n_reads_)::value, n_dma = decltype(n_dma_)::value;
+        constexpr int slots = kReads;
+#pragma unroll
+        for (int r = 0; r < slots; ++r) {
+            __builtin_amdgcn_sched_group_barrier(0x008, 1, kId);                                    // MFMA
+            if (r < n_dma) __builtin_amdgcn_sched_group_barrier(0x020, 1, kId);                     // VMEM read (LDS DMA)
+            if (r < n_reads) __builtin_amdgcn_sched_group_barrier(0x100, 1, kId);                   // DS read
+        }
+        __builtin_amdgcn_sched_group_barrier(0x008, kMfma - slots, kId);
+    };
+    using C0 = std::integral_constant<int, 0>;
+    using CReads = std::integral_constant<int, kReads>;
+    using CDmaA = std::integral_constant<int, DMA_A>;
+    using CDmaB = std::integral_constant<int, DMA_B>;
+    static_assert(DMA_A <= kReads && DMA_B <= kReads, "a k-step hosts at most one DMA issue per fragment read");
+
+    // ---- prologue
+    issue_a(0);
+    issue_b(0);
+    if (kDeep) {
+        issue_a(1);
+        wait_vmcnt<DMA_A>();
+    } else {
+        wait_vmcnt<0>();
+    }
+    block_barrier();
+    bf16x8 fa[2][MI], fb[2][NI];
+    load_frags(0, 0, fa[0], fb[0]);
+
+    // slab k.  first / second: the DMA halves issued under k-steps 0 and 1:
+    //   deep ring:  W rows of slab k + 1 (into the unit slab k - 1 freed), then A rows of slab k + 2
+    //   two stages: A rows, then W rows of slab k + 1
+    auto slab = [&](int k, auto has_next, auto first, auto second) __attribute__((always_inline)) {
+        // k-step 0
+        load_frags(k, 1, fa[1], fb[1]);
+        if (first) { if (kDeep) issue_b(k + 1); else issue_a(k + 1); }
+        mma_step(fa[0], fb[0]);
+        if (first) { if (kDeep) interleave_hint(CReads{}, CDmaB{}, std::integral_constant<int, 0>{}); else interleave_hint(CReads{}, CDmaA{}, std::integral_constant<int, 0>{}); }
+        else interleave_hint(CReads{}, C0{}, std::integral_constant<int, 0>{});
+        __builtin_amdgcn_sched_barrier(0);
+        // k-step 1
+        load_frags(k, 2, fa[0], fb[0]);
+        if (second) { if (kDeep) issue_a(k + 2); else issue_b(k + 1); }
+        mma_step(fa[1], fb[1]);
+        if (second) { if (kDeep) interleave_hint(CReads{}, CDmaA{}, std::integral_constant<int, 1>{}); else interleave_hint(CReads{}, CDmaB{}, std::integral_constant<int, 1>{}); }
+        else interleave_hint(CReads{}, C0{}, std::integral_constant<int, 1>{});
+        __builtin_amdgcn_sched_barrier(0);
+        // k-step 2
+        load_frags(k, 3, fa[1], fb[1]);
+        mma_step(fa[0], fb[0]);
+        interleave_hint(CReads{}, C0{}, std::integral_constant<int, 2>{});
+        __builtin_amdgcn_sched_barrier(0);
+        // k-step 3, then the slab boundary: slab k + 1 has landed for every wave, every wave is done with slab k
+        mma_step(fa[1], fb[1]);
+        if (has_next) {
+            if (kDeep && second) wait_vmcnt<DMA_A>(); else wait_vmcnt<0>();
+            block_barrier();
+            load_frags(k + 1, 0, fa[0], fb[0]);
+        }
+    };
+    struct Yes { constexpr operator bool() const { return true; } };
+    struct No { constexpr operator bool() const { return false; } };
+    int k = 0;
+    if (kDeep) {
+        for (; k + 2 < nk; ++k) slab(k, Yes{}, Yes{}, Yes{});
+        slab(k, Yes{}, Yes{}, No{});          // k = nk - 2: only the W rows of the last slab are left to issue
+        slab(k + 1, No{}, No{}, No{});
+    } else {
+        for (; k + 1 < nk; ++k) slab(k, Yes{}, Yes{}, Yes{});
+        slab(k, No{}, No{}, No{});
+    }
+
+    gemm_epilogue<bf16, MI, NI, EPI>(acc, m0, n0, wm, wn, l32, half, tc.tn, g_out, g_targets, g_partials, g_target_logit, g_rope, g_vt, g);
+}
+
 constexpr int kFastBK = 32;
 #ifndef ATTS_FAST_WAVES_M
 #define ATTS_FAST_WAVES_M 4
@@ -599,11 +802,46 @@ int32_t launch_fast_tile(const GemmArgs& g, hipStream_t stream) {
     return ATTS_OK;
 }
 
+#ifndef ATTS_GEMM_WIDE
+#define ATTS_GEMM_WIDE 1
+#endif
+
+template <int EPI, int MI>
+int32_t launch_wide_tile(const GemmArgs& g, hipStream_t stream) {
+    constexpr int n_out = (EPI == EPI_SWIGLU) ? 128 : 256;
+    constexpr int kWavesM = ATTS_FAST_WAVES_M;
+    constexpr int BM = kWavesM * MI * 32;
+    GemmDims d;
+    d.M = g.M; d.N = g.N; d.Kd = g.Kd;
+    d.lda = g.lda; d.ldw = g.ldw; d.ldc = g.ldc;
+    d.n_part = g.n_part;
+    d.ldv = g.ldv;
+    d.n_rot_heads = g.n_rot_heads;
+    d.nt_m = (int)ceil_div(g.M, BM);
+    d.nt_n = g.N / n_out;
+    d.k_slices = fast_k_slices(EPI, d.nt_m * d.nt_n, g.Kd / 64);
+    const size_t lds = 160 * 1024;
+    auto kern = gemm_bf16_wide_kernel<EPI, kWavesM, MI>;
+    static bool attr_set = false;   // per instantiation
+    if (!attr_set) {
+        ATTS_HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
+                                         hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
+        attr_set = true;
+    }
+    hipLaunchKernelGGL(kern, dim3(d.nt_m * d.nt_n * d.k_slices), dim3(128 * kWavesM), lds, stream,
+                       reinterpret_cast<const char*>(g.a), reinterpret_cast<const char*>(g.w), g.out, g.targets, g.partials,
+                       g.target_logit, g.rope, g.vt, d);
+    ATTS_LAUNCH_CHECK("gemm_bf16_wide_kernel");
+    return ATTS_OK;
+}
+
 template <int EPI>
 int32_t launch_fast(const GemmArgs& g, hipStream_t stream) {
     constexpr int kWavesM = ATTS_FAST_WAVES_M;
-    if (fast_tile_rows(EPI, g) == 384) return launch_fast_tile<EPI, 12 / kWavesM>(g, stream);
-    return launch_fast_tile<EPI, 8 / kWavesM>(g, stream);
+    const bool wide = ATTS_GEMM_WIDE && kWavesM == 4 && g.Kd % 64 == 0 && g.Kd >= 12 * 64;
+    if (fast_tile_rows(EPI, g) == 384)
+        return launch_fast_tile<EPI, 12 / kWavesM>(g, stream);
+    return wide ? launch_wide_tile<EPI, 8 / kWavesM>(g, stream) : launch_fast_tile<EPI, 8 / kWavesM>(g, stream);
 }
 
 template <typename T, int BM, int BN, int EPI>
