@@ -634,14 +634,13 @@ __global__ __launch_bounds__(128 * kWavesM) void gemm_bf16_wide_kernel(const cha
     const int frag_xor = (l32 >> 1) & 7;
     const int a_row_off = (wm * WM + l32) * BKB;
     const int b_row_off = (wn * WN + l32) * BKB;
-    auto load_frags = [&](int k, int s, bf16x8 (&fa)[MI], bf16x8 (&fb)[NI]) __attribute__((always_inline)) {
-        const char* pa = smem + a_slot(k) + a_row_off;
-        const char* pb = smem + b_slot(k) + b_row_off;
-        const int coff = ((2 * s + half) ^ frag_xor) << 4;
+    auto load_a = [&](int k, int s, bf16x8 (&fa)[MI]) __attribute__((always_inline)) {
+        const char* pa = smem + a_slot(k) + a_row_off + (((2 * s + half) ^ frag_xor) << 4);
 #pragma unroll
-        for (int i = 0; i < MI; ++i) fa[i] = *reinterpret_cast<const bf16x8*>(pa + i * 32 * BKB + coff);
-#pragma unroll
-        for (int j = 0; j < NI; ++j) fb[j] = *reinterpret_cast<const bf16x8*>(pb + j * 32 * BKB + coff);
+        for (int i = 0; i < MI; ++i) fa[i] = *reinterpret_cast<const bf16x8*>(pa + i * 32 * BKB);
+    };
+    auto load_b1 = [&](int k, int s, int j) __attribute__((always_inline)) {
+        return *reinterpret_cast<const bf16x8*>(smem + b_slot(k) + b_row_off + j * 32 * BKB + (((2 * s + half) ^ frag_xor) << 4));
     };
 
     f32x16 acc[MI][NI];
@@ -651,32 +650,47 @@ __global__ __launch_bounds__(128 * kWavesM) void gemm_bf16_wide_kernel(const cha
         for (int j = 0; j < NI; ++j)
 #pragma unroll
             for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.f;
-    auto mma_step = [&](bf16x8 (&fa)[MI], bf16x8 (&fb)[NI]) __attribute__((always_inline)) {
+
+    // One k-step, column by column: the MI MFMAs of column j, then the W fragment of column j is replaced in place
+    // by the one of the next k-step (it is free as soon as those MFMAs have issued, and not needed again before the
+    // other columns are through).  Only the A fragments are double-buffered.
+    bf16x8 fa[2][MI], fb[NI];
+    auto kstep = [&](int k, int s, auto cur_, auto reload_) __attribute__((always_inline)) {
+        constexpr int cur = decltype(cur_)::value;
+        constexpr bool reload = decltype(reload_)::value;   // fragments of k-step s + 1 of the same slab
+        if (reload) load_a(k, s + 1, fa[cur ^ 1]);
 #pragma unroll
-        for (int i = 0; i < MI; ++i)
+        for (int j = 0; j < NI; ++j) {
 #pragma unroll
-            for (int j = 0; j < NI; ++j) acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[i], fb[j], acc[i][j], 0, 0, 0);
-    };
-    constexpr int kReads = MI + NI, kMfma = MI * NI;
-    static_assert(kMfma >= kReads, "the hint pairs every fragment read with an MFMA");
-    // one k-step: MFMAs with n_reads fragment reads (of the next k-step) and n_dma DMA issues spread underneath
-    auto interleave_hint = [&](auto n_reads_, auto n_dma_, auto sync_id) __attribute__((always_inline)) {
-        constexpr int kId = decltype(sync_id)::value;
-        constexpr int n_reads = decltype(n_reads_)::value, n_dma = decltype(n_dma_)::value;
-        constexpr int slots = kReads;
-#pragma unroll
-        for (int r = 0; r < slots; ++r) {
-            __builtin_amdgcn_sched_group_barrier(0x008, 1, kId);                                    // MFMA
-            if (r < n_dma) __builtin_amdgcn_sched_group_barrier(0x020, 1, kId);                     // VMEM read (LDS DMA)
-            if (r < n_reads) __builtin_amdgcn_sched_group_barrier(0x100, 1, kId);                   // DS read
+            for (int i = 0; i < MI; ++i) acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[cur][i], fb[j], acc[i][j], 0, 0, 0);
+            if (reload) fb[j] = load_b1(k, s + 1, j);
         }
-        __builtin_amdgcn_sched_group_barrier(0x008, kMfma - slots, kId);
     };
+    // scheduling hint for one k-step with n_dma DMA issues: per column, MI MFMAs with one A read, the DMA issues and
+    // the W reload placed among them
+    auto kstep_hint = [&](auto reload_, auto n_dma_, auto sync_id) __attribute__((always_inline)) {
+        constexpr int kId = decltype(sync_id)::value;
+        constexpr bool reload = decltype(reload_)::value;
+        constexpr int n_dma = decltype(n_dma_)::value;
+        constexpr int per_col = (n_dma + NI - 1) / NI;
+#pragma unroll
+        for (int j = 0; j < NI; ++j) {
+            __builtin_amdgcn_sched_group_barrier(0x008, 1, kId);                                           // MFMA
+            if (reload && j < MI) __builtin_amdgcn_sched_group_barrier(0x100, 1, kId);                     // DS read (A)
+#pragma unroll
+            for (int t = 0; t < per_col; ++t)
+                if (j * per_col + t < n_dma) __builtin_amdgcn_sched_group_barrier(0x020, 1, kId);          // VMEM read (LDS DMA)
+            __builtin_amdgcn_sched_group_barrier(0x008, MI - 1, kId);                                      // MFMA
+            if (reload) __builtin_amdgcn_sched_group_barrier(0x100, 1, kId);                               // DS read (W)
+        }
+    };
+    static_assert(MI <= NI, "one A read per column");
     using C0 = std::integral_constant<int, 0>;
-    using CReads = std::integral_constant<int, kReads>;
+    using C1 = std::integral_constant<int, 1>;
     using CDmaA = std::integral_constant<int, DMA_A>;
     using CDmaB = std::integral_constant<int, DMA_B>;
-    static_assert(DMA_A <= kReads && DMA_B <= kReads, "a k-step hosts at most one DMA issue per fragment read");
+    using T_ = std::true_type;
+    using F_ = std::false_type;
 
     // ---- prologue
     issue_a(0);
@@ -688,38 +702,38 @@ __global__ __launch_bounds__(128 * kWavesM) void gemm_bf16_wide_kernel(const cha
         wait_vmcnt<0>();
     }
     block_barrier();
-    bf16x8 fa[2][MI], fb[2][NI];
-    load_frags(0, 0, fa[0], fb[0]);
+    load_a(0, 0, fa[0]);
+#pragma unroll
+    for (int j = 0; j < NI; ++j) fb[j] = load_b1(0, 0, j);
 
     // slab k.  first / second: the DMA halves issued under k-steps 0 and 1:
     //   deep ring:  W rows of slab k + 1 (into the unit slab k - 1 freed), then A rows of slab k + 2
     //   two stages: A rows, then W rows of slab k + 1
     auto slab = [&](int k, auto has_next, auto first, auto second) __attribute__((always_inline)) {
         // k-step 0
-        load_frags(k, 1, fa[1], fb[1]);
         if (first) { if (kDeep) issue_b(k + 1); else issue_a(k + 1); }
-        mma_step(fa[0], fb[0]);
-        if (first) { if (kDeep) interleave_hint(CReads{}, CDmaB{}, std::integral_constant<int, 0>{}); else interleave_hint(CReads{}, CDmaA{}, std::integral_constant<int, 0>{}); }
-        else interleave_hint(CReads{}, C0{}, std::integral_constant<int, 0>{});
+        kstep(k, 0, C0{}, T_{});
+        if (first) { if (kDeep) kstep_hint(T_{}, CDmaB{}, std::integral_constant<int, 0>{}); else kstep_hint(T_{}, CDmaA{}, std::integral_constant<int, 0>{}); }
+        else kstep_hint(T_{}, C0{}, std::integral_constant<int, 0>{});
         __builtin_amdgcn_sched_barrier(0);
         // k-step 1
-        load_frags(k, 2, fa[0], fb[0]);
         if (second) { if (kDeep) issue_a(k + 2); else issue_b(k + 1); }
-        mma_step(fa[1], fb[1]);
-        if (second) { if (kDeep) interleave_hint(CReads{}, CDmaA{}, std::integral_constant<int, 1>{}); else interleave_hint(CReads{}, CDmaB{}, std::integral_constant<int, 1>{}); }
-        else interleave_hint(CReads{}, C0{}, std::integral_constant<int, 1>{});
+        kstep(k, 1, C1{}, T_{});
+        if (second) { if (kDeep) kstep_hint(T_{}, CDmaA{}, std::integral_constant<int, 1>{}); else kstep_hint(T_{}, CDmaB{}, std::integral_constant<int, 1>{}); }
+        else kstep_hint(T_{}, C0{}, std::integral_constant<int, 1>{});
         __builtin_amdgcn_sched_barrier(0);
         // k-step 2
-        load_frags(k, 3, fa[1], fb[1]);
-        mma_step(fa[0], fb[0]);
-        interleave_hint(CReads{}, C0{}, std::integral_constant<int, 2>{});
+        kstep(k, 2, C0{}, T_{});
+        kstep_hint(T_{}, C0{}, std::integral_constant<int, 2>{});
         __builtin_amdgcn_sched_barrier(0);
         // k-step 3, then the slab boundary: slab k + 1 has landed for every wave, every wave is done with slab k
-        mma_step(fa[1], fb[1]);
+        kstep(k, 3, C1{}, F_{});
         if (has_next) {
             if (kDeep && second) wait_vmcnt<DMA_A>(); else wait_vmcnt<0>();
             block_barrier();
-            load_frags(k + 1, 0, fa[0], fb[0]);
+            load_a(k + 1, 0, fa[0]);
+#pragma unroll
+            for (int j = 0; j < NI; ++j) fb[j] = load_b1(k + 1, 0, j);
         }
     };
     struct Yes { constexpr operator bool() const { return true; } };
@@ -840,7 +854,7 @@ int32_t launch_fast(const GemmArgs& g, hipStream_t stream) {
     constexpr int kWavesM = ATTS_FAST_WAVES_M;
     const bool wide = ATTS_GEMM_WIDE && kWavesM == 4 && g.Kd % 64 == 0 && g.Kd >= 12 * 64;
     if (fast_tile_rows(EPI, g) == 384)
-        return launch_fast_tile<EPI, 12 / kWavesM>(g, stream);
+        return wide ? launch_wide_tile<EPI, 12 / kWavesM>(g, stream) : launch_fast_tile<EPI, 12 / kWavesM>(g, stream);
     return wide ? launch_wide_tile<EPI, 8 / kWavesM>(g, stream) : launch_fast_tile<EPI, 8 / kWavesM>(g, stream);
 }
 
