@@ -673,6 +673,7 @@ __global__ __launch_bounds__(128 * kWavesM) void gemm_bf16_wide_kernel(const cha
         constexpr bool reload = decltype(reload_)::value;
         constexpr int n_dma = decltype(n_dma_)::value;
         constexpr int per_col = (n_dma + NI - 1) / NI;
+        if (MI < 3) return;   // measured: the 256-row tile does better with the compiler's own order
 #pragma unroll
         for (int j = 0; j < NI; ++j) {
             __builtin_amdgcn_sched_group_barrier(0x008, 1, kId);                                           // MFMA
