@@ -672,12 +672,14 @@ __global__ __launch_bounds__(128 * kWavesM) void gemm_bf16_wide_kernel(const cha
         constexpr int kId = decltype(sync_id)::value;
         constexpr bool reload = decltype(reload_)::value;
         constexpr int n_dma = decltype(n_dma_)::value;
-        constexpr int per_col = (n_dma + NI - 1) / NI;
+        constexpr int per_col = (n_dma + NI - 1) / NI, a_per_col = (MI + NI - 1) / NI;
         if (MI < 3) return;   // measured: the 256-row tile does better with the compiler's own order
 #pragma unroll
         for (int j = 0; j < NI; ++j) {
             __builtin_amdgcn_sched_group_barrier(0x008, 1, kId);                                           // MFMA
-            if (reload && j < MI) __builtin_amdgcn_sched_group_barrier(0x100, 1, kId);                     // DS read (A)
+#pragma unroll
+            for (int t = 0; t < a_per_col; ++t)
+                if (reload && j * a_per_col + t < MI) __builtin_amdgcn_sched_group_barrier(0x100, 1, kId);  // DS read (A)
 #pragma unroll
             for (int t = 0; t < per_col; ++t)
                 if (j * per_col + t < n_dma) __builtin_amdgcn_sched_group_barrier(0x020, 1, kId);          // VMEM read (LDS DMA)
@@ -685,7 +687,6 @@ __global__ __launch_bounds__(128 * kWavesM) void gemm_bf16_wide_kernel(const cha
             if (reload) __builtin_amdgcn_sched_group_barrier(0x100, 1, kId);                               // DS read (W)
         }
     };
-    static_assert(MI <= NI, "one A read per column");
     using C0 = std::integral_constant<int, 0>;
     using C1 = std::integral_constant<int, 1>;
     using CDmaA = std::integral_constant<int, DMA_A>;
@@ -853,7 +854,7 @@ int32_t launch_wide_tile(const GemmArgs& g, hipStream_t stream) {
 template <int EPI>
 int32_t launch_fast(const GemmArgs& g, hipStream_t stream) {
     constexpr int kWavesM = ATTS_FAST_WAVES_M;
-    const bool wide = ATTS_GEMM_WIDE && kWavesM == 4 && g.Kd % 64 == 0 && g.Kd >= 12 * 64;
+    const bool wide = ATTS_GEMM_WIDE && g.Kd % 64 == 0 && g.Kd >= 12 * 64;
     if (fast_tile_rows(EPI, g) == 384)
         return wide ? launch_wide_tile<EPI, 12 / kWavesM>(g, stream) : launch_fast_tile<EPI, 12 / kWavesM>(g, stream);
     return wide ? launch_wide_tile<EPI, 8 / kWavesM>(g, stream) : launch_fast_tile<EPI, 8 / kWavesM>(g, stream);
