@@ -28,8 +28,8 @@ HBM_PEAK_GBS = 8000.0
 # (FETCH_SIZE, then WRITE_SIZE), each scaled by what the same counter reads for a plain device copy of known
 # size (--traffic-probe); see profiles/traffic_gemm_gate_up_7b.txt.  Valid only for the kernel source it was
 # taken with: reported as null when the hash of csrc/gemm.hip differs.
-MEASURED_TRAFFIC = {"gemm_sha256": "2fa25c5400cb092a27abd892d9f22254bb5ad6fc151d5d9f9c785663eeab5d82",
-                    "workload": "7b", "bytes_per_launch": 2.697e9}
+MEASURED_TRAFFIC = {"gemm_sha256": "90fe7d583130e9daa75e6b34a3ece1f4eeb523a997ec14e5cd59e617699687bf",
+                    "workload": "7b", "bytes_per_launch": 2.100e9}
 
 
 def measured_traffic(workload):
@@ -191,6 +191,8 @@ def main():
     ap.add_argument("--cpu-layers", type=int, default=2)
     ap.add_argument("--traffic-probe", action="store_true",
                     help="also run one plain 1 GiB device-to-device copy (reference for scaling HBM counters)")
+    ap.add_argument("--skip-extras", action="store_true",
+                    help="leave out the calibration-only, out-of-cache and decode-shaped measurements (profiling runs)")
     ap.add_argument("--calib-batches", type=int, default=-1,
                     help="scoring passes used to pre-sample the calibration set (-1: all ceil(n_cal / K) for tiny/7b, "
                          "2 for the larger models); the rest is drawn from a normal fitted to those scores")
@@ -322,13 +324,13 @@ def main():
         "conformal_decisions_per_s": wl.K * args.steps / dt,
         "algorithmic_tflop_per_step": fl["total"] / 1e12,
         "whole_step_mfma_frac": fl["total"] / (dt / args.steps) / 1e12 / peak,
-        "roofline": {"bound": "mfma", "kernel": f"gemm_nt_kernel<{cfg.dtype}, SwiGLU epilogue> (gate/up projection)",
+        "roofline": {"bound": "mfma", "kernel": f"aligned {cfg.dtype} GEMM, SwiGLU epilogue (gate/up projection)",
                      "achieved": achieved, "peak": peak, "unit": "TFLOP/s", "frac": achieved / peak,
                      "avg_launch_ms": dom_avg_ms, "flops_per_launch": dom_flops,
                      "traffic": measured_traffic(args.workload)},
         "stages": stages,
     }
-    if args.workload != "tiny":
+    if args.workload != "tiny" and not args.skip_extras:
         out["calibration_stage"] = bench_calibration(A, torch, np)
         out["calibration_stage_scaled"] = bench_calibration(A, torch, np, steps=4, scaled=True)
         out["decode_shaped"] = bench_decode_shaped(A, torch, model, cfg, wl, L)
