@@ -39,7 +39,7 @@ constexpr int kSortChunk = 8192;    // keys per block-sort workgroup
 constexpr int kSortThreads = 1024;
 constexpr int kMergeThreads = 256;
 constexpr int kMergeSegSmall = 2048;   // outputs per merge workgroup: cache-resident sizes (more workgroups)
-constexpr int kMergeSegLarge = 8192;   // ... and streaming sizes (the split search is amortised over more keys)
+constexpr int kMergeSegLarge = 4096;   // ... and streaming sizes (split search amortised over more keys; 8 workgroups per CU)
 constexpr int64_t kMergeLargeFrom = (int64_t)1 << 22;
 constexpr int kMaxMultiwayRuns = 16;
 constexpr uint32_t kPadKey = 0xFFFFFFFFu;   // above the key of +inf (0xFF800000)
