@@ -30,11 +30,15 @@ What is defined here, and from where:
   * online calibration (paragraph "Online Calibration"): the calibration multiset grows
     by the scores of newly pre-sampled outputs; every rank refers to the multiset as it
     stands at that moment.
+  * conditional coverage (same paragraph, last sentence; Proposition 2): the same rank,
+    p-value and classes, but each input's candidates are compared with that input's own
+    calibration scores only.
 
 Pins (see tests/test_oracle_*.py): closed forms for the log-softmax and for degenerate
 models, causal-prefix invariances of the forward pass, the uniform distribution of
 p-values for distinct scores and the tie formula of Proposition 1's proof, exact
-enumeration of the coverage guarantee, equivalence of the rank rule with the classic
+enumeration of the coverage guarantee (marginal, and per input for the conditional
+variant: Proposition 2's uniform law), equivalence of the rank rule with the classic
 quantile rule, and hand-worked fixtures under tests/golden/.  The decoder forward has no
 paper-printed numeric example: beyond the invariants and closed forms it is
 "parity unpinned" to any external numeric source.
@@ -235,6 +239,28 @@ def quantile_thresholds(cal: np.ndarray, ranks_r: np.ndarray) -> np.ndarray:
         kth = n + 1 - int(r)
         out[l] = np.inf if kth > n else (-np.inf if kth < 1 else srt[kth - 1])
     return out
+
+
+def conditional_classify(cal_sets, test_sets, alphas: Sequence[float]):
+    """Conditional coverage (Sec. Q2, last sentence of "Online Calibration"; Proposition 2): the candidates of
+    input xi are ranked against the calibration scores of the SAME input only.
+
+    For every input xi with its own m_xi calibration scores and its test scores s:
+        c = #{j : s <= cal_xi[j]},  p = (c + 1) / (m_xi + 1),  class = #{l : c + 1 <= floor(alpha_l (m_xi + 1))}.
+    The comparison direction and the integer form of "p <= alpha" are those of the marginal rule; only the set
+    compared against changes (and with it the normaliser: m_xi + 1, as in Proposition 2's uniform law).
+    Returns three lists (counts int64, p binary64, classes uint8), one array per input.
+    """
+    assert len(cal_sets) == len(test_sets)
+    counts, ps, classes = [], [], []
+    for cal, test in zip(cal_sets, test_sets):
+        cal = np.asarray(cal, dtype=F64)
+        c = rank_counts(cal, np.asarray(test, dtype=F64))
+        r = reject_ranks(alphas, len(cal))
+        counts.append(c)
+        ps.append(p_values(c, len(cal)))
+        classes.append(classify(c, r))
+    return counts, ps, classes
 
 
 class CalibrationSet:

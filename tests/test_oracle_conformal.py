@@ -224,3 +224,73 @@ def test_score_modes():
     assert math.isclose(O.conformity_score(lp, O.SUM_NLL), 37 * O.conformity_score(lp, O.MEAN_NLL))
     assert O.conformity_score(lp, O.MEAN_NLL) > 0          # NLL: larger = less conforming
     assert math.isclose(O.conformity_score(lp, O.SUM_NLL), -math.fsum(lp))
+
+
+# ---- conditional coverage (Proposition 2): every input ranked against its own calibration scores --------
+
+def _read_conditional_fixture():
+    alphas, inputs, cur = None, [], None
+    for line in open(os.path.join(os.path.dirname(GOLDEN), "conditional_small.txt")).read().splitlines():
+        line = line.split("#")[0].strip()
+        if not line:
+            continue
+        key, *vals = line.split()
+        if key == "alpha":
+            alphas = [float(v) for v in vals]
+        elif key == "cal":
+            cur = {"cal": [float(v) for v in vals]}
+            inputs.append(cur)
+        elif key == "pden":
+            cur[key] = int(vals[0])
+        elif key == "test":
+            cur[key] = [float(v) for v in vals]
+        else:
+            cur[key] = [int(v) for v in vals]
+    return alphas, inputs
+
+
+def test_conditional_golden_fixture():
+    alphas, inputs = _read_conditional_fixture()
+    c, p, cls = O.conditional_classify([i["cal"] for i in inputs], [i["test"] for i in inputs], alphas)
+    for k, i in enumerate(inputs):
+        assert c[k].tolist() == i["count"], k
+        assert cls[k].tolist() == i["class"], k
+        assert np.array_equal(p[k], np.array(i["pnum"], dtype=np.float64) / i["pden"]), k
+
+
+def test_conditional_uniform_law_by_enumeration():
+    """Proposition 2: with m distinct calibration scores of the input and one candidate, all exchangeable, the
+    candidate's p-value is uniform on {1/(m+1), ..., 1}: enumerate every ordering of m + 1 distinct values and
+    let each position be the candidate once."""
+    import itertools
+    for m in (1, 2, 4, 5):
+        vals = np.arange(1.0, m + 2.0)
+        hist = np.zeros(m + 2, dtype=np.int64)
+        for perm in itertools.permutations(vals):
+            c, p, _ = O.conditional_classify([perm[:m]], [[perm[m]]], [0.5])
+            hist[int(c[0][0]) + 1] += 1
+            assert p[0][0] == (c[0][0] + 1) / (m + 1)
+        assert hist[0] == 0 and len(set(hist[1:])) == 1                    # every value k/(m+1) equally often
+        for alpha in (0.1, 0.34, 0.5, 0.8):                               # hence P(p <= alpha) = floor(alpha(m+1))/(m+1) <= alpha
+            rej = sum(hist[k] for k in range(1, m + 2) if k / (m + 1) <= alpha) / hist.sum()
+            assert rej == math.floor(alpha * (m + 1)) / (m + 1) <= alpha
+
+
+def test_conditional_is_the_marginal_rule_per_input_and_inputs_do_not_interact():
+    rng = np.random.default_rng(5)
+    cal = [np.round(rng.lognormal(size=n), 1) for n in (0, 1, 16, 33, 128)]
+    test = [np.round(rng.lognormal(size=n), 1) for n in (3, 0, 16, 64, 7)]
+    alphas = [0.05, 0.2, 0.2, 0.7]
+    c, p, cls = O.conditional_classify(cal, test, alphas)
+    for k in range(len(cal)):
+        ck = O.rank_counts_sorted(cal[k], test[k]) if len(cal[k]) else np.zeros(len(test[k]), dtype=np.int64)
+        assert np.array_equal(c[k], ck)
+        assert np.array_equal(cls[k], O.classify(ck, O.reject_ranks(alphas, len(cal[k]))))
+        assert np.array_equal(p[k], O.p_values(ck, len(cal[k])))
+    order = [3, 0, 4, 2, 1]
+    c2, p2, cls2 = O.conditional_classify([cal[i] for i in order], [test[i] for i in order], alphas)
+    for pos, i in enumerate(order):
+        assert np.array_equal(c2[pos], c[i]) and np.array_equal(cls2[pos], cls[i])
+    # pooling the inputs (the marginal rule) gives different counts: the two notions really differ
+    pooled = O.rank_counts(np.concatenate(cal), test[3])
+    assert not np.array_equal(pooled, c[3])
