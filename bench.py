@@ -154,6 +154,28 @@ def bench_calibration(A, torch, np, steps=16, scaled=False):
     return out
 
 
+def bench_conditional(A, torch, np, S=4096, m=64, k=64, reps=20):
+    """Conditional coverage: S inputs, each ranks its k candidates against its own m calibration scores."""
+    from synth import WORKLOADS, lognormal_scores
+    wl = WORKLOADS["calib"]
+    cal = torch.from_numpy(lognormal_scores(S * m, wl.seed + 31)).cuda()
+    test = torch.from_numpy(lognormal_scores(S * k, wl.seed + 32)).cuda()
+    cal_off = torch.arange(0, S * m + 1, m, dtype=torch.int64, device="cuda")
+    test_off = torch.arange(0, S * k + 1, k, dtype=torch.int64, device="cuda")
+    ranks = torch.empty(S * k, dtype=torch.int32, device="cuda")
+    cls = torch.empty(S * k, dtype=torch.uint8, device="cuda")
+    for _ in range(3):
+        A.atts_classify_conditional(cal, cal_off, test, test_off, list(wl.alphas), ranks, None, cls)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(reps):
+        A.atts_classify_conditional(cal, cal_off, test, test_off, list(wl.alphas), ranks, None, cls)
+    torch.cuda.synchronize()
+    dt = (time.perf_counter() - t0) / reps
+    return {"workload": f"{S} inputs x {m} own calibration scores x {k} candidates, alphas {list(wl.alphas)}",
+            "us_per_call": dt * 1e6, "decisions_per_s": S * k / dt, "comparisons_per_s": S * m * k / dt}
+
+
 def bench_decode_shaped(A, torch, model, cfg, wl, L, P=16, K=16, T=8, steps=5):
     """The same resident model at a decode-like shape (P + K T = 144 rows, well under the ~315 flop/byte ridge):
     one scoring pass must stream every layer's weights and the LM head from HBM once, so it is timed against the
@@ -334,6 +356,7 @@ def main():
         out["calibration_stage"] = bench_calibration(A, torch, np)
         out["calibration_stage_scaled"] = bench_calibration(A, torch, np, steps=4, scaled=True)
         out["decode_shaped"] = bench_decode_shaped(A, torch, model, cfg, wl, L)
+        out["conditional_stage"] = bench_conditional(A, torch, np)
     if not args.no_cpu_baseline:
         p0, d0 = ids[0]
         out["cpu_baseline"] = cpu_baseline(cfg, wl, w, p0.cpu().numpy(), d0.cpu().numpy(), L, min(args.cpu_layers, L))

@@ -197,7 +197,7 @@ int32_t atts_attention_shared_prefix(int32_t dtype, const void* qkv, void* out,
 #define ATTS_STAGE_REDUCE      10   /* partial combine + score reduction                    */
 #define ATTS_STAGE_CALIB_SORT  11   /* atts_calibrate_online: sorting the new batch         */
 #define ATTS_STAGE_CALIB_MERGE 12   /* atts_calibrate_online: merge into the resident array */
-#define ATTS_STAGE_CLASSIFY    13   /* atts_classify_ordinal                                */
+#define ATTS_STAGE_CLASSIFY    13   /* atts_classify_ordinal, atts_classify_conditional     */
 #define ATTS_STAGE_COUNT       14
 
 /* on != 0: start recording (clears earlier records); on == 0: stop and drop the records. */
@@ -244,6 +244,26 @@ int32_t atts_classify_ordinal(const atts_calib* calib, const float* test_scores,
                               const double* alphas, int32_t n_alpha,
                               int32_t* ranks, float* pvalues, uint8_t* classes, float* thresholds,
                               void* hip_stream);
+
+/* Conditional coverage (Sec. "Q2", paragraph "Online Calibration", last sentence; Proposition 2): the candidates of
+ * every input are ranked against the calibration scores of the SAME input only.  For input x (0 <= x < n_inputs)
+ * with m_x = cal_offsets[x + 1] - cal_offsets[x] own calibration scores and its candidates
+ * t in [test_offsets[x], test_offsets[x + 1]):
+ *     ranks[t]   = #{ j in input x : test_scores[t] <= cal_scores[j] }
+ *     pvalues[t] = (ranks[t] + 1) / (m_x + 1)
+ *     r_l        = floor(alphas[l] * (m_x + 1))   in binary64
+ *     classes[t] = #{ l : ranks[t] + 1 <= r_l }
+ * i.e. atts_classify_ordinal's rule with the input's own m_x scores as the calibration set (an input without
+ * calibration scores accepts everything: p = 1).  NaN, -0 and +-inf behave as there.  No handle: the scores
+ * need not be sorted and nothing is kept.
+ *   cal_scores dev float [cal_offsets[n_inputs]]; test_scores dev float [test_offsets[n_inputs]];
+ *   cal_offsets, test_offsets dev int64 [n_inputs + 1], non-decreasing, first entry 0 (read by the kernel only:
+ *   a decreasing pair is treated as an empty range); alphas HOST double [n_alpha] as for atts_classify_ordinal;
+ *   ranks dev int32, pvalues dev float or NULL, classes dev uint8: one entry per test score.
+ * One wavefront per input: meant for many small sets (tens to a few thousand scores each). */
+int32_t atts_classify_conditional(const float* cal_scores, const int64_t* cal_offsets, const float* test_scores,
+                                  const int64_t* test_offsets, int64_t n_inputs, const double* alphas, int32_t n_alpha,
+                                  int32_t* ranks, float* pvalues, uint8_t* classes, void* hip_stream);
 
 /* Copies the multiset, in ascending order (NaNs first), to out dev float [size]. */
 int32_t atts_calib_export(const atts_calib* calib, float* out, void* hip_stream);

@@ -28,7 +28,7 @@ EXPORTS = (
     "atts_score_drafts", "atts_model_check", "atts_lmhead_workspace_bytes", "atts_lmhead_logprobs",
     "atts_gemm_nt", "atts_attention_workspace_bytes", "atts_attention_shared_prefix",
     "atts_calib_create", "atts_calib_destroy", "atts_calib_size", "atts_calib_reset",
-    "atts_calibrate_online", "atts_classify_ordinal", "atts_calib_export",
+    "atts_calibrate_online", "atts_classify_ordinal", "atts_classify_conditional", "atts_calib_export",
     "atts_profile_enable", "atts_profile_read",
 )
 
@@ -258,6 +258,31 @@ def atts_classify_ordinal(calib: Calib, test_scores: torch.Tensor, alphas: Seque
                                       _ptr(ranks, torch.int32, "ranks"), _ptr(pvalues, torch.float32, "pvalues"),
                                       _ptr(classes, torch.uint8, "classes"),
                                       _ptr(thresholds, torch.float32, "thresholds"), _stream()))
+
+
+def atts_classify_conditional(cal_scores: torch.Tensor, cal_offsets: torch.Tensor, test_scores: torch.Tensor,
+                              test_offsets: torch.Tensor, alphas: Sequence[float], ranks: torch.Tensor,
+                              pvalues: Optional[torch.Tensor], classes: torch.Tensor) -> None:
+    n_inputs = cal_offsets.numel() - 1
+    if n_inputs < 0 or test_offsets.numel() != n_inputs + 1:
+        raise AttsError(ERR_INVALID_ARG, "cal_offsets and test_offsets must both have n_inputs + 1 elements")
+    M = test_scores.numel()
+    if ranks.numel() != M or classes.numel() != M or (pvalues is not None and pvalues.numel() != M):
+        raise AttsError(ERR_INVALID_ARG, "ranks / pvalues / classes must have one element per test score")
+    arr = (ctypes.c_double * max(len(alphas), 1))(*[float(a) for a in alphas])
+    if n_inputs > 0:                       # the library wants non-NULL arrays; an empty tensor has no address
+        spare = torch.zeros(1, dtype=torch.float32, device=cal_offsets.device)
+        cal_scores = cal_scores if cal_scores.numel() else spare
+        if M == 0:
+            test_scores, ranks, classes = spare, spare.to(torch.int32), spare.to(torch.uint8)
+            pvalues = None
+    _check(_lib.atts_classify_conditional(_ptr(cal_scores, torch.float32, "cal_scores"),
+                                          _ptr(cal_offsets, torch.int64, "cal_offsets"),
+                                          _ptr(test_scores, torch.float32, "test_scores"),
+                                          _ptr(test_offsets, torch.int64, "test_offsets"), ctypes.c_int64(n_inputs),
+                                          arr, ctypes.c_int32(len(alphas)), _ptr(ranks, torch.int32, "ranks"),
+                                          _ptr(pvalues, torch.float32, "pvalues"), _ptr(classes, torch.uint8, "classes"),
+                                          _stream()))
 
 
 def atts_calib_export(calib: Calib, out: torch.Tensor) -> None:

@@ -448,6 +448,54 @@ __global__ __launch_bounds__(256) void classify_kernel(SearchIndex ix, const flo
     }
 }
 
+// ---- conditional coverage: one wavefront per input, its own calibration scores as the set ------------------
+struct ConditionalLevels {
+    double alpha[ATTS_MAX_ALPHAS];
+    int32_t n_alpha;
+};
+
+__global__ __launch_bounds__(256) void conditional_kernel(const float* __restrict__ cal, const int64_t* __restrict__ cal_off,
+                                                          const float* __restrict__ test, const int64_t* __restrict__ test_off,
+                                                          int64_t n_inputs, ConditionalLevels lv, int32_t* __restrict__ ranks,
+                                                          float* __restrict__ pvalues, uint8_t* __restrict__ classes) {
+    const int lane = threadIdx.x & 63;
+    const int64_t x = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
+    if (x >= n_inputs) return;                                   // whole wavefronts leave together
+    const int64_t c0 = cal_off[x], t0 = test_off[x];
+    const int64_t m = max((int64_t)0, cal_off[x + 1] - c0), k = max((int64_t)0, test_off[x + 1] - t0);
+    int64_t r[ATTS_MAX_ALPHAS];
+#pragma unroll
+    for (int l = 0; l < ATTS_MAX_ALPHAS; ++l) r[l] = l < lv.n_alpha ? (int64_t)floor(lv.alpha[l] * (double)(m + 1)) : 0;
+    // 64 candidates at a time, one per lane; the calibration scores pass by in blocks of 64 held one per lane and
+    // broadcast lane by lane
+    for (int64_t tb = 0; tb < k; tb += 64) {
+        const bool has = tb + lane < k;
+        const float s = has ? test[t0 + tb + lane] : 0.f;
+        const uint32_t xk = score_to_key(s);
+        int64_t c = 0;
+        for (int64_t cb = 0; cb < m; cb += 64) {
+            const int nb = (int)min((int64_t)64, m - cb);        // wave-uniform
+            const uint32_t mine = lane < nb ? score_to_key(cal[c0 + cb + lane]) : 0u;   // key 0 (NaN) never counts
+            int cnt = 0;
+#pragma unroll
+            for (int j = 0; j < 64; ++j) {                        // lane j's key through a scalar register
+                const uint32_t kj = (uint32_t)__builtin_amdgcn_readlane((int)mine, j);
+                cnt += (j < nb && kj >= xk) ? 1 : 0;
+            }
+            c += cnt;
+        }
+        if (!has) continue;
+        if (score_is_nan(s)) c = 0;
+        const int64_t t = t0 + tb + lane;
+        ranks[t] = (int32_t)c;
+        if (pvalues) pvalues[t] = (float)((double)(c + 1) / (double)(m + 1));
+        int cls = 0;
+#pragma unroll
+        for (int l = 0; l < ATTS_MAX_ALPHAS; ++l) cls += (l < lv.n_alpha && c + 1 <= r[l]) ? 1 : 0;
+        classes[t] = (uint8_t)cls;
+    }
+}
+
 __global__ void export_kernel(const uint32_t* __restrict__ keys, int64_t n, float* __restrict__ out) {
     const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
     if (i < n) out[i] = key_to_score(keys[i]);
@@ -644,6 +692,36 @@ int32_t atts_classify_ordinal(const atts_calib* c, const float* test_scores, int
     hipLaunchKernelGGL(classify_kernel, dim3(blocks), dim3(256), 0, static_cast<hipStream_t>(hip_stream), ix, test_scores, M,
                        lv, ranks, pvalues, classes, thresholds);
     ATTS_LAUNCH_CHECK("classify_kernel");
+    return ATTS_OK;
+}
+
+int32_t atts_classify_conditional(const float* cal_scores, const int64_t* cal_offsets, const float* test_scores,
+                                  const int64_t* test_offsets, int64_t n_inputs, const double* alphas, int32_t n_alpha,
+                                  int32_t* ranks, float* pvalues, uint8_t* classes, void* hip_stream) {
+    if (n_inputs < 0) return fail(ATTS_ERR_INVALID_ARG, "atts_classify_conditional: n_inputs = %lld < 0", (long long)n_inputs);
+    if (!alphas || n_alpha < 1 || n_alpha > ATTS_MAX_ALPHAS)
+        return fail(ATTS_ERR_INVALID_ARG, "atts_classify_conditional: need 1..%d alpha levels", ATTS_MAX_ALPHAS);
+    ConditionalLevels lv;
+    lv.n_alpha = n_alpha;
+    for (int l = 0; l < ATTS_MAX_ALPHAS; ++l) lv.alpha[l] = 0.0;
+    for (int l = 0; l < n_alpha; ++l) {
+        if (!(alphas[l] > 0.0 && alphas[l] < 1.0))
+            return fail(ATTS_ERR_INVALID_ARG, "atts_classify_conditional: alpha[%d] = %g is not inside (0, 1)", l, alphas[l]);
+        if (l > 0 && alphas[l] < alphas[l - 1])
+            return fail(ATTS_ERR_INVALID_ARG, "atts_classify_conditional: alpha levels must be non-decreasing");
+        lv.alpha[l] = alphas[l];
+    }
+    if (n_inputs == 0) return ATTS_OK;
+    if (!cal_offsets || !test_offsets) return fail(ATTS_ERR_INVALID_ARG, "atts_classify_conditional: offsets must not be NULL");
+    // score and output arrays may be NULL only if every range is empty, which the host cannot see: require them
+    if (!cal_scores || !test_scores || !ranks || !classes)
+        return fail(ATTS_ERR_INVALID_ARG, "atts_classify_conditional: cal_scores, test_scores, ranks and classes must not be NULL");
+    if (n_inputs > ((int64_t)1 << 31) * 2) return fail(ATTS_ERR_INVALID_ARG, "atts_classify_conditional: too many inputs");
+    hipStream_t stream = static_cast<hipStream_t>(hip_stream);
+    StageTimer t_(ATTS_STAGE_CLASSIFY, stream);
+    hipLaunchKernelGGL(conditional_kernel, dim3((unsigned)ceil_div(n_inputs, 4)), dim3(256), 0, stream, cal_scores, cal_offsets,
+                       test_scores, test_offsets, n_inputs, lv, ranks, pvalues, classes);
+    ATTS_LAUNCH_CHECK("conditional_kernel");
     return ATTS_OK;
 }
 
