@@ -141,6 +141,42 @@ int32_t atts_score_drafts(const atts_model* model,
                           float* token_logprobs, float* scores,
                           void* workspace, size_t workspace_bytes, void* hip_stream);
 
+/* ------------------------------------------------------------------------------------
+ * Prefix handle: a prompt prefix prefilled once and reused across turns
+ *
+ * In the turn loop of the method (Sec. "How to perform rejection sampling via conformal prediction": sampling,
+ * verification, continuation, repeated) every turn's drafts continue the same context, and an accepted
+ * continuation becomes part of it; the serving engine the paper builds on keeps that context's keys and values
+ * instead of recomputing them.  The handle holds, per layer, the keys (after RoPE) and values of the prefix rows
+ * in the layouts the attention kernels read, plus the hidden state of the last row (the state that predicts the
+ * first token of every draft).
+ *
+ *   atts_prefix_create          an empty prefix that can grow to `capacity` rows (allocates device memory:
+ *                               2 L capacity n_kv head_dim elements of the model dtype)
+ *   atts_prefix_extend          runs the target model over n more tokens that continue the prefix (plain causal
+ *                               attention over the cached rows and themselves) and appends their keys / values;
+ *                               the first call on an empty handle is the prefill of the prompt.  ids dev int32 [n].
+ *                               Workspace as atts_prefix_extend_workspace_bytes says (scratch, nothing kept).
+ *                               ATTS_ERR_CAPACITY if length + n > capacity (nothing is changed).
+ *   atts_score_drafts_cached    atts_score_drafts with the handle in place of (prefix_ids, P): only the K T_max
+ *                               draft rows go through the model; same outputs, same workspace size as
+ *                               atts_workspace_bytes(model, length, K, T_max).  The handle is not modified.
+ *   atts_prefix_length / reset  rows held / forget them (capacity and memory are kept)
+ * The handle borrows the model (which must outlive it).  Calls that touch one handle must be ordered (one stream,
+ * or externally synchronised).  Out-of-range token ids behave as in atts_score_drafts.
+ * ---------------------------------------------------------------------------------- */
+typedef struct atts_prefix atts_prefix;
+int32_t atts_prefix_create(const atts_model* model, int32_t capacity, atts_prefix** out);
+int32_t atts_prefix_destroy(atts_prefix* prefix);
+int32_t atts_prefix_length(const atts_prefix* prefix, int32_t* out_rows);
+int32_t atts_prefix_reset(atts_prefix* prefix);
+int32_t atts_prefix_extend_workspace_bytes(const atts_prefix* prefix, int32_t n, size_t* out_bytes);
+int32_t atts_prefix_extend(atts_prefix* prefix, const int32_t* ids, int32_t n, void* workspace, size_t workspace_bytes,
+                           void* hip_stream);
+int32_t atts_score_drafts_cached(const atts_prefix* prefix, const int32_t* draft_ids, const int32_t* draft_lens, int32_t K,
+                                 int32_t T_max, int32_t score_mode, float* token_logprobs, float* scores, void* workspace,
+                                 size_t workspace_bytes, void* hip_stream);
+
 /* Synchronises hip_stream, copies the sticky device error flag to *host_flag (0 = clean,
  * 1 = some token id was out of range since the last check) and clears it. */
 int32_t atts_model_check(const atts_model* model, void* hip_stream, int32_t* host_flag);

@@ -25,7 +25,8 @@ MAX_ALPHAS = 8
 
 EXPORTS = (
     "atts_last_error_string", "atts_model_create", "atts_model_destroy", "atts_workspace_bytes",
-    "atts_score_drafts", "atts_model_check", "atts_lmhead_workspace_bytes", "atts_lmhead_logprobs",
+    "atts_score_drafts", "atts_model_check", "atts_prefix_create", "atts_prefix_destroy", "atts_prefix_length",
+    "atts_prefix_reset", "atts_prefix_extend_workspace_bytes", "atts_prefix_extend", "atts_score_drafts_cached", "atts_lmhead_workspace_bytes", "atts_lmhead_logprobs",
     "atts_gemm_nt", "atts_attention_workspace_bytes", "atts_attention_shared_prefix",
     "atts_calib_create", "atts_calib_destroy", "atts_calib_size", "atts_calib_reset",
     "atts_calibrate_online", "atts_classify_ordinal", "atts_classify_conditional", "atts_calib_export",
@@ -154,6 +155,63 @@ def atts_score_drafts(model: Model, prefix_ids: torch.Tensor, draft_ids: torch.T
     _check(_lib.atts_score_drafts(
         model.handle, _ptr(prefix_ids, torch.int32, "prefix_ids"), ctypes.c_int32(prefix_ids.numel()),
         _ptr(draft_ids, torch.int32, "draft_ids"), _ptr(draft_lens, torch.int32, "draft_lens"),
+        ctypes.c_int32(K), ctypes.c_int32(T_max), ctypes.c_int32(score_mode),
+        _ptr(token_logprobs, torch.float32, "token_logprobs"), _ptr(scores, torch.float32, "scores"),
+        _ptr(workspace, torch.uint8, "workspace"), ctypes.c_size_t(workspace.numel()), _stream()))
+
+
+class Prefix:
+    """Handle from atts_prefix_create (keys / values of a prompt prefix, kept across turns); keeps the model alive."""
+
+    def __init__(self, model: Model, capacity: int):
+        self.model = model
+        self.handle = ctypes.c_void_p()
+        _check(_lib.atts_prefix_create(model.handle, ctypes.c_int32(capacity), ctypes.byref(self.handle)))
+
+    def close(self) -> None:
+        if self.handle:
+            _lib.atts_prefix_destroy(self.handle)
+            self.handle = ctypes.c_void_p()
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
+
+
+def atts_prefix_length(prefix: Prefix) -> int:
+    out = ctypes.c_int32()
+    _check(_lib.atts_prefix_length(prefix.handle, ctypes.byref(out)))
+    return out.value
+
+
+def atts_prefix_reset(prefix: Prefix) -> None:
+    _check(_lib.atts_prefix_reset(prefix.handle))
+
+
+def atts_prefix_extend_workspace_bytes(prefix: Prefix, n: int) -> int:
+    out = ctypes.c_size_t()
+    _check(_lib.atts_prefix_extend_workspace_bytes(prefix.handle, ctypes.c_int32(n), ctypes.byref(out)))
+    return out.value
+
+
+def atts_prefix_extend(prefix: Prefix, ids: torch.Tensor, workspace: torch.Tensor) -> None:
+    _check(_lib.atts_prefix_extend(prefix.handle, _ptr(ids, torch.int32, "ids"), ctypes.c_int32(ids.numel()),
+                                   _ptr(workspace, torch.uint8, "workspace"), ctypes.c_size_t(workspace.numel()),
+                                   _stream()))
+
+
+def atts_score_drafts_cached(prefix: Prefix, draft_ids: torch.Tensor, draft_lens: Optional[torch.Tensor], score_mode: int,
+                             token_logprobs: Optional[torch.Tensor], scores: torch.Tensor,
+                             workspace: torch.Tensor) -> None:
+    K, T_max = draft_ids.shape
+    if token_logprobs is not None and tuple(token_logprobs.shape) != (K, T_max):
+        raise AttsError(ERR_INVALID_ARG, "token_logprobs must be [K, T_max]")
+    if scores.numel() != K or (draft_lens is not None and draft_lens.numel() != K):
+        raise AttsError(ERR_INVALID_ARG, "scores / draft_lens must have K elements")
+    _check(_lib.atts_score_drafts_cached(
+        prefix.handle, _ptr(draft_ids, torch.int32, "draft_ids"), _ptr(draft_lens, torch.int32, "draft_lens"),
         ctypes.c_int32(K), ctypes.c_int32(T_max), ctypes.c_int32(score_mode),
         _ptr(token_logprobs, torch.float32, "token_logprobs"), _ptr(scores, torch.float32, "scores"),
         _ptr(workspace, torch.uint8, "workspace"), ctypes.c_size_t(workspace.numel()), _stream()))

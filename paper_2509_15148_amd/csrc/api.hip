@@ -18,6 +18,19 @@ struct atts_model {
     int32_t* err_flag;   // device
 };
 
+// Keys and values of a prompt prefix, kept per layer as the attention kernels read them (keys after RoPE as rows,
+// values transposed for the MFMA attention kernel, else as rows), plus the hidden state of its last row.
+struct atts_prefix {
+    const atts_model* model;
+    int32_t capacity;     // rows the caches can hold
+    int32_t P;            // rows held
+    int64_t cap_ld;       // row pitch of the transposed-value cache (capacity rounded up to 64)
+    bool uses_vt;
+    char* k_cache;        // [L][capacity][n_kv hd]
+    char* v_cache;        // uses_vt: [L][n_kv hd][cap_ld]   else: [L][capacity][n_kv hd]
+    float* h_last;        // [d_model]
+};
+
 namespace atts {
 
 static thread_local char g_error[512] = "";
@@ -80,7 +93,8 @@ bool pads_rows(const atts_model_desc& d) { return d.dtype == ATTS_DTYPE_BF16; }
 Workspace carve(const atts_model_desc& d, ScoreShape s) {
     const size_t es = dtype_size(d.dtype);
     const size_t R = (size_t)s.R(), B = (size_t)s.B();
-    const size_t Ra = pads_rows(d) ? align_up(R, 768) : R, Ba = pads_rows(d) ? align_up(B, 768) : B;
+    // + one more block: with a cached prefix the GEMMs start at row P, not at row 0
+    const size_t Ra = pads_rows(d) ? align_up(R, 768) + 768 : R, Ba = pads_rows(d) ? align_up(B, 768) : B;
     Workspace w{};
     size_t off = 0;
     auto take = [&](size_t bytes) {
@@ -198,29 +212,29 @@ int32_t atts_workspace_bytes(const atts_model* m, int32_t P, int32_t K, int32_t 
     return ATTS_OK;
 }
 
-int32_t atts_score_drafts(const atts_model* m, const int32_t* prefix_ids, int32_t P, const int32_t* draft_ids,
-                          const int32_t* draft_lens, int32_t K, int32_t T_max, int32_t score_mode, float* token_logprobs,
-                          float* scores, void* workspace, size_t workspace_bytes, void* hip_stream) {
-    if (!m) return fail(ATTS_ERR_INVALID_ARG, "atts_score_drafts: NULL model");
-    if (!prefix_ids || !draft_ids || !scores) return fail(ATTS_ERR_INVALID_ARG, "atts_score_drafts: NULL prefix_ids / draft_ids / scores");
-    ATTS_TRY(check_score_shape("atts_score_drafts", P, K, T_max));
-    if (score_mode != ATTS_SCORE_MEAN_NLL && score_mode != ATTS_SCORE_SUM_NLL)
-        return fail(ATTS_ERR_INVALID_ARG, "atts_score_drafts: unknown score_mode %d", score_mode);
-    const atts_model_desc& d = m->desc;
-    const ScoreShape s{P, K, T_max};
-    const Workspace ws = carve(d, s);
-    if (!workspace || ((uintptr_t)workspace & 255)) return fail(ATTS_ERR_WORKSPACE, "atts_score_drafts: workspace is NULL or not 256-byte aligned");
-    if (workspace_bytes < ws.total)
-        return fail(ATTS_ERR_WORKSPACE, "atts_score_drafts: workspace has %zu bytes, %zu needed", workspace_bytes, ws.total);
+}  // extern "C"
 
-    hipStream_t st = static_cast<hipStream_t>(hip_stream);
+namespace atts {
+namespace {
+
+// The forward pass over rows [row0, R) of the token tree s = [prefix (P) | K drafts of T].
+//   row0 == 0:   everything is computed (pre == nullptr).
+//   row0 == P:   keys / values of the prefix rows come from `pre` (pre->P == P), copied into the workspace before
+//                each layer's attention.  save: the new rows' keys / values and the last row's hidden state are
+//                appended to `pre` (K == 1: the new rows continue the prefix as one causal sequence).
+// score: LM head + scores for the K T scoring rows (else the pass stops after the last layer).
+int32_t forward_tree(const atts_model* m, ScoreShape s, int32_t row0, atts_prefix* pre, bool save, bool score,
+                     const int32_t* prefix_ids, const int32_t* draft_ids, const int32_t* draft_lens, int32_t score_mode,
+                     float* token_logprobs, float* scores, void* workspace, hipStream_t st) {
+    const atts_model_desc& d = m->desc;
+    const Workspace ws = carve(d, s);
     char* base = static_cast<char*>(workspace);
     float* h = reinterpret_cast<float*>(base + ws.h);
-    void* xn = base + ws.xn;
-    void* qkv = base + ws.qkv;
-    void* vt = attention_uses_vt(d.dtype, d.head_dim) ? base + ws.vt : nullptr;
-    void* ao = base + ws.ao;
-    void* act = base + ws.act;
+    char* xn = base + ws.xn;
+    char* qkv = base + ws.qkv;
+    char* vt = attention_uses_vt(d.dtype, d.head_dim) ? base + ws.vt : nullptr;
+    char* ao = base + ws.ao;
+    char* act = base + ws.act;
     float2* rope = reinterpret_cast<float2*>(base + ws.rope);
     void* xs = base + ws.xs;
     int32_t* targets = reinterpret_cast<int32_t*>(base + ws.targets);
@@ -229,30 +243,35 @@ int32_t atts_score_drafts(const atts_model* m, const int32_t* prefix_ids, int32_
     float* zt = reinterpret_cast<float*>(base + ws.zt);
     float* lp = reinterpret_cast<float*>(base + ws.lp);
 
-    const int R = s.R(), B = s.B();
-    const int qd = d.n_q_heads * d.head_dim;
+    const size_t es = dtype_size(d.dtype);
+    const int R = s.R(), B = s.B(), M = R - row0;       // M rows go through the projections
+    const int qd = d.n_q_heads * d.head_dim, kvd = d.n_kv_heads * d.head_dim;
     const int qkv_out = (d.n_q_heads + 2 * d.n_kv_heads) * d.head_dim;
     const bool padded = pads_rows(d);
-    const bool fuse_rope = vt != nullptr && qkv_rope_fusable(d.dtype, R, qkv_out, d.d_model, d.head_dim, padded);
+    // the fused epilogue writes 4 transposed-V columns per store: the first computed row must keep them aligned
+    const bool fuse_rope = vt != nullptr && row0 % 4 == 0 && qkv_rope_fusable(d.dtype, M, qkv_out, d.d_model, d.head_dim, padded);
+    float* h0 = h + (size_t)row0 * d.d_model;
 
     {
         StageTimer t_(ATTS_STAGE_EMBED, st);
-        ATTS_TRY(launch_embed(d.dtype, m->tok_embed, d.vocab, d.d_model, prefix_ids, draft_ids, draft_lens, s, h, m->err_flag, st));
-        ATTS_TRY(launch_rope_table(rope, s, d.head_dim, d.rope_theta, st));
+        ATTS_TRY(launch_embed(d.dtype, m->tok_embed, d.vocab, d.d_model, prefix_ids, draft_ids, draft_lens, s, row0, h, m->err_flag, st));
+        ATTS_TRY(launch_rope_table(rope, s, row0, d.head_dim, d.rope_theta, st));
         // the fused QKV epilogue writes only the R real columns of V^T
-        if (fuse_rope) ATTS_TRY(launch_zero_vt_tail(d.dtype, vt, (int64_t)d.n_kv_heads * d.head_dim, R, ws.ldv, st));
+        if (fuse_rope) ATTS_TRY(launch_zero_vt_tail(d.dtype, vt, (int64_t)kvd, R, ws.ldv, st));
     }
     for (int l = 0; l < d.n_layers; ++l) {
         {
             StageTimer t_(ATTS_STAGE_NORM, st);
-            ATTS_TRY(launch_rmsnorm(d.dtype, h, m->attn_norm[l], d.rms_eps, R, d.d_model, xn, st));
+            ATTS_TRY(launch_rmsnorm(d.dtype, h0, m->attn_norm[l], d.rms_eps, M, d.d_model, xn + (size_t)row0 * d.d_model * es, st));
         }
         GemmArgs g{};
-        g.a = xn; g.w = m->wqkv[l]; g.out = qkv; g.M = R; g.N = qkv_out; g.Kd = d.d_model;
+        g.a = xn + (size_t)row0 * d.d_model * es; g.w = m->wqkv[l]; g.out = qkv + (size_t)row0 * qkv_out * es;
+        g.M = M; g.N = qkv_out; g.Kd = d.d_model;
         g.lda = d.d_model; g.ldw = d.d_model; g.ldc = qkv_out; g.a_rows_padded = padded;
         if (fuse_rope) {
             // QKV projection with RoPE and the V transpose applied to the accumulators
-            g.rope = rope; g.vt = vt; g.ldv = ws.ldv; g.n_rot_heads = d.n_q_heads + d.n_kv_heads;
+            g.rope = rope + (size_t)row0 * (d.head_dim / 2); g.vt = vt + (size_t)row0 * es; g.ldv = ws.ldv;
+            g.n_rot_heads = d.n_q_heads + d.n_kv_heads;
             StageTimer t_(ATTS_STAGE_GEMM_QKV, st);
             ATTS_TRY(launch_gemm(d.dtype, EPI_QKV_ROPE, g, st));
         } else {
@@ -261,14 +280,32 @@ int32_t atts_score_drafts(const atts_model* m, const int32_t* prefix_ids, int32_
                 ATTS_TRY(launch_gemm(d.dtype, EPI_STORE_ACT, g, st));
             }
             StageTimer t_(ATTS_STAGE_ROPE, st);
-            ATTS_TRY(launch_rope_split(d.dtype, qkv, rope, s, d.n_q_heads, d.n_kv_heads, d.head_dim, vt, ws.ldv, st));
+            ATTS_TRY(launch_rope_split(d.dtype, qkv, rope, s, row0, d.n_q_heads, d.n_kv_heads, d.head_dim, vt, ws.ldv, st));
+        }
+        if (pre) {
+            // keys / values of the cached prefix rows into place; in save mode the new rows' into the cache
+            StageTimer t_(ATTS_STAGE_ROPE, st);
+            char* kc = pre->k_cache + (size_t)l * pre->capacity * kvd * es;
+            char* wk = qkv + (size_t)qd * es;                                   // key columns of workspace row 0
+            ATTS_TRY(launch_copy2d(d.dtype, kc, kvd, wk, qkv_out, row0, kvd, st));
+            if (save) ATTS_TRY(launch_copy2d(d.dtype, wk + (size_t)row0 * qkv_out * es, qkv_out, kc + (size_t)row0 * kvd * es, kvd, M, kvd, st));
+            if (pre->uses_vt) {
+                char* vc = pre->v_cache + (size_t)l * kvd * pre->cap_ld * es;
+                ATTS_TRY(launch_copy2d(d.dtype, vc, pre->cap_ld, vt, ws.ldv, kvd, row0, st));
+                if (save) ATTS_TRY(launch_copy2d(d.dtype, vt + (size_t)row0 * es, ws.ldv, vc + (size_t)row0 * es, pre->cap_ld, kvd, M, st));
+            } else {
+                char* vc = pre->v_cache + (size_t)l * pre->capacity * kvd * es;
+                char* wv = qkv + (size_t)(qd + kvd) * es;
+                ATTS_TRY(launch_copy2d(d.dtype, vc, kvd, wv, qkv_out, row0, kvd, st));
+                if (save) ATTS_TRY(launch_copy2d(d.dtype, wv + (size_t)row0 * qkv_out * es, qkv_out, vc + (size_t)row0 * kvd * es, kvd, M, kvd, st));
+            }
         }
         {
             StageTimer t_(ATTS_STAGE_ATTENTION, st);
-            ATTS_TRY(launch_attention(d.dtype, qkv, vt, ws.ldv, ao, s, d.n_q_heads, d.n_kv_heads, d.head_dim, st));
+            ATTS_TRY(launch_attention(d.dtype, qkv, vt, ws.ldv, ao, s, row0, d.n_q_heads, d.n_kv_heads, d.head_dim, st));
         }
         g = GemmArgs{};
-        g.a = ao; g.w = m->wo[l]; g.out = h; g.M = R; g.N = d.d_model; g.Kd = qd;
+        g.a = ao + (size_t)row0 * qd * es; g.w = m->wo[l]; g.out = h0; g.M = M; g.N = d.d_model; g.Kd = qd;
         g.lda = qd; g.ldw = qd; g.ldc = d.d_model; g.a_rows_padded = padded;
         {
             StageTimer t_(ATTS_STAGE_GEMM_O, st);
@@ -276,23 +313,28 @@ int32_t atts_score_drafts(const atts_model* m, const int32_t* prefix_ids, int32_
         }
         {
             StageTimer t_(ATTS_STAGE_NORM, st);
-            ATTS_TRY(launch_rmsnorm(d.dtype, h, m->ffn_norm[l], d.rms_eps, R, d.d_model, xn, st));
+            ATTS_TRY(launch_rmsnorm(d.dtype, h0, m->ffn_norm[l], d.rms_eps, M, d.d_model, xn + (size_t)row0 * d.d_model * es, st));
         }
         g = GemmArgs{};
-        g.a = xn; g.w = m->w_gate_up[l]; g.out = act; g.M = R; g.N = d.d_ffn; g.Kd = d.d_model;
+        g.a = xn + (size_t)row0 * d.d_model * es; g.w = m->w_gate_up[l]; g.out = act + (size_t)row0 * d.d_ffn * es;
+        g.M = M; g.N = d.d_ffn; g.Kd = d.d_model;
         g.lda = d.d_model; g.ldw = d.d_model; g.ldc = d.d_ffn; g.a_rows_padded = padded;
         {
             StageTimer t_(ATTS_STAGE_GEMM_GATE_UP, st);
             ATTS_TRY(launch_gemm(d.dtype, EPI_SWIGLU, g, st));
         }
         g = GemmArgs{};
-        g.a = act; g.w = m->w_down[l]; g.out = h; g.M = R; g.N = d.d_model; g.Kd = d.d_ffn;
+        g.a = act + (size_t)row0 * d.d_ffn * es; g.w = m->w_down[l]; g.out = h0; g.M = M; g.N = d.d_model; g.Kd = d.d_ffn;
         g.lda = d.d_ffn; g.ldw = d.d_ffn; g.ldc = d.d_model; g.a_rows_padded = padded;
         {
             StageTimer t_(ATTS_STAGE_GEMM_DOWN, st);
             ATTS_TRY(launch_gemm(d.dtype, EPI_RESID_F32, g, st));
         }
     }
+    if (save) ATTS_HIP_TRY(hipMemcpyAsync(pre->h_last, h + (size_t)(R - 1) * d.d_model, d.d_model * sizeof(float), hipMemcpyDeviceToDevice, st));
+    if (!score) return ATTS_OK;
+    // the first token of every draft is predicted from the last prefix row
+    if (pre && row0 > 0) ATTS_HIP_TRY(hipMemcpyAsync(h + (size_t)(s.P - 1) * d.d_model, pre->h_last, d.d_model * sizeof(float), hipMemcpyDeviceToDevice, st));
     {
         StageTimer t_(ATTS_STAGE_GATHER_NORM, st);
         ATTS_TRY(launch_gather_norm(d.dtype, h, m->final_norm, d.rms_eps, d.d_model, draft_ids, draft_lens, d.vocab, s, xs,
@@ -309,9 +351,128 @@ int32_t atts_score_drafts(const atts_model* m, const int32_t* prefix_ids, int32_
     {
         StageTimer t_(ATTS_STAGE_REDUCE, st);
         ATTS_TRY(launch_lmhead_combine(partials, zt, B, ws.n_part, valid, lp, st));
-        ATTS_TRY(launch_score_reduce(lp, draft_lens, K, T_max, score_mode, token_logprobs, scores, st));
+        ATTS_TRY(launch_score_reduce(lp, draft_lens, s.K, s.T, score_mode, token_logprobs, scores, st));
     }
     return ATTS_OK;
+}
+
+int32_t check_workspace(const char* fn, const atts_model_desc& d, ScoreShape s, void* workspace, size_t workspace_bytes) {
+    const Workspace ws = carve(d, s);
+    if (!workspace || ((uintptr_t)workspace & 255)) return fail(ATTS_ERR_WORKSPACE, "%s: workspace is NULL or not 256-byte aligned", fn);
+    if (workspace_bytes < ws.total) return fail(ATTS_ERR_WORKSPACE, "%s: workspace has %zu bytes, %zu needed", fn, workspace_bytes, ws.total);
+    return ATTS_OK;
+}
+
+}  // namespace
+}  // namespace atts
+
+extern "C" {
+
+int32_t atts_score_drafts(const atts_model* m, const int32_t* prefix_ids, int32_t P, const int32_t* draft_ids,
+                          const int32_t* draft_lens, int32_t K, int32_t T_max, int32_t score_mode, float* token_logprobs,
+                          float* scores, void* workspace, size_t workspace_bytes, void* hip_stream) {
+    if (!m) return fail(ATTS_ERR_INVALID_ARG, "atts_score_drafts: NULL model");
+    if (!prefix_ids || !draft_ids || !scores) return fail(ATTS_ERR_INVALID_ARG, "atts_score_drafts: NULL prefix_ids / draft_ids / scores");
+    ATTS_TRY(check_score_shape("atts_score_drafts", P, K, T_max));
+    if (score_mode != ATTS_SCORE_MEAN_NLL && score_mode != ATTS_SCORE_SUM_NLL)
+        return fail(ATTS_ERR_INVALID_ARG, "atts_score_drafts: unknown score_mode %d", score_mode);
+    const ScoreShape s{P, K, T_max};
+    ATTS_TRY(check_workspace("atts_score_drafts", m->desc, s, workspace, workspace_bytes));
+    return forward_tree(m, s, 0, nullptr, false, true, prefix_ids, draft_ids, draft_lens, score_mode, token_logprobs, scores,
+                        workspace, static_cast<hipStream_t>(hip_stream));
+}
+
+// ---------------------------------------------------------------------------- prefix handle
+
+int32_t atts_prefix_create(const atts_model* m, int32_t capacity, atts_prefix** out) {
+    if (!out) return fail(ATTS_ERR_INVALID_ARG, "atts_prefix_create: out is NULL");
+    *out = nullptr;
+    if (!m) return fail(ATTS_ERR_INVALID_ARG, "atts_prefix_create: NULL model");
+    if (capacity < 1 || capacity > (1 << 20)) return fail(ATTS_ERR_INVALID_ARG, "atts_prefix_create: capacity %d outside [1, 1048576]", capacity);
+    const atts_model_desc& d = m->desc;
+    atts_prefix* p = new (std::nothrow) atts_prefix();
+    if (!p) return fail(ATTS_ERR_HIP, "atts_prefix_create: out of host memory");
+    p->model = m;
+    p->capacity = capacity;
+    p->P = 0;
+    p->cap_ld = (int64_t)align_up((size_t)capacity, 64);
+    p->uses_vt = attention_uses_vt(d.dtype, d.head_dim);
+    p->k_cache = p->v_cache = nullptr;
+    p->h_last = nullptr;
+    const size_t es = dtype_size(d.dtype), kvd = (size_t)d.n_kv_heads * d.head_dim, L = (size_t)(d.n_layers > 0 ? d.n_layers : 1);
+    const size_t kb = L * capacity * kvd * es, vb = L * kvd * (p->uses_vt ? (size_t)p->cap_ld : (size_t)capacity) * es;
+    hipError_t e = hipMalloc(reinterpret_cast<void**>(&p->k_cache), kb);
+    if (e == hipSuccess) e = hipMalloc(reinterpret_cast<void**>(&p->v_cache), vb);
+    if (e == hipSuccess) e = hipMalloc(reinterpret_cast<void**>(&p->h_last), (size_t)d.d_model * sizeof(float));
+    if (e != hipSuccess) {
+        (void)hipFree(p->k_cache);
+        (void)hipFree(p->v_cache);
+        (void)hipFree(p->h_last);
+        delete p;
+        return fail(ATTS_ERR_HIP, "atts_prefix_create: device allocation of %zu bytes failed: %s", kb + vb, hipGetErrorString(e));
+    }
+    *out = p;
+    return ATTS_OK;
+}
+
+int32_t atts_prefix_destroy(atts_prefix* p) {
+    if (!p) return ATTS_OK;
+    (void)hipFree(p->k_cache);
+    (void)hipFree(p->v_cache);
+    (void)hipFree(p->h_last);
+    delete p;
+    return ATTS_OK;
+}
+
+int32_t atts_prefix_length(const atts_prefix* p, int32_t* out_rows) {
+    if (!p || !out_rows) return fail(ATTS_ERR_INVALID_ARG, "atts_prefix_length: NULL argument");
+    *out_rows = p->P;
+    return ATTS_OK;
+}
+
+int32_t atts_prefix_reset(atts_prefix* p) {
+    if (!p) return fail(ATTS_ERR_INVALID_ARG, "atts_prefix_reset: NULL handle");
+    p->P = 0;
+    return ATTS_OK;
+}
+
+int32_t atts_prefix_extend_workspace_bytes(const atts_prefix* p, int32_t n, size_t* out_bytes) {
+    if (!p || !out_bytes) return fail(ATTS_ERR_INVALID_ARG, "atts_prefix_extend_workspace_bytes: NULL argument");
+    if (n < 1 || (int64_t)p->P + n > p->capacity)
+        return fail(ATTS_ERR_CAPACITY, "atts_prefix_extend_workspace_bytes: %d + %d rows exceed the capacity %d", p->P, n, p->capacity);
+    *out_bytes = carve(p->model->desc, ScoreShape{p->P, 1, n}).total;
+    return ATTS_OK;
+}
+
+int32_t atts_prefix_extend(atts_prefix* p, const int32_t* ids, int32_t n, void* workspace, size_t workspace_bytes, void* hip_stream) {
+    if (!p) return fail(ATTS_ERR_INVALID_ARG, "atts_prefix_extend: NULL handle");
+    if (n < 0) return fail(ATTS_ERR_INVALID_ARG, "atts_prefix_extend: n = %d < 0", n);
+    if (n == 0) return ATTS_OK;
+    if (!ids) return fail(ATTS_ERR_INVALID_ARG, "atts_prefix_extend: ids is NULL");
+    if ((int64_t)p->P + n > p->capacity)
+        return fail(ATTS_ERR_CAPACITY, "atts_prefix_extend: %d + %d rows exceed the capacity %d", p->P, n, p->capacity);
+    const ScoreShape s{p->P, 1, n};
+    ATTS_TRY(check_workspace("atts_prefix_extend", p->model->desc, s, workspace, workspace_bytes));
+    // the new rows are one "draft" of n tokens after the cached prefix: plain causal continuation
+    ATTS_TRY(forward_tree(p->model, s, p->P, p, true, false, nullptr, ids, nullptr, ATTS_SCORE_MEAN_NLL, nullptr, nullptr, workspace,
+                          static_cast<hipStream_t>(hip_stream)));
+    p->P += n;
+    return ATTS_OK;
+}
+
+int32_t atts_score_drafts_cached(const atts_prefix* p, const int32_t* draft_ids, const int32_t* draft_lens, int32_t K,
+                                 int32_t T_max, int32_t score_mode, float* token_logprobs, float* scores, void* workspace,
+                                 size_t workspace_bytes, void* hip_stream) {
+    if (!p) return fail(ATTS_ERR_INVALID_ARG, "atts_score_drafts_cached: NULL handle");
+    if (p->P < 1) return fail(ATTS_ERR_INVALID_ARG, "atts_score_drafts_cached: the prefix is empty");
+    if (!draft_ids || !scores) return fail(ATTS_ERR_INVALID_ARG, "atts_score_drafts_cached: NULL draft_ids / scores");
+    ATTS_TRY(check_score_shape("atts_score_drafts_cached", p->P, K, T_max));
+    if (score_mode != ATTS_SCORE_MEAN_NLL && score_mode != ATTS_SCORE_SUM_NLL)
+        return fail(ATTS_ERR_INVALID_ARG, "atts_score_drafts_cached: unknown score_mode %d", score_mode);
+    const ScoreShape s{p->P, K, T_max};
+    ATTS_TRY(check_workspace("atts_score_drafts_cached", p->model->desc, s, workspace, workspace_bytes));
+    return forward_tree(p->model, s, p->P, const_cast<atts_prefix*>(p), false, true, nullptr, draft_ids, draft_lens, score_mode,
+                        token_logprobs, scores, workspace, static_cast<hipStream_t>(hip_stream));
 }
 
 int32_t atts_model_check(const atts_model* m, void* hip_stream, int32_t* host_flag) {
@@ -411,9 +572,9 @@ int32_t atts_attention_shared_prefix(int32_t dtype, const void* qkv, void* out, 
         if (!workspace || ((uintptr_t)workspace & 255) || workspace_bytes < need)
             return fail(ATTS_ERR_WORKSPACE, "atts_attention_shared_prefix: workspace NULL, misaligned or smaller than %zu bytes", need);
         vt = workspace;
-        ATTS_TRY(launch_transpose_v(dtype, qkv, s.R(), n_q, n_kv, hd, vt, ldv, st));
+        ATTS_TRY(launch_transpose_v(dtype, qkv, 0, s.R(), n_q, n_kv, hd, vt, ldv, st));
     }
-    return launch_attention(dtype, qkv, vt, ldv, out, s, n_q, n_kv, hd, st);
+    return launch_attention(dtype, qkv, vt, ldv, out, s, 0, n_q, n_kv, hd, st);
 }
 
 }  // extern "C"

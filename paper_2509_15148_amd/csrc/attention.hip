@@ -29,12 +29,12 @@ __device__ __forceinline__ int seg_start(int r, int P, int T) { return r < P ? 0
 // Simple kernel
 // ------------------------------------------------------------------------------------------
 template <typename T>
-__global__ __launch_bounds__(64) void attn_simple_kernel(const T* __restrict__ qkv, T* __restrict__ out, int P, int Tn,
+__global__ __launch_bounds__(64) void attn_simple_kernel(const T* __restrict__ qkv, T* __restrict__ out, int row0, int P, int Tn,
                                                          int nq, int nkv, int hd, float scale) {
     extern __shared__ float sm[];           // [hd] query, then [n_keys] scores
     float* sq = sm;
     float* sp = sm + hd;
-    const int r = blockIdx.x, head = blockIdx.y, lane = threadIdx.x;
+    const int r = row0 + blockIdx.x, head = blockIdx.y, lane = threadIdx.x;
     const int kvh = head / (nq / nkv);
     const int64_t ld = (int64_t)(nq + 2 * nkv) * hd;
     const T* q = qkv + (int64_t)r * ld + head * hd;
@@ -82,7 +82,7 @@ constexpr int kQTile = 128;   // query rows per workgroup (32 per wave)
 constexpr int kKTile = 64;    // keys per LDS tile
 
 __global__ __launch_bounds__(256, 2) void attn_mfma_kernel(const bf16* __restrict__ qkv, const bf16* __restrict__ vt,
-                                                           int64_t ldv, bf16* __restrict__ out, int R, int P, int Tn,
+                                                           int64_t ldv, bf16* __restrict__ out, int row0, int R, int P, int Tn,
                                                            int nq, int nkv, float scale_log2e) {
     // Two stages of [K tile: 64 keys x 256 B | V^T tile: 128 dims x 128 B], filled by direct global -> LDS loads.
     //   K rows are 256 B: 16-byte chunk index XOR (key & 15);  V^T rows are 128 B: chunk index XOR (dim >> 1) & 7.
@@ -93,7 +93,7 @@ __global__ __launch_bounds__(256, 2) void attn_mfma_kernel(const bf16* __restric
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int l32 = lane & 31, g = lane >> 5;
     const int head = blockIdx.y, kvh = head / (nq / nkv);
-    const int r0 = blockIdx.x * kQTile;
+    const int r0 = row0 + blockIdx.x * kQTile;      // query tiles start at the first computed row
     const int r_last = min(r0 + kQTile, R) - 1;
     const int64_t ld = (int64_t)(nq + 2 * nkv) * kHd;
 
@@ -279,28 +279,28 @@ __global__ __launch_bounds__(256, 2) void attn_mfma_kernel(const bf16* __restric
 
 bool attention_uses_vt(int32_t dtype, int32_t hd) { return dtype == ATTS_DTYPE_BF16 && hd == kHd; }
 
-int32_t launch_attention(int32_t dtype, const void* qkv, const void* vt, int64_t ldv, void* out, ScoreShape s,
+int32_t launch_attention(int32_t dtype, const void* qkv, const void* vt, int64_t ldv, void* out, ScoreShape s, int32_t row0,
                          int32_t nq, int32_t nkv, int32_t hd, hipStream_t stream) {
     const int R = s.R();
     const float scale = 1.f / sqrtf((float)hd);
     if (attention_uses_vt(dtype, hd)) {
         if (!vt || ldv < (int64_t)align_up(R, kKTile) || ldv % 8)
             return fail(ATTS_ERR_WORKSPACE, "attention: transposed-V buffer missing or too narrow");
-        dim3 grid((unsigned)ceil_div(R, kQTile), nq);
+        dim3 grid((unsigned)ceil_div(R - row0, kQTile), nq);
         hipLaunchKernelGGL(attn_mfma_kernel, grid, dim3(256), 0, stream, (const bf16*)qkv, (const bf16*)vt, ldv, (bf16*)out,
-                           R, s.P, s.T, nq, nkv, scale * 1.4426950408889634f);
+                           row0, R, s.P, s.T, nq, nkv, scale * 1.4426950408889634f);
         ATTS_LAUNCH_CHECK("attn_mfma_kernel");
         return ATTS_OK;
     }
     const size_t lds = (size_t)(hd + s.P + s.T) * sizeof(float);
     if (lds > 60 * 1024) return fail(ATTS_ERR_SHAPE, "attention: context of %d keys is too long for this dtype/head_dim", s.P + s.T);
-    dim3 grid(R, nq);
+    dim3 grid(R - row0, nq);
     if (dtype == ATTS_DTYPE_F32)
-        hipLaunchKernelGGL(attn_simple_kernel<float>, grid, dim3(64), lds, stream, (const float*)qkv, (float*)out, s.P, s.T, nq,
-                           nkv, hd, scale);
+        hipLaunchKernelGGL(attn_simple_kernel<float>, grid, dim3(64), lds, stream, (const float*)qkv, (float*)out, row0, s.P, s.T,
+                           nq, nkv, hd, scale);
     else
-        hipLaunchKernelGGL(attn_simple_kernel<bf16>, grid, dim3(64), lds, stream, (const bf16*)qkv, (bf16*)out, s.P, s.T, nq,
-                           nkv, hd, scale);
+        hipLaunchKernelGGL(attn_simple_kernel<bf16>, grid, dim3(64), lds, stream, (const bf16*)qkv, (bf16*)out, row0, s.P, s.T,
+                           nq, nkv, hd, scale);
     ATTS_LAUNCH_CHECK("attn_simple_kernel");
     return ATTS_OK;
 }

@@ -134,17 +134,22 @@ struct ScoreShape {
 
 int32_t launch_embed(int32_t dtype, const void* tok_embed, int32_t vocab, int32_t d,
                      const int32_t* prefix_ids, const int32_t* draft_ids, const int32_t* draft_lens,
-                     ScoreShape s, float* h, int32_t* err_flag, hipStream_t stream);
+                     ScoreShape s, int32_t row0, float* h, int32_t* err_flag, hipStream_t stream);
 int32_t launch_rmsnorm(int32_t dtype, const float* h, const float* gain, float eps, int32_t rows, int32_t d,
                        void* out, hipStream_t stream);
+// Several launchers take row0: only rows [row0, R) of the token tree are produced (rows before it belong to a
+// cached prefix); buffers are always indexed by absolute row.
 // rope table per row of the token tree: cs[r][i] = (cos, sin)(pos(r) * theta^(-2 i / hd)), i < hd / 2
-int32_t launch_rope_table(float2* cs, ScoreShape s, int32_t hd, float theta, hipStream_t stream);
+int32_t launch_rope_table(float2* cs, ScoreShape s, int32_t row0, int32_t hd, float theta, hipStream_t stream);
 // In-place rotate-half RoPE on the q and k columns of qkv [R, (nq + 2 nkv) hd]; writes V transposed
 // to vt [nkv, hd, ldv] (ldv >= R) when vt != NULL.
-int32_t launch_rope_split(int32_t dtype, void* qkv, const float2* cs, ScoreShape s, int32_t nq, int32_t nkv,
+int32_t launch_rope_split(int32_t dtype, void* qkv, const float2* cs, ScoreShape s, int32_t row0, int32_t nq, int32_t nkv,
                           int32_t hd, void* vt, int64_t ldv, hipStream_t stream);
-int32_t launch_transpose_v(int32_t dtype, const void* qkv, int32_t R, int32_t nq, int32_t nkv, int32_t hd,
+int32_t launch_transpose_v(int32_t dtype, const void* qkv, int32_t row0, int32_t R, int32_t nq, int32_t nkv, int32_t hd,
                            void* vt, int64_t ldv, hipStream_t stream);
+// dst[r][c] = src[r][c], rows x cols elements of the model dtype, pitches in elements
+int32_t launch_copy2d(int32_t dtype, const void* src, int64_t src_ld, void* dst, int64_t dst_ld, int64_t rows, int64_t cols,
+                      hipStream_t stream);
 // xs[b] = rmsnorm(h[row(b)]) for the B = K T scoring rows; targets[b] / valid[b] from the draft ids.
 int32_t launch_gather_norm(int32_t dtype, const float* h, const float* gain, float eps, int32_t d,
                            const int32_t* draft_ids, const int32_t* draft_lens, int32_t vocab, ScoreShape s,
@@ -153,7 +158,8 @@ int32_t launch_score_reduce(const float* lp, const int32_t* draft_lens, int32_t 
                             float* token_logprobs, float* scores, hipStream_t stream);
 
 bool attention_uses_vt(int32_t dtype, int32_t hd);
-int32_t launch_attention(int32_t dtype, const void* qkv, const void* vt, int64_t ldv, void* out, ScoreShape s,
+// queries are the rows [row0, R); keys / values of all rows [0, R) must be present
+int32_t launch_attention(int32_t dtype, const void* qkv, const void* vt, int64_t ldv, void* out, ScoreShape s, int32_t row0,
                          int32_t nq, int32_t nkv, int32_t hd, hipStream_t stream);
 
 }  // namespace atts

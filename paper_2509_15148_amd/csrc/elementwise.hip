@@ -37,9 +37,9 @@ template <typename T>
 __global__ __launch_bounds__(256) void embed_kernel(const T* __restrict__ emb, int vocab, int d,
                                                     const int32_t* __restrict__ prefix_ids,
                                                     const int32_t* __restrict__ draft_ids,
-                                                    const int32_t* __restrict__ draft_lens, int P, int Tn,
+                                                    const int32_t* __restrict__ draft_lens, int P, int Tn, int row0,
                                                     float* __restrict__ h, int32_t* __restrict__ err_flag) {
-    const int r = blockIdx.x;
+    const int r = row0 + blockIdx.x;
     int id;
     bool padding = false;
     if (r < P) {
@@ -116,10 +116,12 @@ __global__ __launch_bounds__(256) void rmsnorm_kernel(const float* __restrict__ 
 }
 
 // ---- rotary table per row: (cos, sin)(pos(r) * theta^(-2 i / hd)) in fp64, rounded once ----------
-__global__ void rope_table_kernel(float2* __restrict__ cs, int R, int P, int Tn, int half, double log_theta_over_half) {
+__global__ void rope_table_kernel(float2* __restrict__ cs, int row0, int R, int P, int Tn, int half,
+                                  double log_theta_over_half) {
     int idx = blockIdx.x * blockDim.x + threadIdx.x;
-    if (idx >= R * half) return;
-    int r = idx / half, i = idx % half;
+    if (idx >= (R - row0) * half) return;
+    int r = row0 + idx / half, i = idx % half;
+    idx = r * half + i;
     double ang = (double)tree_position(r, P, Tn) * exp(-(double)i * log_theta_over_half);
     double s, c;
     sincos(ang, &s, &c);
@@ -150,10 +152,10 @@ __global__ __launch_bounds__(256) void rope_kernel(T* __restrict__ qkv, const fl
 // are written as zero: the attention kernel loads whole 64-key tiles and multiplies the masked
 // probabilities (exact zeros) with whatever it finds there.
 template <typename T>
-__global__ __launch_bounds__(256) void transpose_v_kernel(const T* __restrict__ qkv, int R, int64_t ld, int v_off,
+__global__ __launch_bounds__(256) void transpose_v_kernel(const T* __restrict__ qkv, int row0, int R, int64_t ld, int v_off,
                                                           int hd, T* __restrict__ vt, int64_t ldv) {
     __shared__ T tile[64][65];
-    const int r0 = blockIdx.x * 64, c0 = blockIdx.y * 64, kvh = blockIdx.z;
+    const int r0 = row0 / 64 * 64 + blockIdx.x * 64, c0 = blockIdx.y * 64, kvh = blockIdx.z;
     const int tx = threadIdx.x & 63, ty = threadIdx.x >> 6;
     for (int i = ty; i < 64; i += 4) {
         int r = r0 + i, c = c0 + tx;
@@ -162,8 +164,18 @@ __global__ __launch_bounds__(256) void transpose_v_kernel(const T* __restrict__ 
     __syncthreads();
     for (int i = ty; i < 64; i += 4) {
         int c = c0 + i, r = r0 + tx;
-        if (c < hd && r < ldv) vt[((int64_t)kvh * hd + c) * ldv + r] = tile[tx][i];
+        if (c < hd && r >= row0 && r < ldv) vt[((int64_t)kvh * hd + c) * ldv + r] = tile[tx][i];
     }
+}
+
+// dst[r][c] = src[r][c] for a rows x cols block of two pitched arrays (prefix cache <-> workspace)
+template <typename T>
+__global__ __launch_bounds__(256) void copy2d_kernel(const T* __restrict__ src, int64_t src_ld, T* __restrict__ dst,
+                                                     int64_t dst_ld, int64_t rows, int64_t cols) {
+    const int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    if (i >= rows * cols) return;
+    const int64_t r = i / cols, c = i % cols;
+    dst[r * dst_ld + c] = src[r * src_ld + c];
 }
 
 // Zero columns [R, ldv) of every row of V^T (for a producer that writes only the R real columns).
@@ -228,10 +240,10 @@ __global__ __launch_bounds__(256) void score_reduce_kernel(const float* __restri
     }
 
 int32_t launch_embed(int32_t dtype, const void* tok_embed, int32_t vocab, int32_t d, const int32_t* prefix_ids,
-                     const int32_t* draft_ids, const int32_t* draft_lens, ScoreShape s, float* h, int32_t* err_flag,
-                     hipStream_t stream) {
-    DISPATCH_T(dtype, hipLaunchKernelGGL(embed_kernel<T>, dim3(s.R()), dim3(256), 0, stream, (const T*)tok_embed, vocab, d,
-                                         prefix_ids, draft_ids, draft_lens, s.P, s.T, h, err_flag);)
+                     const int32_t* draft_ids, const int32_t* draft_lens, ScoreShape s, int32_t row0, float* h,
+                     int32_t* err_flag, hipStream_t stream) {
+    DISPATCH_T(dtype, hipLaunchKernelGGL(embed_kernel<T>, dim3(s.R() - row0), dim3(256), 0, stream, (const T*)tok_embed, vocab, d,
+                                         prefix_ids, draft_ids, draft_lens, s.P, s.T, row0, h, err_flag);)
     ATTS_LAUNCH_CHECK("embed_kernel");
     return ATTS_OK;
 }
@@ -243,20 +255,20 @@ int32_t launch_rmsnorm(int32_t dtype, const float* h, const float* gain, float e
     return ATTS_OK;
 }
 
-int32_t launch_rope_table(float2* cs, ScoreShape s, int32_t hd, float theta, hipStream_t stream) {
+int32_t launch_rope_table(float2* cs, ScoreShape s, int32_t row0, int32_t hd, float theta, hipStream_t stream) {
     const int half = hd / 2;
-    const int64_t total = (int64_t)s.R() * half;
-    hipLaunchKernelGGL(rope_table_kernel, dim3((unsigned)ceil_div(total, 256)), dim3(256), 0, stream, cs, s.R(), s.P, s.T, half,
+    const int64_t total = (int64_t)(s.R() - row0) * half;
+    hipLaunchKernelGGL(rope_table_kernel, dim3((unsigned)ceil_div(total, 256)), dim3(256), 0, stream, cs, row0, s.R(), s.P, s.T, half,
                        log((double)theta) / (double)half);
     ATTS_LAUNCH_CHECK("rope_table_kernel");
     return ATTS_OK;
 }
 
-int32_t launch_transpose_v(int32_t dtype, const void* qkv, int32_t R, int32_t nq, int32_t nkv, int32_t hd, void* vt,
-                           int64_t ldv, hipStream_t stream) {
+int32_t launch_transpose_v(int32_t dtype, const void* qkv, int32_t row0, int32_t R, int32_t nq, int32_t nkv, int32_t hd,
+                           void* vt, int64_t ldv, hipStream_t stream) {
     const int64_t ld = (int64_t)(nq + 2 * nkv) * hd;
-    dim3 grid((unsigned)ceil_div(R, 64), (unsigned)ceil_div(hd, 64), nkv);
-    DISPATCH_T(dtype, hipLaunchKernelGGL(transpose_v_kernel<T>, grid, dim3(256), 0, stream, (const T*)qkv, R, ld,
+    dim3 grid((unsigned)ceil_div(ldv - row0 / 64 * 64, 64), (unsigned)ceil_div(hd, 64), nkv);
+    DISPATCH_T(dtype, hipLaunchKernelGGL(transpose_v_kernel<T>, grid, dim3(256), 0, stream, (const T*)qkv, row0, R, ld,
                                          (nq + nkv) * hd, hd, (T*)vt, ldv);)
     ATTS_LAUNCH_CHECK("transpose_v_kernel");
     return ATTS_OK;
@@ -272,14 +284,24 @@ int32_t launch_zero_vt_tail(int32_t dtype, void* vt, int64_t rows, int32_t R, in
     return ATTS_OK;
 }
 
-int32_t launch_rope_split(int32_t dtype, void* qkv, const float2* cs, ScoreShape s, int32_t nq, int32_t nkv, int32_t hd,
-                          void* vt, int64_t ldv, hipStream_t stream) {
+int32_t launch_rope_split(int32_t dtype, void* qkv, const float2* cs, ScoreShape s, int32_t row0, int32_t nq, int32_t nkv,
+                          int32_t hd, void* vt, int64_t ldv, hipStream_t stream) {
     const int64_t ld = (int64_t)(nq + 2 * nkv) * hd;
-    const int64_t total = (int64_t)s.R() * (nq + nkv) * (hd / 2);
+    const int rows = s.R() - row0;
+    const int64_t total = (int64_t)rows * (nq + nkv) * (hd / 2);
     DISPATCH_T(dtype, hipLaunchKernelGGL(rope_kernel<T>, dim3((unsigned)ceil_div(total, 256)), dim3(256), 0, stream,
-                                         (T*)qkv, cs, s.R(), nq + nkv, hd, ld);)
+                                         (T*)qkv + (int64_t)row0 * ld, cs + (int64_t)row0 * (hd / 2), rows, nq + nkv, hd, ld);)
     ATTS_LAUNCH_CHECK("rope_kernel");
-    if (vt) return launch_transpose_v(dtype, qkv, s.R(), nq, nkv, hd, vt, ldv, stream);
+    if (vt) return launch_transpose_v(dtype, qkv, row0, s.R(), nq, nkv, hd, vt, ldv, stream);
+    return ATTS_OK;
+}
+
+int32_t launch_copy2d(int32_t dtype, const void* src, int64_t src_ld, void* dst, int64_t dst_ld, int64_t rows, int64_t cols,
+                      hipStream_t stream) {
+    if (rows <= 0 || cols <= 0) return ATTS_OK;
+    DISPATCH_T(dtype, hipLaunchKernelGGL(copy2d_kernel<T>, dim3((unsigned)ceil_div(rows * cols, 256)), dim3(256), 0, stream,
+                                         (const T*)src, src_ld, (T*)dst, dst_ld, rows, cols);)
+    ATTS_LAUNCH_CHECK("copy2d_kernel");
     return ATTS_OK;
 }
 
