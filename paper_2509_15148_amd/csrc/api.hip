@@ -81,7 +81,7 @@ void prof_clear() {
 
 // Sub-buffers of the scoring workspace, each 256-byte aligned.
 struct Workspace {
-    size_t h, xn, qkv, vt, ao, act, rope, xs, targets, valid, partials, zt, lp, total;
+    size_t h, xn, qkv, qkv32, vt, ao, act, rope, xs, targets, valid, partials, zt, lp, total;
     int64_t ldv;
     int32_t n_part;
 };
@@ -89,6 +89,7 @@ struct Workspace {
 // GEMM inputs of the bf16 path are allocated in whole tiles (768 rows = a multiple of both tile heights): the
 // aligned kernel then serves every row count (it reads the pad rows, whatever they hold, and drops their results).
 bool pads_rows(const atts_model_desc& d) { return d.dtype == ATTS_DTYPE_BF16; }
+constexpr int kSplitQkvRows = 128;
 
 Workspace carve(const atts_model_desc& d, ScoreShape s) {
     const size_t es = dtype_size(d.dtype);
@@ -105,6 +106,8 @@ Workspace carve(const atts_model_desc& d, ScoreShape s) {
     w.h = take(R * d.d_model * sizeof(float));
     w.xn = take(Ra * d.d_model * es);
     w.qkv = take(R * (size_t)(d.n_q_heads + 2 * d.n_kv_heads) * d.head_dim * es);
+    // fp32 sums of a K-split QKV projection (calls with at most kSplitQkvRows computed rows)
+    w.qkv32 = take(pads_rows(d) ? (size_t)kSplitQkvRows * (d.n_q_heads + 2 * d.n_kv_heads) * d.head_dim * sizeof(float) : 0);
     w.ldv = (int64_t)align_up(R, 64);
     w.vt = take(attention_uses_vt(d.dtype, d.head_dim) ? (size_t)d.n_kv_heads * d.head_dim * w.ldv * es : 0);
     w.ao = take(Ra * (size_t)d.n_q_heads * d.head_dim * es);
@@ -251,6 +254,10 @@ int32_t forward_tree(const atts_model* m, ScoreShape s, int32_t row0, atts_prefi
     // the fused epilogue writes 4 transposed-V columns per store: the first computed row must keep them aligned
     const bool fuse_rope = vt != nullptr && row0 % 4 == 0 && qkv_rope_fusable(d.dtype, M, qkv_out, d.d_model, d.head_dim, padded);
     float* h0 = h + (size_t)row0 * d.d_model;
+    // few rows: the QKV projection splits its K range like the residual projections do; the workgroups add into an
+    // fp32 buffer and a small kernel applies RoPE / the V transpose afterwards
+    float* qkv32 = reinterpret_cast<float*>(base + ws.qkv32);
+    const bool split_qkv = fuse_rope && M <= kSplitQkvRows && gemm_splits_k(d.dtype, M, qkv_out, d.d_model, padded);
 
     {
         StageTimer t_(ATTS_STAGE_EMBED, st);
@@ -258,6 +265,7 @@ int32_t forward_tree(const atts_model* m, ScoreShape s, int32_t row0, atts_prefi
         ATTS_TRY(launch_rope_table(rope, s, row0, d.head_dim, d.rope_theta, st));
         // the fused QKV epilogue writes only the R real columns of V^T
         if (fuse_rope) ATTS_TRY(launch_zero_vt_tail(d.dtype, vt, (int64_t)kvd, R, ws.ldv, st));
+        if (split_qkv) ATTS_TRY(launch_zero_f32(qkv32, (int64_t)M * qkv_out, st));
     }
     for (int l = 0; l < d.n_layers; ++l) {
         {
@@ -268,7 +276,13 @@ int32_t forward_tree(const atts_model* m, ScoreShape s, int32_t row0, atts_prefi
         g.a = xn + (size_t)row0 * d.d_model * es; g.w = m->wqkv[l]; g.out = qkv + (size_t)row0 * qkv_out * es;
         g.M = M; g.N = qkv_out; g.Kd = d.d_model;
         g.lda = d.d_model; g.ldw = d.d_model; g.ldc = qkv_out; g.a_rows_padded = padded;
-        if (fuse_rope) {
+        if (split_qkv) {
+            g.out = qkv32;
+            StageTimer t_(ATTS_STAGE_GEMM_QKV, st);
+            ATTS_TRY(launch_gemm(d.dtype, EPI_RESID_F32, g, st));
+            ATTS_TRY(launch_qkv_finish(d.dtype, qkv32, rope + (size_t)row0 * (d.head_dim / 2), M, d.n_q_heads, d.n_kv_heads,
+                                       d.head_dim, qkv + (size_t)row0 * qkv_out * es, vt + (size_t)row0 * es, ws.ldv, st));
+        } else if (fuse_rope) {
             // QKV projection with RoPE and the V transpose applied to the accumulators
             g.rope = rope + (size_t)row0 * (d.head_dim / 2); g.vt = vt + (size_t)row0 * es; g.ldv = ws.ldv;
             g.n_rot_heads = d.n_q_heads + d.n_kv_heads;

@@ -147,6 +147,13 @@ int32_t launch_rope_split(int32_t dtype, void* qkv, const float2* cs, ScoreShape
                           int32_t hd, void* vt, int64_t ldv, hipStream_t stream);
 int32_t launch_transpose_v(int32_t dtype, const void* qkv, int32_t row0, int32_t R, int32_t nq, int32_t nkv, int32_t hd,
                            void* vt, int64_t ldv, hipStream_t stream);
+int32_t launch_zero_f32(float* p, int64_t n, hipStream_t stream);
+// acc [rows, (nq + 2 nkv) hd] fp32 (sums of a K-split QKV projection; cleared on return) -> RoPE on the q / k heads
+// (cs, qkv, vt already point at the first of the `rows` rows / columns), stored to qkv; v heads to vt [nkv hd, ldv]
+int32_t launch_qkv_finish(int32_t dtype, float* acc, const float2* cs, int32_t rows, int32_t nq, int32_t nkv, int32_t hd,
+                          void* qkv, void* vt, int64_t ldv, hipStream_t stream);
+// true if a residual-epilogue GEMM of this shape would split its K range (few tiles: weight-streaming regime)
+bool gemm_splits_k(int32_t dtype, int32_t M, int32_t N, int32_t Kd, bool a_rows_padded);
 // dst[r][c] = src[r][c], rows x cols elements of the model dtype, pitches in elements
 int32_t launch_copy2d(int32_t dtype, const void* src, int64_t src_ld, void* dst, int64_t dst_ld, int64_t rows, int64_t cols,
                       hipStream_t stream);

@@ -178,6 +178,42 @@ __global__ __launch_bounds__(256) void copy2d_kernel(const T* __restrict__ src, 
     dst[r * dst_ld + c] = src[r * src_ld + c];
 }
 
+// Finish of a K-split QKV projection: acc [rows, (nq + 2 nkv) hd] holds the fp32 sums of the split workgroups.
+// One thread per (row, head, rotation pair i < hd / 2): q and k heads are rotated (rotate-half RoPE, table row
+// cs[r]) and stored to the qkv row, v heads are stored to the transposed copy vt [nkv hd, ldv] at column r.
+// The accumulator entries are cleared for the next projection.
+template <typename T>
+__global__ __launch_bounds__(256) void qkv_finish_kernel(float* __restrict__ acc, const float2* __restrict__ cs, int rows,
+                                                         int nq, int nkv, int hd, T* __restrict__ qkv,
+                                                         T* __restrict__ vt, int64_t ldv) {
+    const int half = hd >> 1, heads = nq + 2 * nkv;
+    const int64_t idx = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    if (idx >= (int64_t)rows * heads * half) return;
+    const int i = (int)(idx % half);
+    const int head = (int)((idx / half) % heads);
+    const int r = (int)(idx / ((int64_t)half * heads));
+    const int64_t ld = (int64_t)heads * hd;
+    float* a = acc + (int64_t)r * ld + head * hd + i;
+    const float x1 = a[0], x2 = a[half];
+    a[0] = 0.f;
+    a[half] = 0.f;
+    if (head < nq + nkv) {
+        const float2 c_s = cs[(int64_t)r * half + i];
+        T* p = qkv + (int64_t)r * ld + head * hd + i;
+        p[0] = from_f32<T>(x1 * c_s.x - x2 * c_s.y);
+        p[half] = from_f32<T>(x2 * c_s.x + x1 * c_s.y);
+    } else {
+        T* p = vt + ((int64_t)(head - nq - nkv) * hd + i) * ldv + r;
+        p[0] = from_f32<T>(x1);
+        p[(int64_t)half * ldv] = from_f32<T>(x2);
+    }
+}
+
+__global__ __launch_bounds__(256) void zero_f32_kernel(float* __restrict__ p, int64_t n) {
+    const int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    if (i < n) p[i] = 0.f;
+}
+
 // Zero columns [R, ldv) of every row of V^T (for a producer that writes only the R real columns).
 template <typename T>
 __global__ __launch_bounds__(256) void zero_vt_tail_kernel(T* __restrict__ vt, int64_t rows, int R, int64_t ldv) {
@@ -293,6 +329,22 @@ int32_t launch_rope_split(int32_t dtype, void* qkv, const float2* cs, ScoreShape
                                          (T*)qkv + (int64_t)row0 * ld, cs + (int64_t)row0 * (hd / 2), rows, nq + nkv, hd, ld);)
     ATTS_LAUNCH_CHECK("rope_kernel");
     if (vt) return launch_transpose_v(dtype, qkv, row0, s.R(), nq, nkv, hd, vt, ldv, stream);
+    return ATTS_OK;
+}
+
+int32_t launch_zero_f32(float* p, int64_t n, hipStream_t stream) {
+    if (n <= 0) return ATTS_OK;
+    hipLaunchKernelGGL(zero_f32_kernel, dim3((unsigned)ceil_div(n, 256)), dim3(256), 0, stream, p, n);
+    ATTS_LAUNCH_CHECK("zero_f32_kernel");
+    return ATTS_OK;
+}
+
+int32_t launch_qkv_finish(int32_t dtype, float* acc, const float2* cs, int32_t rows, int32_t nq, int32_t nkv, int32_t hd,
+                          void* qkv, void* vt, int64_t ldv, hipStream_t stream) {
+    const int64_t total = (int64_t)rows * (nq + 2 * nkv) * (hd / 2);
+    DISPATCH_T(dtype, hipLaunchKernelGGL(qkv_finish_kernel<T>, dim3((unsigned)ceil_div(total, 256)), dim3(256), 0, stream, acc, cs,
+                                         rows, nq, nkv, hd, (T*)qkv, (T*)vt, ldv);)
+    ATTS_LAUNCH_CHECK("qkv_finish_kernel");
     return ATTS_OK;
 }
 

@@ -560,6 +560,7 @@ __global__ __launch_bounds__(128 * kWavesM) void gemm_bf16_wide_kernel(const cha
     constexpr int DMA_A = BM / ROWS_PER_DMA / kWaves, DMA_B = BN / ROWS_PER_DMA / kWaves;
     static_assert(DMA_A % 2 == 0 && DMA_B % 2 == 0, "the swizzle parity of a DMA instruction must not depend on the wave");
     constexpr bool kDeep = BM == 256;                            // five-unit ring, A two slabs ahead
+    constexpr int kStages = BM == 128 ? 3 : 2;                   // whole-slab stages otherwise (160 KB of LDS)
     constexpr int UNIT_A = BM * BKB, UNIT_B = BN * BKB;
     static_assert(!kDeep || UNIT_A == UNIT_B, "ring units must have one size");
 
@@ -581,8 +582,8 @@ __global__ __launch_bounds__(128 * kWavesM) void gemm_bf16_wide_kernel(const cha
     const int n0 = tc.tn * N_OUT;
 
     // LDS offsets of the operands of slab k
-    auto a_slot = [&](int k) { return kDeep ? ((2 * k) % 5) * UNIT_A : (k & 1) * (UNIT_A + UNIT_B); };
-    auto b_slot = [&](int k) { return kDeep ? ((2 * k + 1) % 5) * UNIT_A : (k & 1) * (UNIT_A + UNIT_B) + UNIT_A; };
+    auto a_slot = [&](int k) { return kDeep ? ((2 * k) % 5) * UNIT_A : (k % kStages) * (UNIT_A + UNIT_B); };
+    auto b_slot = [&](int k) { return kDeep ? ((2 * k + 1) % 5) * UNIT_A : (k % kStages) * (UNIT_A + UNIT_B) + UNIT_A; };
 
     // ---- DMA addressing: instruction j of this wave fills LDS rows r0 = (wave DMA_x + j) 8 ... r0 + 7; lane i lands
     // at row r0 + i / 8, chunk slot i % 8 and fetches logical chunk slot ^ swz(row), swz(row) = (row >> 1) & 7.
@@ -695,31 +696,38 @@ __global__ __launch_bounds__(128 * kWavesM) void gemm_bf16_wide_kernel(const cha
     using F_ = std::false_type;
 
     // ---- prologue
+    constexpr int kLook = kStages - 1;                 // whole-slab stages: slab k + kLook is issued during slab k
+    constexpr int kSteadyWait = kDeep ? DMA_A : (kStages - 2) * (DMA_A + DMA_B);   // loads that may stay in flight
     issue_a(0);
     issue_b(0);
     if (kDeep) {
         issue_a(1);
-        wait_vmcnt<DMA_A>();
     } else {
-        wait_vmcnt<0>();
+#pragma unroll
+        for (int q = 1; q < kLook; ++q) {              // nk >= kStages (checked on the host)
+            issue_a(q);
+            issue_b(q);
+        }
     }
+    wait_vmcnt<kSteadyWait>();
     block_barrier();
     load_a(0, 0, fa[0]);
 #pragma unroll
     for (int j = 0; j < NI; ++j) fb[j] = load_b1(0, 0, j);
 
     // slab k.  first / second: the DMA halves issued under k-steps 0 and 1:
-    //   deep ring:  W rows of slab k + 1 (into the unit slab k - 1 freed), then A rows of slab k + 2
-    //   two stages: A rows, then W rows of slab k + 1
-    auto slab = [&](int k, auto has_next, auto first, auto second) __attribute__((always_inline)) {
+    //   deep ring:         W rows of slab k + 1 (into the unit slab k - 1 freed), then A rows of slab k + 2
+    //   whole-slab stages: A rows, then W rows of slab k + kLook
+    // steady: the loads issued under this slab may stay in flight across its end (else everything is awaited).
+    auto slab = [&](int k, auto has_next, auto first, auto second, auto steady) __attribute__((always_inline)) {
         // k-step 0
-        if (first) { if (kDeep) issue_b(k + 1); else issue_a(k + 1); }
+        if (first) { if (kDeep) issue_b(k + 1); else issue_a(k + kLook); }
         kstep(k, 0, C0{}, T_{});
         if (first) { if (kDeep) kstep_hint(T_{}, CDmaB{}, std::integral_constant<int, 0>{}); else kstep_hint(T_{}, CDmaA{}, std::integral_constant<int, 0>{}); }
         else kstep_hint(T_{}, C0{}, std::integral_constant<int, 0>{});
         __builtin_amdgcn_sched_barrier(0);
         // k-step 1
-        if (second) { if (kDeep) issue_a(k + 2); else issue_b(k + 1); }
+        if (second) { if (kDeep) issue_a(k + 2); else issue_b(k + kLook); }
         kstep(k, 1, C1{}, T_{});
         if (second) { if (kDeep) kstep_hint(T_{}, CDmaA{}, std::integral_constant<int, 1>{}); else kstep_hint(T_{}, CDmaB{}, std::integral_constant<int, 1>{}); }
         else kstep_hint(T_{}, C0{}, std::integral_constant<int, 1>{});
@@ -731,7 +739,7 @@ __global__ __launch_bounds__(128 * kWavesM) void gemm_bf16_wide_kernel(const cha
         // k-step 3, then the slab boundary: slab k + 1 has landed for every wave, every wave is done with slab k
         kstep(k, 3, C1{}, F_{});
         if (has_next) {
-            if (kDeep && second) wait_vmcnt<DMA_A>(); else wait_vmcnt<0>();
+            if (steady) wait_vmcnt<kSteadyWait>(); else wait_vmcnt<0>();
             block_barrier();
             load_a(k + 1, 0, fa[0]);
 #pragma unroll
@@ -742,12 +750,13 @@ __global__ __launch_bounds__(128 * kWavesM) void gemm_bf16_wide_kernel(const cha
     struct No { constexpr operator bool() const { return false; } };
     int k = 0;
     if (kDeep) {
-        for (; k + 2 < nk; ++k) slab(k, Yes{}, Yes{}, Yes{});
-        slab(k, Yes{}, Yes{}, No{});          // k = nk - 2: only the W rows of the last slab are left to issue
-        slab(k + 1, No{}, No{}, No{});
+        for (; k + 2 < nk; ++k) slab(k, Yes{}, Yes{}, Yes{}, Yes{});
+        slab(k, Yes{}, Yes{}, No{}, No{});    // k = nk - 2: only the W rows of the last slab are left to issue
+        slab(k + 1, No{}, No{}, No{}, No{});
     } else {
-        for (; k + 1 < nk; ++k) slab(k, Yes{}, Yes{}, Yes{});
-        slab(k, No{}, No{}, No{});
+        for (; k + kLook < nk; ++k) slab(k, Yes{}, Yes{}, Yes{}, Yes{});
+        for (; k + 1 < nk; ++k) slab(k, Yes{}, No{}, No{}, No{});
+        slab(k, No{}, No{}, No{}, No{});
     }
 
     gemm_epilogue<bf16, MI, NI, EPI>(acc, m0, n0, wm, wn, l32, half, tc.tn, g_out, g_targets, g_partials, g_target_logit, g_rope, g_vt, g);
@@ -771,6 +780,7 @@ bool fast_path_ok(int32_t dtype, int epi, const GemmArgs& g) {
 // 256-row ones and are taken when they do not cost whole extra rounds of workgroups over the 256 CUs.
 int fast_tile_rows(int epi, const GemmArgs& g) {
     const int n_out = epi == EPI_SWIGLU ? 128 : 256;
+    if (g.M <= 128) return 128;                         // one half-height tile row: half the MFMA work per weight byte
     if (!(g.M % 384 == 0 || g.a_rows_padded) || g.M <= 256) return 256;
     const int64_t nt_n = g.N / n_out;
     const int64_t t256 = ceil_div(g.M, 256) * nt_n, t384 = ceil_div(g.M, 384) * nt_n;
@@ -782,8 +792,8 @@ int fast_tile_rows(int epi, const GemmArgs& g) {
 // narrow output: the weight-streaming regime), the K range is cut so that about one workgroup per CU runs.
 int fast_k_slices(int epi, int n_tiles, int nk) {
     if (epi != EPI_RESID_F32 || n_tiles >= 128) return 1;
-    int s = (256 + n_tiles - 1) / n_tiles;
-    const int max_s = nk / (2 * (ATTS_FAST_STAGES + 1));     // every slice keeps the DMA ring busy for a while
+    int s = 256 / n_tiles;                                   // never more workgroups than CUs: no second round
+    const int max_s = nk / (ATTS_FAST_STAGES + 1);           // every slice still fills the DMA ring once
     if (s > max_s) s = max_s;
     return s < 1 ? 1 : s;
 }
@@ -855,6 +865,7 @@ template <int EPI>
 int32_t launch_fast(const GemmArgs& g, hipStream_t stream) {
     constexpr int kWavesM = ATTS_FAST_WAVES_M;
     const bool wide = ATTS_GEMM_WIDE && g.Kd % 64 == 0 && g.Kd >= 12 * 64;
+    if (fast_tile_rows(EPI, g) == 128 && wide && kWavesM == 4) return launch_wide_tile<EPI, 1>(g, stream);
     if (fast_tile_rows(EPI, g) == 384)
         return wide ? launch_wide_tile<EPI, 12 / kWavesM>(g, stream) : launch_fast_tile<EPI, 12 / kWavesM>(g, stream);
     return wide ? launch_wide_tile<EPI, 8 / kWavesM>(g, stream) : launch_fast_tile<EPI, 8 / kWavesM>(g, stream);
@@ -953,6 +964,15 @@ bool qkv_rope_fusable(int32_t dtype, int32_t M, int32_t N, int32_t Kd, int32_t h
     GemmArgs g{};
     g.M = M; g.N = N; g.Kd = Kd; g.lda = Kd; g.ldw = Kd; g.a_rows_padded = a_rows_padded;
     return head_dim == 128 && fast_path_ok(dtype, EPI_QKV_ROPE, g);
+}
+
+bool gemm_splits_k(int32_t dtype, int32_t M, int32_t N, int32_t Kd, bool a_rows_padded) {
+    GemmArgs g{};
+    g.M = M; g.N = N; g.Kd = Kd; g.lda = Kd; g.ldw = Kd; g.a_rows_padded = a_rows_padded;
+    if (!fast_path_ok(dtype, EPI_RESID_F32, g)) return false;
+    const int bm = fast_tile_rows(EPI_RESID_F32, g);
+    const int64_t tiles = ceil_div(M, bm) * (N / 256);
+    return fast_k_slices(EPI_RESID_F32, (int)tiles, Kd / 64) > 1;
 }
 
 int32_t launch_gemm(int32_t dtype, GemmEpilogue epi, const GemmArgs& g, hipStream_t stream) {
