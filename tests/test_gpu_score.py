@@ -66,9 +66,10 @@ def test_small_models_ragged_shapes(cfg, P, K, T):
     assert flag == 0
     assert np.abs(lp - ref_lp).max() <= TOL[cfg.dtype], np.abs(lp - ref_lp).max()
     assert np.abs(sc - ref_s).max() <= TOL[cfg.dtype]
-    # scores only (token_logprobs = NULL) gives the same scores
+    # scores only (token_logprobs = NULL) gives the same scores (calls with this few rows split the K range of
+    # some projections over workgroups that add their partial sums atomically: equal up to rounding order)
     _, sc2, _ = _run_gpu(A, cfg, w_dev, prefix, drafts, want_lp=False)
-    assert np.array_equal(sc, sc2)
+    assert np.abs(sc - sc2).max() <= TOL[cfg.dtype] / 20
 
 
 def test_variable_draft_lengths_and_padding_ids():
