@@ -13,6 +13,8 @@
 //       score: the coarsest index level sits in LDS, every further level costs one aligned 64-byte
 //       line.  The class is an integer comparison of ranks + 1 with r_l = floor(alpha_l (N + 1));
 //       the quantile thresholds of Eq. "quantile" are read straight from the sorted array.
+//   conditional coverage (Proposition 2):  no state; one wavefront ranks the candidates of one input against
+//       that input's own calibration scores.
 #include "common.h"
 
 #include <math.h>

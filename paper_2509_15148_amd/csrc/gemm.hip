@@ -1,19 +1,20 @@
 // NT GEMM on MFMA for gfx950:  acc[M, N] = A[M, Kd] . W[N, Kd]^T  with fused epilogues.
 //
 // Every linear map of the target model (QKV, attention output, SwiGLU feed-forward, LM head)
-// goes through this kernel; scoring the drafts is the compute-bound part of the method
-// (Sec. "Q1"), so this is where the time goes.
+// goes through one of the kernels below; scoring the drafts is the compute-bound part of the
+// method (Sec. "Q1"), so this is where the time goes.
 //
-// Layout of one workgroup (256 threads = 4 wavefronts in a 2 x 2 grid):
-//   * output tile BM x BN, each wave owns (BM/2) x (BN/2) as MI x NI blocks of 32 x 32
-//     (v_mfma_f32_32x32x16_bf16, or v_mfma_f32_32x32x2_f32 for the fp32 model)
-//   * K is walked in slabs of 128 bytes per row (64 bf16 / 32 fp32).  Both operands are
-//     K-contiguous in memory, so A and W tiles are loaded the same way: 16-byte chunks,
-//     global -> registers -> LDS, double-buffered, one barrier per slab.
-//   * LDS rows are 128 bytes; the 16-byte chunk index is XOR-ed with (row >> 1) & 7 so that the
-//     rows a fragment read touches spread over all 64 banks (two rows span the 256-byte bank width).
-//   * workgroup ids are remapped so that the ids dispatched to one XCD (id mod 8) cover a
-//     compact block of tiles, which keeps each XCD's private L2 re-using A and W slabs.
+//   gemm_bf16_wide_kernel   aligned bf16 shapes (every projection of the bf16 models): 8 wavefronts,
+//                           384 x 256, 256 x 256 or 128 x 256 output tiles, operand slabs of 128 bytes
+//                           per row DMA-ed global -> LDS in whole 128-byte lines, explicit waits.
+//   gemm_bf16_fast_kernel   the same with 64-byte slabs and a deeper ring, for inner dimensions
+//                           that are a multiple of 32 but not of 64.
+//   gemm_nt_kernel          any shape, bf16 or fp32 (v_mfma_f32_32x32x2_f32): 4 wavefronts (2 x 2),
+//                           tile BM x BN, 128-byte slabs through registers with bounds checks,
+//                           double-buffered, one barrier per slab; LDS chunk index XOR (row >> 1) & 7.
+// All share gemm_epilogue (store / fp32 residual add / SwiGLU / LM-head partials / QKV + RoPE) and the
+// workgroup-id remap that hands each XCD (id mod 8) a compact block of tiles, so that its private L2
+// re-uses A and W slabs.
 #include "common.h"
 
 #include <type_traits>

@@ -132,7 +132,7 @@ def test_calibration_only_workload_full_size():
 
 
 def test_streaming_merge_sizes():
-    """Batches and totals above 2^22 keys take the streaming merge (8192-key segments, splits found by a
+    """Batches and totals above 2^22 keys take the streaming merge (4096-key segments, splits found by a
     separate kernel) in both its pairwise and its final form; smaller appends into the large set, ragged
     lengths and ties included.  The state must equal the sorted union after every append."""
     import paper_2509_15148_amd as A
