@@ -132,6 +132,16 @@ def bench_calibration(A, torch, np, steps=16, scaled=False):
     torch.cuda.synchronize()
     st = {name: A.atts_profile_read(A.STAGES.index(name))[0] / steps * 1e3 for name in ("calib_sort", "calib_merge", "classify")}
     A.atts_profile_enable(False)
+    # decisions only (ranks = NULL): classes from the threshold form of the rule, no search per score; device time
+    # from the library's events (at the small size a Python call costs more than the kernel)
+    A.atts_classify_ordinal(calib, test[0], list(wl.alphas), None, None, cls, None)
+    torch.cuda.synchronize()
+    A.atts_profile_enable(True)
+    for i in range(steps):
+        A.atts_classify_ordinal(calib, test[i % len(test)], list(wl.alphas), None, None, cls, None)
+    torch.cuda.synchronize()
+    dt_cls = A.atts_profile_read(A.STAGES.index("classify"))[0] / steps * 1e-3
+    A.atts_profile_enable(False)
     n_mid2 = n_mid + n_new * steps
     # bytes the method must move per step: read the set once, read + append the new scores, read the test
     # scores, write ranks (4 B) and classes (1 B).  Keeping the set sorted adds one more pass: the merge reads
@@ -145,6 +155,8 @@ def bench_calibration(A, torch, np, steps=16, scaled=False):
         "algorithmic_bytes_per_step": bytes_step, "achieved_GBs": bytes_step * steps / dt / 1e9,
         "hbm_frac": bytes_step * steps / dt / 1e9 / HBM_PEAK_GBS,
         "stage_us": st,
+        "classes_only": {"device_us_per_call": dt_cls * 1e6, "decisions_per_s": n_test / dt_cls,
+                         "achieved_GBs": 5 * n_test / dt_cls / 1e9, "hbm_frac": 5 * n_test / dt_cls / 1e9 / HBM_PEAK_GBS},
         "merge_kernel": {"bytes_per_launch": merge_bytes, "avg_launch_us": st["calib_merge"],
                          "achieved_GBs": merge_bytes / (st["calib_merge"] * 1e-6) / 1e9 if st["calib_merge"] > 0 else 0.0,
                          "hbm_frac": merge_bytes / (st["calib_merge"] * 1e-6) / 1e9 / HBM_PEAK_GBS if st["calib_merge"] > 0 else 0.0},

@@ -278,7 +278,10 @@ int32_t atts_calibrate_online(atts_calib* calib, const float* new_scores, int64_
  * A NaN test score gets rank 0 (the smallest p-value).
  *   test_scores dev float [M] (M >= 0); alphas HOST double [n_alpha], non-decreasing, each in
  *   (0, 1), 1 <= n_alpha <= ATTS_MAX_ALPHAS; ranks dev int32 [M]; pvalues dev float [M] or
- *   NULL; classes dev uint8 [M]; thresholds dev float [n_alpha] or NULL. */
+ *   NULL; classes dev uint8 [M]; thresholds dev float [n_alpha] or NULL.
+ * ranks == NULL (then pvalues must be NULL too) asks for the decisions only: the classes are then taken from
+ * the equivalent comparison of each score with the thresholds (same classes, bit for bit, no search per
+ * score). */
 int32_t atts_classify_ordinal(const atts_calib* calib, const float* test_scores, int64_t M,
                               const double* alphas, int32_t n_alpha,
                               int32_t* ranks, float* pvalues, uint8_t* classes, float* thresholds,

@@ -302,11 +302,11 @@ def atts_calibrate_online(calib: Calib, new_scores: torch.Tensor) -> None:
                                       ctypes.c_int64(new_scores.numel()), _stream()))
 
 
-def atts_classify_ordinal(calib: Calib, test_scores: torch.Tensor, alphas: Sequence[float], ranks: torch.Tensor,
-                          pvalues: Optional[torch.Tensor], classes: torch.Tensor,
+def atts_classify_ordinal(calib: Calib, test_scores: torch.Tensor, alphas: Sequence[float],
+                          ranks: Optional[torch.Tensor], pvalues: Optional[torch.Tensor], classes: torch.Tensor,
                           thresholds: Optional[torch.Tensor]) -> None:
     M = test_scores.numel()
-    if ranks.numel() != M or classes.numel() != M or (pvalues is not None and pvalues.numel() != M):
+    if (ranks is not None and ranks.numel() != M) or classes.numel() != M or (pvalues is not None and pvalues.numel() != M):
         raise AttsError(ERR_INVALID_ARG, "ranks / pvalues / classes must have M elements")
     if thresholds is not None and thresholds.numel() != len(alphas):
         raise AttsError(ERR_INVALID_ARG, "thresholds must have n_alpha elements")

@@ -450,6 +450,47 @@ __global__ __launch_bounds__(256) void classify_kernel(SearchIndex ix, const flo
     }
 }
 
+// ---- classes only: the decision rule in its quantile form (Eq. "quantile") ------------------------------------
+// ranks + 1 <= r_l  <=>  fewer than r_l calibration scores are >= s  <=>  s > the (N + 1 - r_l)-th smallest one.
+// With the thresholds read from the sorted array once, a class costs n_alpha integer compares and no search:
+// a pure streaming pass.  r_l = 0 never rejects, r_l > N always does; a NaN test score (rank 0) is rejected by
+// every level with r_l >= 1.
+__global__ __launch_bounds__(256) void classify_threshold_kernel(const uint32_t* __restrict__ keys, int64_t n,
+                                                                 const float* __restrict__ test, int64_t m, ClassifyLevels lv,
+                                                                 uint8_t* __restrict__ classes, float* __restrict__ thresholds) {
+    __shared__ uint32_t q_key[ATTS_MAX_ALPHAS];
+    if ((int)threadIdx.x < lv.n_alpha) {
+        const int64_t kth = n + 1 - lv.r[threadIdx.x];        // 1-indexed order statistic
+        const uint32_t qk = (kth >= 1 && kth <= n) ? keys[kth - 1] : 0u;
+        q_key[threadIdx.x] = qk;
+        if (blockIdx.x == 0 && thresholds)
+            thresholds[threadIdx.x] = kth > n ? INFINITY : (kth < 1 ? -INFINITY : key_to_score(qk));
+    }
+    __syncthreads();
+    auto classify_one = [&](float s) {
+        const bool nan = score_is_nan(s);
+        const uint32_t x = score_to_key(s);
+        int cls = 0;
+        for (int l = 0; l < lv.n_alpha; ++l) {
+            const int64_t r = lv.r[l];
+            const bool rej = r > n ? true : (r < 1 ? false : (nan ? true : x > q_key[l]));
+            cls += rej ? 1 : 0;
+        }
+        return (uint32_t)cls;
+    };
+    // four scores per thread and step: one 16-byte load, one 4-byte store (both arrays are 16- / 4-byte aligned at
+    // index 0 whenever the caller's pointers are; a misaligned pair or the tail goes one by one)
+    const int64_t stride = (int64_t)gridDim.x * 256;
+    const bool vec = ((reinterpret_cast<uintptr_t>(test) & 15) | (reinterpret_cast<uintptr_t>(classes) & 3)) == 0;
+    const int64_t m4 = vec ? m / 4 : 0;
+    for (int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x; i < m4; i += stride) {
+        const float4 s4 = reinterpret_cast<const float4*>(test)[i];
+        const uint32_t packed = classify_one(s4.x) | (classify_one(s4.y) << 8) | (classify_one(s4.z) << 16) | (classify_one(s4.w) << 24);
+        reinterpret_cast<uint32_t*>(classes)[i] = packed;
+    }
+    for (int64_t i = m4 * 4 + (int64_t)blockIdx.x * 256 + threadIdx.x; i < m; i += stride) classes[i] = (uint8_t)classify_one(test[i]);
+}
+
 // ---- conditional coverage: one wavefront per input, its own calibration scores as the set ------------------
 struct ConditionalLevels {
     double alpha[ATTS_MAX_ALPHAS];
@@ -667,14 +708,25 @@ int32_t atts_classify_ordinal(const atts_calib* c, const float* test_scores, int
             return fail(ATTS_ERR_INVALID_ARG, "atts_classify_ordinal: alpha levels must be non-decreasing");
     }
     if (c->n < 1) return fail(ATTS_ERR_INVALID_ARG, "atts_classify_ordinal: the calibration set is empty");
-    if (M > 0 && (!test_scores || !ranks || !classes))
-        return fail(ATTS_ERR_INVALID_ARG, "atts_classify_ordinal: test_scores, ranks and classes must not be NULL");
+    if (M > 0 && (!test_scores || !classes))
+        return fail(ATTS_ERR_INVALID_ARG, "atts_classify_ordinal: test_scores and classes must not be NULL");
+    if (!ranks && pvalues) return fail(ATTS_ERR_INVALID_ARG, "atts_classify_ordinal: pvalues without ranks");
     if (M > ((int64_t)1 << 31) * 255) return fail(ATTS_ERR_INVALID_ARG, "atts_classify_ordinal: M too large");
     ClassifyLevels lv;
     lv.n_alpha = n_alpha;
     for (int l = 0; l < ATTS_MAX_ALPHAS; ++l) lv.r[l] = 0;
     for (int l = 0; l < n_alpha; ++l) lv.r[l] = (int64_t)floor(alphas[l] * (double)(c->n + 1));
     if (M == 0 && !thresholds) return ATTS_OK;
+    if (!ranks) {
+        // decisions only: compare with the thresholds, no search
+        const int64_t want = M > 0 ? ceil_div(M, (int64_t)256 * 16) : 1;
+        const unsigned blocks = (unsigned)(want < 1 ? 1 : (want > 4096 ? 4096 : want));
+        StageTimer t_(ATTS_STAGE_CLASSIFY, static_cast<hipStream_t>(hip_stream));
+        hipLaunchKernelGGL(classify_threshold_kernel, dim3(blocks), dim3(256), 0, static_cast<hipStream_t>(hip_stream),
+                           c->keys[c->cur], c->n, test_scores, M, lv, classes, thresholds);
+        ATTS_LAUNCH_CHECK("classify_threshold_kernel");
+        return ATTS_OK;
+    }
     SearchIndex ix;
     ix.lvl[0] = c->keys[c->cur];
     ix.len[0] = c->n;

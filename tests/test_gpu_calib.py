@@ -33,6 +33,20 @@ def _check_against_oracle(A, calib, cal_np, test, alphas, brute=True):
     assert np.array_equal(cls, O.classify(c, r))
     assert np.array_equal(p, O.p_values(c, n).astype(np.float32))
     assert np.array_equal(q, O.quantile_thresholds(cal_np, r).astype(np.float32), equal_nan=True)
+    # decisions only (ranks = NULL): the threshold form of the same rule must give the same classes and thresholds
+    M = len(test)
+    cls2 = torch.full((M,), 77, dtype=torch.uint8, device="cuda")
+    q2 = torch.empty(len(alphas), dtype=torch.float32, device="cuda")
+    A.atts_classify_ordinal(calib, dev(np.asarray(test, dtype=np.float32)), alphas, None, None, cls2, q2)
+    torch.cuda.synchronize()
+    assert np.array_equal(cls2.cpu().numpy(), cls)
+    assert np.array_equal(q2.cpu().numpy(), q, equal_nan=True)
+    if M > 1:                                                  # pointers that are not 16- / 4-byte aligned
+        t_all = dev(np.asarray(test, dtype=np.float32))
+        cls3 = torch.full((M,), 77, dtype=torch.uint8, device="cuda")
+        A.atts_classify_ordinal(calib, t_all[1:], alphas, None, None, cls3[1:], None)
+        torch.cuda.synchronize()
+        assert np.array_equal(cls3.cpu().numpy()[1:], cls[1:])
     return ranks, cls
 
 
@@ -94,6 +108,9 @@ def test_capacity_and_argument_errors():
         with pytest.raises(A.AttsError) as e:
             _classify(A, c, np.zeros(3, np.float32), bad)
         assert e.value.code == A.ERR_INVALID_ARG
+    with pytest.raises(A.AttsError) as e:                      # p-values need the ranks
+        A.atts_classify_ordinal(c, x[:3], [0.5], None, torch.empty(3, device="cuda"), torch.empty(3, dtype=torch.uint8, device="cuda"), None)
+    assert e.value.code == A.ERR_INVALID_ARG
     A.atts_calib_reset(c)
     assert A.atts_calib_size(c) == 0
     A.atts_calibrate_online(c, x[:3])
@@ -124,6 +141,9 @@ def test_calibration_only_workload_full_size():
         assert np.array_equal(ranks.astype(np.int64), cs), step
         assert np.array_equal(cls, O.classify(cs, r)), step
         assert np.array_equal(q, O.quantile_thresholds(cal64, r).astype(np.float32))
+        cls2 = torch.empty(wl.n_test, dtype=torch.uint8, device="cuda")
+        A.atts_classify_ordinal(c, dev(test), list(wl.alphas), None, None, cls2, None)
+        assert np.array_equal(cls2.cpu().numpy(), cls), step
         idx = rng.choice(wl.n_test, 128, replace=False)
         assert np.array_equal(ranks[idx].astype(np.int64), O.rank_counts(cal64, test[idx]))
         counts += np.bincount(cls, minlength=3)
