@@ -375,6 +375,13 @@ def main():
     dom_flops = fl[dom] / max(L, 1)                      # one launch = one layer's gate/up projection
     achieved = dom_flops / (dom_avg_ms * 1e-3) / 1e12 if dom_avg_ms > 0 else 0.0
 
+    # asynchronous arithmetic intensity r = T_c / (T_m + T_s) (Sec. "Q1"), from the per-stage device times of one step:
+    # T_c = contraction stages (GEMMs, attention), T_m = the memory-bound stages between them, T_s = what the
+    # conformal layer costs per step (rank / classify + online calibration; the synchronisation term of the
+    # normalised-score design it replaces)
+    t_c = sum(stages[k]["ms_per_step"] for k in ("gemm_qkv", "attention", "gemm_o", "gemm_gate_up", "gemm_down", "lmhead"))
+    t_m = sum(stages[k]["ms_per_step"] for k in ("embed", "norm", "rope", "gather_norm", "reduce"))
+    t_s = sum(stages[k]["ms_per_step"] for k in ("calib_sort", "calib_merge", "classify"))
     out = {
         "metric": "scored draft tokens/sec (shared-prefix target scoring + online conformal calibration + ordinal "
                   "classification), 1 MI355X",
@@ -396,6 +403,7 @@ def main():
                      "avg_launch_ms": dom_avg_ms, "flops_per_launch": dom_flops,
                      "traffic": measured_traffic(args.workload)},
         "stages": stages,
+        "async_arithmetic_intensity": {"T_c_ms": t_c, "T_m_ms": t_m, "T_s_ms": t_s, "r": t_c / (t_m + t_s) if t_m + t_s > 0 else None},
     }
     if args.workload != "tiny" and not args.skip_extras:
         out["calibration_stage"] = bench_calibration(A, torch, np)
