@@ -24,7 +24,10 @@ namespace {
 
 constexpr int kThreads = 256;
 constexpr int kRowBytes = 128;  // bytes of K per LDS row per slab
-constexpr int kGroupM = 8;
+#ifndef ATTS_GROUP_M
+#define ATTS_GROUP_M 8
+#endif
+constexpr int kGroupM = ATTS_GROUP_M;
 
 template <typename T> struct Mma;
 
