@@ -28,7 +28,7 @@ HBM_PEAK_GBS = 8000.0
 # (FETCH_SIZE, then WRITE_SIZE), each scaled by what the same counter reads for a plain device copy of known
 # size (--traffic-probe); see profiles/traffic_gemm_gate_up_7b.txt.  Valid only for the kernel source it was
 # taken with: reported as null when the hash of csrc/gemm.hip differs.
-MEASURED_TRAFFIC = {"gemm_sha256": "2f241f407fee509a5d803239529e4b19cc2ee1f2f8b86e323d89961833c1974c",
+MEASURED_TRAFFIC = {"gemm_sha256": "bb13763c952ded822477933fb106092f661a81ae2805000df5c77a685dcb3917",
                     "workload": "7b", "bytes_per_launch": 2.115e9}
 
 
