@@ -91,14 +91,17 @@ struct GemmDims {
                             // which add their partial sums to the output with atomics
 };
 
+constexpr int kResidAheadCols = 2;   // column blocks of block row 0 whose old values a kernel may hand to the residual epilogue
+
 // Epilogue shared by both kernels.  acc[i][j][v] is element (row, col) of the tile with
 //   row = wm WM + 32 i + 8 (v / 4) + 4 half + (v % 4),   col = wn WN + 32 j + l32   (WM = 32 MI, WN = 32 NI).
 template <typename T, int MI, int NI, int EPI>
-__device__ __forceinline__ void gemm_epilogue(f32x16 (&acc)[MI][NI], int m0, int n0, int wm, int wn, int l32, int half,
-                                              int tn, void* __restrict__ g_out, const int32_t* __restrict__ g_targets,
-                                              float2* __restrict__ g_partials, float* __restrict__ g_target_logit,
-                                              const float2* __restrict__ g_rope, void* __restrict__ g_vt,
-                                              const GemmDims& g) {
+__device__ __forceinline__ void gemm_epilogue_impl(f32x16 (&acc)[MI][NI], int m0, int n0, int wm, int wn, int l32, int half,
+                                                   int tn, void* __restrict__ g_out, const int32_t* __restrict__ g_targets,
+                                                   float2* __restrict__ g_partials, float* __restrict__ g_target_logit,
+                                                   const float2* __restrict__ g_rope, void* __restrict__ g_vt,
+                                                   const GemmDims& g, const float (&resid0)[NI][16], bool have_resid0) {
+    // resid0 (EPI_RESID_F32 with have_resid0): the output's old values for block row i = 0, loaded earlier by the caller
     constexpr int WM = 32 * MI, WN = 32 * NI;
     const int row_base = m0 + wm * WM + 4 * half;
 
@@ -119,6 +122,7 @@ __device__ __forceinline__ void gemm_epilogue(f32x16 (&acc)[MI][NI], int m0, int
                     if (EPI == EPI_STORE_F32) reinterpret_cast<float*>(g_out)[idx] = acc[i][j][v];
                     if (EPI == EPI_RESID_F32) {
                         if (g.k_slices > 1) unsafeAtomicAdd(reinterpret_cast<float*>(g_out) + idx, acc[i][j][v]);
+                        else if (i == 0 && j < kResidAheadCols && have_resid0) reinterpret_cast<float*>(g_out)[idx] = resid0[j][v] + acc[i][j][v];
                         else reinterpret_cast<float*>(g_out)[idx] += acc[i][j][v];
                     }
                 }
@@ -224,6 +228,17 @@ __device__ __forceinline__ void gemm_epilogue(f32x16 (&acc)[MI][NI], int m0, int
                 if (row_ok && l32 == 0) g_partials[(int64_t)row * g.n_part + part] = make_float2(mx, sum);
             }
     }
+}
+
+template <typename T, int MI, int NI, int EPI>
+__device__ __forceinline__ void gemm_epilogue(f32x16 (&acc)[MI][NI], int m0, int n0, int wm, int wn, int l32, int half,
+                                              int tn, void* __restrict__ g_out, const int32_t* __restrict__ g_targets,
+                                              float2* __restrict__ g_partials, float* __restrict__ g_target_logit,
+                                              const float2* __restrict__ g_rope, void* __restrict__ g_vt,
+                                              const GemmDims& g) {
+    float none[NI][16];   // never read
+    gemm_epilogue_impl<T, MI, NI, EPI>(acc, m0, n0, wm, wn, l32, half, tn, g_out, g_targets, g_partials, g_target_logit, g_rope,
+                                       g_vt, g, none, false);
 }
 
 template <typename T, int BM, int BN, int EPI>
@@ -752,9 +767,30 @@ __global__ __launch_bounds__(128 * kWavesM) void gemm_bf16_wide_kernel(const cha
     };
     struct Yes { constexpr operator bool() const { return true; } };
     struct No { constexpr operator bool() const { return false; } };
+    // Residual epilogue of the 256-row tile (spare registers): the old output values of block row 0 are requested
+    // a dozen slabs before the end, so that half of the epilogue's read latency and traffic lies under the main loop.
+    constexpr bool kResidAhead = EPI == EPI_RESID_F32 && MI == 2;
+    float resid0[NI][16];
+    const bool resid_ahead = kResidAhead && g.k_slices == 1 && nk > 16;
+    auto prefetch_resid = [&]() __attribute__((always_inline)) {
+        const float* o = reinterpret_cast<const float*>(g_out);
+        const int row_base = m0 + wm * WM + 4 * half, col_base = n0 + wn * WN + l32;
+#pragma unroll
+        for (int v = 0; v < 16; ++v) {
+            const int row = row_base + 8 * (v >> 2) + (v & 3);
+#pragma unroll
+            for (int j = 0; j < kResidAheadCols; ++j) {
+                resid0[j][v] = 0.f;
+                if (row < g.M) resid0[j][v] = o[(int64_t)row * g.ldc + col_base + 32 * j];
+            }
+        }
+    };
     int k = 0;
     if (kDeep) {
-        for (; k + 2 < nk; ++k) slab(k, Yes{}, Yes{}, Yes{}, Yes{});
+        for (; k + 2 < nk; ++k) {
+            if (kResidAhead && resid_ahead && k == nk - 14) prefetch_resid();
+            slab(k, Yes{}, Yes{}, Yes{}, Yes{});
+        }
         slab(k, Yes{}, Yes{}, No{}, No{});    // k = nk - 2: only the W rows of the last slab are left to issue
         slab(k + 1, No{}, No{}, No{}, No{});
     } else {
@@ -763,7 +799,8 @@ __global__ __launch_bounds__(128 * kWavesM) void gemm_bf16_wide_kernel(const cha
         slab(k, No{}, No{}, No{}, No{});
     }
 
-    gemm_epilogue<bf16, MI, NI, EPI>(acc, m0, n0, wm, wn, l32, half, tc.tn, g_out, g_targets, g_partials, g_target_logit, g_rope, g_vt, g);
+    gemm_epilogue_impl<bf16, MI, NI, EPI>(acc, m0, n0, wm, wn, l32, half, tc.tn, g_out, g_targets, g_partials, g_target_logit, g_rope,
+                                          g_vt, g, resid0, resid_ahead);
 }
 
 constexpr int kFastBK = 32;
