@@ -30,6 +30,8 @@ What is defined here, and from where:
   * online calibration (paragraph "Online Calibration"): the calibration multiset grows
     by the scores of newly pre-sampled outputs; every rank refers to the multiset as it
     stands at that moment.
+  * target-model continuation of a rejected candidate (paragraph "Target Model Sampling"), greedy:
+    the arg max of the target's next-token logits, token by token.
   * conditional coverage (same paragraph, last sentence; Proposition 2): the same rank,
     p-value and classes, but each input's candidates are compared with that input's own
     calibration scores only.
@@ -150,6 +152,28 @@ def token_logprobs(weights, cfg, prefix_ids, draft_ids) -> np.ndarray:
     h = decoder_hidden(weights, cfg, np.concatenate([prefix_ids, draft_ids]))
     lsm = log_softmax(logits_from_hidden(weights, cfg, h[P - 1: P - 1 + T]))
     return lsm[np.arange(T), draft_ids]
+
+
+def greedy_continuation(weights, cfg, prefix_ids, draft_ids, n_new: int):
+    """Target-model continuation of one candidate (Sec. "How to perform rejection sampling via conformal
+    prediction", paragraph "Target Model Sampling"): the candidate's draft is kept as a prefix and the target model
+    generates n_new more tokens.  Decoding here is greedy: every new token is the arg max of the target's
+    next-token logits given everything before it (first index on exact ties, as numpy's argmax).
+
+    Returns (tokens [n_new] int64, margins [n_new] float64) where margins[t] is the gap between the best and the
+    second-best logit at step t (how close the decision was).
+    """
+    ctx = [int(t) for t in np.concatenate([np.asarray(prefix_ids), np.asarray(draft_ids)])]
+    toks, margins = [], []
+    for _ in range(n_new):
+        h = decoder_hidden(weights, cfg, np.asarray(ctx, dtype=np.int64))
+        z = logits_from_hidden(weights, cfg, h[-1:])[0]
+        best = int(np.argmax(z))
+        second = np.partition(z, -2)[-2]
+        toks.append(best)
+        margins.append(float(z[best] - second))
+        ctx.append(best)
+    return np.asarray(toks, dtype=np.int64), np.asarray(margins, dtype=F64)
 
 
 def conformity_score(logprobs: np.ndarray, mode: int = MEAN_NLL) -> float:

@@ -16,6 +16,7 @@ import torch.nn.functional as F
 
 from oracle import atts_oracle as O
 from synth import ModelConfig, make_token_ids, make_weights
+from util import weights_to_numpy
 
 CFG = ModelConfig(n_layers=2, d_model=32, n_q_heads=4, n_kv_heads=2, head_dim=8, d_ffn=48,
                   vocab=50, dtype="fp32")
@@ -220,3 +221,27 @@ def test_generator_is_device_independent_and_scaled():
     wb = make_weights(ModelConfig(2, 32, 4, 2, 8, 48, 50, "bf16"), 5)
     assert wb["lm_head"].dtype == torch.bfloat16 and wb["final_norm"].dtype == torch.float32
     assert torch.equal(wb["lm_head"], w1["lm_head"].to(torch.bfloat16))
+
+
+# ---- greedy continuation ("Target Model Sampling") ---------------------------------------------------------------
+
+def test_greedy_continuation_is_the_argmax_chain_of_the_scored_distribution():
+    """Two pins that do not re-use the function's own loop: (i) every generated token has the largest log-probability
+    that token_logprobs assigns at its position (checked against every other token of a small vocabulary);
+    (ii) the continuation does not depend on how the context is split into "prefix" and "draft"."""
+    cfg = ModelConfig(2, 48, 4, 2, 12, 80, 37, "fp32")
+    w = weights_to_numpy(make_weights(cfg, seed=11, device="cpu"))
+    prefix = np.array([3, 1, 4, 1, 5, 9, 2, 6]); draft = np.array([5, 3, 5])
+    toks, margins = O.greedy_continuation(w, cfg, prefix, draft, 4)
+    assert toks.shape == (4,) and np.all(margins >= 0)
+    ctx = np.concatenate([prefix, draft])
+    for t in range(4):
+        lp_best = O.token_logprobs(w, cfg, np.concatenate([ctx, toks[:t]]), toks[t:t + 1])[0]
+        for other in range(cfg.vocab):
+            lp = O.token_logprobs(w, cfg, np.concatenate([ctx, toks[:t]]), np.array([other]))[0]
+            assert lp <= lp_best + 1e-12
+    toks2, _ = O.greedy_continuation(w, cfg, ctx[:5], ctx[5:], 4)
+    assert np.array_equal(toks, toks2)
+    # a longer request extends a shorter one
+    toks6, _ = O.greedy_continuation(w, cfg, prefix, draft, 6)
+    assert np.array_equal(toks6[:4], toks)
