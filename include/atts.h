@@ -180,6 +180,20 @@ int32_t atts_score_drafts_cached(const atts_prefix* prefix, const int32_t* draft
                                  int32_t T_max, int32_t score_mode, float* token_logprobs, float* scores, void* workspace,
                                  size_t workspace_bytes, void* hip_stream);
 
+/* Target-model continuation of rejected candidates (Sec. "How to perform rejection sampling via conformal
+ * prediction", paragraph "Target Model Sampling"): each of the K candidates keeps its draft as a prefix and the
+ * target model generates n_new more tokens for it.  Decoding is greedy: out_ids[k][t] is the first arg max of the
+ * target's next-token logits given prefix + draft k + out_ids[k][0 .. t - 1].  All K candidates advance together,
+ * one row per candidate and step (the weight-streaming regime); their keys / values share the cached prefix.
+ *   prefix      handle holding the shared context (length >= 1); not modified
+ *   draft_ids   dev int32 [K, T] row-major, the rejected drafts (all T tokens are used)
+ *   out_ids     dev int32 [K, n_new] row-major
+ *   workspace   dev, 256-byte aligned, >= atts_continue_workspace_bytes(prefix, K, T, n_new) bytes; scratch
+ * 1 <= K <= 768, T >= 1, n_new >= 1, length + T + n_new <= 1048576.  Out-of-range ids as in atts_score_drafts. */
+int32_t atts_continue_workspace_bytes(const atts_prefix* prefix, int32_t K, int32_t T, int32_t n_new, size_t* out_bytes);
+int32_t atts_continue_greedy(const atts_prefix* prefix, const int32_t* draft_ids, int32_t K, int32_t T, int32_t n_new,
+                             int32_t* out_ids, void* workspace, size_t workspace_bytes, void* hip_stream);
+
 /* Synchronises hip_stream, copies the sticky device error flag to *host_flag (0 = clean,
  * 1 = some token id was out of range since the last check) and clears it. */
 int32_t atts_model_check(const atts_model* model, void* hip_stream, int32_t* host_flag);

@@ -226,9 +226,18 @@ namespace {
 //                each layer's attention.  save: the new rows' keys / values and the last row's hidden state are
 //                appended to `pre` (K == 1: the new rows continue the prefix as one causal sequence).
 // score: LM head + scores for the K T scoring rows (else the pass stops after the last layer).
+// Where a continuation call keeps the keys / values of the whole token tree, per layer, as rows
+// (rows [0, P) prefix, P + j Tc + t = token t of branch j).
+struct TreeSave {
+    char* kc;          // [L][Rc][n_kv hd]
+    char* vc;          // same shape
+    int32_t Tc;        // rows reserved per branch
+    size_t layer_bytes;
+};
+
 int32_t forward_tree(const atts_model* m, ScoreShape s, int32_t row0, atts_prefix* pre, bool save, bool score,
                      const int32_t* prefix_ids, const int32_t* draft_ids, const int32_t* draft_lens, int32_t score_mode,
-                     float* token_logprobs, float* scores, void* workspace, hipStream_t st) {
+                     float* token_logprobs, float* scores, void* workspace, hipStream_t st, const TreeSave* tree = nullptr) {
     const atts_model_desc& d = m->desc;
     const Workspace ws = carve(d, s);
     char* base = static_cast<char*>(workspace);
@@ -252,7 +261,8 @@ int32_t forward_tree(const atts_model* m, ScoreShape s, int32_t row0, atts_prefi
     const int qkv_out = (d.n_q_heads + 2 * d.n_kv_heads) * d.head_dim;
     const bool padded = pads_rows(d);
     // the fused epilogue writes 4 transposed-V columns per store: the first computed row must keep them aligned
-    const bool fuse_rope = vt != nullptr && row0 % 4 == 0 && qkv_rope_fusable(d.dtype, M, qkv_out, d.d_model, d.head_dim, padded);
+    // (a continuation call wants the value rows in the qkv buffer: the unfused path leaves them there)
+    const bool fuse_rope = vt != nullptr && !tree && row0 % 4 == 0 && qkv_rope_fusable(d.dtype, M, qkv_out, d.d_model, d.head_dim, padded);
     float* h0 = h + (size_t)row0 * d.d_model;
     // few rows: the QKV projection splits its K range like the residual projections do; the workgroups add into an
     // fp32 buffer and a small kernel applies RoPE / the V transpose afterwards
@@ -313,6 +323,18 @@ int32_t forward_tree(const atts_model* m, ScoreShape s, int32_t row0, atts_prefi
                 ATTS_TRY(launch_copy2d(d.dtype, vc, kvd, wv, qkv_out, row0, kvd, st));
                 if (save) ATTS_TRY(launch_copy2d(d.dtype, wv + (size_t)row0 * qkv_out * es, qkv_out, vc + (size_t)row0 * kvd * es, kvd, M, kvd, st));
             }
+        }
+        if (tree) {
+            // keys / values of the whole tree as rows into the continuation cache of this layer (pre != nullptr)
+            char* kc = tree->kc + (size_t)l * tree->layer_bytes;
+            char* vc = tree->vc + (size_t)l * tree->layer_bytes;
+            ATTS_TRY(launch_copy2d(d.dtype, pre->k_cache + (size_t)l * pre->capacity * kvd * es, kvd, kc, kvd, row0, kvd, st));
+            if (pre->uses_vt)
+                ATTS_TRY(launch_transpose_to_rows(d.dtype, pre->v_cache + (size_t)l * kvd * pre->cap_ld * es, pre->cap_ld, vc, kvd, row0, kvd, st));
+            else
+                ATTS_TRY(launch_copy2d(d.dtype, pre->v_cache + (size_t)l * pre->capacity * kvd * es, kvd, vc, kvd, row0, kvd, st));
+            ATTS_TRY(launch_tree_rows_to_cache(d.dtype, qkv + (size_t)qd * es, qkv_out, kc, kvd, s.P, s.T, tree->Tc, M, kvd, st));
+            ATTS_TRY(launch_tree_rows_to_cache(d.dtype, qkv + (size_t)(qd + kvd) * es, qkv_out, vc, kvd, s.P, s.T, tree->Tc, M, kvd, st));
         }
         {
             StageTimer t_(ATTS_STAGE_ATTENTION, st);
@@ -487,6 +509,145 @@ int32_t atts_score_drafts_cached(const atts_prefix* p, const int32_t* draft_ids,
     ATTS_TRY(check_workspace("atts_score_drafts_cached", p->model->desc, s, workspace, workspace_bytes));
     return forward_tree(p->model, s, p->P, const_cast<atts_prefix*>(p), false, true, nullptr, draft_ids, draft_lens, score_mode,
                         token_logprobs, scores, workspace, static_cast<hipStream_t>(hip_stream));
+}
+
+// ---------------------------------------------------------------------------- continuation
+
+namespace {
+struct ContinueSpace {
+    size_t scoring, kc, vc, h, xn, ao, act, xs, qkv32, q, logits, rope, total;
+    int32_t Tc;
+    size_t layer_bytes;
+};
+
+ContinueSpace carve_continue(const atts_model_desc& d, int32_t P, int32_t Kr, int32_t T, int32_t n_new) {
+    const size_t es = dtype_size(d.dtype);
+    const size_t kvd = (size_t)d.n_kv_heads * d.head_dim, qd = (size_t)d.n_q_heads * d.head_dim;
+    const size_t qkv_out = qd + 2 * kvd, L = (size_t)(d.n_layers > 0 ? d.n_layers : 1);
+    const size_t rows_a = pads_rows(d) ? align_up((size_t)Kr, 768) : (size_t)Kr;    // A operands of the aligned GEMM
+    ContinueSpace c{};
+    c.Tc = T + n_new;
+    const size_t Rc = (size_t)P + (size_t)Kr * c.Tc;
+    c.layer_bytes = align_up(Rc * kvd * es, 256);
+    size_t off = align_up(carve(d, ScoreShape{P, Kr, T}).total, 256);
+    c.scoring = 0;
+    auto take = [&](size_t bytes) {
+        size_t at = off;
+        off += align_up(bytes, 256);
+        return at;
+    };
+    c.kc = take(L * c.layer_bytes);
+    c.vc = take(L * c.layer_bytes);
+    c.h = take((size_t)Kr * d.d_model * sizeof(float));
+    c.xn = take(rows_a * d.d_model * es);
+    c.ao = take(rows_a * qd * es);
+    c.act = take(rows_a * (size_t)d.d_ffn * es);
+    c.xs = take(rows_a * d.d_model * es);
+    c.qkv32 = take((size_t)Kr * qkv_out * sizeof(float));
+    c.q = take((size_t)Kr * qd * es);
+    c.logits = take((size_t)Kr * d.vocab * sizeof(float));
+    c.rope = take(((size_t)P + c.Tc) * (d.head_dim / 2) * sizeof(float2));
+    c.total = off;
+    return c;
+}
+
+int32_t check_continue_shape(const char* fn, const atts_prefix* p, int32_t Kr, int32_t T, int32_t n_new) {
+    if (!p) return fail(ATTS_ERR_INVALID_ARG, "%s: NULL handle", fn);
+    if (p->P < 1) return fail(ATTS_ERR_INVALID_ARG, "%s: the prefix is empty", fn);
+    if (Kr < 1 || Kr > 768 || T < 1 || n_new < 1)
+        return fail(ATTS_ERR_INVALID_ARG, "%s: need 1 <= K <= 768, T >= 1, n_new >= 1 (K = %d, T = %d, n_new = %d)", fn, Kr, T, n_new);
+    return check_score_shape(fn, p->P, Kr, T + n_new);
+}
+}  // namespace
+
+int32_t atts_continue_workspace_bytes(const atts_prefix* p, int32_t K, int32_t T, int32_t n_new, size_t* out_bytes) {
+    if (!out_bytes) return fail(ATTS_ERR_INVALID_ARG, "atts_continue_workspace_bytes: out_bytes is NULL");
+    ATTS_TRY(check_continue_shape("atts_continue_workspace_bytes", p, K, T, n_new));
+    *out_bytes = carve_continue(p->model->desc, p->P, K, T, n_new).total;
+    return ATTS_OK;
+}
+
+int32_t atts_continue_greedy(const atts_prefix* p, const int32_t* draft_ids, int32_t K, int32_t T, int32_t n_new,
+                             int32_t* out_ids, void* workspace, size_t workspace_bytes, void* hip_stream) {
+    ATTS_TRY(check_continue_shape("atts_continue_greedy", p, K, T, n_new));
+    if (!draft_ids || !out_ids) return fail(ATTS_ERR_INVALID_ARG, "atts_continue_greedy: NULL draft_ids / out_ids");
+    const atts_model* m = p->model;
+    const atts_model_desc& d = m->desc;
+    const int32_t P = p->P;
+    const ContinueSpace cs = carve_continue(d, P, K, T, n_new);
+    if (!workspace || ((uintptr_t)workspace & 255)) return fail(ATTS_ERR_WORKSPACE, "atts_continue_greedy: workspace is NULL or not 256-byte aligned");
+    if (workspace_bytes < cs.total)
+        return fail(ATTS_ERR_WORKSPACE, "atts_continue_greedy: workspace has %zu bytes, %zu needed", workspace_bytes, cs.total);
+    hipStream_t st = static_cast<hipStream_t>(hip_stream);
+    char* base = static_cast<char*>(workspace);
+    const size_t es = dtype_size(d.dtype);
+    const int qd = d.n_q_heads * d.head_dim, kvd = d.n_kv_heads * d.head_dim, qkv_out = qd + 2 * kvd, half = d.head_dim / 2;
+    const bool padded = pads_rows(d);
+    const ScoreShape s{P, K, T};
+
+    // 1. the drafts through the model against the cached prefix; keys / values of the whole tree kept per layer
+    TreeSave tree{base + cs.kc, base + cs.vc, cs.Tc, cs.layer_bytes};
+    ATTS_TRY(forward_tree(m, s, P, const_cast<atts_prefix*>(p), false, false, nullptr, draft_ids, nullptr, ATTS_SCORE_MEAN_NLL, nullptr,
+                          nullptr, workspace, st, &tree));
+    const float* h_tree = reinterpret_cast<const float*>(base + carve(d, s).h);
+
+    float* h = reinterpret_cast<float*>(base + cs.h);
+    char* xn = base + cs.xn;
+    char* ao = base + cs.ao;
+    char* act = base + cs.act;
+    char* xs = base + cs.xs;
+    float* qkv32 = reinterpret_cast<float*>(base + cs.qkv32);
+    char* q = base + cs.q;
+    float* logits = reinterpret_cast<float*>(base + cs.logits);
+    float2* rope = reinterpret_cast<float2*>(base + cs.rope);
+    // (cos, sin) rows of the positions the new tokens take: P + T ... P + T + n_new - 1 (indexed by absolute position)
+    ATTS_TRY(launch_rope_table(rope, ScoreShape{P + T, 1, n_new}, P + T, d.head_dim, d.rope_theta, st));
+
+    auto next_token = [&](int t) -> int32_t {     // xs holds the normalised last hidden states: logits, arg max -> out_ids[:, t]
+        GemmArgs g{};
+        g.a = xs; g.w = m->lm_head; g.out = logits; g.M = K; g.N = d.vocab; g.Kd = d.d_model;
+        g.lda = d.d_model; g.ldw = d.d_model; g.ldc = d.vocab; g.a_rows_padded = padded;
+        ATTS_TRY(launch_gemm(d.dtype, EPI_STORE_F32, g, st));
+        return launch_argmax_rows(logits, d.vocab, d.vocab, K, out_ids + t, n_new, st);
+    };
+
+    // 2. token 0 follows from the last draft row of every branch
+    ATTS_TRY(launch_norm_strided_rows(d.dtype, h_tree, m->final_norm, d.rms_eps, d.d_model, (int64_t)P + T - 1, T, K, xs, st));
+    ATTS_TRY(next_token(0));
+
+    // 3. one row per branch and step: token t - 1 goes in at branch position T + t - 1 and predicts token t
+    for (int t = 1; t < n_new; ++t) {
+        const int t_new = T + t - 1;
+        ATTS_TRY(launch_embed_rows(d.dtype, m->tok_embed, d.vocab, d.d_model, out_ids + (t - 1), n_new, K, h, m->err_flag, st));
+        for (int l = 0; l < d.n_layers; ++l) {
+            char* kc = tree.kc + (size_t)l * tree.layer_bytes;
+            char* vc = tree.vc + (size_t)l * tree.layer_bytes;
+            ATTS_TRY(launch_rmsnorm(d.dtype, h, m->attn_norm[l], d.rms_eps, K, d.d_model, xn, st));
+            GemmArgs g{};
+            g.a = xn; g.w = m->wqkv[l]; g.out = qkv32; g.M = K; g.N = qkv_out; g.Kd = d.d_model;
+            g.lda = d.d_model; g.ldw = d.d_model; g.ldc = qkv_out; g.a_rows_padded = padded;
+            ATTS_TRY(launch_gemm(d.dtype, EPI_STORE_F32, g, st));
+            ATTS_TRY(launch_decode_qkv_finish(d.dtype, qkv32, rope + (size_t)(P + t_new) * half, K, d.n_q_heads, d.n_kv_heads,
+                                              d.head_dim, P, cs.Tc, t_new, q, kc, vc, st));
+            ATTS_TRY(launch_attn_decode(d.dtype, q, kc, vc, ao, K, P, cs.Tc, t_new, d.n_q_heads, d.n_kv_heads, d.head_dim, st));
+            g = GemmArgs{};
+            g.a = ao; g.w = m->wo[l]; g.out = h; g.M = K; g.N = d.d_model; g.Kd = qd;
+            g.lda = qd; g.ldw = qd; g.ldc = d.d_model; g.a_rows_padded = padded;
+            ATTS_TRY(launch_gemm(d.dtype, EPI_RESID_F32, g, st));
+            ATTS_TRY(launch_rmsnorm(d.dtype, h, m->ffn_norm[l], d.rms_eps, K, d.d_model, xn, st));
+            g = GemmArgs{};
+            g.a = xn; g.w = m->w_gate_up[l]; g.out = act; g.M = K; g.N = d.d_ffn; g.Kd = d.d_model;
+            g.lda = d.d_model; g.ldw = d.d_model; g.ldc = d.d_ffn; g.a_rows_padded = padded;
+            ATTS_TRY(launch_gemm(d.dtype, EPI_SWIGLU, g, st));
+            g = GemmArgs{};
+            g.a = act; g.w = m->w_down[l]; g.out = h; g.M = K; g.N = d.d_model; g.Kd = d.d_ffn;
+            g.lda = d.d_ffn; g.ldw = d.d_ffn; g.ldc = d.d_model; g.a_rows_padded = padded;
+            ATTS_TRY(launch_gemm(d.dtype, EPI_RESID_F32, g, st));
+        }
+        ATTS_TRY(launch_norm_strided_rows(d.dtype, h, m->final_norm, d.rms_eps, d.d_model, 0, 1, K, xs, st));
+        ATTS_TRY(next_token(t));
+    }
+    return ATTS_OK;
 }
 
 int32_t atts_model_check(const atts_model* m, void* hip_stream, int32_t* host_flag) {

@@ -164,6 +164,23 @@ int32_t launch_gather_norm(int32_t dtype, const float* h, const float* gain, flo
 int32_t launch_score_reduce(const float* lp, const int32_t* draft_lens, int32_t K, int32_t T, int32_t mode,
                             float* token_logprobs, float* scores, hipStream_t stream);
 
+// ---- continuation (decode.hip): key / value cache rows [0, P) prefix, P + j Tc + t = token t of branch j ----------
+int32_t launch_tree_rows_to_cache(int32_t dtype, const void* src, int64_t src_ld, void* dst, int64_t dst_ld, int32_t P, int32_t Tn,
+                                  int32_t Tc, int32_t rows, int32_t cols, hipStream_t stream);
+int32_t launch_transpose_to_rows(int32_t dtype, const void* src, int64_t src_ld, void* dst, int64_t dst_ld, int32_t rows,
+                                 int32_t cols, hipStream_t stream);
+int32_t launch_embed_rows(int32_t dtype, const void* tok_embed, int32_t vocab, int32_t d, const int32_t* ids, int64_t stride,
+                          int32_t rows, float* h, int32_t* err_flag, hipStream_t stream);
+int32_t launch_decode_qkv_finish(int32_t dtype, const float* acc, const float2* cs, int32_t Kr, int32_t nq, int32_t nkv, int32_t hd,
+                                 int32_t P, int32_t Tc, int32_t t_new, void* q_out, void* k_cache, void* v_cache,
+                                 hipStream_t stream);
+int32_t launch_attn_decode(int32_t dtype, const void* q, const void* k_cache, const void* v_cache, void* out, int32_t Kr, int32_t P,
+                           int32_t Tc, int32_t t_new, int32_t nq, int32_t nkv, int32_t hd, hipStream_t stream);
+int32_t launch_argmax_rows(const float* logits, int64_t ld, int32_t V, int32_t rows, int32_t* ids, int64_t stride,
+                           hipStream_t stream);
+int32_t launch_norm_strided_rows(int32_t dtype, const float* h, const float* gain, float eps, int32_t d, int64_t first, int64_t step,
+                                 int32_t rows, void* xs, hipStream_t stream);
+
 bool attention_uses_vt(int32_t dtype, int32_t hd);
 // queries are the rows [row0, R); keys / values of all rows [0, R) must be present
 int32_t launch_attention(int32_t dtype, const void* qkv, const void* vt, int64_t ldv, void* out, ScoreShape s, int32_t row0,

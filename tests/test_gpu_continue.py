@@ -1,0 +1,97 @@
+"""Greedy target-model continuation ("Target Model Sampling") against the oracle's arg-max chain.
+
+The token decided at a step is an arg max over floating-point logits: where the oracle's best and second-best
+logits are closer than the accuracy of the GPU arithmetic, either token is a correct decision; the comparison
+therefore requires equal tokens wherever the oracle's margin exceeds a tolerance, and after a (permitted)
+divergence the rest of that candidate is not compared (its context differs)."""
+import numpy as np
+import pytest
+import torch
+
+from oracle import atts_oracle as O
+from synth import WORKLOADS, ModelConfig, make_token_ids, make_weights
+from util import announce, dev, weights_to_numpy, ws
+
+pytestmark = pytest.mark.gpu
+
+MARGIN = {"fp32": 1e-3, "bf16": 0.15}      # logits here are O(1): bf16 rounding through the model moves them by a few 1e-2
+
+
+def _continue(A, model, prefix, drafts, n_new, chunks=None):
+    pre = A.Prefix(model, capacity=len(prefix))
+    lo = 0
+    for n in (chunks or (len(prefix),)):
+        A.atts_prefix_extend(pre, dev(prefix[lo:lo + n]), ws(A.atts_prefix_extend_workspace_bytes(pre, n)))
+        lo += n
+    K, T = drafts.shape
+    out = torch.full((K, n_new), -1, dtype=torch.int32, device="cuda")
+    A.atts_continue_greedy(pre, dev(drafts), out, ws(A.atts_continue_workspace_bytes(pre, K, T, n_new)))
+    torch.cuda.synchronize()
+    return out.cpu().numpy(), pre
+
+
+def _compare(cfg, w_np, prefix, drafts, got, n_new):
+    agree = 0
+    for k in range(drafts.shape[0]):
+        ref, margins = O.greedy_continuation(w_np, cfg, prefix, drafts[k], n_new)
+        for t in range(n_new):
+            if got[k, t] == ref[t]:
+                agree += 1
+                continue
+            assert margins[t] <= MARGIN[cfg.dtype], (k, t, int(got[k, t]), int(ref[t]), margins[t])
+            # the GPU's token must itself be a near-maximum of the oracle's distribution at that step
+            ctx = np.concatenate([prefix, drafts[k], ref[:t]])
+            lp = O.token_logprobs(w_np, cfg, ctx, np.array([got[k, t], ref[t]]))
+            # (second entry is conditioned on the first; only the first matters here)
+            best = O.token_logprobs(w_np, cfg, ctx, ref[t:t + 1])[0]
+            assert best - lp[0] <= MARGIN[cfg.dtype]
+            break
+    return agree
+
+
+@pytest.mark.parametrize("cfg,P,K,T,n_new,chunks", [
+    (WORKLOADS["tiny"].model, 24, 3, 9, 6, None),                                   # fp32, simple attention
+    (ModelConfig(2, 96, 4, 1, 24, 200, 515, "fp32"), 7, 2, 5, 8, (3, 4)),
+    (ModelConfig(2, 256, 4, 2, 128, 512, 2048, "bf16"), 40, 4, 12, 6, None),         # bf16, transposed-value prefix cache
+    (ModelConfig(2, 256, 4, 2, 128, 520, 2003, "bf16"), 33, 2, 7, 5, (32, 1)),       # general GEMM path
+])
+def test_greedy_continuation_matches_the_oracle(cfg, P, K, T, n_new, chunks):
+    import paper_2509_15148_amd as A
+    announce("continue greedy", cfg, P, K, T, n_new)
+    w_dev = make_weights(cfg, seed=P * 13 + K, device="cuda")
+    prefix, drafts = [x.numpy() for x in make_token_ids(cfg.vocab, P, K, T, P + K)]
+    model = A.Model(cfg, w_dev)
+    got, pre = _continue(A, model, prefix, drafts, n_new, chunks)
+    assert got.min() >= 0 and got.max() < cfg.vocab
+    agree = _compare(cfg, weights_to_numpy(w_dev), prefix, drafts, got, n_new)
+    assert agree >= K * n_new // 2                       # most decisions are clear-cut and must agree exactly
+    assert A.atts_prefix_length(pre) == P and A.atts_model_check(model) == 0
+    # n_new = 1 is the first token of the longer run; a second run reproduces the first (up to near-ties)
+    got1, _ = _continue(A, model, prefix, drafts, 1, chunks)
+    for k in range(K):
+        if got1[k, 0] != got[k, 0]:
+            _, m = O.greedy_continuation(weights_to_numpy(w_dev), cfg, prefix, drafts[k], 1)
+            assert m[0] <= MARGIN[cfg.dtype]
+
+
+def test_continuation_argument_errors():
+    import paper_2509_15148_amd as A
+    cfg = WORKLOADS["tiny"].model
+    announce("continue errors")
+    w_dev = make_weights(cfg, seed=5, device="cuda")
+    model = A.Model(cfg, w_dev)
+    pre = A.Prefix(model, capacity=8)
+    drafts = dev(np.zeros((2, 3), np.int32))
+    out = torch.zeros((2, 4), dtype=torch.int32, device="cuda")
+    with pytest.raises(A.AttsError) as e:                          # empty prefix
+        A.atts_continue_workspace_bytes(pre, 2, 3, 4)
+    assert e.value.code == A.ERR_INVALID_ARG
+    A.atts_prefix_extend(pre, dev(np.arange(5, dtype=np.int32)), ws(A.atts_prefix_extend_workspace_bytes(pre, 5)))
+    need = A.atts_continue_workspace_bytes(pre, 2, 3, 4)
+    with pytest.raises(A.AttsError) as e:
+        A.atts_continue_greedy(pre, drafts, out, ws(need - 256))
+    assert e.value.code == A.ERR_WORKSPACE
+    for K, T, n in ((0, 3, 4), (2, 0, 4), (2, 3, 0), (769, 3, 4)):
+        with pytest.raises(A.AttsError) as e:
+            A.atts_continue_workspace_bytes(pre, K, T, n)
+        assert e.value.code == A.ERR_INVALID_ARG
