@@ -218,6 +218,34 @@ def bench_warm_prefix(A, torch, model, cfg, wl, L, steps=5):
             "mfma_frac": warm / dt / 1e12 / MFMA_PEAK_TFLOPS[cfg.dtype]}
 
 
+def bench_continuation(A, torch, model, cfg, wl, L, K=4, n_new=16):
+    """Target-model continuation of K rejected candidates (about alpha K of a turn): prefix cached, each candidate's
+    T-token draft as its own context, n_new greedy tokens each: one K-row pass per generated token."""
+    from synth import make_token_ids
+    pre = A.Prefix(model, wl.P)
+    p, d = make_token_ids(cfg.vocab, wl.P, K, wl.T, wl.seed + 700001, device="cuda")
+    A.atts_prefix_extend(pre, p, torch.empty(A.atts_prefix_extend_workspace_bytes(pre, wl.P), dtype=torch.uint8, device="cuda"))
+    ws = torch.empty(A.atts_continue_workspace_bytes(pre, K, wl.T, n_new), dtype=torch.uint8, device="cuda")
+    out = torch.empty(K, n_new, dtype=torch.int32, device="cuda")
+    out1 = torch.empty(K, 1, dtype=torch.int32, device="cuda")
+    def timed(o):
+        A.atts_continue_greedy(pre, d, o, ws)
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        A.atts_continue_greedy(pre, d, o, ws)
+        torch.cuda.synchronize()
+        return time.perf_counter() - t0
+    t_full, t_one = timed(out), timed(out1)
+    per_tok = (t_full - t_one) / (n_new - 1)            # the context pass + first token is common to both
+    esz = 2 if cfg.dtype == "bf16" else 4
+    d_, hd = cfg.d_model, cfg.head_dim
+    per_layer = d_ * (cfg.n_q_heads + 2 * cfg.n_kv_heads) * hd + cfg.n_q_heads * hd * d_ + 3 * d_ * cfg.d_ffn
+    wbytes = esz * (per_layer * L + cfg.vocab * d_)
+    return {"workload": f"{wl.name} model, prefix of {wl.P} cached, {K} candidates x {wl.T}-token drafts continued by {n_new} tokens",
+            "context_pass_ms": t_one * 1e3, "ms_per_decode_step": per_tok * 1e3, "generated_tokens_per_s": K / per_tok,
+            "weight_bytes_per_step": wbytes, "achieved_GBs": wbytes / per_tok / 1e9, "hbm_frac": wbytes / per_tok / 1e9 / HBM_PEAK_GBS}
+
+
 def bench_decode_shaped(A, torch, model, cfg, wl, L, K=16, T=8, steps=5):
     """The same resident model at a decode-like shape: the workload's prefix is cached in a prefix handle and only
     K T = 128 draft rows go through the model, well under the ~315 flop/byte ridge: one scoring pass must stream
@@ -411,6 +439,7 @@ def main():
         out["warm_prefix"] = bench_warm_prefix(A, torch, model, cfg, wl, L)
         out["decode_shaped"] = bench_decode_shaped(A, torch, model, cfg, wl, L)
         out["conditional_stage"] = bench_conditional(A, torch, np)
+        out["continuation"] = bench_continuation(A, torch, model, cfg, wl, L)
     if not args.no_cpu_baseline:
         p0, d0 = ids[0]
         out["cpu_baseline"] = cpu_baseline(cfg, wl, w, p0.cpu().numpy(), d0.cpu().numpy(), L, min(args.cpu_layers, L))

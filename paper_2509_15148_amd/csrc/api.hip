@@ -602,6 +602,10 @@ int32_t atts_continue_greedy(const atts_prefix* p, const int32_t* draft_ids, int
     float2* rope = reinterpret_cast<float2*>(base + cs.rope);
     // (cos, sin) rows of the positions the new tokens take: P + T ... P + T + n_new - 1 (indexed by absolute position)
     ATTS_TRY(launch_rope_table(rope, ScoreShape{P + T, 1, n_new}, P + T, d.head_dim, d.rope_theta, st));
+    // the QKV projection of a step has few tiles: where the aligned kernel would split its K range, the workgroups
+    // add into the (cleared) fp32 buffer; otherwise they store
+    const bool split_qkv = gemm_splits_k(d.dtype, K, qkv_out, d.d_model, padded);
+    if (split_qkv) ATTS_TRY(launch_zero_f32(qkv32, (int64_t)K * qkv_out, st));
 
     auto next_token = [&](int t) -> int32_t {     // xs holds the normalised last hidden states: logits, arg max -> out_ids[:, t]
         GemmArgs g{};
@@ -626,7 +630,7 @@ int32_t atts_continue_greedy(const atts_prefix* p, const int32_t* draft_ids, int
             GemmArgs g{};
             g.a = xn; g.w = m->wqkv[l]; g.out = qkv32; g.M = K; g.N = qkv_out; g.Kd = d.d_model;
             g.lda = d.d_model; g.ldw = d.d_model; g.ldc = qkv_out; g.a_rows_padded = padded;
-            ATTS_TRY(launch_gemm(d.dtype, EPI_STORE_F32, g, st));
+            ATTS_TRY(launch_gemm(d.dtype, split_qkv ? EPI_RESID_F32 : EPI_STORE_F32, g, st));
             ATTS_TRY(launch_decode_qkv_finish(d.dtype, qkv32, rope + (size_t)(P + t_new) * half, K, d.n_q_heads, d.n_kv_heads,
                                               d.head_dim, P, cs.Tc, t_new, q, kc, vc, st));
             ATTS_TRY(launch_attn_decode(d.dtype, q, kc, vc, ao, K, P, cs.Tc, t_new, d.n_q_heads, d.n_kv_heads, d.head_dim, st));

@@ -171,7 +171,7 @@ int32_t launch_transpose_to_rows(int32_t dtype, const void* src, int64_t src_ld,
                                  int32_t cols, hipStream_t stream);
 int32_t launch_embed_rows(int32_t dtype, const void* tok_embed, int32_t vocab, int32_t d, const int32_t* ids, int64_t stride,
                           int32_t rows, float* h, int32_t* err_flag, hipStream_t stream);
-int32_t launch_decode_qkv_finish(int32_t dtype, const float* acc, const float2* cs, int32_t Kr, int32_t nq, int32_t nkv, int32_t hd,
+int32_t launch_decode_qkv_finish(int32_t dtype, float* acc, const float2* cs, int32_t Kr, int32_t nq, int32_t nkv, int32_t hd,
                                  int32_t P, int32_t Tc, int32_t t_new, void* q_out, void* k_cache, void* v_cache,
                                  hipStream_t stream);
 int32_t launch_attn_decode(int32_t dtype, const void* q, const void* k_cache, const void* v_cache, void* out, int32_t Kr, int32_t P,

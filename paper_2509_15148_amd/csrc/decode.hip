@@ -54,10 +54,10 @@ __global__ __launch_bounds__(256) void embed_rows_kernel(const T* __restrict__ e
     for (int c = threadIdx.x; c < d; c += 256) h[(int64_t)j * d + c] = to_f32<T>(src[c]);
 }
 
-// One decode row per branch: acc [Kr, (nq + 2 nkv) hd] fp32 -> q (rotated) to q_out [Kr, nq hd]; k (rotated) and v
+// One decode row per branch: acc [Kr, (nq + 2 nkv) hd] fp32 (cleared on return) -> q (rotated) to q_out [Kr, nq hd]; k (rotated) and v
 // to row `P + j Tc + t_new` of the layer's key / value cache.  cs: the (cos, sin) row of the new position.
 template <typename T>
-__global__ __launch_bounds__(256) void decode_qkv_finish_kernel(const float* __restrict__ acc, const float2* __restrict__ cs, int Kr,
+__global__ __launch_bounds__(256) void decode_qkv_finish_kernel(float* __restrict__ acc, const float2* __restrict__ cs, int Kr,
                                                                 int nq, int nkv, int hd, int P, int Tc, int t_new,
                                                                 T* __restrict__ q_out, T* __restrict__ k_cache,
                                                                 T* __restrict__ v_cache) {
@@ -67,8 +67,10 @@ __global__ __launch_bounds__(256) void decode_qkv_finish_kernel(const float* __r
     const int i = (int)(idx % half);
     const int head = (int)((idx / half) % heads);
     const int j = (int)(idx / ((int64_t)half * heads));
-    const float* a = acc + (int64_t)j * heads * hd + head * hd + i;
+    float* a = acc + (int64_t)j * heads * hd + head * hd + i;
     const float x1 = a[0], x2 = a[half];
+    a[0] = 0.f;                                  // left clear for a K-split projection that adds into it
+    a[half] = 0.f;
     const int64_t crow = P + (int64_t)j * Tc + t_new;
     if (head < nq + nkv) {
         const float2 c_s = cs[i];
@@ -83,49 +85,79 @@ __global__ __launch_bounds__(256) void decode_qkv_finish_kernel(const float* __r
     }
 }
 
-// One wavefront per (branch, head): the new row of branch j attends to the prefix rows and to rows 0 .. t_new of
-// its own branch.  Scores in LDS (P + t_new + 1 floats), fixed summation order.
+// One workgroup (4 wavefronts) per (branch, head): the new row of branch j attends to the prefix rows and to rows
+// 0 .. t_new of its own branch.  Scores: one key per thread and pass (16-byte loads along the key row); output:
+// every wavefront accumulates a quarter of the keys (lane = a pair of dims, 128 / 256 contiguous bytes per key), the
+// four partial sums are added in a fixed order.
 template <typename T>
-__global__ __launch_bounds__(64) void attn_decode_kernel(const T* __restrict__ q, const T* __restrict__ k_cache,
-                                                         const T* __restrict__ v_cache, T* __restrict__ out, int P, int Tc,
-                                                         int t_new, int nq, int nkv, int hd, float scale) {
-    extern __shared__ float sm[];           // [hd] query, then [n] scores
+__global__ __launch_bounds__(256) void attn_decode_kernel(const T* __restrict__ q, const T* __restrict__ k_cache,
+                                                          const T* __restrict__ v_cache, T* __restrict__ out, int P, int Tc,
+                                                          int t_new, int nq, int nkv, int hd, float scale) {
+    extern __shared__ float sm[];           // [hd] query | [n] scores | [8] reductions | [4][hd] partial outputs
+    const int n = P + t_new + 1;
     float* sq = sm;
     float* sp = sm + hd;
-    const int j = blockIdx.x, head = blockIdx.y, lane = threadIdx.x;
+    float* red = sp + n;
+    float* so = red + 8;
+    const int j = blockIdx.x, head = blockIdx.y, tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int kvh = head / (nq / nkv);
     const int64_t ld = (int64_t)nkv * hd;
     const T* qp = q + (int64_t)j * nq * hd + head * hd;
-    for (int c = lane; c < hd; c += 64) sq[c] = to_f32<T>(qp[c]) * scale;
+    for (int c = tid; c < hd; c += 256) sq[c] = to_f32<T>(qp[c]) * scale;
     __syncthreads();
-    const int n = P + t_new + 1;
     const int64_t branch0 = P + (int64_t)j * Tc;
     auto key_row = [&](int i) { return i < P ? (int64_t)i : branch0 + (i - P); };
+    constexpr int kVec = 16 / (int)sizeof(T);          // elements per 16-byte load (key rows are 16-byte aligned)
     float mx = -INFINITY;
-    for (int i = lane; i < n; i += 64) {
+    for (int i = tid; i < n; i += 256) {
         const T* k = k_cache + key_row(i) * ld + kvh * hd;
         float s = 0.f;
-        for (int c = 0; c < hd; ++c) s += sq[c] * to_f32<T>(k[c]);
+        if (hd % kVec == 0) {
+            for (int c = 0; c < hd; c += kVec) {
+                const uint4 raw = *reinterpret_cast<const uint4*>(k + c);
+                const T* e = reinterpret_cast<const T*>(&raw);
+#pragma unroll
+                for (int u = 0; u < kVec; ++u) s += sq[c + u] * to_f32<T>(e[u]);
+            }
+        } else {
+            for (int c = 0; c < hd; ++c) s += sq[c] * to_f32<T>(k[c]);
+        }
         sp[i] = s;
         mx = fmaxf(mx, s);
     }
 #pragma unroll
     for (int o = 32; o > 0; o >>= 1) mx = fmaxf(mx, __shfl_xor(mx, o));
+    if (lane == 0) red[wave] = mx;
+    __syncthreads();
+    mx = fmaxf(fmaxf(red[0], red[1]), fmaxf(red[2], red[3]));
     float sum = 0.f;
-    for (int i = lane; i < n; i += 64) {
+    for (int i = tid; i < n; i += 256) {
         const float p = __expf(sp[i] - mx);
         sp[i] = p;
         sum += p;
     }
 #pragma unroll
     for (int o = 32; o > 0; o >>= 1) sum += __shfl_xor(sum, o);
+    if (lane == 0) red[4 + wave] = sum;
     __syncthreads();
-    const float inv = 1.f / sum;
-    for (int c = lane; c < hd; c += 64) {
-        float acc = 0.f;
-        for (int i = 0; i < n; ++i) acc += sp[i] * to_f32<T>(v_cache[key_row(i) * ld + kvh * hd + c]);
-        out[(int64_t)j * nq * hd + head * hd + c] = from_f32<T>(acc * inv);
+    const float inv = 1.f / (red[4] + red[5] + red[6] + red[7]);
+    // output: wavefront w takes keys w, w + 4, ...; lane takes dims 2 c2, 2 c2 + 1 (hd is even)
+    for (int c2 = lane; c2 < hd / 2; c2 += 64) {
+        float a0 = 0.f, a1 = 0.f;
+        const T* vbase = v_cache + kvh * hd + 2 * c2;
+#pragma unroll 4
+        for (int i = wave; i < n; i += 4) {
+            const T* v = vbase + key_row(i) * ld;
+            const float p = sp[i];
+            a0 += p * to_f32<T>(v[0]);
+            a1 += p * to_f32<T>(v[1]);
+        }
+        so[wave * hd + 2 * c2] = a0;
+        so[wave * hd + 2 * c2 + 1] = a1;
     }
+    __syncthreads();
+    for (int c = tid; c < hd; c += 256)
+        out[(int64_t)j * nq * hd + head * hd + c] = from_f32<T>((so[c] + so[hd + c] + so[2 * hd + c] + so[3 * hd + c]) * inv);
 }
 
 // ids[j * stride] = first index of the largest logit of row j
@@ -137,13 +169,23 @@ __global__ __launch_bounds__(256) void argmax_rows_kernel(const float* __restric
     const float* z = logits + (int64_t)j * ld;
     float best = -INFINITY;
     int at = 0x7fffffff;
-    for (int c = threadIdx.x; c < V; c += 256) {
-        const float v = z[c];
-        if (v > best || (v == best && c < at)) {       // NaN never wins; ascending c per thread keeps the first maximum
+    auto consider = [&](float v, int c) {               // NaN never wins; the first maximum is kept
+        if (v > best || (v == best && c < at)) {
             best = v;
             at = c;
         }
+    };
+    const bool vec = (reinterpret_cast<uintptr_t>(z) & 15) == 0;
+    const int v4 = vec ? V / 4 : 0;
+#pragma unroll 4
+    for (int c4 = threadIdx.x; c4 < v4; c4 += 256) {
+        const float4 x = reinterpret_cast<const float4*>(z)[c4];
+        consider(x.x, 4 * c4);
+        consider(x.y, 4 * c4 + 1);
+        consider(x.z, 4 * c4 + 2);
+        consider(x.w, 4 * c4 + 3);
     }
+    for (int c = 4 * v4 + threadIdx.x; c < V; c += 256) consider(z[c], c);
     s_val[threadIdx.x] = best;
     s_idx[threadIdx.x] = at;
     __syncthreads();
@@ -217,7 +259,7 @@ int32_t launch_embed_rows(int32_t dtype, const void* tok_embed, int32_t vocab, i
     return ATTS_OK;
 }
 
-int32_t launch_decode_qkv_finish(int32_t dtype, const float* acc, const float2* cs, int32_t Kr, int32_t nq, int32_t nkv, int32_t hd,
+int32_t launch_decode_qkv_finish(int32_t dtype, float* acc, const float2* cs, int32_t Kr, int32_t nq, int32_t nkv, int32_t hd,
                                  int32_t P, int32_t Tc, int32_t t_new, void* q_out, void* k_cache, void* v_cache,
                                  hipStream_t stream) {
     const int64_t total = (int64_t)Kr * (nq + 2 * nkv) * (hd / 2);
@@ -229,11 +271,11 @@ int32_t launch_decode_qkv_finish(int32_t dtype, const float* acc, const float2* 
 
 int32_t launch_attn_decode(int32_t dtype, const void* q, const void* k_cache, const void* v_cache, void* out, int32_t Kr, int32_t P,
                            int32_t Tc, int32_t t_new, int32_t nq, int32_t nkv, int32_t hd, hipStream_t stream) {
-    const size_t lds = (size_t)(hd + P + t_new + 1) * sizeof(float);
+    const size_t lds = (size_t)(5 * hd + P + t_new + 1 + 8) * sizeof(float);
     if (lds > 60 * 1024) return fail(ATTS_ERR_SHAPE, "continuation: context of %d keys is too long", P + t_new + 1);
     const float scale = 1.f / sqrtf((float)hd);
     dim3 grid(Kr, nq);
-    DISPATCH_T(dtype, hipLaunchKernelGGL(attn_decode_kernel<T>, grid, dim3(64), lds, stream, (const T*)q, (const T*)k_cache,
+    DISPATCH_T(dtype, hipLaunchKernelGGL(attn_decode_kernel<T>, grid, dim3(256), lds, stream, (const T*)q, (const T*)k_cache,
                                          (const T*)v_cache, (T*)out, P, Tc, t_new, nq, nkv, hd, scale);)
     ATTS_LAUNCH_CHECK("attn_decode_kernel");
     return ATTS_OK;

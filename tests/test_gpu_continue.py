@@ -74,6 +74,23 @@ def test_greedy_continuation_matches_the_oracle(cfg, P, K, T, n_new, chunks):
             assert m[0] <= MARGIN[cfg.dtype]
 
 
+def test_7b_width_continuation():
+    """Full 7B width (two layers): the aligned few-row GEMM path (128-row tiles, K-split projections), the
+    transposed-value prefix cache and a vocabulary of 152,064 in the arg max."""
+    import paper_2509_15148_amd as A
+    wl = WORKLOADS["7b"]
+    cfg = wl.model
+    P, K, T, n_new = 24, 2, 6, 3
+    announce("continue greedy 7b width", P, K, T, n_new)
+    w_dev = make_weights(cfg, wl.seed, device="cuda", n_layers=2)
+    prefix, drafts = [x.numpy() for x in make_token_ids(cfg.vocab, P, K, T, 99)]
+    model = A.Model(cfg, w_dev)
+    got, _ = _continue(A, model, prefix, drafts, n_new)
+    assert got.min() >= 0 and got.max() < cfg.vocab
+    agree = _compare(cfg, weights_to_numpy(w_dev), prefix, drafts, got, n_new)
+    assert agree >= 1
+
+
 def test_continuation_argument_errors():
     import paper_2509_15148_amd as A
     cfg = WORKLOADS["tiny"].model
