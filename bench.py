@@ -28,8 +28,8 @@ HBM_PEAK_GBS = 8000.0
 # (FETCH_SIZE, then WRITE_SIZE), each scaled by what the same counter reads for a plain device copy of known
 # size (--traffic-probe); see profiles/traffic_gemm_gate_up_7b.txt.  Valid only for the kernel source it was
 # taken with: reported as null when the hash of csrc/gemm.hip differs.
-MEASURED_TRAFFIC = {"gemm_sha256": "bb13763c952ded822477933fb106092f661a81ae2805000df5c77a685dcb3917",
-                    "workload": "7b", "bytes_per_launch": 2.115e9}
+MEASURED_TRAFFIC = {"gemm_sha256": "80f31ebf2d2103716538b462ee83e1f593c39dd4b464f8ec510400b46b1fbff3",
+                    "workload": "7b", "bytes_per_launch": 2.137e9}
 
 
 def measured_traffic(workload):
