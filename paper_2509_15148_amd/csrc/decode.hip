@@ -85,31 +85,33 @@ __global__ __launch_bounds__(256) void decode_qkv_finish_kernel(float* __restric
     }
 }
 
-// One workgroup (4 wavefronts) per (branch, head): the new row of branch j attends to the prefix rows and to rows
-// 0 .. t_new of its own branch.  Scores: one key per thread and pass (16-byte loads along the key row); output:
-// every wavefront accumulates a quarter of the keys (lane = a pair of dims, 128 / 256 contiguous bytes per key), the
-// four partial sums are added in a fixed order.
+// One workgroup (kDecodeWaves wavefronts) per (branch, head): the new row of branch j attends to the prefix rows and
+// to rows 0 .. t_new of its own branch.  Scores: one key per thread and pass (16-byte loads along the key row);
+// output: every wavefront accumulates its share of the keys (lane = a pair of dims, 128 / 256 contiguous bytes per
+// key), the partial sums are added in a fixed order.
+constexpr int kDecodeWaves = 16, kDecodeThreads = 64 * kDecodeWaves;
+
 template <typename T>
-__global__ __launch_bounds__(256) void attn_decode_kernel(const T* __restrict__ q, const T* __restrict__ k_cache,
-                                                          const T* __restrict__ v_cache, T* __restrict__ out, int P, int Tc,
-                                                          int t_new, int nq, int nkv, int hd, float scale) {
-    extern __shared__ float sm[];           // [hd] query | [n] scores | [8] reductions | [4][hd] partial outputs
+__global__ __launch_bounds__(kDecodeThreads) void attn_decode_kernel(const T* __restrict__ q, const T* __restrict__ k_cache,
+                                                                     const T* __restrict__ v_cache, T* __restrict__ out, int P,
+                                                                     int Tc, int t_new, int nq, int nkv, int hd, float scale) {
+    extern __shared__ float sm[];           // [hd] query | [n] scores | [2 waves] reductions | [waves][hd] partial outputs
     const int n = P + t_new + 1;
     float* sq = sm;
     float* sp = sm + hd;
     float* red = sp + n;
-    float* so = red + 8;
+    float* so = red + 2 * kDecodeWaves;
     const int j = blockIdx.x, head = blockIdx.y, tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int kvh = head / (nq / nkv);
     const int64_t ld = (int64_t)nkv * hd;
     const T* qp = q + (int64_t)j * nq * hd + head * hd;
-    for (int c = tid; c < hd; c += 256) sq[c] = to_f32<T>(qp[c]) * scale;
+    for (int c = tid; c < hd; c += kDecodeThreads) sq[c] = to_f32<T>(qp[c]) * scale;
     __syncthreads();
     const int64_t branch0 = P + (int64_t)j * Tc;
     auto key_row = [&](int i) { return i < P ? (int64_t)i : branch0 + (i - P); };
     constexpr int kVec = 16 / (int)sizeof(T);          // elements per 16-byte load (key rows are 16-byte aligned)
     float mx = -INFINITY;
-    for (int i = tid; i < n; i += 256) {
+    for (int i = tid; i < n; i += kDecodeThreads) {
         const T* k = k_cache + key_row(i) * ld + kvh * hd;
         float s = 0.f;
         if (hd % kVec == 0) {
@@ -129,24 +131,29 @@ __global__ __launch_bounds__(256) void attn_decode_kernel(const T* __restrict__ 
     for (int o = 32; o > 0; o >>= 1) mx = fmaxf(mx, __shfl_xor(mx, o));
     if (lane == 0) red[wave] = mx;
     __syncthreads();
-    mx = fmaxf(fmaxf(red[0], red[1]), fmaxf(red[2], red[3]));
+    mx = red[0];
+#pragma unroll
+    for (int w = 1; w < kDecodeWaves; ++w) mx = fmaxf(mx, red[w]);
     float sum = 0.f;
-    for (int i = tid; i < n; i += 256) {
+    for (int i = tid; i < n; i += kDecodeThreads) {
         const float p = __expf(sp[i] - mx);
         sp[i] = p;
         sum += p;
     }
 #pragma unroll
     for (int o = 32; o > 0; o >>= 1) sum += __shfl_xor(sum, o);
-    if (lane == 0) red[4 + wave] = sum;
+    if (lane == 0) red[kDecodeWaves + wave] = sum;
     __syncthreads();
-    const float inv = 1.f / (red[4] + red[5] + red[6] + red[7]);
-    // output: wavefront w takes keys w, w + 4, ...; lane takes dims 2 c2, 2 c2 + 1 (hd is even)
+    float tot = 0.f;
+#pragma unroll
+    for (int w = 0; w < kDecodeWaves; ++w) tot += red[kDecodeWaves + w];
+    const float inv = 1.f / tot;
+    // output: wavefront w takes keys w, w + kDecodeWaves, ...; lane takes dims 2 c2, 2 c2 + 1 (hd is even)
     for (int c2 = lane; c2 < hd / 2; c2 += 64) {
         float a0 = 0.f, a1 = 0.f;
         const T* vbase = v_cache + kvh * hd + 2 * c2;
 #pragma unroll 4
-        for (int i = wave; i < n; i += 4) {
+        for (int i = wave; i < n; i += kDecodeWaves) {
             const T* v = vbase + key_row(i) * ld;
             const float p = sp[i];
             a0 += p * to_f32<T>(v[0]);
@@ -156,8 +163,12 @@ __global__ __launch_bounds__(256) void attn_decode_kernel(const T* __restrict__ 
         so[wave * hd + 2 * c2 + 1] = a1;
     }
     __syncthreads();
-    for (int c = tid; c < hd; c += 256)
-        out[(int64_t)j * nq * hd + head * hd + c] = from_f32<T>((so[c] + so[hd + c] + so[2 * hd + c] + so[3 * hd + c]) * inv);
+    for (int c = tid; c < hd; c += kDecodeThreads) {
+        float o = 0.f;
+#pragma unroll
+        for (int w = 0; w < kDecodeWaves; ++w) o += so[w * hd + c];
+        out[(int64_t)j * nq * hd + head * hd + c] = from_f32<T>(o * inv);
+    }
 }
 
 // ids[j * stride] = first index of the largest logit of row j
@@ -271,11 +282,11 @@ int32_t launch_decode_qkv_finish(int32_t dtype, float* acc, const float2* cs, in
 
 int32_t launch_attn_decode(int32_t dtype, const void* q, const void* k_cache, const void* v_cache, void* out, int32_t Kr, int32_t P,
                            int32_t Tc, int32_t t_new, int32_t nq, int32_t nkv, int32_t hd, hipStream_t stream) {
-    const size_t lds = (size_t)(5 * hd + P + t_new + 1 + 8) * sizeof(float);
+    const size_t lds = (size_t)((1 + kDecodeWaves) * hd + P + t_new + 1 + 2 * kDecodeWaves) * sizeof(float);
     if (lds > 60 * 1024) return fail(ATTS_ERR_SHAPE, "continuation: context of %d keys is too long", P + t_new + 1);
     const float scale = 1.f / sqrtf((float)hd);
     dim3 grid(Kr, nq);
-    DISPATCH_T(dtype, hipLaunchKernelGGL(attn_decode_kernel<T>, grid, dim3(256), lds, stream, (const T*)q, (const T*)k_cache,
+    DISPATCH_T(dtype, hipLaunchKernelGGL(attn_decode_kernel<T>, grid, dim3(kDecodeThreads), lds, stream, (const T*)q, (const T*)k_cache,
                                          (const T*)v_cache, (T*)out, P, Tc, t_new, nq, nkv, hd, scale);)
     ATTS_LAUNCH_CHECK("attn_decode_kernel");
     return ATTS_OK;
