@@ -30,8 +30,9 @@ What is defined here, and from where:
   * online calibration (paragraph "Online Calibration"): the calibration multiset grows
     by the scores of newly pre-sampled outputs; every rank refers to the multiset as it
     stands at that moment.
-  * target-model continuation of a rejected candidate (paragraph "Target Model Sampling"), greedy:
-    the arg max of the target's next-token logits, token by token.
+  * target-model continuation of a rejected candidate (paragraph "Target Model Sampling"): greedy
+    (the arg max of the target's next-token logits, token by token) or sampled from the
+    temperature-scaled softmax by inverse CDF, the uniform draws being inputs.
   * conditional coverage (same paragraph, last sentence; Proposition 2): the same rank,
     p-value and classes, but each input's candidates are compared with that input's own
     calibration scores only.
@@ -174,6 +175,32 @@ def greedy_continuation(weights, cfg, prefix_ids, draft_ids, n_new: int):
         margins.append(float(z[best] - second))
         ctx.append(best)
     return np.asarray(toks, dtype=np.int64), np.asarray(margins, dtype=F64)
+
+
+def sampled_continuation(weights, cfg, prefix_ids, draft_ids, uniforms, temperature: float):
+    """Target-model continuation by sampling (paragraph "Target Model Sampling"): token t is drawn from
+    softmax(logits / temperature) of the target given everything before it.  The randomness is an input: with
+    u = uniforms[t] in [0, 1) the token is the first index v (vocabulary order) whose cumulative probability
+    reaches u, i.e. inverse-CDF sampling.
+
+    Returns (tokens [n] int64, slack [n] float64): slack[t] is the distance, in probability, from u to the nearer
+    end of the chosen token's CDF interval (how close the draw was to picking a neighbour).
+    """
+    ctx = [int(t) for t in np.concatenate([np.asarray(prefix_ids), np.asarray(draft_ids)])]
+    toks, slack = [], []
+    for u in np.asarray(uniforms, dtype=F64):
+        h = decoder_hidden(weights, cfg, np.asarray(ctx, dtype=np.int64))
+        z = logits_from_hidden(weights, cfg, h[-1:])[0] / float(temperature)
+        p = np.exp(z - z.max())
+        cdf = np.cumsum(p)
+        target = u * cdf[-1]
+        v = int(np.searchsorted(cdf, target, side="left"))
+        v = min(v, len(cdf) - 1)
+        lo = cdf[v - 1] if v > 0 else 0.0
+        toks.append(v)
+        slack.append(float(min(target - lo, cdf[v] - target) / cdf[-1]))
+        ctx.append(v)
+    return np.asarray(toks, dtype=np.int64), np.asarray(slack, dtype=F64)
 
 
 def conformity_score(logprobs: np.ndarray, mode: int = MEAN_NLL) -> float:

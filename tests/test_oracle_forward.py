@@ -245,3 +245,25 @@ def test_greedy_continuation_is_the_argmax_chain_of_the_scored_distribution():
     # a longer request extends a shorter one
     toks6, _ = O.greedy_continuation(w, cfg, prefix, draft, 6)
     assert np.array_equal(toks6[:4], toks)
+
+
+def test_sampled_continuation_follows_the_scored_distribution():
+    """Pins that do not re-use the function's loop: (i) over a fine grid of uniforms the first sampled token hits
+    every token with the frequency token_logprobs assigns it (temperature 1); (ii) temperature -> 0 reproduces the
+    greedy chain; (iii) u = 0 gives token 0, u -> 1 the last token with non-zero mass."""
+    cfg = ModelConfig(1, 32, 2, 1, 16, 48, 11, "fp32")
+    w = weights_to_numpy(make_weights(cfg, seed=3, device="cpu"))
+    prefix = np.array([1, 2, 3, 4]); draft = np.array([5, 6])
+    ctx = np.concatenate([prefix, draft])
+    n = 4000
+    us = (np.arange(n) + 0.5) / n
+    first = np.array([O.sampled_continuation(w, cfg, prefix, draft, [u], 1.0)[0][0] for u in us])
+    freq = np.bincount(first, minlength=cfg.vocab) / n
+    p = np.exp([O.token_logprobs(w, cfg, ctx, np.array([v]))[0] for v in range(cfg.vocab)])
+    assert abs(p.sum() - 1) < 1e-12 and np.abs(freq - p).max() <= 1.0 / n + 1e-12
+    assert np.all(np.diff(first) >= 0)                                   # inverse CDF is monotone in u
+    g, _ = O.greedy_continuation(w, cfg, prefix, draft, 3)
+    t, _ = O.sampled_continuation(w, cfg, prefix, draft, [0.3, 0.9, 0.01], 1e-4)
+    assert np.array_equal(g, t)
+    assert O.sampled_continuation(w, cfg, prefix, draft, [0.0], 1.0)[0][0] == 0
+    assert O.sampled_continuation(w, cfg, prefix, draft, [1.0 - 1e-16], 1.0)[0][0] == cfg.vocab - 1
