@@ -193,6 +193,13 @@ int32_t atts_score_drafts_cached(const atts_prefix* prefix, const int32_t* draft
 int32_t atts_continue_workspace_bytes(const atts_prefix* prefix, int32_t K, int32_t T, int32_t n_new, size_t* out_bytes);
 int32_t atts_continue_greedy(const atts_prefix* prefix, const int32_t* draft_ids, int32_t K, int32_t T, int32_t n_new,
                              int32_t* out_ids, void* workspace, size_t workspace_bytes, void* hip_stream);
+/* The same continuation with sampling instead of the arg max: out_ids[k][t] is drawn from
+ * softmax(logits / temperature) by inverse CDF with the caller's uniform uniforms[k][t] in [0, 1): the first index v
+ * (vocabulary order) whose cumulative probability reaches the uniform.  The random numbers are inputs, so a call
+ * is a deterministic function of its arguments.  temperature > 0; uniforms dev float [K, n_new]. */
+int32_t atts_continue_sample(const atts_prefix* prefix, const int32_t* draft_ids, int32_t K, int32_t T, int32_t n_new,
+                             float temperature, const float* uniforms, int32_t* out_ids, void* workspace,
+                             size_t workspace_bytes, void* hip_stream);
 
 /* Synchronises hip_stream, copies the sticky device error flag to *host_flag (0 = clean,
  * 1 = some token id was out of range since the last check) and clears it. */

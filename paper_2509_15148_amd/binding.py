@@ -27,7 +27,7 @@ EXPORTS = (
     "atts_last_error_string", "atts_model_create", "atts_model_destroy", "atts_workspace_bytes",
     "atts_score_drafts", "atts_model_check", "atts_prefix_create", "atts_prefix_destroy", "atts_prefix_length",
     "atts_prefix_reset", "atts_prefix_extend_workspace_bytes", "atts_prefix_extend", "atts_score_drafts_cached",
-    "atts_continue_workspace_bytes", "atts_continue_greedy", "atts_lmhead_workspace_bytes", "atts_lmhead_logprobs",
+    "atts_continue_workspace_bytes", "atts_continue_greedy", "atts_continue_sample", "atts_lmhead_workspace_bytes", "atts_lmhead_logprobs",
     "atts_gemm_nt", "atts_attention_workspace_bytes", "atts_attention_shared_prefix",
     "atts_calib_create", "atts_calib_destroy", "atts_calib_size", "atts_calib_reset",
     "atts_calibrate_online", "atts_classify_ordinal", "atts_classify_conditional", "atts_calib_export",
@@ -231,6 +231,17 @@ def atts_continue_greedy(prefix: Prefix, draft_ids: torch.Tensor, out_ids: torch
         raise AttsError(ERR_INVALID_ARG, "out_ids must be [K, n_new]")
     _check(_lib.atts_continue_greedy(prefix.handle, _ptr(draft_ids, torch.int32, "draft_ids"), ctypes.c_int32(K), ctypes.c_int32(T),
                                      ctypes.c_int32(out_ids.shape[1]), _ptr(out_ids, torch.int32, "out_ids"),
+                                     _ptr(workspace, torch.uint8, "workspace"), ctypes.c_size_t(workspace.numel()), _stream()))
+
+
+def atts_continue_sample(prefix: Prefix, draft_ids: torch.Tensor, temperature: float, uniforms: torch.Tensor,
+                         out_ids: torch.Tensor, workspace: torch.Tensor) -> None:
+    K, T = draft_ids.shape
+    if out_ids.dim() != 2 or out_ids.shape[0] != K or tuple(uniforms.shape) != tuple(out_ids.shape):
+        raise AttsError(ERR_INVALID_ARG, "out_ids and uniforms must both be [K, n_new]")
+    _check(_lib.atts_continue_sample(prefix.handle, _ptr(draft_ids, torch.int32, "draft_ids"), ctypes.c_int32(K), ctypes.c_int32(T),
+                                     ctypes.c_int32(out_ids.shape[1]), ctypes.c_float(temperature),
+                                     _ptr(uniforms, torch.float32, "uniforms"), _ptr(out_ids, torch.int32, "out_ids"),
                                      _ptr(workspace, torch.uint8, "workspace"), ctypes.c_size_t(workspace.numel()), _stream()))
 
 

@@ -567,17 +567,19 @@ int32_t atts_continue_workspace_bytes(const atts_prefix* p, int32_t K, int32_t T
     return ATTS_OK;
 }
 
-int32_t atts_continue_greedy(const atts_prefix* p, const int32_t* draft_ids, int32_t K, int32_t T, int32_t n_new,
-                             int32_t* out_ids, void* workspace, size_t workspace_bytes, void* hip_stream) {
-    ATTS_TRY(check_continue_shape("atts_continue_greedy", p, K, T, n_new));
-    if (!draft_ids || !out_ids) return fail(ATTS_ERR_INVALID_ARG, "atts_continue_greedy: NULL draft_ids / out_ids");
+namespace {
+// uniforms == nullptr: greedy; else token t of candidate k is drawn with uniforms[k n_new + t] at inv_temp
+int32_t continue_tokens(const char* fn, const atts_prefix* p, const int32_t* draft_ids, int32_t K, int32_t T, int32_t n_new,
+                        const float* uniforms, float inv_temp, int32_t* out_ids, void* workspace, size_t workspace_bytes,
+                        void* hip_stream) {
+    ATTS_TRY(check_continue_shape(fn, p, K, T, n_new));
+    if (!draft_ids || !out_ids) return fail(ATTS_ERR_INVALID_ARG, "%s: NULL draft_ids / out_ids", fn);
     const atts_model* m = p->model;
     const atts_model_desc& d = m->desc;
     const int32_t P = p->P;
     const ContinueSpace cs = carve_continue(d, P, K, T, n_new);
-    if (!workspace || ((uintptr_t)workspace & 255)) return fail(ATTS_ERR_WORKSPACE, "atts_continue_greedy: workspace is NULL or not 256-byte aligned");
-    if (workspace_bytes < cs.total)
-        return fail(ATTS_ERR_WORKSPACE, "atts_continue_greedy: workspace has %zu bytes, %zu needed", workspace_bytes, cs.total);
+    if (!workspace || ((uintptr_t)workspace & 255)) return fail(ATTS_ERR_WORKSPACE, "%s: workspace is NULL or not 256-byte aligned", fn);
+    if (workspace_bytes < cs.total) return fail(ATTS_ERR_WORKSPACE, "%s: workspace has %zu bytes, %zu needed", fn, workspace_bytes, cs.total);
     hipStream_t st = static_cast<hipStream_t>(hip_stream);
     char* base = static_cast<char*>(workspace);
     const size_t es = dtype_size(d.dtype);
@@ -612,6 +614,7 @@ int32_t atts_continue_greedy(const atts_prefix* p, const int32_t* draft_ids, int
         g.a = xs; g.w = m->lm_head; g.out = logits; g.M = K; g.N = d.vocab; g.Kd = d.d_model;
         g.lda = d.d_model; g.ldw = d.d_model; g.ldc = d.vocab; g.a_rows_padded = padded;
         ATTS_TRY(launch_gemm(d.dtype, EPI_STORE_F32, g, st));
+        if (uniforms) return launch_sample_rows(logits, d.vocab, d.vocab, K, inv_temp, uniforms + t, out_ids + t, n_new, st);
         return launch_argmax_rows(logits, d.vocab, d.vocab, K, out_ids + t, n_new, st);
     };
 
@@ -652,6 +655,23 @@ int32_t atts_continue_greedy(const atts_prefix* p, const int32_t* draft_ids, int
         ATTS_TRY(next_token(t));
     }
     return ATTS_OK;
+}
+}  // namespace
+
+int32_t atts_continue_greedy(const atts_prefix* p, const int32_t* draft_ids, int32_t K, int32_t T, int32_t n_new,
+                             int32_t* out_ids, void* workspace, size_t workspace_bytes, void* hip_stream) {
+    return continue_tokens("atts_continue_greedy", p, draft_ids, K, T, n_new, nullptr, 1.f, out_ids, workspace, workspace_bytes,
+                           hip_stream);
+}
+
+int32_t atts_continue_sample(const atts_prefix* p, const int32_t* draft_ids, int32_t K, int32_t T, int32_t n_new,
+                             float temperature, const float* uniforms, int32_t* out_ids, void* workspace,
+                             size_t workspace_bytes, void* hip_stream) {
+    if (!(temperature > 0.f) || !(temperature < INFINITY))
+        return fail(ATTS_ERR_INVALID_ARG, "atts_continue_sample: temperature must be positive and finite");
+    if (!uniforms) return fail(ATTS_ERR_INVALID_ARG, "atts_continue_sample: uniforms is NULL");
+    return continue_tokens("atts_continue_sample", p, draft_ids, K, T, n_new, uniforms, 1.f / temperature, out_ids, workspace,
+                           workspace_bytes, hip_stream);
 }
 
 int32_t atts_model_check(const atts_model* m, void* hip_stream, int32_t* host_flag) {

@@ -178,6 +178,8 @@ int32_t launch_attn_decode(int32_t dtype, const void* q, const void* k_cache, co
                            int32_t Tc, int32_t t_new, int32_t nq, int32_t nkv, int32_t hd, hipStream_t stream);
 int32_t launch_argmax_rows(const float* logits, int64_t ld, int32_t V, int32_t rows, int32_t* ids, int64_t stride,
                            hipStream_t stream);
+int32_t launch_sample_rows(const float* logits, int64_t ld, int32_t V, int32_t rows, float inv_temp, const float* uniforms,
+                           int32_t* ids, int64_t stride, hipStream_t stream);
 int32_t launch_norm_strided_rows(int32_t dtype, const float* h, const float* gain, float eps, int32_t d, int64_t first, int64_t step,
                                  int32_t rows, void* xs, hipStream_t stream);
 

@@ -214,6 +214,71 @@ __global__ __launch_bounds__(256) void argmax_rows_kernel(const float* __restric
     if (threadIdx.x == 0) ids[(int64_t)j * stride] = s_idx[0] == 0x7fffffff ? 0 : s_idx[0];
 }
 
+// ids[j * stride] = inverse-CDF sample of softmax(logits[j] * inv_temp) with the uniform u = uniforms[j * stride]:
+// the first index v (vocabulary order) whose cumulative weight reaches u times the total.  Every thread owns a
+// contiguous chunk of the row; chunk sums are scanned in index order by one thread, then the owner of the chunk the
+// target falls into walks it.  Sums in fp32, fixed order.
+constexpr int kSampleThreads = 1024;
+
+__global__ __launch_bounds__(kSampleThreads) void sample_rows_kernel(const float* __restrict__ logits, int64_t ld, int V,
+                                                                     float inv_temp, const float* __restrict__ uniforms,
+                                                                     int32_t* __restrict__ ids, int64_t stride) {
+    __shared__ float red[kSampleThreads / 64];
+    __shared__ float chunk_sum[kSampleThreads];
+    __shared__ float s_target, s_before;
+    __shared__ int s_chunk;
+    const int j = blockIdx.x, tid = threadIdx.x;
+    const float* z = logits + (int64_t)j * ld;
+    const int per = (V + kSampleThreads - 1) / kSampleThreads;
+    const int c0 = min(tid * per, V), c1 = min(c0 + per, V);
+    float mx = -INFINITY;
+    for (int c = c0; c < c1; ++c) mx = fmaxf(mx, z[c]);
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) mx = fmaxf(mx, __shfl_xor(mx, o));
+    if ((tid & 63) == 0) red[tid >> 6] = mx;
+    __syncthreads();
+    mx = red[0];
+#pragma unroll
+    for (int w = 1; w < kSampleThreads / 64; ++w) mx = fmaxf(mx, red[w]);
+    float sum = 0.f;
+    for (int c = c0; c < c1; ++c) sum += __expf((z[c] - mx) * inv_temp);
+    chunk_sum[tid] = sum;
+    __syncthreads();
+    if (tid == 0) {
+        float total = 0.f;
+        for (int t = 0; t < kSampleThreads; ++t) total += chunk_sum[t];
+        const float target = uniforms[(int64_t)j * stride] * total;
+        float before = 0.f;
+        int chunk = kSampleThreads - 1;
+        for (int t = 0; t < kSampleThreads; ++t) {
+            if (before + chunk_sum[t] >= target && chunk_sum[t] > 0.f) {
+                chunk = t;
+                break;
+            }
+            before += chunk_sum[t];
+        }
+        s_target = target;
+        s_before = before;
+        s_chunk = chunk;
+    }
+    __syncthreads();
+    if (tid == s_chunk) {
+        float run = s_before;
+        int pick = -1, last_mass = -1;
+        for (int c = c0; c < c1; ++c) {
+            const float e = __expf((z[c] - mx) * inv_temp);
+            run += e;
+            if (e > 0.f) last_mass = c;
+            if (run >= s_target) {
+                pick = c;
+                break;
+            }
+        }
+        if (pick < 0) pick = last_mass >= 0 ? last_mass : (c1 > c0 ? c1 - 1 : V - 1);   // rounding left the target just past the chunk
+        ids[(int64_t)j * stride] = pick;
+    }
+}
+
 // xs[j] = rmsnorm(h[rows[j]]) with rows[j] = first + j * step
 template <typename T>
 __global__ __launch_bounds__(256) void norm_strided_rows_kernel(const float* __restrict__ h, const float* __restrict__ gain, float eps,
@@ -296,6 +361,13 @@ int32_t launch_argmax_rows(const float* logits, int64_t ld, int32_t V, int32_t r
                            hipStream_t stream) {
     hipLaunchKernelGGL(argmax_rows_kernel, dim3(rows), dim3(256), 0, stream, logits, ld, V, ids, stride);
     ATTS_LAUNCH_CHECK("argmax_rows_kernel");
+    return ATTS_OK;
+}
+
+int32_t launch_sample_rows(const float* logits, int64_t ld, int32_t V, int32_t rows, float inv_temp, const float* uniforms,
+                           int32_t* ids, int64_t stride, hipStream_t stream) {
+    hipLaunchKernelGGL(sample_rows_kernel, dim3(rows), dim3(kSampleThreads), 0, stream, logits, ld, V, inv_temp, uniforms, ids, stride);
+    ATTS_LAUNCH_CHECK("sample_rows_kernel");
     return ATTS_OK;
 }
 

@@ -74,6 +74,53 @@ def test_greedy_continuation_matches_the_oracle(cfg, P, K, T, n_new, chunks):
             assert m[0] <= MARGIN[cfg.dtype]
 
 
+SLACK = {"fp32": 2e-4, "bf16": 0.05}        # how close (in probability) a draw may be to a CDF boundary for the tokens to differ
+
+
+@pytest.mark.parametrize("cfg,P,K,T,n_new,temperature", [
+    (WORKLOADS["tiny"].model, 24, 3, 9, 6, 1.0),
+    (ModelConfig(2, 96, 4, 1, 24, 200, 515, "fp32"), 7, 4, 5, 5, 0.7),
+    (ModelConfig(2, 256, 4, 2, 128, 512, 2048, "bf16"), 40, 4, 12, 5, 1.3),
+])
+def test_sampled_continuation_matches_the_oracle(cfg, P, K, T, n_new, temperature):
+    """Inverse-CDF sampling with the same uniforms on both sides; a token may differ only where the draw lies within
+    the arithmetic's accuracy of a boundary between two tokens' CDF intervals (then the rest of that candidate is
+    not compared)."""
+    import paper_2509_15148_amd as A
+    announce("continue sample", cfg, P, K, T, n_new, temperature)
+    w_dev = make_weights(cfg, seed=P * 17 + K, device="cuda")
+    prefix, drafts = [x.numpy() for x in make_token_ids(cfg.vocab, P, K, T, P + 3 * K)]
+    model = A.Model(cfg, w_dev)
+    pre = A.Prefix(model, capacity=P)
+    A.atts_prefix_extend(pre, dev(prefix), ws(A.atts_prefix_extend_workspace_bytes(pre, P)))
+    rng = np.random.default_rng(P + K)
+    u = rng.random((K, n_new)).astype(np.float32)
+    u[0, 0] = 0.0
+    out = torch.full((K, n_new), -1, dtype=torch.int32, device="cuda")
+    A.atts_continue_sample(pre, dev(drafts), temperature, dev(u), out, ws(A.atts_continue_workspace_bytes(pre, K, T, n_new)))
+    torch.cuda.synchronize()
+    got = out.cpu().numpy()
+    assert got.min() >= 0 and got.max() < cfg.vocab
+    w_np = weights_to_numpy(w_dev)
+    agree = 0
+    for k in range(K):
+        ref, slack = O.sampled_continuation(w_np, cfg, prefix, drafts[k], u[k].astype(np.float64), temperature)
+        for t in range(n_new):
+            if got[k, t] != ref[t]:
+                assert slack[t] <= SLACK[cfg.dtype] and abs(int(got[k, t]) - int(ref[t])) >= 1, (k, t, got[k, t], ref[t], slack[t])
+                break
+            agree += 1
+    assert agree >= K * n_new // 2
+    # different uniforms give different continuations (the draws are really used)
+    out2 = torch.empty_like(out)
+    A.atts_continue_sample(pre, dev(drafts), temperature, dev(1.0 - 1e-3 - u * 0.5), out2, ws(A.atts_continue_workspace_bytes(pre, K, T, n_new)))
+    assert not torch.equal(out, out2)
+    for bad_t in (0.0, -1.0, float("inf"), float("nan")):
+        with pytest.raises(A.AttsError) as e:
+            A.atts_continue_sample(pre, dev(drafts), bad_t, dev(u), out, ws(A.atts_continue_workspace_bytes(pre, K, T, n_new)))
+        assert e.value.code == A.ERR_INVALID_ARG
+
+
 def test_7b_width_continuation():
     """Full 7B width (two layers): the aligned few-row GEMM path (128-row tiles, K-split projections), the
     transposed-value prefix cache and a vocabulary of 152,064 in the arg max."""
