@@ -283,7 +283,7 @@ def main():
     ap.add_argument("--workload", default="7b", choices=["tiny", "7b", "32b", "70b"])
     ap.add_argument("--layers", type=int, default=0, help="build only the first L layers (debug; result is labelled)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--cpu-layers", type=int, default=2)
+    ap.add_argument("--cpu-layers", type=int, default=8, help="layers of the model the CPU baseline times (extrapolated to all by count)")
     ap.add_argument("--traffic-probe", action="store_true",
                     help="also run one plain 1 GiB device-to-device copy (reference for scaling HBM counters)")
     ap.add_argument("--skip-extras", action="store_true",
