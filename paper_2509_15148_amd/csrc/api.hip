@@ -582,7 +582,6 @@ int32_t continue_tokens(const char* fn, const atts_prefix* p, const int32_t* dra
     if (workspace_bytes < cs.total) return fail(ATTS_ERR_WORKSPACE, "%s: workspace has %zu bytes, %zu needed", fn, workspace_bytes, cs.total);
     hipStream_t st = static_cast<hipStream_t>(hip_stream);
     char* base = static_cast<char*>(workspace);
-    const size_t es = dtype_size(d.dtype);
     const int qd = d.n_q_heads * d.head_dim, kvd = d.n_kv_heads * d.head_dim, qkv_out = qd + 2 * kvd, half = d.head_dim / 2;
     const bool padded = pads_rows(d);
     const ScoreShape s{P, K, T};

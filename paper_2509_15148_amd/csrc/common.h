@@ -116,6 +116,9 @@ struct GemmArgs {
 int32_t lmhead_num_partials(int32_t dtype, int32_t M, int32_t N, int32_t Kd, bool a_rows_padded);
 int32_t lmhead_max_partials(int32_t N);
 int32_t launch_gemm(int32_t dtype, GemmEpilogue epi, const GemmArgs& g, hipStream_t stream);
+// The kernel for at most 16 rows of A (skinny.hip): launch_gemm hands it the calls it serves.
+bool gemm_skinny_ok(int32_t dtype, GemmEpilogue epi, const GemmArgs& g);
+int32_t launch_gemm_skinny(GemmEpilogue epi, const GemmArgs& g, hipStream_t stream);
 // true if the EPI_QKV_ROPE epilogue can serve this QKV projection (else: EPI_STORE_ACT + launch_rope_split)
 bool qkv_rope_fusable(int32_t dtype, int32_t M, int32_t N, int32_t Kd, int32_t head_dim, bool a_rows_padded);
 // vt [rows, ldv]: zero columns [R, ldv) of every row (the attention kernel reads whole 64-key tiles of V^T).
@@ -152,7 +155,8 @@ int32_t launch_zero_f32(float* p, int64_t n, hipStream_t stream);
 // (cs, qkv, vt already point at the first of the `rows` rows / columns), stored to qkv; v heads to vt [nkv hd, ldv]
 int32_t launch_qkv_finish(int32_t dtype, float* acc, const float2* cs, int32_t rows, int32_t nq, int32_t nkv, int32_t hd,
                           void* qkv, void* vt, int64_t ldv, hipStream_t stream);
-// true if a residual-epilogue GEMM of this shape would split its K range (few tiles: weight-streaming regime)
+// true if a residual-epilogue GEMM of this shape may split its K range (few tiles or few rows: weight-streaming
+// regime): partial sums are then added with atomics
 bool gemm_splits_k(int32_t dtype, int32_t M, int32_t N, int32_t Kd, bool a_rows_padded);
 // dst[r][c] = src[r][c], rows x cols elements of the model dtype, pitches in elements
 int32_t launch_copy2d(int32_t dtype, const void* src, int64_t src_ld, void* dst, int64_t dst_ld, int64_t rows, int64_t cols,

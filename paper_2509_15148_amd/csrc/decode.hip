@@ -7,6 +7,8 @@
 // and a decode step sends one row per branch through the model.
 #include "common.h"
 
+#include <type_traits>
+
 namespace atts {
 namespace {
 
@@ -168,6 +170,170 @@ __global__ __launch_bounds__(kDecodeThreads) void attn_decode_kernel(const T* __
 #pragma unroll
         for (int w = 0; w < kDecodeWaves; ++w) o += so[w * hd + c];
         out[(int64_t)j * nq * hd + head * hd + c] = from_f32<T>(o * inv);
+    }
+}
+
+// Dot product of two 16-byte pieces (8 bf16 or 4 fp32 elements).
+template <typename T> __device__ __forceinline__ float dot_piece(const uint4& a, const uint4& b);
+template <> __device__ __forceinline__ float dot_piece<float>(const uint4& a, const uint4& b) {
+    const float* x = reinterpret_cast<const float*>(&a);
+    const float* y = reinterpret_cast<const float*>(&b);
+    return x[0] * y[0] + x[1] * y[1] + x[2] * y[2] + x[3] * y[3];
+}
+template <> __device__ __forceinline__ float dot_piece<bf16>(const uint4& a, const uint4& b) {
+    typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
+    const bf16x2* x = reinterpret_cast<const bf16x2*>(&a);
+    const bf16x2* y = reinterpret_cast<const bf16x2*>(&b);
+    float s = 0.f;
+#pragma unroll
+    for (int u = 0; u < 4; ++u) s = __builtin_amdgcn_fdot2_f32_bf16(x[u], y[u], s, false);   // fp32 accumulation
+    return s;
+}
+
+// Sum of s over aligned groups of `lanes` (a power of two <= 64) neighbouring lanes, in every lane of the group.  Inside a
+// row of 16 lanes the exchanges are DPP permutations (pairs, quads, mirrored half rows, mirrored rows: any pairing of
+// disjoint partial sums will do); beyond that, LDS-crossbar shuffles.
+__device__ __forceinline__ float group_sum(float s, int lanes) {
+    auto dpp = [](float v, auto ctrl) __attribute__((always_inline)) {
+        return __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(v), decltype(ctrl)::value, 0xf, 0xf, true));
+    };
+    if (lanes > 1) s += dpp(s, std::integral_constant<int, 0xB1>{});     // quad_perm [1, 0, 3, 2]
+    if (lanes > 2) s += dpp(s, std::integral_constant<int, 0x4E>{});     // quad_perm [2, 3, 0, 1]
+    if (lanes > 4) s += dpp(s, std::integral_constant<int, 0x141>{});    // row_half_mirror
+    if (lanes > 8) s += dpp(s, std::integral_constant<int, 0x140>{});    // row_mirror
+    for (int o = 16; o < lanes; o <<= 1) s += __shfl_xor(s, o);
+    return s;
+}
+
+// The same attention step when a key / value row of one head is a power-of-two number of 16-byte pieces (every bf16
+// model with head_dim 128): lanes_per_key lanes cover one row, so a wavefront reads g = 64 / lanes_per_key whole rows
+// per instruction; lane (sub = lane / lanes_per_key, piece = lane % lanes_per_key) of wavefront w takes the keys
+// (w g + sub) + kDecodeWaves g m, in batches of kDecodeBatch.  One CU serves a whole (branch, head), so the step is
+// bound by memory round trips and by instruction issue, not by bytes:
+//   * two key batches and two value batches are requested before anything is waited for: a context of up to
+//     2 kDecodeBatch kDecodeWaves g keys costs one round trip (longer ones: one more per further batch);
+//   * every wavefront runs its own softmax over its keys (running maximum m, sum l and unnormalised output, all in
+//     registers: a lane's probabilities multiply the value rows the same lane loaded), and the wavefronts are
+//     merged once at the end with the weights exp(m_w - max m): one barrier, no per-key LDS, no limit on the context;
+//   * the query piece stays in registers in the model dtype (bf16: packed dot products, v_dot2_f32_bf16), the
+//     1 / sqrt(head_dim) factor is applied to the finished score, and the group sums use DPP.
+constexpr int kDecodeBatch = 7;
+
+template <typename T>
+__global__ __launch_bounds__(kDecodeThreads) void attn_decode_pieces_kernel(const T* __restrict__ q, const T* __restrict__ k_cache,
+                                                                            const T* __restrict__ v_cache, T* __restrict__ out,
+                                                                            int P, int Tc, int t_new, int nq, int nkv, int hd,
+                                                                            float scale) {
+    extern __shared__ float sm[];           // [waves] running maxima | [waves] sums | [waves][hd] unnormalised outputs
+    constexpr int kVec = 16 / (int)sizeof(T);
+    const int n = P + t_new + 1;
+    float* red = sm;
+    float* so = sm + 2 * kDecodeWaves;
+    const int j = blockIdx.x, head = blockIdx.y, tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int kvh = head / (nq / nkv);
+    const int64_t ld = (int64_t)nkv * hd;
+    const int lanes_per_key = hd / kVec, g = 64 / lanes_per_key, sub = lane / lanes_per_key, piece = lane % lanes_per_key;
+    const int stride = kDecodeWaves * g, span = kDecodeBatch * stride;
+    const int first = wave * g;                         // wave-uniform; the lane's keys are first + sub + stride m
+    // cache row of key i: i (prefix) or P + j Tc + (i - P) (own branch) = i + (i >= P ? j Tc : 0)
+    const int64_t own = (int64_t)j * Tc * ld;
+    const int64_t lane_off = (int64_t)kvh * hd + piece * kVec + (int64_t)sub * ld;
+    auto load_rows = [&](const T* base, int i0, uint4 (&raw)[kDecodeBatch]) __attribute__((always_inline)) {
+        const T* p0 = base + lane_off + (int64_t)i0 * ld;
+#pragma unroll
+        for (int b = 0; b < kDecodeBatch; ++b) {
+            const int i = i0 + sub + b * stride;
+            const T* p = p0 + (int64_t)b * stride * ld + (i >= P ? own : 0);
+            raw[b] = i < n ? *reinterpret_cast<const uint4*>(p) : make_uint4(0, 0, 0, 0);
+        }
+    };
+    uint4 k0[kDecodeBatch], k1[kDecodeBatch], v0[kDecodeBatch], v1[kDecodeBatch];
+    load_rows(k_cache, first, k0);
+    load_rows(k_cache, first + span, k1);
+    load_rows(v_cache, first, v0);
+    load_rows(v_cache, first + span, v1);
+    const uint4 qv = *reinterpret_cast<const uint4*>(q + (int64_t)j * nq * hd + head * hd + piece * kVec);
+
+    // scores of a batch (-inf past the end) and their maximum; every lane of the wavefront takes part
+    auto score = [&](int i0, const uint4 (&raw)[kDecodeBatch], float (&sc)[kDecodeBatch]) __attribute__((always_inline)) {
+        float bm = -INFINITY;
+#pragma unroll
+        for (int b = 0; b < kDecodeBatch; ++b) {
+            const float s = group_sum(dot_piece<T>(qv, raw[b]), lanes_per_key) * scale;
+            sc[b] = i0 + sub + b * stride < n ? s : -INFINITY;
+            bm = fmaxf(bm, sc[b]);
+        }
+        return bm;
+    };
+    auto wave_max = [&](float v) __attribute__((always_inline)) {      // the lanes of a key hold equal values: only the groups differ
+        for (int o = lanes_per_key; o < 64; o <<= 1) v = fmaxf(v, __shfl_xor(v, o));
+        return v;
+    };
+    float m = -INFINITY, l = 0.f;                       // running maximum (wave-uniform), sum over this lane's keys
+    float acc[kVec];
+#pragma unroll
+    for (int u = 0; u < kVec; ++u) acc[u] = 0.f;
+    auto rescale = [&](float m_new) __attribute__((always_inline)) {   // m_new finite
+        const float corr = __expf(m - m_new);           // m = -inf: 0 (nothing accumulated yet)
+        l *= corr;
+#pragma unroll
+        for (int u = 0; u < kVec; ++u) acc[u] *= corr;
+        m = m_new;
+    };
+    auto accumulate = [&](const float (&sc)[kDecodeBatch], const uint4 (&raw)[kDecodeBatch]) __attribute__((always_inline)) {
+#pragma unroll
+        for (int b = 0; b < kDecodeBatch; ++b) {
+            const float p = __expf(sc[b] - m);          // -inf score: 0
+            l += p;
+            const T* e = reinterpret_cast<const T*>(&raw[b]);
+#pragma unroll
+            for (int u = 0; u < kVec; ++u) acc[u] += p * to_f32<T>(e[u]);
+        }
+    };
+    {
+        float s0[kDecodeBatch], s1[kDecodeBatch];
+        const float bm = wave_max(fmaxf(score(first, k0, s0), score(first + span, k1, s1)));
+        if (bm > -INFINITY) {                           // wave-uniform: the wavefront has at least one key
+            rescale(bm);
+            accumulate(s0, v0);
+            accumulate(s1, v1);
+        }
+    }
+    for (int i0 = first + 2 * span; i0 < n; i0 += span) {              // long contexts: one batch at a time
+        float s0[kDecodeBatch];
+        load_rows(k_cache, i0, k0);
+        load_rows(v_cache, i0, v0);
+        const float bm = wave_max(score(i0, k0, s0));
+        if (bm > -INFINITY) {
+            if (bm > m) rescale(bm);
+            accumulate(s0, v0);
+        }
+    }
+    // the piece lanes of a key all added its probability to their l: the sum over the groups counts every key once
+    for (int o = lanes_per_key; o < 64; o <<= 1) l += __shfl_xor(l, o);
+#pragma unroll
+    for (int u = 0; u < kVec; ++u) {
+        for (int o = lanes_per_key; o < 64; o <<= 1) acc[u] += __shfl_xor(acc[u], o);
+        if (sub == 0) so[wave * hd + piece * kVec + u] = acc[u];
+    }
+    if (lane == 0) {
+        red[wave] = m;
+        red[kDecodeWaves + wave] = l;
+    }
+    __syncthreads();
+    for (int c = tid; c < hd; c += kDecodeThreads) {
+        float top = red[0];
+#pragma unroll
+        for (int w = 1; w < kDecodeWaves; ++w) top = fmaxf(top, red[w]);           // finite: wavefront 0 holds key 0
+        float tot = 0.f, o = 0.f;
+#pragma unroll
+        for (int w = 0; w < kDecodeWaves; ++w) {
+            const float wgt = __expf(red[w] - top);                                // a wavefront without keys: 0
+            tot += wgt * red[kDecodeWaves + w];
+            o += wgt * so[w * hd + c];
+        }
+        out[(int64_t)j * nq * hd + head * hd + c] = from_f32<T>(o / tot);
     }
 }
 
@@ -347,10 +513,18 @@ int32_t launch_decode_qkv_finish(int32_t dtype, float* acc, const float2* cs, in
 
 int32_t launch_attn_decode(int32_t dtype, const void* q, const void* k_cache, const void* v_cache, void* out, int32_t Kr, int32_t P,
                            int32_t Tc, int32_t t_new, int32_t nq, int32_t nkv, int32_t hd, hipStream_t stream) {
-    const size_t lds = (size_t)((1 + kDecodeWaves) * hd + P + t_new + 1 + 2 * kDecodeWaves) * sizeof(float);
-    if (lds > 60 * 1024) return fail(ATTS_ERR_SHAPE, "continuation: context of %d keys is too long", P + t_new + 1);
     const float scale = 1.f / sqrtf((float)hd);
     dim3 grid(Kr, nq);
+    const int lanes_per_key = hd * (int)dtype_size(dtype) / 16;
+    if ((hd * dtype_size(dtype)) % 16 == 0 && lanes_per_key <= 64 && (lanes_per_key & (lanes_per_key - 1)) == 0) {
+        const size_t lds = (size_t)(kDecodeWaves * hd + 2 * kDecodeWaves) * sizeof(float);
+        DISPATCH_T(dtype, hipLaunchKernelGGL(attn_decode_pieces_kernel<T>, grid, dim3(kDecodeThreads), lds, stream, (const T*)q,
+                                             (const T*)k_cache, (const T*)v_cache, (T*)out, P, Tc, t_new, nq, nkv, hd, scale);)
+        ATTS_LAUNCH_CHECK("attn_decode_pieces_kernel");
+        return ATTS_OK;
+    }
+    const size_t lds = (size_t)((1 + kDecodeWaves) * hd + P + t_new + 1 + 2 * kDecodeWaves) * sizeof(float);
+    if (lds > 60 * 1024) return fail(ATTS_ERR_SHAPE, "continuation: context of %d keys is too long", P + t_new + 1);
     DISPATCH_T(dtype, hipLaunchKernelGGL(attn_decode_kernel<T>, grid, dim3(kDecodeThreads), lds, stream, (const T*)q, (const T*)k_cache,
                                          (const T*)v_cache, (T*)out, P, Tc, t_new, nq, nkv, hd, scale);)
     ATTS_LAUNCH_CHECK("attn_decode_kernel");

@@ -1010,6 +1010,7 @@ bool qkv_rope_fusable(int32_t dtype, int32_t M, int32_t N, int32_t Kd, int32_t h
 bool gemm_splits_k(int32_t dtype, int32_t M, int32_t N, int32_t Kd, bool a_rows_padded) {
     GemmArgs g{};
     g.M = M; g.N = N; g.Kd = Kd; g.lda = Kd; g.ldw = Kd; g.a_rows_padded = a_rows_padded;
+    if (gemm_skinny_ok(dtype, EPI_RESID_F32, g)) return true;     // always the accumulating form
     if (!fast_path_ok(dtype, EPI_RESID_F32, g)) return false;
     const int bm = fast_tile_rows(EPI_RESID_F32, g);
     const int64_t tiles = ceil_div(M, bm) * (N / 256);
@@ -1030,6 +1031,11 @@ int32_t launch_gemm(int32_t dtype, GemmEpilogue epi, const GemmArgs& g, hipStrea
             return fail(ATTS_ERR_SHAPE, "gemm: the fused QKV epilogue does not apply to this call");
         return launch_fast<EPI_QKV_ROPE>(g, stream);
     }
+    // A decoding step (at most 16 rows) streams the weights once.  Narrow outputs with the residual epilogue go to
+    // the kernel that cuts K over single wavefronts; wide outputs (SwiGLU, logits) already give the aligned kernel
+    // enough tiles, and it streams them as fast, so they only go there when it cannot serve the shape.
+    if (gemm_skinny_ok(dtype, epi, g) && (epi == EPI_RESID_F32 || !fast_path_ok(dtype, epi, g)))
+        return launch_gemm_skinny(epi, g, stream);
     return dtype == ATTS_DTYPE_F32 ? launch_t<float>(epi, g, stream) : launch_t<bf16>(epi, g, stream);
 }
 

@@ -54,6 +54,11 @@ def _compare(cfg, w_np, prefix, drafts, got, n_new):
     (ModelConfig(2, 96, 4, 1, 24, 200, 515, "fp32"), 7, 2, 5, 8, (3, 4)),
     (ModelConfig(2, 256, 4, 2, 128, 512, 2048, "bf16"), 40, 4, 12, 6, None),         # bf16, transposed-value prefix cache
     (ModelConfig(2, 256, 4, 2, 128, 520, 2003, "bf16"), 33, 2, 7, 5, (32, 1)),       # general GEMM path
+    # decode attention by 16-byte pieces: 8 / 32 / 8 lanes per key, and contexts beyond the batches requested up front
+    (ModelConfig(2, 128, 4, 2, 32, 192, 515, "fp32"), 70, 3, 20, 4, None),
+    (ModelConfig(2, 256, 2, 1, 128, 256, 515, "fp32"), 500, 2, 6, 4, None),
+    (ModelConfig(2, 256, 4, 2, 64, 512, 2048, "bf16"), 300, 3, 10, 4, None),
+    (ModelConfig(2, 256, 4, 2, 128, 512, 2048, "bf16"), 950, 2, 8, 4, None),
 ])
 def test_greedy_continuation_matches_the_oracle(cfg, P, K, T, n_new, chunks):
     import paper_2509_15148_amd as A

@@ -22,7 +22,9 @@ def _rand(shape, seed, dtype, scale=1.0):
 # ------------------------------------------------------------------------------------ GEMM
 @pytest.mark.parametrize("dtype", [torch.float32, torch.bfloat16])
 @pytest.mark.parametrize("shape", [(1, 1, 8), (33, 70, 72), (300, 200, 136), (257, 513, 1000), (128, 128, 64),
-                                   (3584, 3600, 264)])
+                                   (3584, 3600, 264),
+                                   # at most 16 rows: the weight-streaming kernel (bf16), ragged columns and k-step counts
+                                   (1, 1, 32), (4, 100, 96), (7, 4608, 256), (16, 33, 2080), (16, 530, 3584), (3, 48, 18944)])
 def test_gemm_nt_matches_float64_matmul(dtype, shape):
     import paper_2509_15148_amd as A
     M, N, Kd = shape
