@@ -186,20 +186,26 @@ int32_t atts_score_drafts_cached(const atts_prefix* prefix, const int32_t* draft
  * target's next-token logits given prefix + draft k + out_ids[k][0 .. t - 1].  All K candidates advance together,
  * one row per candidate and step (the weight-streaming regime); their keys / values share the cached prefix.
  *   prefix      handle holding the shared context (length >= 1); not modified
- *   draft_ids   dev int32 [K, T] row-major, the rejected drafts (all T tokens are used)
+ *   draft_ids   dev int32 [K, T] row-major, the rejected drafts
+ *   draft_lens  dev int32 [K], each in [1, T] (values outside are read as clamped): candidate k continues after
+ *               its first draft_lens[k] tokens, the rest of its row is padding; NULL = every draft has T tokens
+ *   eos_id      >= 0: the end-of-sequence token; once a candidate has produced it, all its later out_ids are
+ *               eos_id too (its rows keep going through the model with the others, their results are dropped);
+ *               < 0: no such token
  *   out_ids     dev int32 [K, n_new] row-major
  *   workspace   dev, 256-byte aligned, >= atts_continue_workspace_bytes(prefix, K, T, n_new) bytes; scratch
  * 1 <= K <= 768, T >= 1, n_new >= 1, length + T + n_new <= 1048576.  Out-of-range ids as in atts_score_drafts. */
 int32_t atts_continue_workspace_bytes(const atts_prefix* prefix, int32_t K, int32_t T, int32_t n_new, size_t* out_bytes);
-int32_t atts_continue_greedy(const atts_prefix* prefix, const int32_t* draft_ids, int32_t K, int32_t T, int32_t n_new,
-                             int32_t* out_ids, void* workspace, size_t workspace_bytes, void* hip_stream);
+int32_t atts_continue_greedy(const atts_prefix* prefix, const int32_t* draft_ids, const int32_t* draft_lens, int32_t K, int32_t T,
+                             int32_t n_new, int32_t eos_id, int32_t* out_ids, void* workspace, size_t workspace_bytes,
+                             void* hip_stream);
 /* The same continuation with sampling instead of the arg max: out_ids[k][t] is drawn from
  * softmax(logits / temperature) by inverse CDF with the caller's uniform uniforms[k][t] in [0, 1): the first index v
  * (vocabulary order) whose cumulative probability reaches the uniform.  The random numbers are inputs, so a call
  * is a deterministic function of its arguments.  temperature > 0; uniforms dev float [K, n_new]. */
-int32_t atts_continue_sample(const atts_prefix* prefix, const int32_t* draft_ids, int32_t K, int32_t T, int32_t n_new,
-                             float temperature, const float* uniforms, int32_t* out_ids, void* workspace,
-                             size_t workspace_bytes, void* hip_stream);
+int32_t atts_continue_sample(const atts_prefix* prefix, const int32_t* draft_ids, const int32_t* draft_lens, int32_t K, int32_t T,
+                             int32_t n_new, int32_t eos_id, float temperature, const float* uniforms, int32_t* out_ids,
+                             void* workspace, size_t workspace_bytes, void* hip_stream);
 
 /* Synchronises hip_stream, copies the sticky device error flag to *host_flag (0 = clean,
  * 1 = some token id was out of range since the last check) and clears it. */

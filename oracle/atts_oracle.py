@@ -155,18 +155,23 @@ def token_logprobs(weights, cfg, prefix_ids, draft_ids) -> np.ndarray:
     return lsm[np.arange(T), draft_ids]
 
 
-def greedy_continuation(weights, cfg, prefix_ids, draft_ids, n_new: int):
+def greedy_continuation(weights, cfg, prefix_ids, draft_ids, n_new: int, eos_id=None):
     """Target-model continuation of one candidate (Sec. "How to perform rejection sampling via conformal
     prediction", paragraph "Target Model Sampling"): the candidate's draft is kept as a prefix and the target model
     generates n_new more tokens.  Decoding here is greedy: every new token is the arg max of the target's
     next-token logits given everything before it (first index on exact ties, as numpy's argmax).
 
     Returns (tokens [n_new] int64, margins [n_new] float64) where margins[t] is the gap between the best and the
-    second-best logit at step t (how close the decision was).
+    second-best logit at step t (how close the decision was).  With eos_id, a candidate that has produced that
+    token has ended: the rest of its fixed-size output repeats eos_id (margin inf: nothing was decided there).
     """
     ctx = [int(t) for t in np.concatenate([np.asarray(prefix_ids), np.asarray(draft_ids)])]
     toks, margins = [], []
     for _ in range(n_new):
+        if eos_id is not None and toks and toks[-1] == eos_id:
+            toks.append(int(eos_id))
+            margins.append(np.inf)
+            continue
         h = decoder_hidden(weights, cfg, np.asarray(ctx, dtype=np.int64))
         z = logits_from_hidden(weights, cfg, h[-1:])[0]
         best = int(np.argmax(z))
@@ -177,18 +182,23 @@ def greedy_continuation(weights, cfg, prefix_ids, draft_ids, n_new: int):
     return np.asarray(toks, dtype=np.int64), np.asarray(margins, dtype=F64)
 
 
-def sampled_continuation(weights, cfg, prefix_ids, draft_ids, uniforms, temperature: float):
+def sampled_continuation(weights, cfg, prefix_ids, draft_ids, uniforms, temperature: float, eos_id=None):
     """Target-model continuation by sampling (paragraph "Target Model Sampling"): token t is drawn from
     softmax(logits / temperature) of the target given everything before it.  The randomness is an input: with
     u = uniforms[t] in [0, 1) the token is the first index v (vocabulary order) whose cumulative probability
     reaches u, i.e. inverse-CDF sampling.
 
     Returns (tokens [n] int64, slack [n] float64): slack[t] is the distance, in probability, from u to the nearer
-    end of the chosen token's CDF interval (how close the draw was to picking a neighbour).
+    end of the chosen token's CDF interval (how close the draw was to picking a neighbour).  eos_id as in
+    greedy_continuation (slack inf after the end; the uniforms of those positions are not used).
     """
     ctx = [int(t) for t in np.concatenate([np.asarray(prefix_ids), np.asarray(draft_ids)])]
     toks, slack = [], []
     for u in np.asarray(uniforms, dtype=F64):
+        if eos_id is not None and toks and toks[-1] == eos_id:
+            toks.append(int(eos_id))
+            slack.append(np.inf)
+            continue
         h = decoder_hidden(weights, cfg, np.asarray(ctx, dtype=np.int64))
         z = logits_from_hidden(weights, cfg, h[-1:])[0] / float(temperature)
         p = np.exp(z - z.max())

@@ -225,24 +225,30 @@ def atts_continue_workspace_bytes(prefix: Prefix, K: int, T: int, n_new: int) ->
     return out.value
 
 
-def atts_continue_greedy(prefix: Prefix, draft_ids: torch.Tensor, out_ids: torch.Tensor, workspace: torch.Tensor) -> None:
+def atts_continue_greedy(prefix: Prefix, draft_ids: torch.Tensor, out_ids: torch.Tensor, workspace: torch.Tensor,
+                         draft_lens: Optional[torch.Tensor] = None, eos_id: int = -1) -> None:
     K, T = draft_ids.shape
-    if out_ids.dim() != 2 or out_ids.shape[0] != K:
-        raise AttsError(ERR_INVALID_ARG, "out_ids must be [K, n_new]")
-    _check(_lib.atts_continue_greedy(prefix.handle, _ptr(draft_ids, torch.int32, "draft_ids"), ctypes.c_int32(K), ctypes.c_int32(T),
-                                     ctypes.c_int32(out_ids.shape[1]), _ptr(out_ids, torch.int32, "out_ids"),
-                                     _ptr(workspace, torch.uint8, "workspace"), ctypes.c_size_t(workspace.numel()), _stream()))
+    if out_ids.dim() != 2 or out_ids.shape[0] != K or (draft_lens is not None and draft_lens.numel() != K):
+        raise AttsError(ERR_INVALID_ARG, "out_ids must be [K, n_new], draft_lens [K]")
+    _check(_lib.atts_continue_greedy(prefix.handle, _ptr(draft_ids, torch.int32, "draft_ids"), _ptr(draft_lens, torch.int32, "draft_lens"),
+                                     ctypes.c_int32(K), ctypes.c_int32(T), ctypes.c_int32(out_ids.shape[1]), ctypes.c_int32(eos_id),
+                                     _ptr(out_ids, torch.int32, "out_ids"), _ptr(workspace, torch.uint8, "workspace"),
+                                     ctypes.c_size_t(workspace.numel()), _stream()))
 
 
 def atts_continue_sample(prefix: Prefix, draft_ids: torch.Tensor, temperature: float, uniforms: torch.Tensor,
-                         out_ids: torch.Tensor, workspace: torch.Tensor) -> None:
+                         out_ids: torch.Tensor, workspace: torch.Tensor, draft_lens: Optional[torch.Tensor] = None,
+                         eos_id: int = -1) -> None:
     K, T = draft_ids.shape
     if out_ids.dim() != 2 or out_ids.shape[0] != K or tuple(uniforms.shape) != tuple(out_ids.shape):
         raise AttsError(ERR_INVALID_ARG, "out_ids and uniforms must both be [K, n_new]")
-    _check(_lib.atts_continue_sample(prefix.handle, _ptr(draft_ids, torch.int32, "draft_ids"), ctypes.c_int32(K), ctypes.c_int32(T),
-                                     ctypes.c_int32(out_ids.shape[1]), ctypes.c_float(temperature),
-                                     _ptr(uniforms, torch.float32, "uniforms"), _ptr(out_ids, torch.int32, "out_ids"),
-                                     _ptr(workspace, torch.uint8, "workspace"), ctypes.c_size_t(workspace.numel()), _stream()))
+    if draft_lens is not None and draft_lens.numel() != K:
+        raise AttsError(ERR_INVALID_ARG, "draft_lens must have K elements")
+    _check(_lib.atts_continue_sample(prefix.handle, _ptr(draft_ids, torch.int32, "draft_ids"), _ptr(draft_lens, torch.int32, "draft_lens"),
+                                     ctypes.c_int32(K), ctypes.c_int32(T), ctypes.c_int32(out_ids.shape[1]), ctypes.c_int32(eos_id),
+                                     ctypes.c_float(temperature), _ptr(uniforms, torch.float32, "uniforms"),
+                                     _ptr(out_ids, torch.int32, "out_ids"), _ptr(workspace, torch.uint8, "workspace"),
+                                     ctypes.c_size_t(workspace.numel()), _stream()))
 
 
 def atts_model_check(model: Model) -> int:

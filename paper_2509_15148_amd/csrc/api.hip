@@ -569,9 +569,9 @@ int32_t atts_continue_workspace_bytes(const atts_prefix* p, int32_t K, int32_t T
 
 namespace {
 // uniforms == nullptr: greedy; else token t of candidate k is drawn with uniforms[k n_new + t] at inv_temp
-int32_t continue_tokens(const char* fn, const atts_prefix* p, const int32_t* draft_ids, int32_t K, int32_t T, int32_t n_new,
-                        const float* uniforms, float inv_temp, int32_t* out_ids, void* workspace, size_t workspace_bytes,
-                        void* hip_stream) {
+int32_t continue_tokens(const char* fn, const atts_prefix* p, const int32_t* draft_ids, const int32_t* draft_lens, int32_t K,
+                        int32_t T, int32_t n_new, int32_t eos_id, const float* uniforms, float inv_temp, int32_t* out_ids,
+                        void* workspace, size_t workspace_bytes, void* hip_stream) {
     ATTS_TRY(check_continue_shape(fn, p, K, T, n_new));
     if (!draft_ids || !out_ids) return fail(ATTS_ERR_INVALID_ARG, "%s: NULL draft_ids / out_ids", fn);
     const atts_model* m = p->model;
@@ -582,14 +582,14 @@ int32_t continue_tokens(const char* fn, const atts_prefix* p, const int32_t* dra
     if (workspace_bytes < cs.total) return fail(ATTS_ERR_WORKSPACE, "%s: workspace has %zu bytes, %zu needed", fn, workspace_bytes, cs.total);
     hipStream_t st = static_cast<hipStream_t>(hip_stream);
     char* base = static_cast<char*>(workspace);
-    const int qd = d.n_q_heads * d.head_dim, kvd = d.n_kv_heads * d.head_dim, qkv_out = qd + 2 * kvd, half = d.head_dim / 2;
+    const int qd = d.n_q_heads * d.head_dim, kvd = d.n_kv_heads * d.head_dim, qkv_out = qd + 2 * kvd;
     const bool padded = pads_rows(d);
     const ScoreShape s{P, K, T};
 
     // 1. the drafts through the model against the cached prefix; keys / values of the whole tree kept per layer
     TreeSave tree{base + cs.kc, base + cs.vc, cs.Tc, cs.layer_bytes};
-    ATTS_TRY(forward_tree(m, s, P, const_cast<atts_prefix*>(p), false, false, nullptr, draft_ids, nullptr, ATTS_SCORE_MEAN_NLL, nullptr,
-                          nullptr, workspace, st, &tree));
+    ATTS_TRY(forward_tree(m, s, P, const_cast<atts_prefix*>(p), false, false, nullptr, draft_ids, draft_lens, ATTS_SCORE_MEAN_NLL,
+                          nullptr, nullptr, workspace, st, &tree));
     const float* h_tree = reinterpret_cast<const float*>(base + carve(d, s).h);
 
     float* h = reinterpret_cast<float*>(base + cs.h);
@@ -601,8 +601,8 @@ int32_t continue_tokens(const char* fn, const atts_prefix* p, const int32_t* dra
     char* q = base + cs.q;
     float* logits = reinterpret_cast<float*>(base + cs.logits);
     float2* rope = reinterpret_cast<float2*>(base + cs.rope);
-    // (cos, sin) rows of the positions the new tokens take: P + T ... P + T + n_new - 1 (indexed by absolute position)
-    ATTS_TRY(launch_rope_table(rope, ScoreShape{P + T, 1, n_new}, P + T, d.head_dim, d.rope_theta, st));
+    // (cos, sin) rows of the positions new tokens can take: P + 1 ... P + T + n_new - 1 (indexed by absolute position)
+    ATTS_TRY(launch_rope_table(rope, ScoreShape{P, 1, cs.Tc}, P, d.head_dim, d.rope_theta, st));
     // the QKV projection of a step has few tiles: where the aligned kernel would split its K range, the workgroups
     // add into the (cleared) fp32 buffer; otherwise they store
     const bool split_qkv = gemm_splits_k(d.dtype, K, qkv_out, d.d_model, padded);
@@ -613,17 +613,19 @@ int32_t continue_tokens(const char* fn, const atts_prefix* p, const int32_t* dra
         g.a = xs; g.w = m->lm_head; g.out = logits; g.M = K; g.N = d.vocab; g.Kd = d.d_model;
         g.lda = d.d_model; g.ldw = d.d_model; g.ldc = d.vocab; g.a_rows_padded = padded;
         ATTS_TRY(launch_gemm(d.dtype, EPI_STORE_F32, g, st));
-        if (uniforms) return launch_sample_rows(logits, d.vocab, d.vocab, K, inv_temp, uniforms + t, out_ids + t, n_new, st);
-        return launch_argmax_rows(logits, d.vocab, d.vocab, K, out_ids + t, n_new, st);
+        if (uniforms)
+            return launch_sample_rows(logits, d.vocab, d.vocab, K, inv_temp, uniforms + t, out_ids + t, n_new, eos_id, t > 0, st);
+        return launch_argmax_rows(logits, d.vocab, d.vocab, K, out_ids + t, n_new, eos_id, t > 0, st);
     };
 
-    // 2. token 0 follows from the last draft row of every branch
-    ATTS_TRY(launch_norm_strided_rows(d.dtype, h_tree, m->final_norm, d.rms_eps, d.d_model, (int64_t)P + T - 1, T, K, xs, st));
+    // 2. token 0 follows from the last draft row of every branch: row P + j T + len_j - 1 of the tree
+    ATTS_TRY(launch_norm_strided_rows(d.dtype, h_tree, m->final_norm, d.rms_eps, d.d_model, (int64_t)P - 1, T,
+                                      BranchPos{draft_lens, T, 0}, K, xs, st));
     ATTS_TRY(next_token(0));
 
-    // 3. one row per branch and step: token t - 1 goes in at branch position T + t - 1 and predicts token t
+    // 3. one row per branch and step: token t - 1 goes in at branch position len_j + t - 1 and predicts token t
     for (int t = 1; t < n_new; ++t) {
-        const int t_new = T + t - 1;
+        const BranchPos pos{draft_lens, T, t - 1};
         ATTS_TRY(launch_embed_rows(d.dtype, m->tok_embed, d.vocab, d.d_model, out_ids + (t - 1), n_new, K, h, m->err_flag, st));
         for (int l = 0; l < d.n_layers; ++l) {
             char* kc = tree.kc + (size_t)l * tree.layer_bytes;
@@ -633,9 +635,9 @@ int32_t continue_tokens(const char* fn, const atts_prefix* p, const int32_t* dra
             g.a = xn; g.w = m->wqkv[l]; g.out = qkv32; g.M = K; g.N = qkv_out; g.Kd = d.d_model;
             g.lda = d.d_model; g.ldw = d.d_model; g.ldc = qkv_out; g.a_rows_padded = padded;
             ATTS_TRY(launch_gemm(d.dtype, split_qkv ? EPI_RESID_F32 : EPI_STORE_F32, g, st));
-            ATTS_TRY(launch_decode_qkv_finish(d.dtype, qkv32, rope + (size_t)(P + t_new) * half, K, d.n_q_heads, d.n_kv_heads,
-                                              d.head_dim, P, cs.Tc, t_new, q, kc, vc, st));
-            ATTS_TRY(launch_attn_decode(d.dtype, q, kc, vc, ao, K, P, cs.Tc, t_new, d.n_q_heads, d.n_kv_heads, d.head_dim, st));
+            ATTS_TRY(launch_decode_qkv_finish(d.dtype, qkv32, rope, K, d.n_q_heads, d.n_kv_heads, d.head_dim, P, cs.Tc, pos, q, kc, vc,
+                                              st));
+            ATTS_TRY(launch_attn_decode(d.dtype, q, kc, vc, ao, K, P, cs.Tc, pos, d.n_q_heads, d.n_kv_heads, d.head_dim, st));
             g = GemmArgs{};
             g.a = ao; g.w = m->wo[l]; g.out = h; g.M = K; g.N = d.d_model; g.Kd = qd;
             g.lda = qd; g.ldw = qd; g.ldc = d.d_model; g.a_rows_padded = padded;
@@ -650,27 +652,28 @@ int32_t continue_tokens(const char* fn, const atts_prefix* p, const int32_t* dra
             g.lda = d.d_ffn; g.ldw = d.d_ffn; g.ldc = d.d_model; g.a_rows_padded = padded;
             ATTS_TRY(launch_gemm(d.dtype, EPI_RESID_F32, g, st));
         }
-        ATTS_TRY(launch_norm_strided_rows(d.dtype, h, m->final_norm, d.rms_eps, d.d_model, 0, 1, K, xs, st));
+        ATTS_TRY(launch_norm_strided_rows(d.dtype, h, m->final_norm, d.rms_eps, d.d_model, 0, 1, BranchPos{nullptr, 0, 0}, K, xs, st));
         ATTS_TRY(next_token(t));
     }
     return ATTS_OK;
 }
 }  // namespace
 
-int32_t atts_continue_greedy(const atts_prefix* p, const int32_t* draft_ids, int32_t K, int32_t T, int32_t n_new,
-                             int32_t* out_ids, void* workspace, size_t workspace_bytes, void* hip_stream) {
-    return continue_tokens("atts_continue_greedy", p, draft_ids, K, T, n_new, nullptr, 1.f, out_ids, workspace, workspace_bytes,
-                           hip_stream);
+int32_t atts_continue_greedy(const atts_prefix* p, const int32_t* draft_ids, const int32_t* draft_lens, int32_t K, int32_t T,
+                             int32_t n_new, int32_t eos_id, int32_t* out_ids, void* workspace, size_t workspace_bytes,
+                             void* hip_stream) {
+    return continue_tokens("atts_continue_greedy", p, draft_ids, draft_lens, K, T, n_new, eos_id, nullptr, 1.f, out_ids, workspace,
+                           workspace_bytes, hip_stream);
 }
 
-int32_t atts_continue_sample(const atts_prefix* p, const int32_t* draft_ids, int32_t K, int32_t T, int32_t n_new,
-                             float temperature, const float* uniforms, int32_t* out_ids, void* workspace,
-                             size_t workspace_bytes, void* hip_stream) {
+int32_t atts_continue_sample(const atts_prefix* p, const int32_t* draft_ids, const int32_t* draft_lens, int32_t K, int32_t T,
+                             int32_t n_new, int32_t eos_id, float temperature, const float* uniforms, int32_t* out_ids,
+                             void* workspace, size_t workspace_bytes, void* hip_stream) {
     if (!(temperature > 0.f) || !(temperature < INFINITY))
         return fail(ATTS_ERR_INVALID_ARG, "atts_continue_sample: temperature must be positive and finite");
     if (!uniforms) return fail(ATTS_ERR_INVALID_ARG, "atts_continue_sample: uniforms is NULL");
-    return continue_tokens("atts_continue_sample", p, draft_ids, K, T, n_new, uniforms, 1.f / temperature, out_ids, workspace,
-                           workspace_bytes, hip_stream);
+    return continue_tokens("atts_continue_sample", p, draft_ids, draft_lens, K, T, n_new, eos_id, uniforms, 1.f / temperature, out_ids,
+                           workspace, workspace_bytes, hip_stream);
 }
 
 int32_t atts_model_check(const atts_model* m, void* hip_stream, int32_t* host_flag) {

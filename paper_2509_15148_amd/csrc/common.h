@@ -175,17 +175,27 @@ int32_t launch_transpose_to_rows(int32_t dtype, const void* src, int64_t src_ld,
                                  int32_t cols, hipStream_t stream);
 int32_t launch_embed_rows(int32_t dtype, const void* tok_embed, int32_t vocab, int32_t d, const int32_t* ids, int64_t stride,
                           int32_t rows, float* h, int32_t* err_flag, hipStream_t stream);
+// Branch j of a continuation holds len_j = lens[j] draft tokens (read as clamped to [1, T]; T when lens is NULL) and `done`
+// generated ones: at(j) = len_j + done is the position, inside the branch, of the row a decoding step appends.
+struct BranchPos {
+    const int32_t* lens;   // device [Kr] or NULL
+    int32_t T, done;
+    __device__ int at(int j) const { return (lens ? min(max(lens[j], 1), T) : T) + done; }
+};
+// cs: (cos, sin) rows indexed by absolute position (prefix length + position in the branch)
 int32_t launch_decode_qkv_finish(int32_t dtype, float* acc, const float2* cs, int32_t Kr, int32_t nq, int32_t nkv, int32_t hd,
-                                 int32_t P, int32_t Tc, int32_t t_new, void* q_out, void* k_cache, void* v_cache,
+                                 int32_t P, int32_t Tc, BranchPos pos, void* q_out, void* k_cache, void* v_cache,
                                  hipStream_t stream);
 int32_t launch_attn_decode(int32_t dtype, const void* q, const void* k_cache, const void* v_cache, void* out, int32_t Kr, int32_t P,
-                           int32_t Tc, int32_t t_new, int32_t nq, int32_t nkv, int32_t hd, hipStream_t stream);
-int32_t launch_argmax_rows(const float* logits, int64_t ld, int32_t V, int32_t rows, int32_t* ids, int64_t stride,
-                           hipStream_t stream);
+                           int32_t Tc, BranchPos pos, int32_t nq, int32_t nkv, int32_t hd, hipStream_t stream);
+// eos_id >= 0 and has_prev: a row whose previous token (ids[j stride - 1]) is eos_id gets eos_id again
+int32_t launch_argmax_rows(const float* logits, int64_t ld, int32_t V, int32_t rows, int32_t* ids, int64_t stride, int32_t eos_id,
+                           bool has_prev, hipStream_t stream);
 int32_t launch_sample_rows(const float* logits, int64_t ld, int32_t V, int32_t rows, float inv_temp, const float* uniforms,
-                           int32_t* ids, int64_t stride, hipStream_t stream);
+                           int32_t* ids, int64_t stride, int32_t eos_id, bool has_prev, hipStream_t stream);
+// xs[j] = rmsnorm(h[first + j step + pos.at(j)])
 int32_t launch_norm_strided_rows(int32_t dtype, const float* h, const float* gain, float eps, int32_t d, int64_t first, int64_t step,
-                                 int32_t rows, void* xs, hipStream_t stream);
+                                 BranchPos pos, int32_t rows, void* xs, hipStream_t stream);
 
 bool attention_uses_vt(int32_t dtype, int32_t hd);
 // queries are the rows [row0, R); keys / values of all rows [0, R) must be present

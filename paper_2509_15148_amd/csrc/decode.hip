@@ -57,10 +57,10 @@ __global__ __launch_bounds__(256) void embed_rows_kernel(const T* __restrict__ e
 }
 
 // One decode row per branch: acc [Kr, (nq + 2 nkv) hd] fp32 (cleared on return) -> q (rotated) to q_out [Kr, nq hd]; k (rotated) and v
-// to row `P + j Tc + t_new` of the layer's key / value cache.  cs: the (cos, sin) row of the new position.
+// to row `P + j Tc + pos.at(j)` of the layer's key / value cache.  cs: (cos, sin) rows indexed by absolute position.
 template <typename T>
 __global__ __launch_bounds__(256) void decode_qkv_finish_kernel(float* __restrict__ acc, const float2* __restrict__ cs, int Kr,
-                                                                int nq, int nkv, int hd, int P, int Tc, int t_new,
+                                                                int nq, int nkv, int hd, int P, int Tc, BranchPos pos,
                                                                 T* __restrict__ q_out, T* __restrict__ k_cache,
                                                                 T* __restrict__ v_cache) {
     const int half = hd >> 1, heads = nq + 2 * nkv;
@@ -73,9 +73,10 @@ __global__ __launch_bounds__(256) void decode_qkv_finish_kernel(float* __restric
     const float x1 = a[0], x2 = a[half];
     a[0] = 0.f;                                  // left clear for a K-split projection that adds into it
     a[half] = 0.f;
+    const int t_new = pos.at(j);
     const int64_t crow = P + (int64_t)j * Tc + t_new;
     if (head < nq + nkv) {
-        const float2 c_s = cs[i];
+        const float2 c_s = cs[(int64_t)(P + t_new) * half + i];
         const float y1 = x1 * c_s.x - x2 * c_s.y, y2 = x2 * c_s.x + x1 * c_s.y;
         T* p = head < nq ? q_out + (int64_t)j * nq * hd + head * hd + i : k_cache + crow * nkv * hd + (head - nq) * hd + i;
         p[0] = from_f32<T>(y1);
@@ -88,7 +89,7 @@ __global__ __launch_bounds__(256) void decode_qkv_finish_kernel(float* __restric
 }
 
 // One workgroup (kDecodeWaves wavefronts) per (branch, head): the new row of branch j attends to the prefix rows and
-// to rows 0 .. t_new of its own branch.  Scores: one key per thread and pass (16-byte loads along the key row);
+// to rows 0 .. pos.at(j) of its own branch.  Scores: one key per thread and pass (16-byte loads along the key row);
 // output: every wavefront accumulates its share of the keys (lane = a pair of dims, 128 / 256 contiguous bytes per
 // key), the partial sums are added in a fixed order.
 constexpr int kDecodeWaves = 16, kDecodeThreads = 64 * kDecodeWaves;
@@ -96,9 +97,9 @@ constexpr int kDecodeWaves = 16, kDecodeThreads = 64 * kDecodeWaves;
 template <typename T>
 __global__ __launch_bounds__(kDecodeThreads) void attn_decode_kernel(const T* __restrict__ q, const T* __restrict__ k_cache,
                                                                      const T* __restrict__ v_cache, T* __restrict__ out, int P,
-                                                                     int Tc, int t_new, int nq, int nkv, int hd, float scale) {
+                                                                     int Tc, BranchPos pos, int nq, int nkv, int hd, float scale) {
     extern __shared__ float sm[];           // [hd] query | [n] scores | [2 waves] reductions | [waves][hd] partial outputs
-    const int n = P + t_new + 1;
+    const int n = P + pos.at(blockIdx.x) + 1;
     float* sq = sm;
     float* sp = sm + hd;
     float* red = sp + n;
@@ -222,11 +223,11 @@ constexpr int kDecodeBatch = 7;
 template <typename T>
 __global__ __launch_bounds__(kDecodeThreads) void attn_decode_pieces_kernel(const T* __restrict__ q, const T* __restrict__ k_cache,
                                                                             const T* __restrict__ v_cache, T* __restrict__ out,
-                                                                            int P, int Tc, int t_new, int nq, int nkv, int hd,
+                                                                            int P, int Tc, BranchPos pos, int nq, int nkv, int hd,
                                                                             float scale) {
     extern __shared__ float sm[];           // [waves] running maxima | [waves] sums | [waves][hd] unnormalised outputs
     constexpr int kVec = 16 / (int)sizeof(T);
-    const int n = P + t_new + 1;
+    const int n = P + pos.at(blockIdx.x) + 1;
     float* red = sm;
     float* so = sm + 2 * kDecodeWaves;
     const int j = blockIdx.x, head = blockIdx.y, tid = threadIdx.x, lane = tid & 63;
@@ -339,10 +340,14 @@ __global__ __launch_bounds__(kDecodeThreads) void attn_decode_pieces_kernel(cons
 
 // ids[j * stride] = first index of the largest logit of row j
 __global__ __launch_bounds__(256) void argmax_rows_kernel(const float* __restrict__ logits, int64_t ld, int V, int32_t* __restrict__ ids,
-                                                          int64_t stride) {
+                                                          int64_t stride, int eos_id, bool has_prev) {
     __shared__ float s_val[256];
     __shared__ int s_idx[256];
     const int j = blockIdx.x;
+    if (eos_id >= 0 && has_prev && ids[(int64_t)j * stride - 1] == eos_id) {      // the branch has ended: it stays ended
+        if (threadIdx.x == 0) ids[(int64_t)j * stride] = eos_id;
+        return;
+    }
     const float* z = logits + (int64_t)j * ld;
     float best = -INFINITY;
     int at = 0x7fffffff;
@@ -388,12 +393,17 @@ constexpr int kSampleThreads = 1024;
 
 __global__ __launch_bounds__(kSampleThreads) void sample_rows_kernel(const float* __restrict__ logits, int64_t ld, int V,
                                                                      float inv_temp, const float* __restrict__ uniforms,
-                                                                     int32_t* __restrict__ ids, int64_t stride) {
+                                                                     int32_t* __restrict__ ids, int64_t stride, int eos_id,
+                                                                     bool has_prev) {
     __shared__ float red[kSampleThreads / 64];
     __shared__ float chunk_sum[kSampleThreads];
     __shared__ float s_target, s_before;
     __shared__ int s_chunk;
     const int j = blockIdx.x, tid = threadIdx.x;
+    if (eos_id >= 0 && has_prev && ids[(int64_t)j * stride - 1] == eos_id) {      // the branch has ended: it stays ended
+        if (tid == 0) ids[(int64_t)j * stride] = eos_id;
+        return;
+    }
     const float* z = logits + (int64_t)j * ld;
     const int per = (V + kSampleThreads - 1) / kSampleThreads;
     const int c0 = min(tid * per, V), c1 = min(c0 + per, V);
@@ -445,13 +455,13 @@ __global__ __launch_bounds__(kSampleThreads) void sample_rows_kernel(const float
     }
 }
 
-// xs[j] = rmsnorm(h[rows[j]]) with rows[j] = first + j * step
+// xs[j] = rmsnorm(h[rows[j]]) with rows[j] = first + j * step + pos.at(j)
 template <typename T>
 __global__ __launch_bounds__(256) void norm_strided_rows_kernel(const float* __restrict__ h, const float* __restrict__ gain, float eps,
-                                                                int d, int64_t first, int64_t step, T* __restrict__ xs) {
+                                                                int d, int64_t first, int64_t step, BranchPos pos, T* __restrict__ xs) {
     __shared__ float red[4];
     const int j = blockIdx.x;
-    const float* x = h + (first + (int64_t)j * step) * d;
+    const float* x = h + (first + (int64_t)j * step + pos.at(j)) * d;
     float ss = 0.f;
     for (int c = threadIdx.x; c < d; c += 256) ss += x[c] * x[c];
 #pragma unroll
@@ -502,53 +512,55 @@ int32_t launch_embed_rows(int32_t dtype, const void* tok_embed, int32_t vocab, i
 }
 
 int32_t launch_decode_qkv_finish(int32_t dtype, float* acc, const float2* cs, int32_t Kr, int32_t nq, int32_t nkv, int32_t hd,
-                                 int32_t P, int32_t Tc, int32_t t_new, void* q_out, void* k_cache, void* v_cache,
+                                 int32_t P, int32_t Tc, BranchPos pos, void* q_out, void* k_cache, void* v_cache,
                                  hipStream_t stream) {
     const int64_t total = (int64_t)Kr * (nq + 2 * nkv) * (hd / 2);
     DISPATCH_T(dtype, hipLaunchKernelGGL(decode_qkv_finish_kernel<T>, dim3((unsigned)ceil_div(total, 256)), dim3(256), 0, stream, acc,
-                                         cs, Kr, nq, nkv, hd, P, Tc, t_new, (T*)q_out, (T*)k_cache, (T*)v_cache);)
+                                         cs, Kr, nq, nkv, hd, P, Tc, pos, (T*)q_out, (T*)k_cache, (T*)v_cache);)
     ATTS_LAUNCH_CHECK("decode_qkv_finish_kernel");
     return ATTS_OK;
 }
 
 int32_t launch_attn_decode(int32_t dtype, const void* q, const void* k_cache, const void* v_cache, void* out, int32_t Kr, int32_t P,
-                           int32_t Tc, int32_t t_new, int32_t nq, int32_t nkv, int32_t hd, hipStream_t stream) {
+                           int32_t Tc, BranchPos pos, int32_t nq, int32_t nkv, int32_t hd, hipStream_t stream) {
     const float scale = 1.f / sqrtf((float)hd);
     dim3 grid(Kr, nq);
     const int lanes_per_key = hd * (int)dtype_size(dtype) / 16;
     if ((hd * dtype_size(dtype)) % 16 == 0 && lanes_per_key <= 64 && (lanes_per_key & (lanes_per_key - 1)) == 0) {
         const size_t lds = (size_t)(kDecodeWaves * hd + 2 * kDecodeWaves) * sizeof(float);
         DISPATCH_T(dtype, hipLaunchKernelGGL(attn_decode_pieces_kernel<T>, grid, dim3(kDecodeThreads), lds, stream, (const T*)q,
-                                             (const T*)k_cache, (const T*)v_cache, (T*)out, P, Tc, t_new, nq, nkv, hd, scale);)
+                                             (const T*)k_cache, (const T*)v_cache, (T*)out, P, Tc, pos, nq, nkv, hd, scale);)
         ATTS_LAUNCH_CHECK("attn_decode_pieces_kernel");
         return ATTS_OK;
     }
-    const size_t lds = (size_t)((1 + kDecodeWaves) * hd + P + t_new + 1 + 2 * kDecodeWaves) * sizeof(float);
-    if (lds > 60 * 1024) return fail(ATTS_ERR_SHAPE, "continuation: context of %d keys is too long", P + t_new + 1);
+    const int n_max = P + pos.T + pos.done + 1;        // the longest branch
+    const size_t lds = (size_t)((1 + kDecodeWaves) * hd + n_max + 2 * kDecodeWaves) * sizeof(float);
+    if (lds > 60 * 1024) return fail(ATTS_ERR_SHAPE, "continuation: context of %d keys is too long", n_max);
     DISPATCH_T(dtype, hipLaunchKernelGGL(attn_decode_kernel<T>, grid, dim3(kDecodeThreads), lds, stream, (const T*)q, (const T*)k_cache,
-                                         (const T*)v_cache, (T*)out, P, Tc, t_new, nq, nkv, hd, scale);)
+                                         (const T*)v_cache, (T*)out, P, Tc, pos, nq, nkv, hd, scale);)
     ATTS_LAUNCH_CHECK("attn_decode_kernel");
     return ATTS_OK;
 }
 
-int32_t launch_argmax_rows(const float* logits, int64_t ld, int32_t V, int32_t rows, int32_t* ids, int64_t stride,
-                           hipStream_t stream) {
-    hipLaunchKernelGGL(argmax_rows_kernel, dim3(rows), dim3(256), 0, stream, logits, ld, V, ids, stride);
+int32_t launch_argmax_rows(const float* logits, int64_t ld, int32_t V, int32_t rows, int32_t* ids, int64_t stride, int32_t eos_id,
+                           bool has_prev, hipStream_t stream) {
+    hipLaunchKernelGGL(argmax_rows_kernel, dim3(rows), dim3(256), 0, stream, logits, ld, V, ids, stride, eos_id, has_prev);
     ATTS_LAUNCH_CHECK("argmax_rows_kernel");
     return ATTS_OK;
 }
 
 int32_t launch_sample_rows(const float* logits, int64_t ld, int32_t V, int32_t rows, float inv_temp, const float* uniforms,
-                           int32_t* ids, int64_t stride, hipStream_t stream) {
-    hipLaunchKernelGGL(sample_rows_kernel, dim3(rows), dim3(kSampleThreads), 0, stream, logits, ld, V, inv_temp, uniforms, ids, stride);
+                           int32_t* ids, int64_t stride, int32_t eos_id, bool has_prev, hipStream_t stream) {
+    hipLaunchKernelGGL(sample_rows_kernel, dim3(rows), dim3(kSampleThreads), 0, stream, logits, ld, V, inv_temp, uniforms, ids, stride,
+                       eos_id, has_prev);
     ATTS_LAUNCH_CHECK("sample_rows_kernel");
     return ATTS_OK;
 }
 
 int32_t launch_norm_strided_rows(int32_t dtype, const float* h, const float* gain, float eps, int32_t d, int64_t first, int64_t step,
-                                 int32_t rows, void* xs, hipStream_t stream) {
+                                 BranchPos pos, int32_t rows, void* xs, hipStream_t stream) {
     DISPATCH_T(dtype, hipLaunchKernelGGL(norm_strided_rows_kernel<T>, dim3(rows), dim3(256), 0, stream, h, gain, eps, d, first, step,
-                                         (T*)xs);)
+                                         pos, (T*)xs);)
     ATTS_LAUNCH_CHECK("norm_strided_rows_kernel");
     return ATTS_OK;
 }

@@ -164,3 +164,77 @@ def test_continuation_argument_errors():
         with pytest.raises(A.AttsError) as e:
             A.atts_continue_workspace_bytes(pre, K, T, n)
         assert e.value.code == A.ERR_INVALID_ARG
+
+
+@pytest.mark.parametrize("cfg,P,T,lens,n_new", [
+    (ModelConfig(2, 96, 4, 1, 24, 200, 515, "fp32"), 9, 7, (7, 1, 4), 6),                 # general attention kernel
+    (ModelConfig(2, 256, 4, 2, 128, 512, 2048, "bf16"), 40, 12, (3, 12, 8, 1), 6),       # pieces kernel, few-row GEMM
+    (ModelConfig(2, 256, 2, 1, 128, 256, 515, "fp32"), 450, 30, (30, 2), 4),             # branches on both sides of a key batch
+])
+def test_ragged_drafts_and_end_of_sequence(cfg, P, T, lens, n_new):
+    """Candidates of different lengths continue after their own last token (the padding of their rows, here out-of-
+    vocabulary garbage, is never read), and a candidate that has produced the end token stays ended."""
+    import paper_2509_15148_amd as A
+    K = len(lens)
+    announce("continue ragged", cfg, P, K, T, lens, n_new)
+    w_dev = make_weights(cfg, seed=P + 5 * K, device="cuda")
+    w_np = weights_to_numpy(w_dev)
+    prefix, drafts = [x.numpy() for x in make_token_ids(cfg.vocab, P, K, T, 7 * P + K)]
+    padded = drafts.copy()
+    for k, n in enumerate(lens):
+        padded[k, n:] = cfg.vocab + 17                      # must never be embedded
+    model = A.Model(cfg, w_dev)
+    pre = A.Prefix(model, capacity=P)
+    A.atts_prefix_extend(pre, dev(prefix), ws(A.atts_prefix_extend_workspace_bytes(pre, P)))
+    lens_dev = dev(np.asarray(lens, dtype=np.int32))
+    out = torch.full((K, n_new), -1, dtype=torch.int32, device="cuda")
+    wsb = A.atts_continue_workspace_bytes(pre, K, T, n_new)
+    A.atts_continue_greedy(pre, dev(padded), out, ws(wsb), draft_lens=lens_dev)
+    torch.cuda.synchronize()
+    got = out.cpu().numpy()
+    assert A.atts_model_check(model) == 0
+    agree = 0
+    for k, n in enumerate(lens):
+        ref, margins = O.greedy_continuation(w_np, cfg, prefix, drafts[k, :n], n_new)
+        for t in range(n_new):
+            if got[k, t] != ref[t]:
+                assert margins[t] <= MARGIN[cfg.dtype], (k, t, int(got[k, t]), int(ref[t]), margins[t])
+                break
+            agree += 1
+    assert agree >= K * n_new // 2
+    # end of sequence: take the token candidate 0 produced at step 1 as the end token
+    eos = int(got[0, 1])
+    out_e = torch.full((K, n_new), -1, dtype=torch.int32, device="cuda")
+    A.atts_continue_greedy(pre, dev(padded), out_e, ws(wsb), draft_lens=lens_dev, eos_id=eos)
+    torch.cuda.synchronize()
+    got_e = out_e.cpu().numpy()
+    for k in range(K):
+        hits = np.flatnonzero(got[k] == eos)
+        if len(hits) == 0:
+            if not np.array_equal(got_e[k], got[k]):        # only a near-tie may move a token between two runs
+                t = int(np.flatnonzero(got_e[k] != got[k])[0])
+                _, m = O.greedy_continuation(w_np, cfg, prefix, np.concatenate([drafts[k, :lens[k]], got[k, :t]]), 1)
+                assert m[0] <= MARGIN[cfg.dtype]
+            continue
+        first = int(hits[0])
+        if np.array_equal(got_e[k, :first + 1], got[k, :first + 1]):
+            assert np.all(got_e[k, first + 1:] == eos), (k, got_e[k], got[k])
+    assert np.all(got_e[0, 2:] == eos) or got_e[0, 1] != eos
+    # sampled: the same freezing rule, uniforms of the frozen positions unused
+    u = np.random.default_rng(K).random((K, n_new)).astype(np.float32)
+    out_s = torch.full((K, n_new), -1, dtype=torch.int32, device="cuda")
+    A.atts_continue_sample(pre, dev(padded), 1.0, dev(u), out_s, ws(wsb), draft_lens=lens_dev)
+    torch.cuda.synchronize()
+    got_s = out_s.cpu().numpy()
+    eos_s = int(got_s[K - 1, 0])
+    A.atts_continue_sample(pre, dev(padded), 1.0, dev(u), out_s, ws(wsb), draft_lens=lens_dev, eos_id=eos_s)
+    torch.cuda.synchronize()
+    got_se = out_s.cpu().numpy()
+    if got_se[K - 1, 0] == eos_s:
+        assert np.all(got_se[K - 1] == eos_s)
+    for k, n in enumerate(lens):
+        ref, slack = O.sampled_continuation(w_np, cfg, prefix, drafts[k, :n], u[k].astype(np.float64), 1.0, eos_id=eos_s)
+        for t in range(n_new):
+            if got_se[k, t] != ref[t]:
+                assert slack[t] <= SLACK[cfg.dtype], (k, t, got_se[k, t], ref[t], slack[t])
+                break

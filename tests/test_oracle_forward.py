@@ -267,3 +267,25 @@ def test_sampled_continuation_follows_the_scored_distribution():
     assert np.array_equal(g, t)
     assert O.sampled_continuation(w, cfg, prefix, draft, [0.0], 1.0)[0][0] == 0
     assert O.sampled_continuation(w, cfg, prefix, draft, [1.0 - 1e-16], 1.0)[0][0] == cfg.vocab - 1
+
+
+def test_end_of_sequence_freezes_a_continuation():
+    """With an end token the chain is the unconstrained chain up to and including the first occurrence of that token
+    and the token itself afterwards; a token that never occurs changes nothing."""
+    cfg = ModelConfig(2, 48, 4, 2, 12, 80, 37, "fp32")
+    w = weights_to_numpy(make_weights(cfg, seed=11, device="cpu"))
+    prefix = np.array([3, 1, 4, 1, 5, 9, 2, 6]); draft = np.array([5, 3, 5])
+    free, _ = O.greedy_continuation(w, cfg, prefix, draft, 6)
+    for s in range(6):
+        eos = int(free[s])
+        first = int(np.argmax(free == eos))                 # the token may already occur before step s
+        got, m = O.greedy_continuation(w, cfg, prefix, draft, 6, eos_id=eos)
+        assert np.array_equal(got[:first + 1], free[:first + 1]) and np.all(got[first + 1:] == eos)
+        assert np.all(np.isinf(m[first + 1:])) and np.all(np.isfinite(m[:first + 1]))
+    absent = next(v for v in range(cfg.vocab) if v not in set(free.tolist()))
+    assert np.array_equal(O.greedy_continuation(w, cfg, prefix, draft, 6, eos_id=absent)[0], free)
+    us = [0.3, 0.9, 0.01, 0.5, 0.7]
+    sfree, _ = O.sampled_continuation(w, cfg, prefix, draft, us, 1.0)
+    eos = int(sfree[1]); first = int(np.argmax(sfree == eos))
+    sgot, sl = O.sampled_continuation(w, cfg, prefix, draft, us, 1.0, eos_id=eos)
+    assert np.array_equal(sgot[:first + 1], sfree[:first + 1]) and np.all(sgot[first + 1:] == eos) and np.all(np.isinf(sl[first + 1:]))
