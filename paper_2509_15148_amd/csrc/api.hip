@@ -515,7 +515,7 @@ int32_t atts_score_drafts_cached(const atts_prefix* p, const int32_t* draft_ids,
 
 namespace {
 struct ContinueSpace {
-    size_t scoring, kc, vc, h, xn, ao, act, xs, qkv32, q, logits, rope, total;
+    size_t scoring, kc, vc, h, xn, ao, act, xs, qkv32, q, logits, argmax, rope, total;
     int32_t Tc;
     size_t layer_bytes;
 };
@@ -546,6 +546,7 @@ ContinueSpace carve_continue(const atts_model_desc& d, int32_t P, int32_t Kr, in
     c.qkv32 = take((size_t)Kr * qkv_out * sizeof(float));
     c.q = take((size_t)Kr * qd * es);
     c.logits = take((size_t)Kr * d.vocab * sizeof(float));
+    c.argmax = take(argmax_scratch_bytes(Kr));
     c.rope = take(((size_t)P + c.Tc) * (d.head_dim / 2) * sizeof(float2));
     c.total = off;
     return c;
@@ -615,7 +616,7 @@ int32_t continue_tokens(const char* fn, const atts_prefix* p, const int32_t* dra
         ATTS_TRY(launch_gemm(d.dtype, EPI_STORE_F32, g, st));
         if (uniforms)
             return launch_sample_rows(logits, d.vocab, d.vocab, K, inv_temp, uniforms + t, out_ids + t, n_new, eos_id, t > 0, st);
-        return launch_argmax_rows(logits, d.vocab, d.vocab, K, out_ids + t, n_new, eos_id, t > 0, st);
+        return launch_argmax_rows(logits, d.vocab, d.vocab, K, base + cs.argmax, out_ids + t, n_new, eos_id, t > 0, st);
     };
 
     // 2. token 0 follows from the last draft row of every branch: row P + j T + len_j - 1 of the tree

@@ -338,51 +338,69 @@ __global__ __launch_bounds__(kDecodeThreads) void attn_decode_pieces_kernel(cons
     }
 }
 
-// ids[j * stride] = first index of the largest logit of row j
-__global__ __launch_bounds__(256) void argmax_rows_kernel(const float* __restrict__ logits, int64_t ld, int V, int32_t* __restrict__ ids,
-                                                          int64_t stride, int eos_id, bool has_prev) {
+// ids[j * stride] = first index of the largest logit of row j, in two launches: kArgmaxChunks workgroups per row each
+// reduce a slice of the vocabulary to (value, index), then one wavefront per row reduces those.  (One workgroup per
+// row cannot pull a row of 150k logits through a single CU fast enough.)
+constexpr int kArgmaxChunks = 32;
+struct ArgmaxPart {
+    float v;
+    int32_t at;
+};
+__device__ __forceinline__ void argmax_take(float& best, int& at, float v, int c) {   // NaN never wins; the first maximum is kept
+    if (v > best || (v == best && c < at)) {
+        best = v;
+        at = c;
+    }
+}
+
+__global__ __launch_bounds__(256) void argmax_partial_kernel(const float* __restrict__ logits, int64_t ld, int V,
+                                                             ArgmaxPart* __restrict__ part) {
     __shared__ float s_val[256];
     __shared__ int s_idx[256];
-    const int j = blockIdx.x;
-    if (eos_id >= 0 && has_prev && ids[(int64_t)j * stride - 1] == eos_id) {      // the branch has ended: it stays ended
-        if (threadIdx.x == 0) ids[(int64_t)j * stride] = eos_id;
-        return;
-    }
+    const int j = blockIdx.x, chunk = blockIdx.y;
     const float* z = logits + (int64_t)j * ld;
+    const int per = (int)((V + kArgmaxChunks * 4 - 1) / (kArgmaxChunks * 4)) * 4;      // columns per chunk, a multiple of 4
+    const int c0 = min(chunk * per, V), c1 = min(c0 + per, V);
     float best = -INFINITY;
     int at = 0x7fffffff;
-    auto consider = [&](float v, int c) {               // NaN never wins; the first maximum is kept
-        if (v > best || (v == best && c < at)) {
-            best = v;
-            at = c;
-        }
-    };
     const bool vec = (reinterpret_cast<uintptr_t>(z) & 15) == 0;
-    const int v4 = vec ? V / 4 : 0;
+    const int q0 = c0 / 4, q1 = vec ? c1 / 4 : q0;                                     // whole float4 groups of the chunk
 #pragma unroll 4
-    for (int c4 = threadIdx.x; c4 < v4; c4 += 256) {
+    for (int c4 = q0 + threadIdx.x; c4 < q1; c4 += 256) {
         const float4 x = reinterpret_cast<const float4*>(z)[c4];
-        consider(x.x, 4 * c4);
-        consider(x.y, 4 * c4 + 1);
-        consider(x.z, 4 * c4 + 2);
-        consider(x.w, 4 * c4 + 3);
+        argmax_take(best, at, x.x, 4 * c4);
+        argmax_take(best, at, x.y, 4 * c4 + 1);
+        argmax_take(best, at, x.z, 4 * c4 + 2);
+        argmax_take(best, at, x.w, 4 * c4 + 3);
     }
-    for (int c = 4 * v4 + threadIdx.x; c < V; c += 256) consider(z[c], c);
+    for (int c = 4 * q1 + threadIdx.x; c < c1; c += 256) argmax_take(best, at, z[c], c);
     s_val[threadIdx.x] = best;
     s_idx[threadIdx.x] = at;
     __syncthreads();
     for (int o = 128; o > 0; o >>= 1) {
-        if ((int)threadIdx.x < o) {
-            const float v = s_val[threadIdx.x + o];
-            const int c = s_idx[threadIdx.x + o];
-            if (v > s_val[threadIdx.x] || (v == s_val[threadIdx.x] && c < s_idx[threadIdx.x])) {
-                s_val[threadIdx.x] = v;
-                s_idx[threadIdx.x] = c;
-            }
-        }
+        if ((int)threadIdx.x < o) argmax_take(s_val[threadIdx.x], s_idx[threadIdx.x], s_val[threadIdx.x + o], s_idx[threadIdx.x + o]);
         __syncthreads();
     }
-    if (threadIdx.x == 0) ids[(int64_t)j * stride] = s_idx[0] == 0x7fffffff ? 0 : s_idx[0];
+    if (threadIdx.x == 0) part[j * kArgmaxChunks + chunk] = ArgmaxPart{s_val[0], s_idx[0]};
+}
+
+__global__ __launch_bounds__(64) void argmax_final_kernel(const ArgmaxPart* __restrict__ part, int32_t* __restrict__ ids, int64_t stride,
+                                                          int eos_id, bool has_prev) {
+    const int j = blockIdx.x, lane = threadIdx.x;
+    if (eos_id >= 0 && has_prev && ids[(int64_t)j * stride - 1] == eos_id) {      // the branch has ended: it stays ended
+        if (lane == 0) ids[(int64_t)j * stride] = eos_id;
+        return;
+    }
+    static_assert(kArgmaxChunks <= 64, "one wavefront reduces the partial results");
+    float best = -INFINITY;
+    int at = 0x7fffffff;
+    if (lane < kArgmaxChunks) {
+        const ArgmaxPart p = part[j * kArgmaxChunks + lane];
+        argmax_take(best, at, p.v, p.at);
+    }
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) argmax_take(best, at, __shfl_xor(best, o), __shfl_xor(at, o));
+    if (lane == 0) ids[(int64_t)j * stride] = at == 0x7fffffff ? 0 : at;
 }
 
 // ids[j * stride] = inverse-CDF sample of softmax(logits[j] * inv_temp) with the uniform u = uniforms[j * stride]:
@@ -542,10 +560,15 @@ int32_t launch_attn_decode(int32_t dtype, const void* q, const void* k_cache, co
     return ATTS_OK;
 }
 
-int32_t launch_argmax_rows(const float* logits, int64_t ld, int32_t V, int32_t rows, int32_t* ids, int64_t stride, int32_t eos_id,
-                           bool has_prev, hipStream_t stream) {
-    hipLaunchKernelGGL(argmax_rows_kernel, dim3(rows), dim3(256), 0, stream, logits, ld, V, ids, stride, eos_id, has_prev);
-    ATTS_LAUNCH_CHECK("argmax_rows_kernel");
+size_t argmax_scratch_bytes(int32_t rows) { return (size_t)rows * kArgmaxChunks * sizeof(ArgmaxPart); }
+
+int32_t launch_argmax_rows(const float* logits, int64_t ld, int32_t V, int32_t rows, void* scratch, int32_t* ids, int64_t stride,
+                           int32_t eos_id, bool has_prev, hipStream_t stream) {
+    ArgmaxPart* part = static_cast<ArgmaxPart*>(scratch);
+    hipLaunchKernelGGL(argmax_partial_kernel, dim3(rows, kArgmaxChunks), dim3(256), 0, stream, logits, ld, V, part);
+    ATTS_LAUNCH_CHECK("argmax_partial_kernel");
+    hipLaunchKernelGGL(argmax_final_kernel, dim3(rows), dim3(64), 0, stream, part, ids, stride, eos_id, has_prev);
+    ATTS_LAUNCH_CHECK("argmax_final_kernel");
     return ATTS_OK;
 }
 
