@@ -37,6 +37,24 @@ def test_gemm_nt_matches_float64_matmul(dtype, shape):
     assert np.allclose(c.cpu().numpy(), ref, rtol=1e-5, atol=2e-5 * math.sqrt(Kd))
 
 
+def test_gemm_few_rows_random_shapes():
+    """Seeded sweep over the shapes the weight-streaming kernel serves (1..16 rows, any column count, inner
+    dimension a multiple of 32 up to several K slices), against the float64 product."""
+    import paper_2509_15148_amd as A
+    rng = np.random.default_rng(2509)
+    for case in range(24):
+        M = int(rng.integers(1, 17))
+        N = int(rng.choice([1, 15, 16, 17, 31, 32, 33, 100, 255, 256, 1000, 3584, 4608]))
+        Kd = 32 * int(rng.choice([1, 2, 3, 7, 8, 9, 16, 17, 63, 112, 129]))
+        announce("gemm few rows", case, (M, N, Kd))
+        a, w = _rand((M, Kd), 100 + case, torch.bfloat16), _rand((N, Kd), 200 + case, torch.bfloat16)
+        c = torch.full((M, N), float("nan"), dtype=torch.float32, device="cuda")
+        A.atts_gemm_nt(a.cuda(), w.cuda(), c)
+        torch.cuda.synchronize()
+        ref = a.double().numpy() @ w.double().numpy().T
+        assert np.allclose(c.cpu().numpy(), ref, rtol=1e-5, atol=2e-5 * math.sqrt(Kd)), (M, N, Kd)
+
+
 def test_gemm_rejects_unaligned_k():
     import paper_2509_15148_amd as A
     a = torch.zeros(4, 12, dtype=torch.bfloat16, device="cuda")
