@@ -59,6 +59,9 @@ def _compare(cfg, w_np, prefix, drafts, got, n_new):
     (ModelConfig(2, 256, 2, 1, 128, 256, 515, "fp32"), 500, 2, 6, 4, None),
     (ModelConfig(2, 256, 4, 2, 64, 512, 2048, "bf16"), 300, 3, 10, 4, None),
     (ModelConfig(2, 256, 4, 2, 128, 512, 2048, "bf16"), 950, 2, 8, 4, None),
+    # more candidates than the 16-row kernel takes: the decoding steps go through the tiled GEMMs
+    (ModelConfig(2, 256, 4, 2, 128, 512, 2048, "bf16"), 20, 20, 4, 3, None),
+    (ModelConfig(2, 96, 4, 1, 24, 200, 515, "fp32"), 6, 18, 3, 3, None),
 ])
 def test_greedy_continuation_matches_the_oracle(cfg, P, K, T, n_new, chunks):
     import paper_2509_15148_amd as A
