@@ -237,12 +237,22 @@ def bench_continuation(A, torch, model, cfg, wl, L, K=4, n_new=16):
         return time.perf_counter() - t0
     t_full, t_one = timed(out), timed(out1)
     per_tok = (t_full - t_one) / (n_new - 1)            # the context pass + first token is common to both
+    u = torch.rand(K, n_new, device="cuda", generator=torch.Generator(device="cuda").manual_seed(wl.seed))
+    def timed_sampled(o, uu):
+        A.atts_continue_sample(pre, d, 1.0, uu, o, ws)
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        A.atts_continue_sample(pre, d, 1.0, uu, o, ws)
+        torch.cuda.synchronize()
+        return time.perf_counter() - t0
+    per_tok_sampled = (timed_sampled(out, u) - timed_sampled(out1, u[:, :1].contiguous())) / (n_new - 1)
     esz = 2 if cfg.dtype == "bf16" else 4
     d_, hd = cfg.d_model, cfg.head_dim
     per_layer = d_ * (cfg.n_q_heads + 2 * cfg.n_kv_heads) * hd + cfg.n_q_heads * hd * d_ + 3 * d_ * cfg.d_ffn
     wbytes = esz * (per_layer * L + cfg.vocab * d_)
     return {"workload": f"{wl.name} model, prefix of {wl.P} cached, {K} candidates x {wl.T}-token drafts continued by {n_new} tokens",
             "context_pass_ms": t_one * 1e3, "ms_per_decode_step": per_tok * 1e3, "generated_tokens_per_s": K / per_tok,
+            "ms_per_decode_step_sampled": per_tok_sampled * 1e3,
             "weight_bytes_per_step": wbytes, "achieved_GBs": wbytes / per_tok / 1e9, "hbm_frac": wbytes / per_tok / 1e9 / HBM_PEAK_GBS}
 
 

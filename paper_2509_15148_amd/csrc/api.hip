@@ -615,7 +615,8 @@ int32_t continue_tokens(const char* fn, const atts_prefix* p, const int32_t* dra
         g.lda = d.d_model; g.ldw = d.d_model; g.ldc = d.vocab; g.a_rows_padded = padded;
         ATTS_TRY(launch_gemm(d.dtype, EPI_STORE_F32, g, st));
         if (uniforms)
-            return launch_sample_rows(logits, d.vocab, d.vocab, K, inv_temp, uniforms + t, out_ids + t, n_new, eos_id, t > 0, st);
+            return launch_sample_rows(logits, d.vocab, d.vocab, K, inv_temp, uniforms + t, base + cs.argmax, out_ids + t, n_new, eos_id,
+                                      t > 0, st);
         return launch_argmax_rows(logits, d.vocab, d.vocab, K, base + cs.argmax, out_ids + t, n_new, eos_id, t > 0, st);
     };
 

@@ -189,12 +189,13 @@ int32_t launch_decode_qkv_finish(int32_t dtype, float* acc, const float2* cs, in
 int32_t launch_attn_decode(int32_t dtype, const void* q, const void* k_cache, const void* v_cache, void* out, int32_t Kr, int32_t P,
                            int32_t Tc, BranchPos pos, int32_t nq, int32_t nkv, int32_t hd, hipStream_t stream);
 // eos_id >= 0 and has_prev: a row whose previous token (ids[j stride - 1]) is eos_id gets eos_id again
-// scratch: argmax_scratch_bytes(rows) bytes (per-slice results of the first of the two launches)
+// scratch: argmax_scratch_bytes(rows) bytes (per-slice results of the first of the two launches; launch_sample_rows
+// takes the same)
 size_t argmax_scratch_bytes(int32_t rows);
 int32_t launch_argmax_rows(const float* logits, int64_t ld, int32_t V, int32_t rows, void* scratch, int32_t* ids, int64_t stride,
                            int32_t eos_id, bool has_prev, hipStream_t stream);
 int32_t launch_sample_rows(const float* logits, int64_t ld, int32_t V, int32_t rows, float inv_temp, const float* uniforms,
-                           int32_t* ids, int64_t stride, int32_t eos_id, bool has_prev, hipStream_t stream);
+                           void* scratch, int32_t* ids, int64_t stride, int32_t eos_id, bool has_prev, hipStream_t stream);
 // xs[j] = rmsnorm(h[first + j step + pos.at(j)])
 int32_t launch_norm_strided_rows(int32_t dtype, const float* h, const float* gain, float eps, int32_t d, int64_t first, int64_t step,
                                  BranchPos pos, int32_t rows, void* xs, hipStream_t stream);

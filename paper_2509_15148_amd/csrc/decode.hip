@@ -404,63 +404,125 @@ __global__ __launch_bounds__(64) void argmax_final_kernel(const ArgmaxPart* __re
 }
 
 // ids[j * stride] = inverse-CDF sample of softmax(logits[j] * inv_temp) with the uniform u = uniforms[j * stride]:
-// the first index v (vocabulary order) whose cumulative weight reaches u times the total.  Every thread owns a
-// contiguous chunk of the row; chunk sums are scanned in index order by one thread, then the owner of the chunk the
-// target falls into walks it.  Sums in fp32, fixed order.
-constexpr int kSampleThreads = 1024;
+// the first index v (vocabulary order) whose cumulative weight reaches u times the total.  Two launches, like the
+// arg max: kArgmaxChunks workgroups per row reduce a contiguous slice of the vocabulary to (slice maximum m_c,
+// S_c = sum exp((z - m_c) inv_temp)); then one workgroup per row puts the slices on the row maximum, finds the slice
+// the target falls into by adding the slice weights in index order, gives each thread a contiguous piece of that
+// slice, finds the piece the same way and walks it.  Sums in fp32, fixed order.
+struct SamplePart {
+    float m, s;
+};
+constexpr int kSampleThreads = 256;
 
-__global__ __launch_bounds__(kSampleThreads) void sample_rows_kernel(const float* __restrict__ logits, int64_t ld, int V,
-                                                                     float inv_temp, const float* __restrict__ uniforms,
-                                                                     int32_t* __restrict__ ids, int64_t stride, int eos_id,
-                                                                     bool has_prev) {
-    __shared__ float red[kSampleThreads / 64];
-    __shared__ float chunk_sum[kSampleThreads];
-    __shared__ float s_target, s_before;
-    __shared__ int s_chunk;
+__device__ __forceinline__ int sample_slice_len(int V) { return (int)((V + kArgmaxChunks * 4 - 1) / (kArgmaxChunks * 4)) * 4; }
+
+__global__ __launch_bounds__(256) void sample_partial_kernel(const float* __restrict__ logits, int64_t ld, int V, float inv_temp,
+                                                             SamplePart* __restrict__ part) {
+    __shared__ float red[4];
+    const int j = blockIdx.x, chunk = blockIdx.y, tid = threadIdx.x;
+    const float* z = logits + (int64_t)j * ld;
+    const int per = sample_slice_len(V);
+    const int c0 = min(chunk * per, V), c1 = min(c0 + per, V);
+    float mx = -INFINITY;
+    for (int c = c0 + tid; c < c1; c += 256) mx = fmaxf(mx, z[c]);
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) mx = fmaxf(mx, __shfl_xor(mx, o));
+    if ((tid & 63) == 0) red[tid >> 6] = mx;
+    __syncthreads();
+    mx = fmaxf(fmaxf(red[0], red[1]), fmaxf(red[2], red[3]));
+    __syncthreads();
+    float sum = 0.f;
+    for (int c = c0 + tid; c < c1; c += 256) sum += __expf((z[c] - mx) * inv_temp);
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) sum += __shfl_xor(sum, o);
+    if ((tid & 63) == 0) red[tid >> 6] = sum;
+    __syncthreads();
+    if (tid == 0) part[j * kArgmaxChunks + chunk] = SamplePart{mx, red[0] + red[1] + red[2] + red[3]};   // empty slice: (-inf, 0)
+}
+
+__global__ __launch_bounds__(kSampleThreads) void sample_final_kernel(const float* __restrict__ logits, int64_t ld, int V, float inv_temp,
+                                                                      const SamplePart* __restrict__ part,
+                                                                      const float* __restrict__ uniforms, int32_t* __restrict__ ids,
+                                                                      int64_t stride, int eos_id, bool has_prev) {
+    __shared__ float piece_sum[kSampleThreads];
+    __shared__ float s_top, s_target, s_before;
+    __shared__ int s_chunk, s_piece;
     const int j = blockIdx.x, tid = threadIdx.x;
     if (eos_id >= 0 && has_prev && ids[(int64_t)j * stride - 1] == eos_id) {      // the branch has ended: it stays ended
         if (tid == 0) ids[(int64_t)j * stride] = eos_id;
         return;
     }
     const float* z = logits + (int64_t)j * ld;
-    const int per = (V + kSampleThreads - 1) / kSampleThreads;
-    const int c0 = min(tid * per, V), c1 = min(c0 + per, V);
-    float mx = -INFINITY;
-    for (int c = c0; c < c1; ++c) mx = fmaxf(mx, z[c]);
-#pragma unroll
-    for (int o = 32; o > 0; o >>= 1) mx = fmaxf(mx, __shfl_xor(mx, o));
-    if ((tid & 63) == 0) red[tid >> 6] = mx;
-    __syncthreads();
-    mx = red[0];
-#pragma unroll
-    for (int w = 1; w < kSampleThreads / 64; ++w) mx = fmaxf(mx, red[w]);
-    float sum = 0.f;
-    for (int c = c0; c < c1; ++c) sum += __expf((z[c] - mx) * inv_temp);
-    chunk_sum[tid] = sum;
-    __syncthreads();
     if (tid == 0) {
-        float total = 0.f;
-        for (int t = 0; t < kSampleThreads; ++t) total += chunk_sum[t];
+        const SamplePart* p = part + j * kArgmaxChunks;
+        float top = -INFINITY;
+        for (int c = 0; c < kArgmaxChunks; ++c) top = fmaxf(top, p[c].m);
+        float w[kArgmaxChunks], total = 0.f;
+        for (int c = 0; c < kArgmaxChunks; ++c) {
+            w[c] = p[c].s > 0.f ? p[c].s * __expf((p[c].m - top) * inv_temp) : 0.f;
+            total += w[c];
+        }
         const float target = uniforms[(int64_t)j * stride] * total;
         float before = 0.f;
-        int chunk = kSampleThreads - 1;
-        for (int t = 0; t < kSampleThreads; ++t) {
-            if (before + chunk_sum[t] >= target && chunk_sum[t] > 0.f) {
-                chunk = t;
-                break;
+        int chunk = -1, last_mass = 0;
+        for (int c = 0; c < kArgmaxChunks; ++c) {
+            if (w[c] > 0.f) {
+                last_mass = c;
+                if (before + w[c] >= target) {
+                    chunk = c;
+                    break;
+                }
             }
-            before += chunk_sum[t];
+            before += w[c];
         }
+        if (chunk < 0) {                                 // rounding left the target just past the end: the last slice with mass
+            chunk = last_mass;
+            before = 0.f;
+            for (int c = 0; c < chunk; ++c) before += w[c];
+        }
+        s_top = top;
         s_target = target;
         s_before = before;
         s_chunk = chunk;
     }
     __syncthreads();
-    if (tid == s_chunk) {
+    // the slice, cut into one contiguous piece per thread
+    const int per = sample_slice_len(V);
+    const int c0 = min(s_chunk * per, V), c1 = min(c0 + per, V);
+    const int piece = (c1 - c0 + kSampleThreads - 1) / kSampleThreads;
+    const int q0 = min(c0 + tid * piece, c1), q1 = min(q0 + piece, c1);
+    const float top = s_top;
+    float sum = 0.f;
+    for (int c = q0; c < q1; ++c) sum += __expf((z[c] - top) * inv_temp);
+    piece_sum[tid] = sum;
+    __syncthreads();
+    if (tid == 0) {
+        float before = s_before;
+        int pick = -1, last_mass = 0;
+        for (int t = 0; t < kSampleThreads; ++t) {
+            if (piece_sum[t] > 0.f) {
+                last_mass = t;
+                if (before + piece_sum[t] >= s_target) {
+                    pick = t;
+                    break;
+                }
+            }
+            before += piece_sum[t];
+        }
+        if (pick < 0) {
+            pick = last_mass;
+            before = s_before;
+            for (int t = 0; t < pick; ++t) before += piece_sum[t];
+        }
+        s_piece = pick;
+        s_before = before;
+    }
+    __syncthreads();
+    if (tid == s_piece) {
         float run = s_before;
         int pick = -1, last_mass = -1;
-        for (int c = c0; c < c1; ++c) {
-            const float e = __expf((z[c] - mx) * inv_temp);
+        for (int c = q0; c < q1; ++c) {
+            const float e = __expf((z[c] - top) * inv_temp);
             run += e;
             if (e > 0.f) last_mass = c;
             if (run >= s_target) {
@@ -468,7 +530,7 @@ __global__ __launch_bounds__(kSampleThreads) void sample_rows_kernel(const float
                 break;
             }
         }
-        if (pick < 0) pick = last_mass >= 0 ? last_mass : (c1 > c0 ? c1 - 1 : V - 1);   // rounding left the target just past the chunk
+        if (pick < 0) pick = last_mass >= 0 ? last_mass : (q1 > q0 ? q1 - 1 : V - 1);   // rounding left the target just past the piece
         ids[(int64_t)j * stride] = pick;
     }
 }
@@ -573,10 +635,14 @@ int32_t launch_argmax_rows(const float* logits, int64_t ld, int32_t V, int32_t r
 }
 
 int32_t launch_sample_rows(const float* logits, int64_t ld, int32_t V, int32_t rows, float inv_temp, const float* uniforms,
-                           int32_t* ids, int64_t stride, int32_t eos_id, bool has_prev, hipStream_t stream) {
-    hipLaunchKernelGGL(sample_rows_kernel, dim3(rows), dim3(kSampleThreads), 0, stream, logits, ld, V, inv_temp, uniforms, ids, stride,
-                       eos_id, has_prev);
-    ATTS_LAUNCH_CHECK("sample_rows_kernel");
+                           void* scratch, int32_t* ids, int64_t stride, int32_t eos_id, bool has_prev, hipStream_t stream) {
+    static_assert(sizeof(SamplePart) == sizeof(ArgmaxPart), "both selections use the same per-slice scratch");
+    SamplePart* part = static_cast<SamplePart*>(scratch);
+    hipLaunchKernelGGL(sample_partial_kernel, dim3(rows, kArgmaxChunks), dim3(256), 0, stream, logits, ld, V, inv_temp, part);
+    ATTS_LAUNCH_CHECK("sample_partial_kernel");
+    hipLaunchKernelGGL(sample_final_kernel, dim3(rows), dim3(kSampleThreads), 0, stream, logits, ld, V, inv_temp, part, uniforms, ids,
+                       stride, eos_id, has_prev);
+    ATTS_LAUNCH_CHECK("sample_final_kernel");
     return ATTS_OK;
 }
 

@@ -142,8 +142,27 @@ def test_7b_width_continuation():
     model = A.Model(cfg, w_dev)
     got, _ = _continue(A, model, prefix, drafts, n_new)
     assert got.min() >= 0 and got.max() < cfg.vocab
-    agree = _compare(cfg, weights_to_numpy(w_dev), prefix, drafts, got, n_new)
+    w_np = weights_to_numpy(w_dev)
+    agree = _compare(cfg, w_np, prefix, drafts, got, n_new)
     assert agree >= 1
+    # sampling over the same vocabulary, at a temperature low enough for the distribution to have wide CDF intervals
+    pre = A.Prefix(model, capacity=P)
+    A.atts_prefix_extend(pre, dev(prefix), ws(A.atts_prefix_extend_workspace_bytes(pre, P)))
+    temperature = 0.02
+    u = np.random.default_rng(7).random((K, n_new)).astype(np.float32)
+    out = torch.full((K, n_new), -1, dtype=torch.int32, device="cuda")
+    A.atts_continue_sample(pre, dev(drafts), temperature, dev(u), out, ws(A.atts_continue_workspace_bytes(pre, K, T, n_new)))
+    torch.cuda.synchronize()
+    got_s = out.cpu().numpy()
+    assert got_s.min() >= 0 and got_s.max() < cfg.vocab
+    for k in range(K):
+        ref, slack = O.sampled_continuation(w_np, cfg, prefix, drafts[k], u[k].astype(np.float64), temperature)
+        for t in range(n_new):
+            if got_s[k, t] != ref[t]:
+                # logits move by a few 1e-2 in bf16, i.e. by O(1) after division by the temperature: the draw must
+                # at least have been close to a boundary of the oracle's interval
+                assert slack[t] <= 0.35, (k, t, got_s[k, t], ref[t], slack[t])
+                break
 
 
 def test_continuation_argument_errors():
