@@ -194,7 +194,10 @@ int32_t atts_score_drafts_cached(const atts_prefix* prefix, const int32_t* draft
  *               < 0: no such token
  *   out_ids     dev int32 [K, n_new] row-major
  *   workspace   dev, 256-byte aligned, >= atts_continue_workspace_bytes(prefix, K, T, n_new) bytes; scratch
- * 1 <= K <= 768, T >= 1, n_new >= 1, length + T + n_new <= 1048576.  Out-of-range ids as in atts_score_drafts. */
+ * 1 <= K <= 768, T >= 1, n_new >= 1, length + T + n_new <= 1048576.  Out-of-range ids as in atts_score_drafts.
+ * When a head's row (head_dim elements of the model dtype) is not a power-of-two number of 16-byte pieces, the
+ * decoding steps use a general attention kernel that holds one score per key in LDS: contexts beyond about 13,000
+ * keys are then refused with ATTS_ERR_SHAPE. */
 int32_t atts_continue_workspace_bytes(const atts_prefix* prefix, int32_t K, int32_t T, int32_t n_new, size_t* out_bytes);
 int32_t atts_continue_greedy(const atts_prefix* prefix, const int32_t* draft_ids, const int32_t* draft_lens, int32_t K, int32_t T,
                              int32_t n_new, int32_t eos_id, int32_t* out_ids, void* workspace, size_t workspace_bytes,
