@@ -561,7 +561,7 @@ __global__ __launch_bounds__(128 * kWavesM) void gemm_bf16_fast_kernel(const cha
 // a 384 x 256 tile.  A slab is four MFMA k-steps; the DMA of the following slabs is issued under the first two,
 // one wait + barrier per slab at its end.
 // ---------------------------------------------------------------------------------------------
-template <int EPI, int kWavesM, int MI>
+template <int EPI, int kWavesM, int MI, int NI = 4 /* 32-column blocks per wave: 4 = 256-column tiles, 2 = 128-column tiles */>
 __global__ __launch_bounds__(128 * kWavesM) void gemm_bf16_wide_kernel(const char* __restrict__ gA,
                                                                        const char* __restrict__ gW,
                                                                        void* __restrict__ g_out,
@@ -570,7 +570,7 @@ __global__ __launch_bounds__(128 * kWavesM) void gemm_bf16_wide_kernel(const cha
                                                                        float* __restrict__ g_target_logit,
                                                                        const float2* __restrict__ g_rope,
                                                                        void* __restrict__ g_vt, const GemmDims g) {
-    constexpr int BN = 256, NI = 4, WN = 128;
+    constexpr int WN = 32 * NI, BN = 2 * WN;
     constexpr int WM = 32 * MI, BM = kWavesM * WM;
     constexpr int kWaves = 2 * kWavesM;
     constexpr int N_OUT = (EPI == EPI_SWIGLU) ? BN / 2 : BN;
@@ -873,9 +873,9 @@ int32_t launch_fast_tile(const GemmArgs& g, hipStream_t stream) {
 #define ATTS_GEMM_WIDE 1
 #endif
 
-template <int EPI, int MI>
+template <int EPI, int MI, int NI = 4>
 int32_t launch_wide_tile(const GemmArgs& g, hipStream_t stream) {
-    constexpr int n_out = (EPI == EPI_SWIGLU) ? 128 : 256;
+    constexpr int n_out = (EPI == EPI_SWIGLU) ? 32 * NI : 64 * NI;
     constexpr int kWavesM = ATTS_FAST_WAVES_M;
     constexpr int BM = kWavesM * MI * 32;
     GemmDims d;
@@ -888,7 +888,7 @@ int32_t launch_wide_tile(const GemmArgs& g, hipStream_t stream) {
     d.nt_n = g.N / n_out;
     d.k_slices = fast_k_slices(EPI, d.nt_m * d.nt_n, g.Kd / 64);
     const size_t lds = 160 * 1024;
-    auto kern = gemm_bf16_wide_kernel<EPI, kWavesM, MI>;
+    auto kern = gemm_bf16_wide_kernel<EPI, kWavesM, MI, NI>;
     static bool attr_set = false;   // per instantiation
     if (!attr_set) {
         ATTS_HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
@@ -906,7 +906,11 @@ template <int EPI>
 int32_t launch_fast(const GemmArgs& g, hipStream_t stream) {
     constexpr int kWavesM = ATTS_FAST_WAVES_M;
     const bool wide = ATTS_GEMM_WIDE && g.Kd % 64 == 0 && g.Kd >= 12 * 64;
-    if (fast_tile_rows(EPI, g) == 128 && wide && kWavesM == 4) return launch_wide_tile<EPI, 1>(g, stream);
+    if (fast_tile_rows(EPI, g) == 128 && wide && kWavesM == 4) {
+        // narrow outputs that split K: 128-column tiles double the tiles, so half as many K slices (and atomics) fill the chip
+        if constexpr (EPI == EPI_RESID_F32) return launch_wide_tile<EPI, 1, 2>(g, stream);
+        return launch_wide_tile<EPI, 1>(g, stream);
+    }
     if (fast_tile_rows(EPI, g) == 384)
         return wide ? launch_wide_tile<EPI, 12 / kWavesM>(g, stream) : launch_fast_tile<EPI, 12 / kWavesM>(g, stream);
     return wide ? launch_wide_tile<EPI, 8 / kWavesM>(g, stream) : launch_fast_tile<EPI, 8 / kWavesM>(g, stream);
@@ -1013,7 +1017,7 @@ bool gemm_splits_k(int32_t dtype, int32_t M, int32_t N, int32_t Kd, bool a_rows_
     if (gemm_skinny_ok(dtype, EPI_RESID_F32, g)) return true;     // always the accumulating form
     if (!fast_path_ok(dtype, EPI_RESID_F32, g)) return false;
     const int bm = fast_tile_rows(EPI_RESID_F32, g);
-    const int64_t tiles = ceil_div(M, bm) * (N / 256);
+    const int64_t tiles = ceil_div(M, bm) * (N / (bm == 128 ? 128 : 256));
     return fast_k_slices(EPI_RESID_F32, (int)tiles, Kd / 64) > 1;
 }
 
