@@ -444,7 +444,7 @@ __global__ __launch_bounds__(kSampleThreads) void sample_final_kernel(const floa
                                                                       const SamplePart* __restrict__ part,
                                                                       const float* __restrict__ uniforms, int32_t* __restrict__ ids,
                                                                       int64_t stride, int eos_id, bool has_prev) {
-    __shared__ float piece_sum[kSampleThreads];
+    __shared__ float piece_sum[kSampleThreads], group_sum[kSampleThreads / 16];
     __shared__ float s_top, s_target, s_before;
     __shared__ int s_chunk, s_piece;
     const int j = blockIdx.x, tid = threadIdx.x;
@@ -496,24 +496,39 @@ __global__ __launch_bounds__(kSampleThreads) void sample_final_kernel(const floa
     for (int c = q0; c < q1; ++c) sum += __expf((z[c] - top) * inv_temp);
     piece_sum[tid] = sum;
     __syncthreads();
+    // pieces are added in index order in two levels (16 groups of 16, then the groups): 48 dependent steps, not 256
+    constexpr int kGroup = 16, kGroups = kSampleThreads / kGroup;
+    if (tid < kGroups) {
+        float gs = 0.f;
+        for (int t = 0; t < kGroup; ++t) gs += piece_sum[tid * kGroup + t];
+        group_sum[tid] = gs;
+    }
+    __syncthreads();
     if (tid == 0) {
-        float before = s_before;
-        int pick = -1, last_mass = 0;
-        for (int t = 0; t < kSampleThreads; ++t) {
-            if (piece_sum[t] > 0.f) {
-                last_mass = t;
-                if (before + piece_sum[t] >= s_target) {
-                    pick = t;
-                    break;
+        // first unit (group, then piece) with mass whose running total reaches the target; else the last one with mass
+        auto locate = [&](const float* w, int n, float& before) {
+            const float start = before;
+            int pick = -1, last_mass = 0;
+            for (int t = 0; t < n; ++t) {
+                if (w[t] > 0.f) {
+                    last_mass = t;
+                    if (before + w[t] >= s_target) {
+                        pick = t;
+                        break;
+                    }
                 }
+                before += w[t];
             }
-            before += piece_sum[t];
-        }
-        if (pick < 0) {
-            pick = last_mass;
-            before = s_before;
-            for (int t = 0; t < pick; ++t) before += piece_sum[t];
-        }
+            if (pick < 0) {
+                pick = last_mass;
+                before = start;
+                for (int t = 0; t < pick; ++t) before += w[t];
+            }
+            return pick;
+        };
+        float before = s_before;
+        const int grp = locate(group_sum, kGroups, before);
+        const int pick = grp * kGroup + locate(piece_sum + grp * kGroup, kGroup, before);
         s_piece = pick;
         s_before = before;
     }
