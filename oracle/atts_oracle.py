@@ -182,6 +182,16 @@ def greedy_continuation(weights, cfg, prefix_ids, draft_ids, n_new: int, eos_id=
     return np.asarray(toks, dtype=np.int64), np.asarray(margins, dtype=F64)
 
 
+def next_token_cdf(weights, cfg, context_ids, temperature: float) -> np.ndarray:
+    """Cumulative distribution, in vocabulary order, of the target's next token after `context_ids` under
+    softmax(logits / temperature) (paragraph "Target Model Sampling"): cdf[v] = P(token <= v), cdf[-1] = 1.
+    Token v owns the interval (cdf[v - 1], cdf[v]] of a uniform draw (cdf[-1] read as 0)."""
+    h = decoder_hidden(weights, cfg, np.asarray(context_ids, dtype=np.int64))
+    z = logits_from_hidden(weights, cfg, h[-1:])[0] / float(temperature)
+    c = np.cumsum(np.exp(z - z.max()))
+    return c / c[-1]
+
+
 def sampled_continuation(weights, cfg, prefix_ids, draft_ids, uniforms, temperature: float, eos_id=None):
     """Target-model continuation by sampling (paragraph "Target Model Sampling"): token t is drawn from
     softmax(logits / temperature) of the target given everything before it.  The randomness is an input: with

@@ -85,6 +85,47 @@ def test_greedy_continuation_matches_the_oracle(cfg, P, K, T, n_new, chunks):
 SLACK = {"fp32": 2e-4, "bf16": 0.05}        # how close (in probability) a draw may be to a CDF boundary for the tokens to differ
 
 
+def _check_sampled(cfg, w_np, prefix, draft, u_row, temperature, got_row, tol, eos_id=None):
+    """One candidate's sampled tokens against the oracle's chain for the same draws.  Returns the number of leading
+    tokens that agree.  At the first token that differs, the GPU's token must be one the draw could have picked
+    within the arithmetic's accuracy: the interval (cdf[v - 1], cdf[v]] that the ORACLE's distribution gives the
+    GPU's token v must lie within `tol` (in probability) of the draw; the rest of the candidate is then not
+    compared (its context differs)."""
+    ref, _ = O.sampled_continuation(w_np, cfg, prefix, draft, np.asarray(u_row, dtype=np.float64), temperature, eos_id=eos_id)
+    for t in range(len(ref)):
+        if int(got_row[t]) == int(ref[t]):
+            continue
+        cdf = O.next_token_cdf(w_np, cfg, np.concatenate([prefix, draft, ref[:t]]), temperature)
+        v, u = int(got_row[t]), float(u_row[t])
+        lo, hi = (cdf[v - 1] if v > 0 else 0.0), cdf[v]
+        dist = max(lo - u, u - hi, 0.0)
+        assert dist <= tol, (t, v, int(ref[t]), u, lo, hi, dist)
+        return t
+    return len(ref)
+
+
+def _guided_uniforms(cfg, w_np, prefix, draft, n_new, temperature, rng):
+    """Draws for one candidate chosen with the oracle so that most of them are clear decisions: at every step the
+    draw is the midpoint of the CDF interval of one of the oracle's most probable tokens (picked at random among
+    those that hold at least a fifth of the largest mass), rounded to fp32; the chain then follows the oracle's
+    own choice for that draw.  Every other step keeps a plain uniform draw instead."""
+    us, ctx = [], np.concatenate([prefix, draft])
+    for t in range(n_new):
+        cdf = O.next_token_cdf(w_np, cfg, ctx, temperature)
+        mass = np.diff(np.concatenate([[0.0], cdf]))
+        if t % 2 == 0:
+            big = np.flatnonzero(mass >= 0.2 * mass.max())
+            v = int(big[rng.integers(len(big))])
+            u = np.float32((cdf[v] - 0.5 * mass[v]))
+        else:
+            u = np.float32(rng.random())
+        u = float(min(u, np.float32(1.0 - 2.0 ** -24)))
+        v = min(int(np.searchsorted(cdf, u, side="left")), len(cdf) - 1)
+        us.append(u)
+        ctx = np.concatenate([ctx, [v]])
+    return np.asarray(us, dtype=np.float32)
+
+
 @pytest.mark.parametrize("cfg,P,K,T,n_new,temperature", [
     (WORKLOADS["tiny"].model, 24, 3, 9, 6, 1.0),
     (ModelConfig(2, 96, 4, 1, 24, 200, 515, "fp32"), 7, 4, 5, 5, 0.7),
@@ -110,14 +151,7 @@ def test_sampled_continuation_matches_the_oracle(cfg, P, K, T, n_new, temperatur
     got = out.cpu().numpy()
     assert got.min() >= 0 and got.max() < cfg.vocab
     w_np = weights_to_numpy(w_dev)
-    agree = 0
-    for k in range(K):
-        ref, slack = O.sampled_continuation(w_np, cfg, prefix, drafts[k], u[k].astype(np.float64), temperature)
-        for t in range(n_new):
-            if got[k, t] != ref[t]:
-                assert slack[t] <= SLACK[cfg.dtype] and abs(int(got[k, t]) - int(ref[t])) >= 1, (k, t, got[k, t], ref[t], slack[t])
-                break
-            agree += 1
+    agree = sum(_check_sampled(cfg, w_np, prefix, drafts[k], u[k], temperature, got[k], SLACK[cfg.dtype]) for k in range(K))
     assert agree >= K * n_new // 2
     # different uniforms give different continuations (the draws are really used)
     out2 = torch.empty_like(out)
@@ -144,25 +178,47 @@ def test_7b_width_continuation():
     assert got.min() >= 0 and got.max() < cfg.vocab
     w_np = weights_to_numpy(w_dev)
     agree = _compare(cfg, w_np, prefix, drafts, got, n_new)
-    assert agree >= 1
-    # sampling over the same vocabulary, at a temperature low enough for the distribution to have wide CDF intervals
+    assert agree >= K * n_new // 2
+    # sampling over the same vocabulary.  With 152,064 tokens of O(1) logits a plain draw at temperature 1 lands in
+    # an interval 1e-5 wide, which no bf16 model can resolve; at temperature 0.1 the few most probable tokens hold most of
+    # the mass, and the draws are chosen with the oracle (midpoints of wide intervals, alternating with plain
+    # uniforms) so that most decisions are clear.  A token that differs must still be one the draw could have
+    # picked within the bf16 accuracy.
     pre = A.Prefix(model, capacity=P)
     A.atts_prefix_extend(pre, dev(prefix), ws(A.atts_prefix_extend_workspace_bytes(pre, P)))
-    temperature = 0.02
-    u = np.random.default_rng(7).random((K, n_new)).astype(np.float32)
+    temperature = 0.1
+    rng = np.random.default_rng(7)
+    u = np.stack([_guided_uniforms(cfg, w_np, prefix, drafts[k], n_new, temperature, rng) for k in range(K)])
     out = torch.full((K, n_new), -1, dtype=torch.int32, device="cuda")
     A.atts_continue_sample(pre, dev(drafts), temperature, dev(u), out, ws(A.atts_continue_workspace_bytes(pre, K, T, n_new)))
     torch.cuda.synchronize()
     got_s = out.cpu().numpy()
     assert got_s.min() >= 0 and got_s.max() < cfg.vocab
-    for k in range(K):
-        ref, slack = O.sampled_continuation(w_np, cfg, prefix, drafts[k], u[k].astype(np.float64), temperature)
-        for t in range(n_new):
-            if got_s[k, t] != ref[t]:
-                # logits move by a few 1e-2 in bf16, i.e. by O(1) after division by the temperature: the draw must
-                # at least have been close to a boundary of the oracle's interval
-                assert slack[t] <= 0.35, (k, t, got_s[k, t], ref[t], slack[t])
-                break
+    agree_s = sum(_check_sampled(cfg, w_np, prefix, drafts[k], u[k], temperature, got_s[k], SLACK["bf16"]) for k in range(K))
+    assert agree_s >= K * n_new // 2, (agree_s, got_s)
+
+
+@pytest.mark.timeout(900)
+def test_7b_width_continuation_at_the_benchmark_shape():
+    """The continuation leg bench.py times: 7B width (two layers), a 512-token prefix cached, 4 rejected candidates
+    with 256-token drafts, 4 new tokens each (context pass over 1024 draft rows, then three decoding steps of 4
+    rows).  The oracle runs every candidate as its own plain causal sequence."""
+    import paper_2509_15148_amd as A
+    wl = WORKLOADS["7b"]
+    cfg = wl.model
+    P, K, T, n_new = wl.P, 4, wl.T, 4
+    announce("continue greedy 7b width, benchmark shape", P, K, T, n_new)
+    w_dev = make_weights(cfg, wl.seed, device="cuda", n_layers=2)
+    prefix, drafts = [x.numpy() for x in make_token_ids(cfg.vocab, P, K, T, wl.seed + 700001)]
+    model = A.Model(cfg, w_dev)
+    got, _ = _continue(A, model, prefix, drafts, n_new)
+    assert got.min() >= 0 and got.max() < cfg.vocab and A.atts_model_check(model) == 0
+    w_np = weights_to_numpy(w_dev)
+    del w_dev, model
+    torch.cuda.empty_cache()
+    agree = _compare(cfg, w_np, prefix, drafts, got, n_new)
+    print(f"[continue 7b bench shape] {agree} of {K * n_new} decisions equal", flush=True)
+    assert agree >= K * n_new // 2
 
 
 def test_continuation_argument_errors():
@@ -255,8 +311,4 @@ def test_ragged_drafts_and_end_of_sequence(cfg, P, T, lens, n_new):
     if got_se[K - 1, 0] == eos_s:
         assert np.all(got_se[K - 1] == eos_s)
     for k, n in enumerate(lens):
-        ref, slack = O.sampled_continuation(w_np, cfg, prefix, drafts[k, :n], u[k].astype(np.float64), 1.0, eos_id=eos_s)
-        for t in range(n_new):
-            if got_se[k, t] != ref[t]:
-                assert slack[t] <= SLACK[cfg.dtype], (k, t, got_se[k, t], ref[t], slack[t])
-                break
+        _check_sampled(cfg, w_np, prefix, drafts[k, :n], u[k], 1.0, got_se[k], SLACK[cfg.dtype], eos_id=eos_s)

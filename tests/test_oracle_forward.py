@@ -269,6 +269,27 @@ def test_sampled_continuation_follows_the_scored_distribution():
     assert O.sampled_continuation(w, cfg, prefix, draft, [1.0 - 1e-16], 1.0)[0][0] == cfg.vocab - 1
 
 
+def test_next_token_cdf_is_the_running_sum_of_the_scored_distribution():
+    """The CDF helper against token_logprobs (not against its own softmax): its increments are the probabilities the
+    scoring path assigns, at temperature tau they are proportional to p^(1/tau), and the token sampled_continuation
+    draws for u is the one whose interval (cdf[v - 1], cdf[v]] holds u."""
+    cfg = ModelConfig(1, 32, 2, 1, 16, 48, 11, "fp32")
+    w = weights_to_numpy(make_weights(cfg, seed=3, device="cpu"))
+    prefix = np.array([1, 2, 3, 4]); draft = np.array([5, 6])
+    ctx = np.concatenate([prefix, draft])
+    p = np.exp([O.token_logprobs(w, cfg, ctx, np.array([v]))[0] for v in range(cfg.vocab)])
+    cdf = O.next_token_cdf(w, cfg, ctx, 1.0)
+    assert cdf.shape == (cfg.vocab,) and abs(cdf[-1] - 1.0) < 1e-15 and np.all(np.diff(cdf) > 0)
+    assert np.abs(np.diff(np.concatenate([[0.0], cdf])) - p).max() < 1e-12
+    tau = 0.37
+    q = p ** (1.0 / tau)
+    assert np.abs(np.diff(np.concatenate([[0.0], O.next_token_cdf(w, cfg, ctx, tau)])) - q / q.sum()).max() < 1e-12
+    for u in (0.0, 0.013, 0.25, 0.5, 0.77, 0.999):
+        v = int(O.sampled_continuation(w, cfg, prefix, draft, [u], 1.0)[0][0])
+        lo = cdf[v - 1] if v > 0 else 0.0
+        assert (lo < u <= cdf[v]) or (u == 0.0 and v == 0)
+
+
 def test_end_of_sequence_freezes_a_continuation():
     """With an end token the chain is the unconstrained chain up to and including the first occurrence of that token
     and the token itself afterwards; a token that never occurs changes nothing."""
