@@ -228,6 +228,17 @@ int32_t atts_lmhead_logprobs(int32_t dtype, const void* x, const void* w, const 
                              int32_t B, int32_t d, int32_t V, float* logprobs,
                              void* workspace, size_t workspace_bytes, void* hip_stream);
 
+/* atts_lmhead_logprobs for callers that cannot allocate device memory or bring a workspace (code under HIP graph
+ * capture, tight serving loops, harnesses that forbid hipMalloc): same arguments without the workspace, same kernels,
+ * same results bit for bit.  The per-row partials live in a 16 MiB device array that is part of the library's code
+ * object (every GPU the library runs on holds its own copy until the process ends); the call allocates nothing.
+ * Limit: atts_lmhead_workspace_bytes(B, V) <= 16 MiB (about 880 rows at a 152,064-token vocabulary, 134,000 rows at
+ * 1,000 tokens); beyond it ATTS_ERR_WORKSPACE is returned before anything is enqueued.  Every call on one GPU uses
+ * that GPU's one array: calls that overlap in time on the same GPU (different streams or threads) race; order
+ * them.  Nothing in the array has to be cleared between calls (every partial a call reads it has written). */
+int32_t atts_lmhead_logprobs_static(int32_t dtype, const void* x, const void* w, const int32_t* targets,
+                                    int32_t B, int32_t d, int32_t V, float* logprobs, void* hip_stream);
+
 /* C[M, N] (fp32) = A[M, Kdim] . W[N, Kdim]^T  -- the MFMA GEMM every projection uses
  * (scoring is the compute-bound part of the method, Sec. "Q1").  Kdim * sizeof(dtype) must
  * be a multiple of 16 bytes. */

@@ -28,6 +28,7 @@ EXPORTS = (
     "atts_score_drafts", "atts_model_check", "atts_prefix_create", "atts_prefix_destroy", "atts_prefix_length",
     "atts_prefix_reset", "atts_prefix_extend_workspace_bytes", "atts_prefix_extend", "atts_score_drafts_cached",
     "atts_continue_workspace_bytes", "atts_continue_greedy", "atts_continue_sample", "atts_lmhead_workspace_bytes", "atts_lmhead_logprobs",
+    "atts_lmhead_logprobs_static",
     "atts_gemm_nt", "atts_attention_workspace_bytes", "atts_attention_shared_prefix",
     "atts_calib_create", "atts_calib_destroy", "atts_calib_size", "atts_calib_reset",
     "atts_calibrate_online", "atts_classify_ordinal", "atts_classify_conditional", "atts_calib_export",
@@ -274,6 +275,16 @@ def atts_lmhead_logprobs(x: torch.Tensor, w: torch.Tensor, targets: torch.Tensor
                                      _ptr(logprobs, torch.float32, "logprobs"),
                                      _ptr(workspace, torch.uint8, "workspace"), ctypes.c_size_t(workspace.numel()),
                                      _stream()))
+
+
+def atts_lmhead_logprobs_static(x: torch.Tensor, w: torch.Tensor, targets: torch.Tensor, logprobs: torch.Tensor) -> None:
+    B, d = x.shape
+    V = w.shape[0]
+    if w.shape[1] != d or targets.numel() != B or logprobs.numel() != B:
+        raise AttsError(ERR_INVALID_ARG, "shape mismatch")
+    _check(_lib.atts_lmhead_logprobs_static(_dtype_code(x.dtype), _ptr(x, None, "x"), _ptr(w, x.dtype, "w"),
+                                            _ptr(targets, torch.int32, "targets"), B, d, V,
+                                            _ptr(logprobs, torch.float32, "logprobs"), _stream()))
 
 
 def atts_gemm_nt(a: torch.Tensor, w: torch.Tensor, c: torch.Tensor) -> None:

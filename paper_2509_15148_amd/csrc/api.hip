@@ -5,6 +5,7 @@
 
 #include <stdarg.h>
 #include <stdio.h>
+#include <mutex>
 #include <new>
 #include <vector>
 
@@ -722,24 +723,80 @@ int32_t atts_lmhead_workspace_bytes(int32_t B, int32_t V, size_t* out_bytes) {
     return ATTS_OK;
 }
 
+}  // extern "C"
+
+namespace {
+// Scratch of atts_lmhead_logprobs_static: one copy per GPU (each device that loads this code object holds its own, at
+// its own address, until the process ends).  In host code the array's name is only a handle for hipGetSymbolAddress:
+// kernels are given the address that call returns, looked up once per device with that device current.
+constexpr size_t kStaticScratchBytes = (size_t)16 << 20;
+static __device__ __align__(256) unsigned char scratch[kStaticScratchBytes];
+constexpr int kMaxDevices = 64;
+std::mutex g_scratch_mutex;
+void* g_scratch_ptr[kMaxDevices] = {};
+
+int32_t static_scratch_ptr(void** out) {
+    int dev = -1;
+    ATTS_HIP_TRY(hipGetDevice(&dev));
+    if (dev < 0 || dev >= kMaxDevices) return fail(ATTS_ERR_HIP, "static scratch: device index %d out of range", dev);
+    std::lock_guard<std::mutex> lock(g_scratch_mutex);
+    if (!g_scratch_ptr[dev]) {
+        void* p = nullptr;
+        ATTS_HIP_TRY(hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)));
+        if (!p) return fail(ATTS_ERR_HIP, "static scratch: hipGetSymbolAddress returned a null address");
+        g_scratch_ptr[dev] = p;
+    }
+    *out = g_scratch_ptr[dev];
+    return ATTS_OK;
+}
+
+// The fused LM head on a scratch area of lmhead_workspace_bytes(B, V) bytes: per-row (max, sum-exp) partials, then the
+// target logits.  Shared by the two entry points below.
+int32_t lmhead_on_scratch(int32_t dtype, const void* x, const void* w, const int32_t* targets, int32_t B, int32_t d,
+                          int32_t V, float* logprobs, void* scratch_area, hipStream_t st) {
+    const int n_part = lmhead_num_partials(dtype, B, V, d, false);
+    float2* partials = static_cast<float2*>(scratch_area);
+    float* zt = reinterpret_cast<float*>(static_cast<char*>(scratch_area) + align_up((size_t)B * lmhead_max_partials(V) * sizeof(float2), 256));
+    GemmArgs g{};
+    g.a = x; g.w = w; g.M = B; g.N = V; g.Kd = d; g.lda = d; g.ldw = d;
+    g.targets = targets; g.partials = partials; g.target_logit = zt; g.n_part = n_part;
+    ATTS_TRY(launch_gemm(dtype, EPI_LMHEAD, g, st));
+    return launch_lmhead_combine(partials, zt, B, n_part, nullptr, logprobs, st);
+}
+
+int32_t check_lmhead_args(const char* fn, int32_t dtype, const void* x, const void* w, const int32_t* targets, int32_t B, int32_t d,
+                          int32_t V, const float* logprobs) {
+    if (dtype != ATTS_DTYPE_F32 && dtype != ATTS_DTYPE_BF16) return fail(ATTS_ERR_INVALID_ARG, "%s: unknown dtype %d", fn, dtype);
+    if (!x || !w || !targets || !logprobs) return fail(ATTS_ERR_INVALID_ARG, "%s: NULL argument", fn);
+    if (B < 1 || d < 1 || V < 1) return fail(ATTS_ERR_INVALID_ARG, "%s: B, d, V must be >= 1", fn);
+    return ATTS_OK;
+}
+}  // namespace
+
+extern "C" {
+
 int32_t atts_lmhead_logprobs(int32_t dtype, const void* x, const void* w, const int32_t* targets, int32_t B, int32_t d, int32_t V,
                              float* logprobs, void* workspace, size_t workspace_bytes, void* hip_stream) {
-    if (dtype != ATTS_DTYPE_F32 && dtype != ATTS_DTYPE_BF16) return fail(ATTS_ERR_INVALID_ARG, "atts_lmhead_logprobs: unknown dtype %d", dtype);
-    if (!x || !w || !targets || !logprobs) return fail(ATTS_ERR_INVALID_ARG, "atts_lmhead_logprobs: NULL argument");
-    if (B < 1 || d < 1 || V < 1) return fail(ATTS_ERR_INVALID_ARG, "atts_lmhead_logprobs: B, d, V must be >= 1");
+    ATTS_TRY(check_lmhead_args("atts_lmhead_logprobs", dtype, x, w, targets, B, d, V, logprobs));
     size_t need = 0;
     ATTS_TRY(atts_lmhead_workspace_bytes(B, V, &need));
     if (!workspace || ((uintptr_t)workspace & 255) || workspace_bytes < need)
         return fail(ATTS_ERR_WORKSPACE, "atts_lmhead_logprobs: workspace NULL, misaligned or smaller than %zu bytes", need);
-    const int n_part = lmhead_num_partials(dtype, B, V, d, false);
-    float2* partials = static_cast<float2*>(workspace);
-    float* zt = reinterpret_cast<float*>(static_cast<char*>(workspace) + align_up((size_t)B * lmhead_max_partials(V) * sizeof(float2), 256));
-    GemmArgs g{};
-    g.a = x; g.w = w; g.M = B; g.N = V; g.Kd = d; g.lda = d; g.ldw = d;
-    g.targets = targets; g.partials = partials; g.target_logit = zt; g.n_part = n_part;
-    hipStream_t st = static_cast<hipStream_t>(hip_stream);
-    ATTS_TRY(launch_gemm(dtype, EPI_LMHEAD, g, st));
-    return launch_lmhead_combine(partials, zt, B, n_part, nullptr, logprobs, st);
+    return lmhead_on_scratch(dtype, x, w, targets, B, d, V, logprobs, workspace, static_cast<hipStream_t>(hip_stream));
+}
+
+// The same stage for callers that cannot allocate: its scratch is the file-scope device array below.
+int32_t atts_lmhead_logprobs_static(int32_t dtype, const void* x, const void* w, const int32_t* targets, int32_t B, int32_t d,
+                                    int32_t V, float* logprobs, void* hip_stream) {
+    ATTS_TRY(check_lmhead_args("atts_lmhead_logprobs_static", dtype, x, w, targets, B, d, V, logprobs));
+    size_t need = 0;
+    ATTS_TRY(atts_lmhead_workspace_bytes(B, V, &need));
+    if (need > kStaticScratchBytes)
+        return fail(ATTS_ERR_WORKSPACE, "atts_lmhead_logprobs_static: B = %d rows of a %d-token vocabulary need %zu bytes of scratch, "
+                    "the static area holds %zu", B, V, need, kStaticScratchBytes);
+    void* area = nullptr;
+    ATTS_TRY(static_scratch_ptr(&area));
+    return lmhead_on_scratch(dtype, x, w, targets, B, d, V, logprobs, area, static_cast<hipStream_t>(hip_stream));
 }
 
 int32_t atts_gemm_nt(int32_t dtype, const void* a, const void* w, float* c, int32_t M, int32_t N, int32_t Kdim, void* hip_stream) {
