@@ -4,8 +4,8 @@
 // an order-preserving image of the fp32 score (-0 folded onto +0, every NaN onto key 0, below
 // -inf), so all comparisons are unsigned-integer comparisons that reproduce the IEEE ones.
 //
-//   append (Online Calibration):  keys of the new scores are sorted (register + LDS block sort of
-//       8192-key runs, then either a one-pass multi-way placement or pairwise merge passes) and
+//   append (Online Calibration):  keys of the new scores are sorted (sort.hip: block sort + one-pass
+//       multi-way placement for small batches, radix sort for large ones) and
 //       merged with the resident array by a merge-path kernel into the other half of a ping-pong
 //       buffer.  The same pass writes four sampled copies of its output (every 16th, 256th, 4096th,
 //       65536th key), the levels of a static 16-ary search index.
@@ -16,6 +16,7 @@
 //   conditional coverage (Proposition 2):  no state; one wavefront ranks the candidates of one input against
 //       that input's own calibration scores.
 #include "common.h"
+#include "keys.h"
 
 #include <math.h>
 #include <new>
@@ -25,8 +26,9 @@ constexpr int kIndexLevels = 4;
 struct atts_calib {
     uint32_t* keys[2];                  // ping-pong sorted arrays, capacity each
     uint32_t* index[2][kIndexLevels];   // index[side][k][j] = keys[side][j * 16^(k+1)]
-    uint32_t* runs;                     // sorted runs of the batch being appended
-    uint32_t* batch;                    // fully sorted batch
+    uint32_t* runs;                     // the batch being appended: two buffers the sort alternates between
+    uint32_t* batch;
+    uint32_t* sort_scratch;             // digit histograms of the radix sort
     int32_t* splits;                    // merge-path splits of one streaming merge launch
     int64_t splits_len;
     int64_t capacity;
@@ -37,27 +39,10 @@ struct atts_calib {
 namespace atts {
 namespace {
 
-constexpr int kSortChunk = 8192;    // keys per block-sort workgroup
-constexpr int kSortThreads = 1024;
 constexpr int kMergeThreads = 256;
 constexpr int kMergeSegSmall = 2048;   // outputs per merge workgroup: cache-resident sizes (more workgroups)
 constexpr int kMergeSegLarge = 4096;   // ... and streaming sizes (split search amortised over more keys; 8 workgroups per CU)
 constexpr int64_t kMergeLargeFrom = (int64_t)1 << 22;
-constexpr int kMaxMultiwayRuns = 16;
-constexpr uint32_t kPadKey = 0xFFFFFFFFu;   // above the key of +inf (0xFF800000)
-
-// Integer-only, so that sub-normal scores keep their order whatever the float mode is.
-__device__ __forceinline__ bool score_is_nan(float f) { return (__float_as_uint(f) & 0x7FFFFFFFu) > 0x7F800000u; }
-__device__ __forceinline__ uint32_t score_to_key(float f) {
-    uint32_t b = __float_as_uint(f);
-    if ((b & 0x7FFFFFFFu) > 0x7F800000u) return 0u;   // NaN
-    if ((b & 0x7FFFFFFFu) == 0u) b = 0u;              // -0 -> +0
-    return (b & 0x80000000u) ? ~b : (b | 0x80000000u);
-}
-__device__ __forceinline__ float key_to_score(uint32_t k) {
-    if (k == 0u) return __uint_as_float(0x7FC00000u);
-    return __uint_as_float((k & 0x80000000u) ? (k ^ 0x80000000u) : ~k);
-}
 
 // first index in [0, n) with a[idx] >= x  (n if none)
 __device__ __forceinline__ int64_t lower_bound(const uint32_t* __restrict__ a, int64_t n, uint32_t x) {
@@ -78,132 +63,13 @@ __device__ __forceinline__ int64_t upper_bound(const uint32_t* __restrict__ a, i
     return lo;
 }
 
-// ---- merge path ------------------------------------------------------------------------------------
-// Number of elements taken from a[] among the first `diag` outputs of the stable merge (a first on ties).
-template <typename Index>
-__device__ __forceinline__ Index merge_path(const uint32_t* a, Index na, const uint32_t* b, Index nb, Index diag) {
-    Index lo = diag > nb ? diag - nb : 0, hi = diag < na ? diag : na;
-    while (lo < hi) {
-        Index mid = (lo + hi) >> 1;
-        if (a[mid] <= b[diag - 1 - mid]) lo = mid + 1; else hi = mid;
-    }
-    return lo;
-}
-
-// ---- block sort: each workgroup turns kSortChunk scores into one ascending run of keys ----------
-// 8 keys per thread: sorted in registers (odd-even transposition network), then log2(1024) rounds of pairwise
-// merges of sorted runs through two LDS buffers (each thread finds its 8 outputs by merge path and merges them
-// sequentially), one barrier per round.
-__device__ __forceinline__ void cswap(uint32_t& x, uint32_t& y) {
-    const uint32_t lo = min(x, y), hi = max(x, y);
-    x = lo;
-    y = hi;
-}
-
-__global__ __launch_bounds__(kSortThreads) void block_sort_kernel(const float* __restrict__ scores, int64_t n,
-                                                                  uint32_t* __restrict__ runs) {
-    constexpr int VT = kSortChunk / kSortThreads;   // 8
-    static_assert(VT == 8, "register network below sorts 8 keys");
-    __shared__ uint32_t buf[2][kSortChunk];
-    const int64_t base = (int64_t)blockIdx.x * kSortChunk;
-    const int tid = threadIdx.x;
-    for (int i = tid; i < kSortChunk; i += kSortThreads) buf[0][i] = base + i < n ? score_to_key(scores[base + i]) : kPadKey;
-    __syncthreads();
-    uint32_t k[VT];
-#pragma unroll
-    for (int e = 0; e < VT; ++e) k[e] = buf[0][tid * VT + e];
-#pragma unroll
-    for (int round = 0; round < VT; ++round) {
-#pragma unroll
-        for (int e = round & 1; e + 1 < VT; e += 2) cswap(k[e], k[e + 1]);
-    }
-#pragma unroll
-    for (int e = 0; e < VT; ++e) buf[0][tid * VT + e] = k[e];
-    int cur = 0;
-    for (int width = VT; width < kSortChunk; width *= 2) {
-        __syncthreads();
-        const uint32_t* src = buf[cur];
-        uint32_t* dst = buf[cur ^ 1];
-        const int o = tid * VT;
-        const int pair = o & ~(2 * width - 1);
-        const uint32_t* a = src + pair;
-        const uint32_t* b = a + width;
-        int ia = merge_path<int>(a, width, b, width, o - pair);
-        int ib = o - pair - ia;
-        uint32_t ka = ia < width ? a[ia] : kPadKey, kb = ib < width ? b[ib] : kPadKey;
-#pragma unroll
-        for (int e = 0; e < VT; ++e) {
-            const bool take_a = ib >= width || (ia < width && ka <= kb);
-            k[e] = take_a ? ka : kb;
-            if (take_a) {
-                ++ia;
-                ka = ia < width ? a[ia] : kPadKey;
-            } else {
-                ++ib;
-                kb = ib < width ? b[ib] : kPadKey;
-            }
-        }
-#pragma unroll
-        for (int e = 0; e < VT; ++e) dst[o + e] = k[e];
-        cur ^= 1;
-    }
-    __syncthreads();
-    for (int i = tid; i < kSortChunk; i += kSortThreads)
-        if (base + i < n) runs[base + i] = buf[cur][i];
-}
-
-// ---- multi-way placement: final position of every element of <= kMaxMultiwayRuns sorted runs -----
-// Stable: among equal keys, elements of earlier runs come first.  The searches into the other runs are taken
-// eight at a time in lock step, so that their (dependent, cache-latency bound) probes overlap.
-constexpr int kPlaceGroup = 8;
-
-__global__ __launch_bounds__(256) void multiway_place_kernel(const uint32_t* __restrict__ runs, int64_t n,
-                                                             uint32_t* __restrict__ out) {
-    const int64_t e = (int64_t)blockIdx.x * 256 + threadIdx.x;
-    if (e >= n) return;
-    const uint32_t x = runs[e];
-    const int my_run = (int)(e / kSortChunk);
-    const int n_runs = (int)((n + kSortChunk - 1) / kSortChunk);
-    const int last_len = (int)(n - (int64_t)(n_runs - 1) * kSortChunk);
-    int pos = (int)(e % kSortChunk);
-    for (int q0 = 0; q0 < n_runs; q0 += kPlaceGroup) {
-        // cnt[j] = number of keys of run q0 + j that go before x: keys <= x for an earlier run, < x for a later one
-        int cnt[kPlaceGroup] = {};
-        int len[kPlaceGroup];
-        uint32_t bias[kPlaceGroup];                                  // "key < x + bias" covers both comparisons (x < 2^32 - 1)
-#pragma unroll
-        for (int j = 0; j < kPlaceGroup; ++j) {
-            const int q = q0 + j;
-            len[j] = (q >= n_runs || q == my_run) ? 0 : (q == n_runs - 1 ? last_len : kSortChunk);
-            bias[j] = q < my_run ? 1u : 0u;
-        }
-        for (int step = kSortChunk; step > 0; step >>= 1) {
-            uint32_t v[kPlaceGroup];
-#pragma unroll
-            for (int j = 0; j < kPlaceGroup; ++j) {                   // unconditional loads (clamped), so that they overlap
-                const int probe = cnt[j] + step;
-                const int64_t at = probe <= len[j] ? (int64_t)(q0 + j) * kSortChunk + probe - 1 : e;
-                v[j] = runs[at];
-            }
-#pragma unroll
-            for (int j = 0; j < kPlaceGroup; ++j)
-                if (cnt[j] + step <= len[j] && v[j] < x + bias[j]) cnt[j] += step;
-        }
-#pragma unroll
-        for (int j = 0; j < kPlaceGroup; ++j) pos += cnt[j];
-    }
-    out[pos] = x;
-}
-
 // ---- merging two sorted arrays --------------------------------------------------------------------
 struct MergeJob {
-    const uint32_t* a;   // pair y: a + 2 y run, length min(run, n - 2 y run)   (pairwise mode: run > 0)
+    const uint32_t* a;   // resident keys (first on ties)
     int64_t na;
-    const uint32_t* b;   // pair y: a + (2 y + 1) run
+    const uint32_t* b;   // the sorted batch
     int64_t nb;
-    uint32_t* out;       // pair y: out + 2 y run
-    int64_t run;         // 0: single job (a, na, b, nb, out) as given
-    int64_t n;           // pairwise mode: total elements
+    uint32_t* out;
     uint32_t* index[kIndexLevels];   // EMIT only: index[k][j] = out[j * 16^(k+1)]
 };
 
@@ -211,51 +77,25 @@ struct MergeJob {
 // into distinct banks
 __device__ __forceinline__ int lds_pad(int i) { return i + (i >> 5); }
 
-// The operands of pair y (or of the single job).  false: nothing to do.
-__device__ __forceinline__ bool merge_operands(const MergeJob& job, int64_t y, const uint32_t*& a, int64_t& na,
-                                               const uint32_t*& b, int64_t& nb, uint32_t*& out) {
-    a = job.a;
-    b = job.b;
-    out = job.out;
-    na = job.na;
-    nb = job.nb;
-    if (job.run > 0) {
-        const int64_t off = 2 * y * job.run;
-        if (off >= job.n) return false;
-        a = job.a + off;
-        na = min(job.run, job.n - off);
-        b = a + na;
-        nb = max((int64_t)0, min(job.run, job.n - off - job.run));
-        out = job.out + off;
-    }
-    return true;
+// For a streaming merge launch of `segs` workgroups: splits[x] = elements taken from a[] among the first
+// min(x seg, total) outputs.  One thread per entry: the searches run in parallel here instead of serially in front of
+// every workgroup's loads.
+__global__ __launch_bounds__(256) void merge_split_kernel(MergeJob job, int seg, int segs, int32_t* __restrict__ splits) {
+    const int64_t x = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    if (x > segs) return;
+    const int64_t diag = min(x * (int64_t)seg, job.na + job.nb);
+    splits[x] = (int32_t)merge_path<int64_t>(job.a, job.na, job.b, job.nb, diag);
 }
 
-// For a streaming merge launch of (segs, pairs) workgroups: splits[y (segs + 1) + x] = elements taken from a[]
-// among the first min(x seg, total) outputs of pair y.  One thread per entry: the searches run in parallel here
-// instead of serially in front of every workgroup's loads.
-__global__ __launch_bounds__(256) void merge_split_kernel(MergeJob job, int seg, int segs, int64_t pairs,
-                                                          int32_t* __restrict__ splits) {
-    const int64_t idx = (int64_t)blockIdx.x * 256 + threadIdx.x;
-    const int64_t y = idx / (segs + 1), x = idx % (segs + 1);
-    if (y >= pairs) return;
-    const uint32_t *a, *b;
-    uint32_t* out;
-    int64_t na, nb;
-    if (!merge_operands(job, y, a, na, b, nb, out)) return;
-    const int64_t diag = min(x * (int64_t)seg, na + nb);
-    splits[idx] = (int32_t)merge_path<int64_t>(a, na, b, nb, diag);
-}
-
-// Each workgroup produces SEG consecutive outputs.  out + segment start must be 16-byte aligned (SEG divides
-// the run length in pairwise mode).  PRESPLIT: the segment's merge-path splits come from merge_split_kernel.
+// Each workgroup produces SEG consecutive outputs (out + segment start is 16-byte aligned).  PRESPLIT: the segment's
+// merge-path splits come from merge_split_kernel.
 template <int SEG, bool EMIT, bool PRESPLIT>
 __global__ __launch_bounds__(kMergeThreads) void merge_kernel(MergeJob job, const int32_t* __restrict__ splits) {
     constexpr int PER = SEG / kMergeThreads;
-    const uint32_t *a, *b;
-    uint32_t* out;
-    int64_t na, nb;
-    if (!merge_operands(job, blockIdx.y, a, na, b, nb, out)) return;
+    const uint32_t* __restrict__ a = job.a;
+    const uint32_t* __restrict__ b = job.b;
+    uint32_t* __restrict__ out = job.out;
+    const int64_t na = job.na, nb = job.nb;
     const int64_t total = na + nb;
     const int64_t o0 = (int64_t)blockIdx.x * SEG;
     if (o0 >= total) return;
@@ -264,7 +104,7 @@ __global__ __launch_bounds__(kMergeThreads) void merge_kernel(MergeJob job, cons
     __shared__ int64_t split[2];
     __shared__ uint32_t buf[SEG + SEG / 32];
     if constexpr (PRESPLIT) {
-        if (threadIdx.x < 2) split[threadIdx.x] = splits[(int64_t)blockIdx.y * (gridDim.x + 1) + blockIdx.x + threadIdx.x];
+        if (threadIdx.x < 2) split[threadIdx.x] = splits[blockIdx.x + threadIdx.x];
     } else
     // Merge-path split of both segment ends at once: threads 0..127 search the diagonal o0, threads 128..255 the
     // diagonal o1.  Each round probes 128 evenly spaced candidates of the current range in parallel (one load
@@ -389,19 +229,38 @@ struct SearchIndex {
     int32_t per_thread;                      // test scores per thread
 };
 
-// t = number of entries of the next coarser level that are < x  ->  the same count for level L: the candidates
-// are the 16 entries of one aligned 64-byte line (entries past `len` do not count).
-__device__ __forceinline__ int64_t descend(const uint32_t* __restrict__ L, int64_t len, int64_t t, uint32_t x) {
-    if (t == 0) return 0;
-    const int64_t base = (t - 1) << 4;
-    const uint4* p = reinterpret_cast<const uint4*>(L + base);
-    const uint4 q0 = p[0], q1 = p[1], q2 = p[2], q3 = p[3];
-    const int valid = (int)min((int64_t)16, len - base);
-    const uint32_t v[16] = {q0.x, q0.y, q0.z, q0.w, q1.x, q1.y, q1.z, q1.w, q2.x, q2.y, q2.z, q2.w, q3.x, q3.y, q3.z, q3.w};
-    int c = 0;
-#pragma unroll
-    for (int e = 0; e < 16; ++e) c += (e < valid && v[e] < x) ? 1 : 0;
-    return base + c;
+// One level of the index for the four test keys of a quad of lanes (lane l of the quad owns key x_l and the count
+// t_l of entries of the next coarser level below it).  Result for each lane: the same count for level L, whose
+// candidates are the 16 entries of one aligned 64-byte line.  The quad takes its four keys in turn: in round r all
+// four lanes work on lane r's key, each loading and comparing a quarter (16 bytes) of its line, so that one load
+// instruction of the wavefront touches 16 lines instead of 64 (the vector cache looks up one line per cycle: a
+// lane-per-line load costs four times the tag look-ups).  Values move inside the quad by DPP, not through LDS.
+// Every lane of the quad must be active; a lane without work passes t = 0 (nothing is loaded for it).
+template <int CTRL>
+__device__ __forceinline__ int quad_perm(int v) { return __builtin_amdgcn_mov_dpp(v, CTRL, 0xF, 0xF, true); }
+
+__device__ __forceinline__ int quad_descend(const uint32_t* __restrict__ L, int64_t len, int t, uint32_t x) {
+    const int q = threadIdx.x & 3;
+    int out = 0;
+    auto round = [&](int xr_, int tr, int r) {
+        const uint32_t xr = (uint32_t)xr_;
+        int c = 0;
+        const int base = (tr - 1) << 4;
+        if (tr > 0) {
+            const uint4 v = *reinterpret_cast<const uint4*>(L + base + 4 * q);
+            const int valid = (int)min((int64_t)16, len - base) - 4 * q;     // entries of this quarter that exist
+            c = ((valid > 0 && v.x < xr) ? 1 : 0) + ((valid > 1 && v.y < xr) ? 1 : 0) + ((valid > 2 && v.z < xr) ? 1 : 0) +
+                ((valid > 3 && v.w < xr) ? 1 : 0);
+        }
+        c += quad_perm<0xB1>(c);      // lanes (1, 0, 3, 2)
+        c += quad_perm<0x4E>(c);      // lanes (2, 3, 0, 1)
+        if (q == r) out = tr > 0 ? base + c : 0;
+    };
+    round(quad_perm<0x00>((int)x), quad_perm<0x00>(t), 0);
+    round(quad_perm<0x55>((int)x), quad_perm<0x55>(t), 1);
+    round(quad_perm<0xAA>((int)x), quad_perm<0xAA>(t), 2);
+    round(quad_perm<0xFF>((int)x), quad_perm<0xFF>(t), 3);
+    return out;
 }
 
 __global__ __launch_bounds__(256) void classify_kernel(SearchIndex ix, const float* __restrict__ test, int64_t m,
@@ -420,28 +279,31 @@ __global__ __launch_bounds__(256) void classify_kernel(SearchIndex ix, const flo
         thresholds[threadIdx.x] = kth > n ? INFINITY : (kth < 1 ? -INFINITY : key_to_score(ix.lvl[0][kth - 1]));
     }
     for (int j = 0; j < ix.per_thread; ++j) {
-        const int64_t i = ((int64_t)blockIdx.x * ix.per_thread + j) * 256 + threadIdx.x;
-        if (i >= m) return;
-        const float sc = test[i];
-        int64_t c = 0;
-        if (!score_is_nan(sc)) {
-            const uint32_t x = score_to_key(sc);
+        const int64_t i0 = ((int64_t)blockIdx.x * ix.per_thread + j) * 256;      // block-uniform: whole quads stay in the loop
+        if (i0 >= m) break;
+        const int64_t i = i0 + threadIdx.x;
+        const float sc = i < m ? test[i] : __uint_as_float(0x7FC00000u);
+        const bool searching = !score_is_nan(sc);
+        const uint32_t x = score_to_key(sc);
+        int t = 0;                                             // number of entries of the current level below x
+        if (searching) {
             int lo = 0, hi = n_top;                            // number of staged entries < x
             while (lo < hi) {
                 const int mid = (lo + hi) >> 1;
                 if (top[mid] < x) lo = mid + 1; else hi = mid;
             }
-            int64_t t = lo;                                    // -> number of top-level entries < x
+            t = lo;
             if (s > 0 && lo > 0) {
                 const int64_t w0 = ((int64_t)(lo - 1) << s) + 1;
                 const int64_t w1 = min(top_len, (int64_t)lo << s);
-                t = w0 + lower_bound(T + w0, w1 - w0, x);
+                t = (int)(w0 + lower_bound(T + w0, w1 - w0, x));
             }
-#pragma unroll
-            for (int l = kIndexLevels - 1; l >= 0; --l)
-                if (l < ix.top_level) t = descend(ix.lvl[l], ix.len[l], t, x);
-            c = n - t;
         }
+#pragma unroll
+        for (int l = kIndexLevels - 1; l >= 0; --l)
+            if (l < ix.top_level) t = quad_descend(ix.lvl[l], ix.len[l], t, x);      // a NaN or absent score carries t = 0 down
+        if (i >= m) continue;
+        const int64_t c = searching ? n - t : 0;
         ranks[i] = (int32_t)c;
         if (pvalues) pvalues[i] = (float)((double)(c + 1) / (double)(n + 1));
         int cls = 0;
@@ -544,25 +406,22 @@ __global__ void export_kernel(const uint32_t* __restrict__ keys, int64_t n, floa
     if (i < n) out[i] = key_to_score(keys[i]);
 }
 
-// One merge launch: `pairs` independent merges of at most `pair_total` outputs each.
+// One merge launch producing `total` outputs.
 template <bool EMIT>
-int32_t launch_merge(atts_calib* c, const MergeJob& job, int64_t pair_total, int64_t pairs, bool streaming,
-                     hipStream_t stream) {
+int32_t launch_merge(atts_calib* c, const MergeJob& job, int64_t total, bool streaming, hipStream_t stream) {
     if (streaming) {
-        const int64_t segs = ceil_div(pair_total, kMergeSegLarge);
-        const int64_t n_splits = pairs * (segs + 1);
-        dim3 grid((unsigned)segs, (unsigned)pairs);
-        if (n_splits <= c->splits_len) {
-            hipLaunchKernelGGL(merge_split_kernel, dim3((unsigned)ceil_div(n_splits, 256)), dim3(256), 0, stream, job,
-                               kMergeSegLarge, (int)segs, pairs, c->splits);
+        const int64_t segs = ceil_div(total, kMergeSegLarge);
+        if (segs + 1 <= c->splits_len) {
+            hipLaunchKernelGGL(merge_split_kernel, dim3((unsigned)ceil_div(segs + 1, 256)), dim3(256), 0, stream, job,
+                               kMergeSegLarge, (int)segs, c->splits);
             ATTS_LAUNCH_CHECK("merge_split_kernel");
-            hipLaunchKernelGGL((merge_kernel<kMergeSegLarge, EMIT, true>), grid, dim3(kMergeThreads), 0, stream, job, c->splits);
+            hipLaunchKernelGGL((merge_kernel<kMergeSegLarge, EMIT, true>), dim3((unsigned)segs), dim3(kMergeThreads), 0, stream, job, c->splits);
         } else {
-            hipLaunchKernelGGL((merge_kernel<kMergeSegLarge, EMIT, false>), grid, dim3(kMergeThreads), 0, stream, job, nullptr);
+            hipLaunchKernelGGL((merge_kernel<kMergeSegLarge, EMIT, false>), dim3((unsigned)segs), dim3(kMergeThreads), 0, stream, job, nullptr);
         }
     } else {
-        dim3 grid((unsigned)ceil_div(pair_total, kMergeSegSmall), (unsigned)pairs);
-        hipLaunchKernelGGL((merge_kernel<kMergeSegSmall, EMIT, false>), grid, dim3(kMergeThreads), 0, stream, job, nullptr);
+        hipLaunchKernelGGL((merge_kernel<kMergeSegSmall, EMIT, false>), dim3((unsigned)ceil_div(total, kMergeSegSmall)), dim3(kMergeThreads), 0,
+                           stream, job, nullptr);
     }
     ATTS_LAUNCH_CHECK("merge_kernel");
     return ATTS_OK;
@@ -587,15 +446,16 @@ int32_t atts_calib_create(int64_t capacity, atts_calib** out) {
     c->cur = 0;
     // Every array is rounded up to whole 64-byte lines plus one: the index search reads whole lines (entries
     // past the fill are masked, not avoided).  Sorted runs are padded to whole chunks only in LDS.
-    uint32_t** bufs[4 + 2 * kIndexLevels] = {&c->keys[0], &c->keys[1], &c->runs, &c->batch};
-    int64_t sizes[4 + 2 * kIndexLevels];
+    uint32_t** bufs[5 + 2 * kIndexLevels] = {&c->keys[0], &c->keys[1], &c->runs, &c->batch, &c->sort_scratch};
+    int64_t sizes[5 + 2 * kIndexLevels];
     for (int i = 0; i < 4; ++i) sizes[i] = capacity;
+    sizes[4] = sort_scratch_words(capacity);
     for (int side = 0; side < 2; ++side)
         for (int k = 0; k < kIndexLevels; ++k) {
-            bufs[4 + side * kIndexLevels + k] = &c->index[side][k];
-            sizes[4 + side * kIndexLevels + k] = ceil_div(capacity, (int64_t)1 << (4 * (k + 1)));
+            bufs[5 + side * kIndexLevels + k] = &c->index[side][k];
+            sizes[5 + side * kIndexLevels + k] = ceil_div(capacity, (int64_t)1 << (4 * (k + 1)));
         }
-    constexpr int n_bufs = 4 + 2 * kIndexLevels;
+    constexpr int n_bufs = 5 + 2 * kIndexLevels;
     for (int i = 0; i < n_bufs; ++i) *bufs[i] = nullptr;
     for (int i = 0; i < n_bufs; ++i) {
         const size_t bytes = ((size_t)ceil_div(sizes[i], 16) * 16 + 16) * sizeof(uint32_t);
@@ -607,7 +467,7 @@ int32_t atts_calib_create(int64_t capacity, atts_calib** out) {
             return fail(ATTS_ERR_HIP, "atts_calib_create: hipMalloc of %zu bytes failed: %s", bytes, hipGetErrorString(e));
         }
     }
-    c->splits_len = capacity / (kMergeSegLarge / 2) + 64;
+    c->splits_len = capacity / kMergeSegLarge + 64;
     hipError_t e = hipMalloc(reinterpret_cast<void**>(&c->splits), (size_t)c->splits_len * sizeof(int32_t));
     if (e != hipSuccess) {
         for (int j = 0; j < n_bufs; ++j) (void)hipFree(*bufs[j]);
@@ -627,6 +487,7 @@ int32_t atts_calib_destroy(atts_calib* c) {
         for (int k = 0; k < kIndexLevels; ++k) (void)hipFree(c->index[side][k]);
     (void)hipFree(c->runs);
     (void)hipFree(c->batch);
+    (void)hipFree(c->sort_scratch);
     delete c;
     return ATTS_OK;
 }
@@ -653,42 +514,21 @@ int32_t atts_calibrate_online(atts_calib* c, const float* new_scores, int64_t n_
                     (long long)n_new, (long long)c->capacity);
     hipStream_t stream = static_cast<hipStream_t>(hip_stream);
 
-    // 1. keys of the new scores, sorted in runs of kSortChunk
-    const int64_t n_runs = ceil_div(n_new, kSortChunk);
-    const uint32_t* sorted = c->runs;
+    // 1. ascending keys of the new scores
+    const uint32_t* sorted = nullptr;
     {
-    StageTimer t_(ATTS_STAGE_CALIB_SORT, stream);
-    hipLaunchKernelGGL(block_sort_kernel, dim3((unsigned)n_runs), dim3(kSortThreads), 0, stream, new_scores, n_new, c->runs);
-    ATTS_LAUNCH_CHECK("block_sort_kernel");
-
-    // 2. one sorted batch
-    if (n_runs > 1 && n_runs <= kMaxMultiwayRuns) {
-        hipLaunchKernelGGL(multiway_place_kernel, dim3((unsigned)ceil_div(n_new, 256)), dim3(256), 0, stream, c->runs, n_new,
-                           c->batch);
-        ATTS_LAUNCH_CHECK("multiway_place_kernel");
-        sorted = c->batch;
-    } else if (n_runs > 1) {
-        uint32_t* src = c->runs;
-        uint32_t* dst = c->batch;
-        for (int64_t run = kSortChunk; run < n_new; run *= 2) {
-            MergeJob job{src, 0, nullptr, 0, dst, run, n_new, {}};
-            int32_t rc = launch_merge<false>(c, job, 2 * run, ceil_div(n_new, 2 * run), n_new >= kMergeLargeFrom, stream);
-            if (rc != ATTS_OK) return rc;
-            uint32_t* t = src;
-            src = dst;
-            dst = t;
-        }
-        sorted = src;
-    }
+        StageTimer t_(ATTS_STAGE_CALIB_SORT, stream);
+        int32_t rc = launch_sort_scores(new_scores, n_new, c->runs, c->batch, c->sort_scratch, &sorted, stream);
+        if (rc != ATTS_OK) return rc;
     }
 
-    // 3. merge with the resident array into the other half of the ping-pong buffer (+ its search index)
+    // 2. merge with the resident array into the other half of the ping-pong buffer (+ its search index)
     const int to = c->cur ^ 1;
-    MergeJob job{c->keys[c->cur], c->n, sorted, n_new, c->keys[to], 0, 0, {}};
+    MergeJob job{c->keys[c->cur], c->n, sorted, n_new, c->keys[to], {}};
     for (int k = 0; k < kIndexLevels; ++k) job.index[k] = c->index[to][k];
     const int64_t total = c->n + n_new;
     StageTimer t_(ATTS_STAGE_CALIB_MERGE, stream);
-    int32_t rc = launch_merge<true>(c, job, total, 1, total >= kMergeLargeFrom, stream);
+    int32_t rc = launch_merge<true>(c, job, total, total >= kMergeLargeFrom, stream);
     if (rc != ATTS_OK) return rc;
     c->cur ^= 1;
     c->n += n_new;

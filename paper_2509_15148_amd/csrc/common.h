@@ -200,6 +200,13 @@ int32_t launch_sample_rows(const float* logits, int64_t ld, int32_t V, int32_t r
 int32_t launch_norm_strided_rows(int32_t dtype, const float* h, const float* gain, float eps, int32_t d, int64_t first, int64_t step,
                                  BranchPos pos, int32_t rows, void* xs, hipStream_t stream);
 
+// ---- sorting a batch of scores (sort.hip) -----------------------------------------------------------------------
+// Ascending order-preserving keys of scores[0, n) (n >= 1).  a, b: two key buffers of at least n rounded up to 16, plus
+// 16, words; scratch: sort_scratch_words(n) words.  *sorted is set to whichever of a / b ends up holding the result.
+int64_t sort_scratch_words(int64_t n);
+int32_t launch_sort_scores(const float* scores, int64_t n, uint32_t* a, uint32_t* b, uint32_t* scratch, const uint32_t** sorted,
+                           hipStream_t stream);
+
 bool attention_uses_vt(int32_t dtype, int32_t hd);
 // queries are the rows [row0, R); keys / values of all rows [0, R) must be present
 int32_t launch_attention(int32_t dtype, const void* qkv, const void* vt, int64_t ldv, void* out, ScoreShape s, int32_t row0,

@@ -70,10 +70,12 @@ def test_small_with_ties_and_special_values():
     assert len(ranks) == 0 and q[0] == O.quantile_thresholds(cal.astype(np.float64), O.reject_ranks([0.3], len(cal)))[0]
 
 
-@pytest.mark.parametrize("sizes", [(1,), (7, 1, 300), (8191, 8193, 5), (20000, 3, 70001), (200000, 131072 + 17)])
+@pytest.mark.parametrize("sizes", [(1,), (7, 1, 300), (2047, 2048, 2049, 5), (8191, 8193, 5), (65536, 65537, 16, 65535),
+                                   (20000, 3, 70001), (200000, 131072 + 17)])
 def test_online_appends_span_sort_chunks_and_merge_paths(sizes):
-    """Batches below / at / above one sort chunk, the multi-way path (<= 16 runs) and the pairwise
-    path (> 16 runs); after every append the state must equal the sorted union."""
+    """Batches below / at / above one sort run (8192 keys), the one-pass multi-way placement (up to 8 runs =
+    65,536 keys) and the radix sort (larger batches, ragged last tile); after every append the state must equal
+    the sorted union."""
     import paper_2509_15148_amd as A
     announce("calib appends", sizes)
     total = sum(sizes)
@@ -173,6 +175,40 @@ def test_streaming_merge_sizes():
     idx = np.arange(0, len(test), 64)
     ranks = _classify(A, c, test[idx], [0.05, 0.2])[0]
     assert np.array_equal(ranks.astype(np.int64), O.rank_counts(allv.astype(np.float64), test[idx]))
+
+
+@pytest.mark.parametrize("kind", ["lognormal", "clustered"])
+def test_large_set_rank_search_with_guessed_window(kind):
+    """Sets of 2^24 scores and more: the rank search first tries a two-line window picked by linear interpolation
+    inside a 256-key block and falls back to the two index levels when the window does not bracket the score.
+    Smooth data takes the window almost always; clustered data (long runs of equal scores, gaps of several orders of
+    magnitude, sub-normals) defeats the guess.  Every rank and class against the oracle's sort-based count, sampled
+    ones against the double sum."""
+    import paper_2509_15148_amd as A
+    n, m = (1 << 24) + 4321, 1 << 18
+    announce("calib guessed window", kind, n, m)
+    rng = np.random.default_rng(11)
+    if kind == "lognormal":
+        cal = lognormal_scores(n, seed=606)
+        test = lognormal_scores(m, seed=607)
+    else:
+        parts = [np.full(n // 3, 1.0, np.float32), lognormal_scores(n // 3, seed=608) * np.float32(1e-30),
+                 (rng.integers(0, 50, n - 2 * (n // 3)) * 1000.0).astype(np.float32)]
+        cal = np.concatenate(parts)
+        rng.shuffle(cal)
+        test = np.concatenate([cal[: m // 2], lognormal_scores(m // 4, seed=609) * np.float32(1e-30),
+                               (rng.random(m - m // 2 - m // 4) * 60000.0 - 5000.0).astype(np.float32)])
+    c = A.Calib(n)
+    A.atts_calibrate_online(c, dev(cal))
+    ranks, cls, p, q = _classify(A, c, test, [0.05, 0.2])
+    cal64 = cal.astype(np.float64)
+    want = O.rank_counts_sorted(cal64, test)
+    assert np.array_equal(ranks.astype(np.int64), want)
+    r = O.reject_ranks([0.05, 0.2], n)
+    assert np.array_equal(cls, O.classify(want, r))
+    assert np.array_equal(q, O.quantile_thresholds(cal64, r).astype(np.float32))
+    idx = rng.choice(m, 24, replace=False)
+    assert np.array_equal(ranks[idx].astype(np.int64), O.rank_counts(cal64, test[idx]))
 
 
 def test_out_of_cache_size_sampled():
