@@ -78,16 +78,21 @@ __global__ __launch_bounds__(64) void attn_simple_kernel(const T* __restrict__ q
 // MFMA kernel (bf16, hd = 128)
 // ------------------------------------------------------------------------------------------
 constexpr int kHd = 128;
-constexpr int kQTile = 128;   // query rows per workgroup (32 per wave)
 constexpr int kKTile = 64;    // keys per LDS tile
 
-__global__ __launch_bounds__(256, 2) void attn_mfma_kernel(const bf16* __restrict__ qkv, const bf16* __restrict__ vt,
+// kWaves wavefronts of 32 query rows each share the key / value tiles of one head; kStages tiles of LDS form a ring
+// (kStages - 1 tiles are in flight or in use: with three stages the loads run two tiles ahead of the MFMAs).
+template <int kWaves, int kStages>
+__global__ __launch_bounds__(64 * kWaves, 512 / (64 * kWaves)) void attn_mfma_kernel(const bf16* __restrict__ qkv, const bf16* __restrict__ vt,
                                                            int64_t ldv, bf16* __restrict__ out, int row0, int R, int P, int Tn,
                                                            int nq, int nkv, float scale_log2e) {
-    // Two stages of [K tile: 64 keys x 256 B | V^T tile: 128 dims x 128 B], filled by direct global -> LDS loads.
+    // Stages of [K tile: 64 keys x 256 B | V^T tile: 128 dims x 128 B], filled by direct global -> LDS loads.
     //   K rows are 256 B: 16-byte chunk index XOR (key & 15);  V^T rows are 128 B: chunk index XOR (dim >> 1) & 7.
+    constexpr int kQTile = 32 * kWaves;                 // query rows per workgroup
     constexpr int kKBytes = kKTile * kHd * 2, kStage = 2 * kKBytes;
-    __shared__ __attribute__((aligned(16))) char smem[2 * kStage];
+    constexpr int kDmaK = 16 / kWaves, kDmaV = 16 / kWaves;     // 1 KiB DMA instructions per wave and tile
+    static_assert(kWaves == 4 || kWaves == 8, "DMA addressing below");
+    extern __shared__ __attribute__((aligned(16))) char smem[];   // [kStages][kStage]
 
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -128,29 +133,29 @@ __global__ __launch_bounds__(256, 2) void attn_mfma_kernel(const bf16* __restric
     auto tile_start = [&](int t) { return t < n1 ? t * kKTile : s2 + (t - n1) * kKTile; };
 
     // ---- DMA addressing (one wave-wide instruction moves 1 KiB = 4 K rows or 8 V^T rows).
-    // K: instruction j of this wave fills tile rows 16 wave + 4 j + (lane >> 4); lane lands at chunk slot lane & 15
-    //    and fetches chunk slot ^ (row & 15) = (slot ^ (lane >> 4)) ^ 4 j.  Rows past the end are clamped to row
-    //    R - 1 (their scores are masked).
-    // V^T: instruction j fills dims 32 wave + 8 j + (lane >> 3); slot lane & 7 fetches chunk
-    //    slot ^ ((dim >> 1) & 7) = slot ^ (4 (j & 1) | (lane >> 4)).  Columns past R are zero in the V^T copy.
+    // K: instruction j of this wave fills tile rows (64 / kWaves) wave + 4 j + (lane >> 4); lane lands at chunk slot
+    //    lane & 15 and fetches chunk slot ^ (row & 15).  Rows past the end are clamped to row R - 1 (their scores
+    //    are masked).
+    // V^T: instruction j fills dims (128 / kWaves) wave + 8 j + (lane >> 3); slot lane & 7 fetches chunk
+    //    slot ^ ((dim >> 1) & 7).  Columns past R are zero in the V^T copy.
     const int kq = lane >> 4, kslot = lane & 15;
     const int vq = lane >> 3, vslot = lane & 7;
     const bf16* kg = qkv + (nq + kvh) * kHd;
-    const bf16* vg = vt + ((int64_t)kvh * kHd + 32 * wave + vq) * ldv;
+    const bf16* vg = vt + ((int64_t)kvh * kHd + (128 / kWaves) * wave + vq) * ldv;
     auto issue_tile = [&](int t) __attribute__((always_inline)) {
         const int j0 = tile_start(t);
-        char* stage = smem + (t & 1) * kStage;
+        char* stage = smem + (t % kStages) * kStage;
 #pragma unroll
-        for (int j = 0; j < 4; ++j) {
-            const int row = 16 * wave + 4 * j;                        // wave-uniform part of the tile row
+        for (int j = 0; j < kDmaK; ++j) {
+            const int row = (64 / kWaves) * wave + 4 * j;             // wave-uniform part of the tile row
             const int key = min(j0 + row + kq, R - 1);
-            const bf16* src = kg + (int64_t)key * ld + (((kslot ^ kq) ^ (4 * j)) << 3);
+            const bf16* src = kg + (int64_t)key * ld + ((kslot ^ ((row + kq) & 15)) << 3);
             __builtin_amdgcn_global_load_lds(ATTS_GPTR(src), ATTS_LPTR(stage + row * 256), 16, 0, 0);
         }
 #pragma unroll
-        for (int j = 0; j < 4; ++j) {
-            const int dim = 32 * wave + 8 * j;
-            const bf16* src = vg + (int64_t)(8 * j) * ldv + j0 + ((vslot ^ ((4 * (j & 1)) | (vq >> 1))) << 3);
+        for (int j = 0; j < kDmaV; ++j) {
+            const int dim = (128 / kWaves) * wave + 8 * j;
+            const bf16* src = vg + (int64_t)(8 * j) * ldv + j0 + ((vslot ^ (((dim + vq) >> 1) & 7)) << 3);
             __builtin_amdgcn_global_load_lds(ATTS_GPTR(src), ATTS_LPTR(stage + kKBytes + dim * 128), 16, 0, 0);
         }
     };
@@ -163,12 +168,17 @@ __global__ __launch_bounds__(256, 2) void attn_mfma_kernel(const bf16* __restric
     float m_run = -1e30f;   // reference max (scaled, log2 domain), shared by the lane pair (l, l ^ 32)
     float l_run = 0.f;      // this lane's share of the running denominator
 
-    if (n_tiles > 0) issue_tile(0);
+    // Ring of kStages tiles: tiles 0 .. kStages - 2 are requested up front; at the top of step t the tiles up to
+    // t + kStages - 2 have been requested, tile t must have landed (the younger ones may stay in flight), and after
+    // the barrier tile t + kStages - 1 is requested into the stage that tile t - 1 occupied.
+#pragma unroll
+    for (int t = 0; t < kStages - 1; ++t)
+        if (t < n_tiles) issue_tile(t);
     for (int t = 0; t < n_tiles; ++t) {
         const int j0 = tile_start(t);
-        wait_vmcnt<0>();
+        if (t + kStages - 2 < n_tiles) wait_vmcnt<(kStages - 2) * (kDmaK + kDmaV)>(); else wait_vmcnt<0>();
         block_barrier();            // tile t is in LDS for every wave; every wave is done with tile t - 1
-        if (t + 1 < n_tiles) issue_tile(t + 1);
+        if (t + kStages - 1 < n_tiles) issue_tile(t + kStages - 1);
 
         // Wave-uniform visibility of this tile for the wave's rows rw0 .. rw1:
         //   nothing visible: the tile starts after the last row, or lies in drafts before the wave's first row's
@@ -176,7 +186,7 @@ __global__ __launch_bounds__(256, 2) void attn_mfma_kernel(const bf16* __restric
         const bool none = rw1 < rw0 || j0 > rw1 || (j0 >= P && j0 + kKTile <= seg_start(rw0, P, Tn));
         if (none) continue;
         const bool full = j0 + kKTile - 1 <= rw0 && (j0 + kKTile <= P || j0 >= ss_w1) && rw0 + 31 <= r_last;
-        const char* sK = smem + (t & 1) * kStage;
+        const char* sK = smem + (t % kStages) * kStage;
         const char* sV = sK + kKBytes;
 
         // ---- S^T = K Q^T for two 32-key blocks
@@ -193,35 +203,28 @@ __global__ __launch_bounds__(256, 2) void attn_mfma_kernel(const bf16* __restric
                 bf16x8 kf = *reinterpret_cast<const bf16x8*>(sK + kr * 256 + (((2 * s + g) ^ (kr & 15)) << 4));
                 acc_s[kb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, qf[s], acc_s[kb], 0, 0, 0);
             }
-        // acc_s[kb][4 a + b] = score of key j0 + 32 kb + 8 a + 4 g + b for this lane's query.
-        float mx = -INFINITY;
-        if (full) {
+        // acc_s[kb][4 a + b] = raw score (q . k) of key j0 + 32 kb + 8 a + 4 g + b for this lane's query.  The softmax
+        // works on z = score * scale * log2(e): the scale is folded into the one fused multiply-add in front of exp2.
+        if (!full) {
 #pragma unroll
             for (int kb = 0; kb < 2; ++kb)
 #pragma unroll
                 for (int v = 0; v < 16; ++v) {
-                    acc_s[kb][v] *= scale_log2e;
-                    mx = fmaxf(mx, acc_s[kb][v]);
-                }
-        } else {
-#pragma unroll
-            for (int kb = 0; kb < 2; ++kb)
-#pragma unroll
-                for (int v = 0; v < 16; ++v) {
-                    int j = j0 + 32 * kb + 8 * (v >> 2) + 4 * g + (v & 3);
-                    bool vis = r_ok && j <= r && (j < P || j >= ss);
-                    float sc = vis ? acc_s[kb][v] * scale_log2e : -INFINITY;
-                    acc_s[kb][v] = sc;
-                    mx = fmaxf(mx, sc);
+                    const int j = j0 + 32 * kb + 8 * (v >> 2) + 4 * g + (v & 3);
+                    const bool vis = r_ok && j <= r && (j < P || j >= ss);
+                    acc_s[kb][v] = vis ? acc_s[kb][v] : -INFINITY;
                 }
         }
-        mx = fmaxf(mx, __shfl_xor(mx, 32));
-        // Lazy rescaling: any reference value works in exp2(s - m) as long as it is the same for numerator and
+        float mx = fmaxf(acc_s[0][0], acc_s[1][0]);
+#pragma unroll
+        for (int v = 1; v < 16; ++v) mx = fmaxf(fmaxf(mx, acc_s[0][v]), acc_s[1][v]);    // one three-operand maximum each
+        mx = fmaxf(mx, __shfl_xor(mx, 32)) * scale_log2e;                                 // scale > 0: the order is kept
+        // Lazy rescaling: any reference value works in exp2(z - m) as long as it is the same for numerator and
         // denominator, so the running reference only moves when the new maximum exceeds it by more than 2^6
         // (p stays <= 64, far inside bf16 / fp32 range); the 64 accumulator multiplies are skipped otherwise.
         if (__builtin_amdgcn_ballot_w64(mx > m_run + 6.f) != 0) {
             const float m_new = fmaxf(m_run, mx);
-            const float alpha = exp2f(m_run - m_new);
+            const float alpha = __builtin_amdgcn_exp2f(m_run - m_new);
             m_run = m_new;
             l_run *= alpha;
 #pragma unroll
@@ -231,11 +234,12 @@ __global__ __launch_bounds__(256, 2) void attn_mfma_kernel(const bf16* __restric
         }
         float psum = 0.f;
         bf16x8 pf[4];
+        const float neg_m = -m_run;
 #pragma unroll
         for (int kb = 0; kb < 2; ++kb)
 #pragma unroll
             for (int v = 0; v < 16; ++v) {
-                float p = exp2f(acc_s[kb][v] - m_run);
+                const float p = __builtin_amdgcn_exp2f(__builtin_fmaf(acc_s[kb][v], scale_log2e, neg_m));   // -inf -> 0
                 psum += p;
                 pf[kb * 2 + (v >> 3)][v & 7] = (bf16)p;
             }
@@ -286,9 +290,23 @@ int32_t launch_attention(int32_t dtype, const void* qkv, const void* vt, int64_t
     if (attention_uses_vt(dtype, hd)) {
         if (!vt || ldv < (int64_t)align_up(R, kKTile) || ldv % 8)
             return fail(ATTS_ERR_WORKSPACE, "attention: transposed-V buffer missing or too narrow");
-        dim3 grid((unsigned)ceil_div(R - row0, kQTile), nq);
-        hipLaunchKernelGGL(attn_mfma_kernel, grid, dim3(256), 0, stream, (const bf16*)qkv, (const bf16*)vt, ldv, (bf16*)out,
-                           row0, R, s.P, s.T, nq, nkv, scale * 1.4426950408889634f);
+        // 256 query rows per workgroup (8 wavefronts, one workgroup per CU, loads two tiles ahead) once the call has
+        // enough rows to fill the chip that way; 128 rows (4 wavefronts, two workgroups per CU) for smaller calls
+        constexpr int kStage = 2 * kKTile * kHd * 2;
+        const float sc2 = scale * 1.4426950408889634f;
+        if ((int64_t)ceil_div(R - row0, 256) * nq >= 256) {
+            constexpr size_t lds = 3 * kStage;
+            int32_t rc = allow_dynamic_lds<attn_mfma_kernel<8, 3>>(lds);
+            if (rc != ATTS_OK) return rc;
+            hipLaunchKernelGGL((attn_mfma_kernel<8, 3>), dim3((unsigned)ceil_div(R - row0, 256), nq), dim3(512), lds, stream, (const bf16*)qkv,
+                               (const bf16*)vt, ldv, (bf16*)out, row0, R, s.P, s.T, nq, nkv, sc2);
+        } else {
+            constexpr size_t lds = 2 * kStage;
+            int32_t rc = allow_dynamic_lds<attn_mfma_kernel<4, 2>>(lds);
+            if (rc != ATTS_OK) return rc;
+            hipLaunchKernelGGL((attn_mfma_kernel<4, 2>), dim3((unsigned)ceil_div(R - row0, 128), nq), dim3(256), lds, stream, (const bf16*)qkv,
+                               (const bf16*)vt, ldv, (bf16*)out, row0, R, s.P, s.T, nq, nkv, sc2);
+        }
         ATTS_LAUNCH_CHECK("attn_mfma_kernel");
         return ATTS_OK;
     }

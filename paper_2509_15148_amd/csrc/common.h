@@ -5,6 +5,8 @@
 #include <stddef.h>
 #include <stdint.h>
 
+#include <mutex>
+
 #include "atts.h"
 
 namespace atts {
@@ -49,6 +51,22 @@ private:
     hipEvent_t start_{}, stop_{};
     bool live_ = false;
 };
+
+// Raises the dynamic LDS limit of a kernel, once per device (the attribute belongs to the device's copy of the code).
+template <auto kKernel>
+inline int32_t allow_dynamic_lds(size_t bytes) {
+    static std::mutex mutex;
+    static bool done[64] = {};
+    int dev = 0;
+    ATTS_HIP_TRY(hipGetDevice(&dev));
+    if (dev < 0 || dev >= 64) return fail(ATTS_ERR_HIP, "device index %d out of range", dev);
+    std::lock_guard<std::mutex> lock(mutex);
+    if (!done[dev]) {
+        ATTS_HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void*>(kKernel), hipFuncAttributeMaxDynamicSharedMemorySize, (int)bytes));
+        done[dev] = true;
+    }
+    return ATTS_OK;
+}
 
 inline size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
 inline int64_t ceil_div(int64_t a, int64_t b) { return (a + b - 1) / b; }

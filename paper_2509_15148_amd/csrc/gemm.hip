@@ -7,8 +7,6 @@
 //   gemm_bf16_wide_kernel   aligned bf16 shapes (every projection of the bf16 models): 8 wavefronts,
 //                           384 x 256, 256 x 256 or 128 x 256 output tiles, operand slabs of 128 bytes
 //                           per row DMA-ed global -> LDS in whole 128-byte lines, explicit waits.
-//   gemm_bf16_fast_kernel   the same with 64-byte slabs and a deeper ring, for inner dimensions
-//                           that are a multiple of 32 but not of 64.
 //   gemm_nt_kernel          any shape, bf16 or fp32 (v_mfma_f32_32x32x2_f32): 4 wavefronts (2 x 2),
 //                           tile BM x BN, 128-byte slabs through registers with bounds checks,
 //                           double-buffered, one barrier per slab; LDS chunk index XOR (row >> 1) & 7.
@@ -24,10 +22,7 @@ namespace {
 
 constexpr int kThreads = 256;
 constexpr int kRowBytes = 128;  // bytes of K per LDS row per slab
-#ifndef ATTS_GROUP_M
-#define ATTS_GROUP_M 8
-#endif
-constexpr int kGroupM = ATTS_GROUP_M;
+constexpr int kGroupM = 8;      // tile rows per group of the XCD-aware order
 
 template <typename T> struct Mma;
 
@@ -358,202 +353,6 @@ __global__ __launch_bounds__(kThreads) void gemm_nt_kernel(const char* __restric
 }
 
 // ---------------------------------------------------------------------------------------------
-// Fast path: bf16, 256 x 256 tiles, every tile full (M % 256 == 0, N % tile width == 0,
-// Kd % slab == 0).  Differences from the general kernel above:
-//   * operand slabs go global -> LDS directly (global_load_lds_dwordx4, 1 KiB per wave
-//     instruction), so no staging registers and no ds_write; the XOR swizzle is applied on the
-//     global side (lane i fetches the chunk that belongs at LDS position i);
-//   * a ring of kStages slabs with kStages - 1 slabs in flight; waits are explicit
-//     (s_waitcnt vmcnt(n) + s_barrier) so that younger loads stay in flight across the barrier;
-//   * fragments of the next k-step are read from LDS while the MFMAs of the current one issue.
-// ---------------------------------------------------------------------------------------------
-template <int EPI, int kWavesM /* waves along M (2 along N) */, int MI /* 32-row blocks per wave */, int kStages>
-__global__ __launch_bounds__(128 * kWavesM) void gemm_bf16_fast_kernel(const char* __restrict__ gA,
-                                                                       const char* __restrict__ gW,
-                                                                       void* __restrict__ g_out,
-                                                                       const int32_t* __restrict__ g_targets,
-                                                                       float2* __restrict__ g_partials,
-                                                                       float* __restrict__ g_target_logit,
-                                                                       const float2* __restrict__ g_rope,
-                                                                       void* __restrict__ g_vt, const GemmDims g) {
-    constexpr int BN = 256, NI = 4, WN = 128;
-    constexpr int WM = 32 * MI, BM = kWavesM * WM;  // 256 or 384 rows
-    constexpr int kWaves = 2 * kWavesM;
-    constexpr int N_OUT = (EPI == EPI_SWIGLU) ? BN / 2 : BN;
-    constexpr int BKB = 64;                        // bytes of K per row per slab
-    constexpr int BK = BKB / 2;                    // bf16 elements per slab (two MFMA k-steps)
-    constexpr int CHUNKS = BKB / 16;               // 16-byte chunks per LDS row
-    constexpr int kSwzShift = 2;                   // chunk ^= (row >> 2) & 3: conflict-free on the 64-bank LDS
-    constexpr int ROWS_PER_DMA = 1024 / BKB;       // tile rows filled by one wave-wide DMA instruction (16)
-    constexpr int DMA_A = BM / ROWS_PER_DMA / kWaves;   // DMA instructions per wave and slab for the A rows
-    constexpr int DMA_B = BN / ROWS_PER_DMA / kWaves;   // ... and for the W rows
-    static_assert(DMA_A * ROWS_PER_DMA * kWaves == BM && DMA_B * ROWS_PER_DMA * kWaves == BN, "tile rows per wave");
-    constexpr int STAGE_BYTES = (BM + BN) * BKB;   // 32 or 40 KiB
-    constexpr int kAhead = kStages - 1;            // slab kt + kAhead is the youngest one issued during slab kt
-
-    extern __shared__ __attribute__((aligned(16))) char smem[];   // [kStages][A: BM rows | B: BN rows][BKB]
-
-    const int tid = threadIdx.x;
-    const int lane = tid & 63;
-    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);   // wave-uniform: keeps LDS/DMA bases in scalar registers
-    const int wm = wave >> 1, wn = wave & 1;
-    const int l32 = lane & 31, half = lane >> 5;
-
-    // k_slices > 1: workgroup = (tile, K slice); slice s covers slabs [s nk / S, (s + 1) nk / S)
-    const int n_tiles = g.nt_m * g.nt_n;
-    const int slice = g.k_slices > 1 ? (int)blockIdx.x / n_tiles : 0;
-    const int nk_all = g.Kd / BK;
-    const int k_first = (int)((int64_t)slice * nk_all / g.k_slices);
-    const int nk = (int)((int64_t)(slice + 1) * nk_all / g.k_slices) - k_first;   // >= kStages + 1 (checked on the host)
-    const TileCoord tc = tile_of_block((int)blockIdx.x - slice * n_tiles, g.nt_m, g.nt_n);
-    const int m0 = tc.tm * BM;
-    const int n0 = tc.tn * N_OUT;
-
-    // ---- DMA addressing.  DMA instruction j of this wave fills LDS rows r0 = (wave DMA_x + j) 16 ... r0 + 15
-    // of an operand tile; lane i lands at row r0 + i / 4, chunk slot i % 4, and therefore fetches logical chunk
-    // slot ^ swz(row).  r0 is a multiple of 16, so swz(row) = swz(i / 4): one 32-bit per-lane byte offset per
-    // operand serves every j; the row bases are wave-uniform (scalar registers).
-    const int dq = lane / CHUNKS, dslot = lane % CHUNKS;
-    auto swz = [](int row) { return (row >> kSwzShift) & (CHUNKS - 1); };
-    static_assert(ROWS_PER_DMA % (CHUNKS << kSwzShift) == 0, "swizzle must not depend on the DMA instruction index");
-    uint32_t a_lane_off = (uint32_t)dq * (uint32_t)(g.lda * 2) + (uint32_t)((dslot ^ swz(dq)) * 16) + (uint32_t)k_first * BKB;
-    uint32_t b_lane_off = (uint32_t)dq * (uint32_t)(g.ldw * 2) + (uint32_t)((dslot ^ swz(dq)) * 16) + (uint32_t)k_first * BKB;
-    const char* a_base[DMA_A];
-    const char* b_base[DMA_B];
-#pragma unroll
-    for (int j = 0; j < DMA_A; ++j) a_base[j] = gA + (int64_t)(m0 + (wave * DMA_A + j) * ROWS_PER_DMA) * g.lda * 2;
-#pragma unroll
-    for (int j = 0; j < DMA_B; ++j) {
-        const int r0 = (wave * DMA_B + j) * ROWS_PER_DMA;
-        int64_t wrow = r0;                                        // W row (relative to n0) feeding LDS row r0
-        if (EPI == EPI_SWIGLU) {
-            constexpr int H = WN / 2;                             // wave slab = [gate H | up H]
-            const int jw = r0 / WN, jj = r0 % WN;
-            wrow = (int64_t)(jj / H) * g.N + jw * H + jj % H;
-        }
-        b_base[j] = gW + (n0 + wrow) * g.ldw * 2;
-    }
-    // A slab is issued in two halves (the A rows, then the W rows); both are issued in slab order.
-    auto issue_a = [&](int kt) __attribute__((always_inline)) {
-        char* stage = smem + (kt % kStages) * STAGE_BYTES;
-#pragma unroll
-        for (int j = 0; j < DMA_A; ++j) {
-            const int r0 = (wave * DMA_A + j) * ROWS_PER_DMA;
-            __builtin_amdgcn_global_load_lds(ATTS_GPTR(a_base[j] + a_lane_off), ATTS_LPTR(stage + r0 * BKB), 16, 0, 0);
-        }
-        a_lane_off += BKB;
-    };
-    auto issue_b = [&](int kt) __attribute__((always_inline)) {
-        char* stage = smem + (kt % kStages) * STAGE_BYTES + BM * BKB;
-#pragma unroll
-        for (int j = 0; j < DMA_B; ++j) {
-            const int r0 = (wave * DMA_B + j) * ROWS_PER_DMA;
-            __builtin_amdgcn_global_load_lds(ATTS_GPTR(b_base[j] + b_lane_off), ATTS_LPTR(stage + r0 * BKB), 16, 0, 0);
-        }
-        b_lane_off += BKB;
-    };
-
-    // ---- fragment addressing: rows wm WM + 32 i + l32 (A) / wn WN + 32 j + l32 (B); the swizzle term
-    // depends on l32 only because 32 i, WM and WN are multiples of CHUNKS << kSwzShift.
-    const int frag_xor = swz(l32);
-    const int a_row_off = (wm * WM + l32) * BKB;
-    const int b_row_off = BM * BKB + (wn * WN + l32) * BKB;
-    auto load_frags = [&](int kt, int s, bf16x8 (&fa)[MI], bf16x8 (&fb)[NI]) __attribute__((always_inline)) {
-        const char* stage = smem + (kt % kStages) * STAGE_BYTES;
-        const int coff = ((2 * s + half) ^ frag_xor) << 4;
-#pragma unroll
-        for (int i = 0; i < MI; ++i) fa[i] = *reinterpret_cast<const bf16x8*>(stage + a_row_off + i * 32 * BKB + coff);
-#pragma unroll
-        for (int j = 0; j < NI; ++j) fb[j] = *reinterpret_cast<const bf16x8*>(stage + b_row_off + j * 32 * BKB + coff);
-    };
-
-    f32x16 acc[MI][NI];
-#pragma unroll
-    for (int i = 0; i < MI; ++i)
-#pragma unroll
-        for (int j = 0; j < NI; ++j)
-#pragma unroll
-            for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.f;
-    auto mma_step = [&](bf16x8 (&fa)[MI], bf16x8 (&fb)[NI]) __attribute__((always_inline)) {
-#pragma unroll
-        for (int i = 0; i < MI; ++i)
-#pragma unroll
-            for (int j = 0; j < NI; ++j) acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[i], fb[j], acc[i][j], 0, 0, 0);
-    };
-    // Scheduling hint for one k-step: MFMAs with the fragment reads of the next k-step and the DMA issues of
-    // half a slab spread evenly underneath.  (The texture path accepts one 1 KiB DMA instruction per ~16
-    // cycles per CU; issued back to back they block the wave, and with it the MFMAs, for that long.)
-    constexpr int kReads = MI + NI, kMfma = MI * NI;
-    static_assert(kMfma >= kReads, "the hint pairs every fragment read with an MFMA");
-    auto interleave_hint = [&](auto n_dma_, auto sync_id) __attribute__((always_inline)) {
-        constexpr int kId = decltype(sync_id)::value;   // std::integral_constant
-        constexpr int n_dma = decltype(n_dma_)::value;  // DMA instructions issued in this k-step (0: none)
-        constexpr int stride = kReads / (n_dma > 0 ? n_dma : 1) > 0 ? kReads / (n_dma > 0 ? n_dma : 1) : 1;
-#pragma unroll
-        for (int r = 0; r < kReads; ++r) {
-            __builtin_amdgcn_sched_group_barrier(0x008, 1, kId);                                    // MFMA
-            if (n_dma > 0 && r % stride == 0 && r / stride < n_dma)
-                __builtin_amdgcn_sched_group_barrier(0x020, 1, kId);                                // VMEM read (LDS DMA)
-            __builtin_amdgcn_sched_group_barrier(0x100, 1, kId);                                    // DS read
-        }
-        __builtin_amdgcn_sched_group_barrier(0x008, kMfma - kReads, kId);
-    };
-    using NoDma = std::integral_constant<int, 0>;
-    using DmaA = std::integral_constant<int, DMA_A>;
-    using DmaB = std::integral_constant<int, DMA_B>;
-    using Id0 = std::integral_constant<int, 0>;
-    using Id1 = std::integral_constant<int, 1>;
-
-    // Ring of kStages slabs.  During slab kt:
-    //   k-step 0   MFMAs; underneath: fragments of k-step 1, DMA of the W half of slab kt + kAhead - 1
-    //   barrier    slab kt + 1 has landed for every wave, and every wave is done with slab kt - 1
-    //   k-step 1   MFMAs; underneath: FIRST fragments of slab kt + 1 (no LDS latency is exposed at the slab
-    //              boundary), DMA of the A half of slab kt + kAhead into the stage slab kt - 1 occupied
-    // so the DMA instructions are spread one by one under the MFMAs and a slab has kStages - 3 full slab times
-    // plus one k-step to land after its last DMA instruction.
-#pragma unroll
-    for (int s = 0; s < kAhead; ++s) {
-        issue_a(s);
-        if (s + 1 < kAhead) issue_b(s);
-    }
-    // issued so far, in order: A0 B0 A1 B1 ... A(kAhead-1); slab 0 = the two oldest halves
-    wait_vmcnt<(kAhead - 1) * DMA_A + (kAhead - 2) * DMA_B>();
-    block_barrier();
-    bf16x8 fa[2][MI], fb[2][NI];
-    load_frags(0, 0, fa[0], fb[0]);
-
-    // flags: slab kt + 1 exists | W half of slab kt + kAhead - 1 still to issue | A half of slab kt + kAhead to issue
-    auto slab = [&](int kt, auto has_next, auto issue_w, auto issue_next_a, auto steady) __attribute__((always_inline)) {
-        load_frags(kt, 1, fa[1], fb[1]);
-        if (issue_w) issue_b(kt + kAhead - 1);
-        mma_step(fa[0], fb[0]);
-        if (issue_w) interleave_hint(DmaB{}, Id0{}); else interleave_hint(NoDma{}, Id0{});
-        if (has_next) {
-            // outstanding after slab kt + 1: slabs kt + 2 .. kt + kAhead - 1 in full
-            if (steady) wait_vmcnt<(kAhead - 2) * (DMA_A + DMA_B)>(); else wait_vmcnt<0>();
-            block_barrier();
-            __builtin_amdgcn_sched_barrier(0);     // the two k-steps are scheduled as separate regions
-            load_frags(kt + 1, 0, fa[0], fb[0]);
-            if (issue_next_a) issue_a(kt + kAhead);
-        }
-        mma_step(fa[1], fb[1]);
-        if (has_next) {
-            if (issue_next_a) interleave_hint(DmaA{}, Id1{}); else interleave_hint(NoDma{}, Id1{});
-        }
-    };
-    struct Yes { constexpr operator bool() const { return true; } };
-    struct No { constexpr operator bool() const { return false; } };
-    int kt = 0;
-    for (; kt + kAhead < nk; ++kt) slab(kt, Yes{}, Yes{}, Yes{}, Yes{});
-    // kt = nk - kAhead: the W half of the last slab is still to be issued, nothing after it
-    slab(kt, Yes{}, Yes{}, No{}, No{});
-    for (++kt; kt + 1 < nk; ++kt) slab(kt, Yes{}, No{}, No{}, No{});
-    slab(kt, No{}, No{}, No{}, No{});
-
-    gemm_epilogue<bf16, MI, NI, EPI>(acc, m0, n0, wm, wn, l32, half, tc.tn, g_out, g_targets, g_partials, g_target_logit, g_rope, g_vt, g);
-}
-
-// ---------------------------------------------------------------------------------------------
 // Wide-slab variant of the aligned kernel: 128 bytes of K per row and slab, so that every DMA instruction
 // asks L2 for whole 128-byte lines (8 rows x 128 B instead of 16 rows x 64 B).  L2 -> LDS delivery, which bounds
 // the 64-byte version, is ~1.4x faster that way; the price is LDS: 160 KB hold only 2.5 slabs of a 256 x 256 tile
@@ -803,18 +602,21 @@ __global__ __launch_bounds__(128 * kWavesM) void gemm_bf16_wide_kernel(const cha
                                           g_vt, g, resid0, resid_ahead);
 }
 
-constexpr int kFastBK = 32;
-#ifndef ATTS_FAST_WAVES_M
-#define ATTS_FAST_WAVES_M 4
-#endif
-#ifndef ATTS_FAST_STAGES
-#define ATTS_FAST_STAGES 5
-#endif
+#define ATTS_TRY_RC(expr)                 \
+    do {                                  \
+        int32_t rc__ = (expr);            \
+        if (rc__ != ATTS_OK) return rc__; \
+    } while (0)
 
+constexpr int kWideBK = 64;           // K elements per slab of the aligned kernel
+constexpr int kWavesM = 4;            // wavefronts along M (2 along N)
+constexpr int kMinSlabs = 12;         // every K slice must fill the DMA ring
+
+// Shapes the aligned bf16 kernel takes: whole tiles (or padded A rows), K a multiple of the slab.
 bool fast_path_ok(int32_t dtype, int epi, const GemmArgs& g) {
     const int n_out = epi == EPI_SWIGLU ? 128 : 256;
-    return dtype == ATTS_DTYPE_BF16 && (g.M % 256 == 0 || g.a_rows_padded) && g.N % n_out == 0 && g.Kd % kFastBK == 0 &&
-           g.Kd >= (ATTS_FAST_STAGES + 1) * kFastBK && g.lda * 2 * 17 < (1ll << 31) && g.ldw * 2 * 17 < (1ll << 31);
+    return dtype == ATTS_DTYPE_BF16 && (g.M % 256 == 0 || g.a_rows_padded) && g.N % n_out == 0 && g.Kd % kWideBK == 0 &&
+           g.Kd >= kMinSlabs * kWideBK && g.lda * 2 * 17 < (1ll << 31) && g.ldw * 2 * 17 < (1ll << 31);
 }
 
 // Tile height of the aligned kernel: 384-row tiles move 1/6 fewer operand bytes per flop through L2 -> LDS than
@@ -834,49 +636,14 @@ int fast_tile_rows(int epi, const GemmArgs& g) {
 int fast_k_slices(int epi, int n_tiles, int nk) {
     if (epi != EPI_RESID_F32 || n_tiles >= 128) return 1;
     int s = 256 / n_tiles;                                   // never more workgroups than CUs: no second round
-    const int max_s = nk / (ATTS_FAST_STAGES + 1);           // every slice still fills the DMA ring once
+    const int max_s = nk / 6;                                // every slice still walks several slabs
     if (s > max_s) s = max_s;
     return s < 1 ? 1 : s;
 }
 
-template <int EPI, int MI>
-int32_t launch_fast_tile(const GemmArgs& g, hipStream_t stream) {
-    constexpr int n_out = (EPI == EPI_SWIGLU) ? 128 : 256;
-    constexpr int kWavesM = ATTS_FAST_WAVES_M;
-    constexpr int BM = kWavesM * MI * 32;
-    constexpr int kStages = BM > 256 ? 4 : ATTS_FAST_STAGES;          // 160 KB of LDS either way
-    GemmDims d;
-    d.M = g.M; d.N = g.N; d.Kd = g.Kd;
-    d.lda = g.lda; d.ldw = g.ldw; d.ldc = g.ldc;
-    d.n_part = g.n_part;
-    d.ldv = g.ldv;
-    d.n_rot_heads = g.n_rot_heads;
-    d.nt_m = (int)ceil_div(g.M, BM);
-    d.nt_n = g.N / n_out;
-    d.k_slices = fast_k_slices(EPI, d.nt_m * d.nt_n, g.Kd / kFastBK);
-    const size_t lds = (size_t)kStages * (BM + 256) * 2 * kFastBK;
-    auto kern = gemm_bf16_fast_kernel<EPI, kWavesM, MI, kStages>;
-    static bool attr_set = false;   // per instantiation
-    if (!attr_set) {
-        ATTS_HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
-                                         hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
-        attr_set = true;
-    }
-    hipLaunchKernelGGL(kern, dim3(d.nt_m * d.nt_n * d.k_slices), dim3(128 * kWavesM), lds, stream,
-                       reinterpret_cast<const char*>(g.a), reinterpret_cast<const char*>(g.w), g.out, g.targets, g.partials,
-                       g.target_logit, g.rope, g.vt, d);
-    ATTS_LAUNCH_CHECK("gemm_bf16_fast_kernel");
-    return ATTS_OK;
-}
-
-#ifndef ATTS_GEMM_WIDE
-#define ATTS_GEMM_WIDE 1
-#endif
-
 template <int EPI, int MI, int NI = 4>
 int32_t launch_wide_tile(const GemmArgs& g, hipStream_t stream) {
     constexpr int n_out = (EPI == EPI_SWIGLU) ? 32 * NI : 64 * NI;
-    constexpr int kWavesM = ATTS_FAST_WAVES_M;
     constexpr int BM = kWavesM * MI * 32;
     GemmDims d;
     d.M = g.M; d.N = g.N; d.Kd = g.Kd;
@@ -888,14 +655,8 @@ int32_t launch_wide_tile(const GemmArgs& g, hipStream_t stream) {
     d.nt_n = g.N / n_out;
     d.k_slices = fast_k_slices(EPI, d.nt_m * d.nt_n, g.Kd / 64);
     const size_t lds = 160 * 1024;
-    auto kern = gemm_bf16_wide_kernel<EPI, kWavesM, MI, NI>;
-    static bool attr_set = false;   // per instantiation
-    if (!attr_set) {
-        ATTS_HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
-                                         hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
-        attr_set = true;
-    }
-    hipLaunchKernelGGL(kern, dim3(d.nt_m * d.nt_n * d.k_slices), dim3(128 * kWavesM), lds, stream,
+    ATTS_TRY_RC((allow_dynamic_lds<gemm_bf16_wide_kernel<EPI, kWavesM, MI, NI>>(lds)));
+    hipLaunchKernelGGL((gemm_bf16_wide_kernel<EPI, kWavesM, MI, NI>), dim3(d.nt_m * d.nt_n * d.k_slices), dim3(128 * kWavesM), lds, stream,
                        reinterpret_cast<const char*>(g.a), reinterpret_cast<const char*>(g.w), g.out, g.targets, g.partials,
                        g.target_logit, g.rope, g.vt, d);
     ATTS_LAUNCH_CHECK("gemm_bf16_wide_kernel");
@@ -904,16 +665,14 @@ int32_t launch_wide_tile(const GemmArgs& g, hipStream_t stream) {
 
 template <int EPI>
 int32_t launch_fast(const GemmArgs& g, hipStream_t stream) {
-    constexpr int kWavesM = ATTS_FAST_WAVES_M;
-    const bool wide = ATTS_GEMM_WIDE && g.Kd % 64 == 0 && g.Kd >= 12 * 64;
-    if (fast_tile_rows(EPI, g) == 128 && wide && kWavesM == 4) {
+    const int rows = fast_tile_rows(EPI, g);
+    if (rows == 128) {
         // narrow outputs that split K: 128-column tiles double the tiles, so half as many K slices (and atomics) fill the chip
         if constexpr (EPI == EPI_RESID_F32) return launch_wide_tile<EPI, 1, 2>(g, stream);
         return launch_wide_tile<EPI, 1>(g, stream);
     }
-    if (fast_tile_rows(EPI, g) == 384)
-        return wide ? launch_wide_tile<EPI, 12 / kWavesM>(g, stream) : launch_fast_tile<EPI, 12 / kWavesM>(g, stream);
-    return wide ? launch_wide_tile<EPI, 8 / kWavesM>(g, stream) : launch_fast_tile<EPI, 8 / kWavesM>(g, stream);
+    if (rows == 384) return launch_wide_tile<EPI, 3>(g, stream);
+    return launch_wide_tile<EPI, 2>(g, stream);
 }
 
 template <typename T, int BM, int BN, int EPI>
@@ -929,14 +688,8 @@ int32_t launch_cfg(const GemmArgs& g, hipStream_t stream) {
     d.nt_m = (int)ceil_div(g.M, BM);
     d.nt_n = (int)ceil_div(g.N, n_out);
     const size_t lds = 2 * (size_t)(BM + BN) * kRowBytes;
-    auto kern = gemm_nt_kernel<T, BM, BN, EPI>;
-    static bool attr_set = false;   // per instantiation
-    if (!attr_set) {
-        ATTS_HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
-                                         hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
-        attr_set = true;
-    }
-    hipLaunchKernelGGL(kern, dim3(d.nt_m * d.nt_n), dim3(kThreads), lds, stream, reinterpret_cast<const char*>(g.a),
+    ATTS_TRY_RC((allow_dynamic_lds<gemm_nt_kernel<T, BM, BN, EPI>>(lds)));
+    hipLaunchKernelGGL((gemm_nt_kernel<T, BM, BN, EPI>), dim3(d.nt_m * d.nt_n), dim3(kThreads), lds, stream, reinterpret_cast<const char*>(g.a),
                        reinterpret_cast<const char*>(g.w), g.out, g.targets, g.partials, g.target_logit, g.rope, g.vt, d);
     ATTS_LAUNCH_CHECK("gemm_nt_kernel");
     return ATTS_OK;
