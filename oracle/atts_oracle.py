@@ -36,13 +36,21 @@ What is defined here, and from where:
   * conditional coverage (same paragraph, last sentence; Proposition 2): the same rank,
     p-value and classes, but each input's candidates are compared with that input's own
     calibration scores only.
+  * the classic, synchronous pipeline the method is measured against (Sec. "Preliminary",
+    "Classic Setup"): scores normalised over the m candidates of an input (Eq. "softmax"),
+    one global threshold tau = an order statistic of ALL normalised calibration scores
+    (Eq. "quantile") and the prediction set {k : s^k >= tau} (Eq. "pred_set").  No candidate of
+    an input can be decided before all m of its scores are there: the synchronisation the
+    asynchronous arithmetic intensity of Sec. "Q1" charges as T_s.
 
 Pins (see tests/test_oracle_*.py): closed forms for the log-softmax and for degenerate
 models, causal-prefix invariances of the forward pass, the uniform distribution of
 p-values for distinct scores and the tie formula of Proposition 1's proof, exact
 enumeration of the coverage guarantee (marginal, and per input for the conditional
 variant: Proposition 2's uniform law), equivalence of the rank rule with the classic
-quantile rule, and hand-worked fixtures under tests/golden/.  The decoder forward has no
+quantile rule, hand-worked fixtures under tests/golden/, and for the classic pipeline the
+logistic closed form of a two-candidate softmax, shift invariance, the brute-force
+definition of an order statistic and the set size floor(alpha (N + 1)) on distinct scores.  The decoder forward has no
 paper-printed numeric example: beyond the invariants and closed forms it is
 "parity unpinned" to any external numeric source.
 """
@@ -332,6 +340,44 @@ def conditional_classify(cal_sets, test_sets, alphas: Sequence[float]):
         ps.append(p_values(c, len(cal)))
         classes.append(classify(c, r))
     return counts, ps, classes
+
+
+# --------------------------------------------------------------------------------------
+# The classic (synchronous) pipeline: normalised scores, global quantile, prediction sets
+# --------------------------------------------------------------------------------------
+
+def classic_softmax_scores(nll: np.ndarray) -> np.ndarray:
+    """Eq. "softmax": s[i, k] = exp(-l[i, k]) / sum_j exp(-l[i, j]) over the m candidates of input i.
+
+    `nll` [n, m] holds l(X_i, Y_i^k) >= 0, the negative log-likelihood of candidate k (the unnormalised
+    score of the asynchronous design), so s is the candidate's share of the likelihood mass of its input:
+    larger = more likely.  The row minimum of l is subtracted from the row before exponentiating; the
+    quotient is unchanged by it (numerator and denominator are both multiplied by exp(min l)) and rows with
+    l in the thousands (SUM scores of long drafts) do not underflow to 0 / 0."""
+    l = np.asarray(nll, dtype=F64)
+    assert l.ndim == 2
+    e = np.exp(-(l - l.min(axis=1, keepdims=True)))
+    return e / e.sum(axis=1, keepdims=True)
+
+
+def classic_threshold(cal_scores: np.ndarray, alpha: float) -> float:
+    """Eq. "quantile": tau = the p-quantile of ALL N normalised calibration scores, p = ceil((N + 1)(1 - alpha)) / N,
+    i.e. the k-th smallest of them with k = ceil((N + 1)(1 - alpha)) = N + 1 - floor(alpha (N + 1))
+    (the floor taken of one binary64 product, the same integer the rank rule uses); +inf if k > N, -inf if k < 1.
+    This is the global sort every turn of the synchronous design pays for."""
+    s = np.sort(np.asarray(cal_scores, dtype=F64).ravel())
+    n = len(s)
+    k = n + 1 - math.floor(float(alpha) * float(n + 1))
+    if k > n:
+        return math.inf
+    if k < 1:
+        return -math.inf
+    return float(s[k - 1])
+
+
+def classic_prediction_sets(scores: np.ndarray, tau: float) -> np.ndarray:
+    """Eq. "pred_set": C(X_i) = {k : s[i, k] >= tau}, returned as a uint8 membership mask shaped like `scores`."""
+    return (np.asarray(scores, dtype=F64) >= tau).astype(np.uint8)
 
 
 class CalibrationSet:
