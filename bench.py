@@ -82,15 +82,36 @@ def cpu_baseline(cfg, wl, w_dev, prefix, drafts, n_layers_full, budget_layers):
     t2 = time.perf_counter()
     t_layers, t_head = t1 - t0, t2 - t1
     t_full = t_layers * n_layers_full / max(budget_layers, 1) + t_head
+    whole = budget_layers == n_layers_full
     return {
         "value": wl.T / t_full, "unit": "tokens/s", "cores": torch.get_num_threads(), "kind": "oracle",
-        "sample": (f"numpy fp64 oracle, 1 of {wl.K} drafts ({wl.P}+{wl.T} tokens), {budget_layers} of "
-                   f"{n_layers_full} layers timed ({t_layers:.1f} s) + LM head ({t_head:.1f} s); value = "
-                   f"{wl.T} tokens / (layer time x {n_layers_full}/{budget_layers} + head time), an extrapolation"),
+        "extrapolated": not whole,
+        "sample": (f"numpy fp64 oracle, 1 of {wl.K} drafts ({wl.P}+{wl.T} tokens) through "
+                   + (f"all {n_layers_full} layers ({t_layers:.1f} s) + LM head ({t_head:.1f} s); value = {wl.T} tokens / that time"
+                      if whole else
+                      f"{budget_layers} of {n_layers_full} layers ({t_layers:.1f} s) + LM head ({t_head:.1f} s); value = "
+                      f"{wl.T} tokens / (layer time x {n_layers_full}/{budget_layers} + head time), an extrapolation by layer count")),
     }
 
 
-def bench_calibration(A, torch, np, steps=16, scaled=False):
+def calibration_cpu_baseline(np, torch, n_cal, n_new, n_test, alphas, draw, steps, note):
+    """The oracle's conformal layer on the calibration-only step: append n_new scores, then ranks (library sort + binary
+    search form of Eq. "p-value"), classes and thresholds of n_test scores; wall time per step on the host cores."""
+    from oracle import atts_oracle as O
+    cs = O.CalibrationSet()
+    cs.append(draw(n_cal, 1))
+    new = [draw(n_new, 10 + i) for i in range(steps)]
+    test = [draw(n_test, 100 + i) for i in range(steps)]
+    t0 = time.perf_counter()
+    for i in range(steps):
+        cs.append(new[i])
+        cs.classify(test[i], alphas, brute_force=False)
+    dt = (time.perf_counter() - t0) / steps
+    return {"value": n_test / dt, "unit": "decisions/s", "cores": torch.get_num_threads(), "kind": "oracle",
+            "us_per_step": dt * 1e6, "sample": note}
+
+
+def bench_calibration(A, torch, np, steps=16, scaled=False, cpu=True):
     """The calibration-only workload: 2^20 resident scores, then per step append 65,536 and classify 65,536 at
     two alpha levels.  scaled=True: the same step at an out-of-cache size (2^28 resident scores = 1 GiB of keys,
     2^24 appended and 2^24 classified per step), where the HBM roofline is the meaningful bound; its scores are
@@ -163,6 +184,18 @@ def bench_calibration(A, torch, np, steps=16, scaled=False):
     }
     if not scaled:
         out["note"] = "working set (4-8 MB) is cache resident and a step is a few short kernels: latency bound, not HBM bound"
+    if cpu:
+        host_draw = lambda n, seed: lognormal_scores(n, wl.seed + 5000 + seed)
+        if scaled:       # a bounded sample: 1/16 of the resident set and of the batches
+            out["cpu_baseline"] = calibration_cpu_baseline(
+                np, torch, n_cal >> 4, n_new >> 4, n_test >> 4, list(wl.alphas), host_draw, 2,
+                f"numpy fp64 oracle (sort + binary search), 2 steps at 1/16 of the sizes: {n_cal >> 4} resident scores, "
+                f"{n_new >> 4} appended and {n_test >> 4} classified per step")
+        else:
+            out["cpu_baseline"] = calibration_cpu_baseline(
+                np, torch, n_cal, n_new, n_test, list(wl.alphas), host_draw, 4,
+                f"numpy fp64 oracle (sort + binary search), 4 full steps of the workload: {n_cal} resident scores, {n_new} appended "
+                f"and {n_test} classified per step")
     return out
 
 
@@ -186,6 +219,128 @@ def bench_conditional(A, torch, np, S=4096, m=64, k=64, reps=20):
     dt = (time.perf_counter() - t0) / reps
     return {"workload": f"{S} inputs x {m} own calibration scores x {k} candidates, alphas {list(wl.alphas)}",
             "us_per_call": dt * 1e6, "decisions_per_s": S * k / dt, "comparisons_per_s": S * m * k / dt}
+
+
+def bench_decision_flips(A, torch, np, n_batches=25):
+    """End-to-end decision flips: config 1 (Tiny: 200 calibration scores from 25 batches of 8 drafts, alpha 0.1), the same
+    token ids through the HIP path and through the oracle; every candidate of 25 further batches is classified by the
+    same rule on each side with that side's own scores.  A flip = a candidate whose two classes differ; it can only come
+    from the score error (the classifiers agree bit for bit given equal scores).  Done for the fp32 model and for the
+    same architecture stored in bf16."""
+    import dataclasses
+    from oracle import atts_oracle as O
+    from synth import WORKLOADS, make_token_ids, make_weights
+    wl = WORKLOADS["tiny"]
+    res = {}
+    for dtype in ("fp32", "bf16"):
+        cfg = dataclasses.replace(wl.model, dtype=dtype)
+        w = make_weights(cfg, wl.seed, device="cuda")
+        w_np = {k: ([t.float().cpu().numpy() for t in v] if isinstance(v, list) else v.float().cpu().numpy()) for k, v in w.items()}
+        model = A.Model(cfg, w)
+        ws = torch.empty(A.atts_workspace_bytes(model, wl.P, wl.K, wl.T), dtype=torch.uint8, device="cuda")
+        sc = torch.empty(wl.K, dtype=torch.float32, device="cuda")
+        g_scores, o_scores = [], []
+        for i in range(2 * n_batches):
+            pi, di = make_token_ids(cfg.vocab, wl.P, wl.K, wl.T, wl.seed + 300007 + i, device="cuda")
+            A.atts_score_drafts(model, pi, di, None, A.SCORE_MEAN_NLL, None, sc, ws)
+            g_scores.append(sc.cpu().numpy().copy())
+            o_scores.append(O.score_drafts(w_np, cfg, pi.cpu().numpy(), di.cpu().numpy())[1].astype(np.float32))
+        g = np.concatenate(g_scores)
+        o = np.concatenate(o_scores)
+        n_cal = n_batches * wl.K
+        calib = A.Calib(n_cal)
+        A.atts_calibrate_online(calib, torch.from_numpy(g[:n_cal]).cuda())
+        test = torch.from_numpy(g[n_cal:]).cuda()
+        ranks = torch.empty(test.numel(), dtype=torch.int32, device="cuda")
+        cls = torch.empty(test.numel(), dtype=torch.uint8, device="cuda")
+        A.atts_classify_ordinal(calib, test, list(wl.alphas), ranks, None, cls, None)
+        torch.cuda.synchronize()
+        oc = O.CalibrationSet()
+        oc.append(o[:n_cal])
+        o_cls = oc.classify(o[n_cal:], list(wl.alphas))[2]
+        g_cls = cls.cpu().numpy()
+        res[dtype] = {"candidates": int(test.numel()), "n_cal": n_cal, "flips": int((g_cls != o_cls).sum()),
+                      "rejected_gpu": int((g_cls > 0).sum()), "rejected_oracle": int((o_cls > 0).sum()),
+                      "max_abs_score_error": float(np.abs(g.astype(np.float64) - o).max()),
+                      "score_std": float(o.std())}
+        calib.close()
+    return {"workload": f"tiny (config 1): {n_batches} calibration + {n_batches} test batches of K={wl.K} x T={wl.T}, alpha={list(wl.alphas)}",
+            **res}
+
+
+def bench_sync_vs_async(A, torch, np, model, cfg, wl, cal_scores, t_m_ms, requests=(2, 4, 8), n_streams=2):
+    """Asynchronous arithmetic intensity r = T_c / (T_m + T_s) (Sec. "Q1") of both designs with several requests in
+    flight.  A turn = R requests (inputs), each scoring its m = K candidates with one atts_score_drafts call, the calls
+    spread over `n_streams` HIP streams.
+      asynchronous (the method): a request's candidates are ranked against the calibration set as soon as its own
+        scores exist (atts_classify_ordinal on the request's stream); T_s = that launch.
+      synchronous (classic setup): normalise over each input's m candidates, global threshold over ALL normalised
+        calibration + turn scores (a sort), prediction sets; the chain starts when the LAST request of the turn has
+        been scored, so T_s of a request = wait for the others + the chain.
+    T_c = scoring time per request (wall time of the turn's scoring / R); T_m = the memory-bound stages of one scoring
+    pass (from the stage timers of the headline step)."""
+    m = wl.K
+    streams = [torch.cuda.Stream() for _ in range(n_streams)]
+    ws = [torch.empty(A.atts_workspace_bytes(model, wl.P, wl.K, wl.T), dtype=torch.uint8, device="cuda") for _ in range(n_streams)]
+    r_max = max(requests)
+    from synth import make_token_ids
+    ids = [make_token_ids(cfg.vocab, wl.P, wl.K, wl.T, wl.seed + 1100001 + i, device="cuda") for i in range(r_max)]
+    sc = torch.empty(r_max, m, dtype=torch.float32, device="cuda")
+    ranks = torch.empty(r_max, m, dtype=torch.int32, device="cuda")
+    cls = torch.empty(r_max, m, dtype=torch.uint8, device="cuda")
+    n_cal_in = cal_scores.numel() // m
+    cal_nll = cal_scores[: n_cal_in * m].view(n_cal_in, m).contiguous()
+    calib = A.Calib(cal_nll.numel() + 16 * r_max * m)
+    A.atts_calibrate_online(calib, cal_nll.view(-1))
+    cap = cal_nll.numel() + r_max * m
+    s_all = torch.empty(cap, dtype=torch.float32, device="cuda")                    # normalised calibration scores, then the turn's
+    A.atts_classic_normalize(cal_nll, s_all[: cal_nll.numel()].view(n_cal_in, m))
+    tau = torch.empty(1, dtype=torch.float32, device="cuda")
+    member = torch.empty(r_max, m, dtype=torch.uint8, device="cuda")
+    cws = torch.empty(A.atts_classic_workspace_bytes(cap), dtype=torch.uint8, device="cuda")
+    main = torch.cuda.current_stream()
+    ev = lambda: torch.cuda.Event(enable_timing=True)
+    out = {}
+    for R in requests:
+        res = {}
+        for design in ("asynchronous", "synchronous"):
+            for rep in range(2):                                                    # the first repetition warms up
+                start, scored, decided = ev(), [ev() for _ in range(R)], [ev() for _ in range(R)]
+                torch.cuda.synchronize()
+                start.record(main)
+                for st in streams:
+                    st.wait_event(start)
+                for r in range(R):
+                    st = streams[r % n_streams]
+                    with torch.cuda.stream(st):
+                        p, d = ids[r]
+                        A.atts_score_drafts(model, p, d, None, A.SCORE_MEAN_NLL, None, sc[r], ws[r % n_streams])
+                        scored[r].record(st)
+                        if design == "asynchronous":
+                            A.atts_classify_ordinal(calib, sc[r], list(wl.alphas), ranks[r], None, cls[r], None)
+                            decided[r].record(st)
+                for r in range(R):
+                    main.wait_event(scored[r])
+                if design == "synchronous":
+                    n0 = cal_nll.numel()
+                    A.atts_classic_normalize(sc[:R], s_all[n0: n0 + R * m].view(R, m))
+                    A.atts_classic_threshold(s_all[: n0 + R * m], wl.alphas[-1], tau, cws)
+                    A.atts_classic_prediction_sets(s_all[n0: n0 + R * m], tau, member[:R].view(-1))
+                    end = ev()
+                    end.record(main)
+                    decided = [end] * R
+                torch.cuda.synchronize()
+            t_scoring = max(start.elapsed_time(e) for e in scored)
+            t_s = [scored[r].elapsed_time(decided[r]) for r in range(R)]
+            t_c = t_scoring / R
+            res[design] = {"T_c_ms": t_c, "T_s_ms_mean": float(np.mean(t_s)), "T_s_ms_max": float(np.max(t_s)),
+                           "r": t_c / (t_m_ms + float(np.mean(t_s)))}
+        out[f"R={R}"] = res
+    calib.close()
+    return {"workload": (f"{wl.name}: turns of R requests x m={m} candidates x T={wl.T} tokens, prefix {wl.P}, {n_streams} streams; "
+                         f"{cal_nll.numel()} calibration scores; T_m = {t_m_ms:.3f} ms per request"),
+            "definition": "r = T_c / (T_m + T_s); T_s = time from a request's scores being ready to its decisions being ready",
+            **out}
 
 
 def bench_warm_prefix(A, torch, model, cfg, wl, L, steps=5):
@@ -293,7 +448,8 @@ def main():
     ap.add_argument("--workload", default="7b", choices=["tiny", "7b", "32b", "70b"])
     ap.add_argument("--layers", type=int, default=0, help="build only the first L layers (debug; result is labelled)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--cpu-layers", type=int, default=8, help="layers of the model the CPU baseline times (extrapolated to all by count)")
+    ap.add_argument("--cpu-layers", type=int, default=0,
+                    help="layers of the model the CPU baseline times (0 = all of them; fewer are extrapolated to all by count and labelled)")
     ap.add_argument("--traffic-probe", action="store_true",
                     help="also run one plain 1 GiB device-to-device copy (reference for scaling HBM counters)")
     ap.add_argument("--skip-extras", action="store_true",
@@ -350,11 +506,12 @@ def main():
         A.atts_score_drafts(model, p, d, None, A.SCORE_MEAN_NLL, None, sc, ws)
         A.atts_calibrate_online(calib, sc)
         seen.append(sc.clone())
+    seen = torch.cat(seen)
     if n_real < n_cal_batches:
-        seen = torch.cat(seen)
         g = torch.Generator(device="cuda").manual_seed(wl.seed)
         fill = seen.mean() + seen.std() * torch.randn((n_cal_batches - n_real) * wl.K, device="cuda", generator=g)
         A.atts_calibrate_online(calib, fill.float().contiguous())
+        seen = torch.cat([seen, fill.float()])
     torch.cuda.synchronize()
     calib_note = (f"{n_real} scoring passes" if n_real == n_cal_batches else
                   f"{n_real} scoring passes + {(n_cal_batches - n_real) * wl.K} scores from a normal fitted to them")
@@ -439,20 +596,25 @@ def main():
         "roofline": {"bound": "mfma", "kernel": f"aligned {cfg.dtype} GEMM, SwiGLU epilogue (gate/up projection)",
                      "achieved": achieved, "peak": peak, "unit": "TFLOP/s", "frac": achieved / peak,
                      "avg_launch_ms": dom_avg_ms, "flops_per_launch": dom_flops,
-                     "traffic": measured_traffic(args.workload)},
+                     "traffic": measured_traffic(args.workload),
+                     "traffic_source": "recorded constant from profiles/traffic_gemm_gate_up_7b.txt (rocprofv3 --pmc FETCH_SIZE / "
+                                       "WRITE_SIZE), not measured by this run; null when csrc/gemm.hip has changed since"},
         "stages": stages,
         "async_arithmetic_intensity": {"T_c_ms": t_c, "T_m_ms": t_m, "T_s_ms": t_s, "r": t_c / (t_m + t_s) if t_m + t_s > 0 else None},
     }
     if args.workload != "tiny" and not args.skip_extras:
-        out["calibration_stage"] = bench_calibration(A, torch, np)
-        out["calibration_stage_scaled"] = bench_calibration(A, torch, np, steps=4, scaled=True)
+        out["calibration_stage"] = bench_calibration(A, torch, np, cpu=not args.no_cpu_baseline)
+        out["calibration_stage_scaled"] = bench_calibration(A, torch, np, steps=4, scaled=True, cpu=not args.no_cpu_baseline)
         out["warm_prefix"] = bench_warm_prefix(A, torch, model, cfg, wl, L)
         out["decode_shaped"] = bench_decode_shaped(A, torch, model, cfg, wl, L)
         out["conditional_stage"] = bench_conditional(A, torch, np)
         out["continuation"] = bench_continuation(A, torch, model, cfg, wl, L)
+        out["sync_vs_async"] = bench_sync_vs_async(A, torch, np, model, cfg, wl, seen, t_m)
     if not args.no_cpu_baseline:
         p0, d0 = ids[0]
-        out["cpu_baseline"] = cpu_baseline(cfg, wl, w, p0.cpu().numpy(), d0.cpu().numpy(), L, min(args.cpu_layers, L))
+        out["decision_flips"] = bench_decision_flips(A, torch, np)
+        out["cpu_baseline"] = cpu_baseline(cfg, wl, w, p0.cpu().numpy(), d0.cpu().numpy(), L,
+                                           min(args.cpu_layers, L) if args.cpu_layers > 0 else L)
     print(json.dumps(out))
 
 

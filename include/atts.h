@@ -351,6 +351,41 @@ int32_t atts_classify_conditional(const float* cal_scores, const int64_t* cal_of
 /* Copies the multiset, in ascending order (NaNs first), to out dev float [size]. */
 int32_t atts_calib_export(const atts_calib* calib, float* out, void* hip_stream);
 
+/* Restores a multiset that atts_calib_export wrote (checkpoint / resume of "Online Calibration"): the handle's
+ * contents are REPLACED by scores dev float [n], which must be in the order atts_calib_export produces (ascending,
+ * NaNs first, by the comparison rules above; -0 and +0 in any order).  n >= 0 (0 empties the handle).  The order
+ * is the caller's promise and is not verified (device data); unsorted input gives wrong ranks, never a fault.
+ * Ranks, classes and thresholds after an import equal those of the handle that was exported, bit for bit.
+ * ATTS_ERR_CAPACITY if n > capacity (nothing is changed). */
+int32_t atts_calib_import(atts_calib* calib, const float* scores, int64_t n, void* hip_stream);
+
+/* ------------------------------------------------------------------------------------
+ * The classic, synchronous pipeline (Sec. "Preliminary", "Classic Setup"): the design the
+ * asynchronous rule is measured against.  Built as the comparator for the asynchronous
+ * arithmetic intensity r = T_c / (T_m + T_s) of Sec. "Q1": none of the three steps can run
+ * for an input before ALL m of its candidates have been scored.
+ *
+ *   atts_classic_normalize        Eq. "softmax": scores[i, k] = exp(-nll[i, k]) / sum_j exp(-nll[i, j]), the share of
+ *                                 candidate k in the likelihood of the m candidates of input i (nll = the unnormalised
+ *                                 score atts_score_drafts returns; larger share = more likely).  fp32; a NaN loss makes
+ *                                 every score of its input NaN.  nll, scores dev float [n_inputs, m] row-major; m >= 1.
+ *   atts_classic_threshold        Eq. "quantile": tau[0] = the k-th smallest of ALL n_scores normalised calibration
+ *                                 scores, k = ceil((N + 1)(1 - alpha)) = N + 1 - floor(alpha (N + 1)) with the floor of
+ *                                 one binary64 product (+inf if k > N): a global sort of the set.  cal_scores dev float
+ *                                 [n_scores] (read only), 1 <= n_scores <= 2^30; alpha in (0, 1); tau dev float [1];
+ *                                 workspace dev, 256-byte aligned, >= atts_classic_workspace_bytes(n_scores), scratch.
+ *   atts_classic_prediction_sets  Eq. "pred_set": member[i] = 1 if scores[i] >= tau[0] else 0 (ties with the threshold
+ *                                 are members; a NaN score is not).  scores dev float [count], tau dev float [1] (read
+ *                                 on the device, so the three calls chain on one stream without a host round trip),
+ *                                 member dev uint8 [count].
+ * Host-detectable errors (NULLs, sizes, alpha, workspace) are reported before anything is enqueued.
+ * ---------------------------------------------------------------------------------- */
+int32_t atts_classic_workspace_bytes(int64_t n_scores, size_t* out_bytes);
+int32_t atts_classic_normalize(const float* nll, int64_t n_inputs, int32_t m, float* scores, void* hip_stream);
+int32_t atts_classic_threshold(const float* cal_scores, int64_t n_scores, double alpha, float* tau, void* workspace,
+                               size_t workspace_bytes, void* hip_stream);
+int32_t atts_classic_prediction_sets(const float* scores, int64_t count, const float* tau, uint8_t* member, void* hip_stream);
+
 #ifdef __cplusplus
 }
 #endif

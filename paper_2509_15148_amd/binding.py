@@ -32,6 +32,8 @@ EXPORTS = (
     "atts_gemm_nt", "atts_attention_workspace_bytes", "atts_attention_shared_prefix",
     "atts_calib_create", "atts_calib_destroy", "atts_calib_size", "atts_calib_reset",
     "atts_calibrate_online", "atts_classify_ordinal", "atts_classify_conditional", "atts_calib_export",
+    "atts_calib_import", "atts_classic_workspace_bytes", "atts_classic_normalize", "atts_classic_threshold",
+    "atts_classic_prediction_sets",
     "atts_profile_enable", "atts_profile_read",
 )
 
@@ -390,6 +392,39 @@ def atts_classify_conditional(cal_scores: torch.Tensor, cal_offsets: torch.Tenso
 
 def atts_calib_export(calib: Calib, out: torch.Tensor) -> None:
     _check(_lib.atts_calib_export(calib.handle, _ptr(out, torch.float32, "out"), _stream()))
+
+
+def atts_calib_import(calib: Calib, scores: torch.Tensor) -> None:
+    _check(_lib.atts_calib_import(calib.handle, _ptr(scores, torch.float32, "scores") if scores.numel() else ctypes.c_void_p(0),
+                                  ctypes.c_int64(scores.numel()), _stream()))
+
+
+def atts_classic_workspace_bytes(n_scores: int) -> int:
+    out = ctypes.c_size_t()
+    _check(_lib.atts_classic_workspace_bytes(ctypes.c_int64(n_scores), ctypes.byref(out)))
+    return out.value
+
+
+def atts_classic_normalize(nll: torch.Tensor, scores: torch.Tensor) -> None:
+    if nll.dim() != 2 or tuple(scores.shape) != tuple(nll.shape):
+        raise AttsError(ERR_INVALID_ARG, "nll and scores must both be [n_inputs, m]")
+    _check(_lib.atts_classic_normalize(_ptr(nll, torch.float32, "nll"), ctypes.c_int64(nll.shape[0]), ctypes.c_int32(nll.shape[1]),
+                                       _ptr(scores, torch.float32, "scores"), _stream()))
+
+
+def atts_classic_threshold(cal_scores: torch.Tensor, alpha: float, tau: torch.Tensor, workspace: torch.Tensor) -> None:
+    if tau.numel() != 1:
+        raise AttsError(ERR_INVALID_ARG, "tau must have one element")
+    _check(_lib.atts_classic_threshold(_ptr(cal_scores, torch.float32, "cal_scores"), ctypes.c_int64(cal_scores.numel()),
+                                       ctypes.c_double(alpha), _ptr(tau, torch.float32, "tau"),
+                                       _ptr(workspace, torch.uint8, "workspace"), ctypes.c_size_t(workspace.numel()), _stream()))
+
+
+def atts_classic_prediction_sets(scores: torch.Tensor, tau: torch.Tensor, member: torch.Tensor) -> None:
+    if member.numel() != scores.numel() or tau.numel() != 1:
+        raise AttsError(ERR_INVALID_ARG, "member must have one element per score, tau one element")
+    _check(_lib.atts_classic_prediction_sets(_ptr(scores, torch.float32, "scores"), ctypes.c_int64(scores.numel()),
+                                             _ptr(tau, torch.float32, "tau"), _ptr(member, torch.uint8, "member"), _stream()))
 
 
 def atts_profile_enable(on: bool) -> None:

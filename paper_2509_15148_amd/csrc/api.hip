@@ -393,7 +393,10 @@ int32_t forward_tree(const atts_model* m, ScoreShape s, int32_t row0, atts_prefi
     return ATTS_OK;
 }
 
+// Everything about a forward pass over the token tree that the host can refuse: the attention kernel's context limit
+// and the workspace.  Called before the first launch of every entry point that runs forward_tree.
 int32_t check_workspace(const char* fn, const atts_model_desc& d, ScoreShape s, void* workspace, size_t workspace_bytes) {
+    ATTS_TRY(attention_context_check(fn, d.dtype, d.head_dim, s.P, s.T));
     const Workspace ws = carve(d, s);
     if (!workspace || ((uintptr_t)workspace & 255)) return fail(ATTS_ERR_WORKSPACE, "%s: workspace is NULL or not 256-byte aligned", fn);
     if (workspace_bytes < ws.total) return fail(ATTS_ERR_WORKSPACE, "%s: workspace has %zu bytes, %zu needed", fn, workspace_bytes, ws.total);
@@ -579,6 +582,8 @@ int32_t continue_tokens(const char* fn, const atts_prefix* p, const int32_t* dra
     const atts_model* m = p->model;
     const atts_model_desc& d = m->desc;
     const int32_t P = p->P;
+    ATTS_TRY(attention_context_check(fn, d.dtype, d.head_dim, P, T));
+    ATTS_TRY(decode_context_check(fn, d.dtype, d.head_dim, (int64_t)P + T + n_new));
     const ContinueSpace cs = carve_continue(d, P, K, T, n_new);
     if (!workspace || ((uintptr_t)workspace & 255)) return fail(ATTS_ERR_WORKSPACE, "%s: workspace is NULL or not 256-byte aligned", fn);
     if (workspace_bytes < cs.total) return fail(ATTS_ERR_WORKSPACE, "%s: workspace has %zu bytes, %zu needed", fn, workspace_bytes, cs.total);
@@ -823,6 +828,7 @@ int32_t atts_attention_shared_prefix(int32_t dtype, const void* qkv, void* out, 
     if (K == 0) T = 1;
     ATTS_TRY(check_score_shape("atts_attention_shared_prefix", P, K > 0 ? K : 1, T));
     const ScoreShape s{P, K, T};
+    ATTS_TRY(attention_context_check("atts_attention_shared_prefix", dtype, hd, P, T));
     size_t need = 0;
     ATTS_TRY(atts_attention_workspace_bytes(dtype, s.R(), n_kv, hd, &need));
     void* vt = nullptr;

@@ -283,6 +283,16 @@ __global__ __launch_bounds__(64 * kWaves, 512 / (64 * kWaves)) void attn_mfma_ke
 
 bool attention_uses_vt(int32_t dtype, int32_t hd) { return dtype == ATTS_DTYPE_BF16 && hd == kHd; }
 
+// the general kernel keeps one score per key of the longest context (prefix + one draft) in LDS
+constexpr size_t kSimpleLdsMax = 60 * 1024;
+static size_t simple_attention_lds(int32_t hd, int32_t P, int32_t T) { return ((size_t)hd + (size_t)P + (size_t)T) * sizeof(float); }
+
+int32_t attention_context_check(const char* fn, int32_t dtype, int32_t hd, int32_t P, int32_t T) {
+    if (attention_uses_vt(dtype, hd) || simple_attention_lds(hd, P, T) <= kSimpleLdsMax) return ATTS_OK;
+    return fail(ATTS_ERR_SHAPE, "%s: a context of %lld keys (prefix + one draft) is too long for the attention kernel of this dtype / head_dim",
+                fn, (long long)P + T);
+}
+
 int32_t launch_attention(int32_t dtype, const void* qkv, const void* vt, int64_t ldv, void* out, ScoreShape s, int32_t row0,
                          int32_t nq, int32_t nkv, int32_t hd, hipStream_t stream) {
     const int R = s.R();
@@ -310,8 +320,8 @@ int32_t launch_attention(int32_t dtype, const void* qkv, const void* vt, int64_t
         ATTS_LAUNCH_CHECK("attn_mfma_kernel");
         return ATTS_OK;
     }
-    const size_t lds = (size_t)(hd + s.P + s.T) * sizeof(float);
-    if (lds > 60 * 1024) return fail(ATTS_ERR_SHAPE, "attention: context of %d keys is too long for this dtype/head_dim", s.P + s.T);
+    const size_t lds = simple_attention_lds(hd, s.P, s.T);
+    if (lds > kSimpleLdsMax) return fail(ATTS_ERR_SHAPE, "attention: context of %d keys is too long for this dtype/head_dim", s.P + s.T);
     dim3 grid(R - row0, nq);
     if (dtype == ATTS_DTYPE_F32)
         hipLaunchKernelGGL(attn_simple_kernel<float>, grid, dim3(64), lds, stream, (const float*)qkv, (float*)out, row0, s.P, s.T,

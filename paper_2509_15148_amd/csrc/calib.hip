@@ -406,6 +406,23 @@ __global__ void export_kernel(const uint32_t* __restrict__ keys, int64_t n, floa
     if (i < n) out[i] = key_to_score(keys[i]);
 }
 
+// keys and the four index levels of an array that is already in key order
+struct ImportJob {
+    uint32_t* keys;
+    uint32_t* index[kIndexLevels];
+};
+__global__ void import_kernel(const float* __restrict__ scores, int64_t n, ImportJob job) {
+    const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (i >= n) return;
+    const uint32_t k = score_to_key(scores[i]);
+    job.keys[i] = k;
+#pragma unroll
+    for (int lvl = 0; lvl < kIndexLevels; ++lvl) {
+        const int shift = 4 * (lvl + 1);
+        if ((i & (((int64_t)1 << shift) - 1)) == 0) job.index[lvl][i >> shift] = k;
+    }
+}
+
 // One merge launch producing `total` outputs.
 template <bool EMIT>
 int32_t launch_merge(atts_calib* c, const MergeJob& job, int64_t total, bool streaming, hipStream_t stream) {
@@ -626,6 +643,22 @@ int32_t atts_calib_export(const atts_calib* c, float* out, void* hip_stream) {
     hipLaunchKernelGGL(export_kernel, dim3((unsigned)ceil_div(c->n, 256)), dim3(256), 0, static_cast<hipStream_t>(hip_stream),
                        c->keys[c->cur], c->n, out);
     ATTS_LAUNCH_CHECK("export_kernel");
+    return ATTS_OK;
+}
+
+int32_t atts_calib_import(atts_calib* c, const float* scores, int64_t n, void* hip_stream) {
+    if (!c) return fail(ATTS_ERR_INVALID_ARG, "atts_calib_import: NULL handle");
+    if (n < 0) return fail(ATTS_ERR_INVALID_ARG, "atts_calib_import: n = %lld < 0", (long long)n);
+    if (n > c->capacity)
+        return fail(ATTS_ERR_CAPACITY, "atts_calib_import: %lld scores exceed the capacity %lld", (long long)n, (long long)c->capacity);
+    if (n > 0 && !scores) return fail(ATTS_ERR_INVALID_ARG, "atts_calib_import: scores is NULL");
+    if (n > 0) {
+        ImportJob job{c->keys[c->cur], {}};
+        for (int k = 0; k < kIndexLevels; ++k) job.index[k] = c->index[c->cur][k];
+        hipLaunchKernelGGL(import_kernel, dim3((unsigned)ceil_div(n, 256)), dim3(256), 0, static_cast<hipStream_t>(hip_stream), scores, n, job);
+        ATTS_LAUNCH_CHECK("import_kernel");
+    }
+    c->n = n;
     return ATTS_OK;
 }
 

@@ -226,6 +226,10 @@ int32_t launch_sort_scores(const float* scores, int64_t n, uint32_t* a, uint32_t
                            hipStream_t stream);
 
 bool attention_uses_vt(int32_t dtype, int32_t hd);
+// ATTS_OK if launch_attention / launch_attn_decode can serve the context, else ATTS_ERR_SHAPE (host only: callers ask before
+// they enqueue anything).  P + T = prefix + longest draft; n_max = keys of the longest branch of a continuation.
+int32_t attention_context_check(const char* fn, int32_t dtype, int32_t hd, int32_t P, int32_t T);
+int32_t decode_context_check(const char* fn, int32_t dtype, int32_t hd, int64_t n_max);
 // queries are the rows [row0, R); keys / values of all rows [0, R) must be present
 int32_t launch_attention(int32_t dtype, const void* qkv, const void* vt, int64_t ldv, void* out, ScoreShape s, int32_t row0,
                          int32_t nq, int32_t nkv, int32_t hd, hipStream_t stream);

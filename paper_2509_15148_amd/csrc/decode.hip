@@ -616,12 +616,25 @@ int32_t launch_decode_qkv_finish(int32_t dtype, float* acc, const float2* cs, in
     return ATTS_OK;
 }
 
+// head rows that are a power-of-two number of 16-byte pieces take the kernel without a context limit; the general one
+// holds one score per key in LDS
+static bool decode_by_pieces(int32_t dtype, int32_t hd) {
+    const int lanes_per_key = hd * (int)dtype_size(dtype) / 16;
+    return (hd * dtype_size(dtype)) % 16 == 0 && lanes_per_key <= 64 && (lanes_per_key & (lanes_per_key - 1)) == 0;
+}
+static size_t decode_general_lds(int32_t hd, int64_t n_max) { return (size_t)((1 + kDecodeWaves) * hd + n_max + 2 * kDecodeWaves) * sizeof(float); }
+
+int32_t decode_context_check(const char* fn, int32_t dtype, int32_t hd, int64_t n_max) {
+    if (decode_by_pieces(dtype, hd) || decode_general_lds(hd, n_max) <= 60 * 1024) return ATTS_OK;
+    return fail(ATTS_ERR_SHAPE, "%s: a context of %lld keys is too long for the decoding attention of this dtype / head_dim", fn,
+                (long long)n_max);
+}
+
 int32_t launch_attn_decode(int32_t dtype, const void* q, const void* k_cache, const void* v_cache, void* out, int32_t Kr, int32_t P,
                            int32_t Tc, BranchPos pos, int32_t nq, int32_t nkv, int32_t hd, hipStream_t stream) {
     const float scale = 1.f / sqrtf((float)hd);
     dim3 grid(Kr, nq);
-    const int lanes_per_key = hd * (int)dtype_size(dtype) / 16;
-    if ((hd * dtype_size(dtype)) % 16 == 0 && lanes_per_key <= 64 && (lanes_per_key & (lanes_per_key - 1)) == 0) {
+    if (decode_by_pieces(dtype, hd)) {
         const size_t lds = (size_t)(kDecodeWaves * hd + 2 * kDecodeWaves) * sizeof(float);
         DISPATCH_T(dtype, hipLaunchKernelGGL(attn_decode_pieces_kernel<T>, grid, dim3(kDecodeThreads), lds, stream, (const T*)q,
                                              (const T*)k_cache, (const T*)v_cache, (T*)out, P, Tc, pos, nq, nkv, hd, scale);)
@@ -629,7 +642,7 @@ int32_t launch_attn_decode(int32_t dtype, const void* q, const void* k_cache, co
         return ATTS_OK;
     }
     const int n_max = P + pos.T + pos.done + 1;        // the longest branch
-    const size_t lds = (size_t)((1 + kDecodeWaves) * hd + n_max + 2 * kDecodeWaves) * sizeof(float);
+    const size_t lds = decode_general_lds(hd, n_max);
     if (lds > 60 * 1024) return fail(ATTS_ERR_SHAPE, "continuation: context of %d keys is too long", n_max);
     DISPATCH_T(dtype, hipLaunchKernelGGL(attn_decode_kernel<T>, grid, dim3(kDecodeThreads), lds, stream, (const T*)q, (const T*)k_cache,
                                          (const T*)v_cache, (T*)out, P, Tc, pos, nq, nkv, hd, scale);)

@@ -118,14 +118,13 @@ __global__ __launch_bounds__(256) void rmsnorm_kernel(const float* __restrict__ 
 // ---- rotary table per row: (cos, sin)(pos(r) * theta^(-2 i / hd)) in fp64, rounded once ----------
 __global__ void rope_table_kernel(float2* __restrict__ cs, int row0, int R, int P, int Tn, int half,
                                   double log_theta_over_half) {
-    int idx = blockIdx.x * blockDim.x + threadIdx.x;
-    if (idx >= (R - row0) * half) return;
-    int r = row0 + idx / half, i = idx % half;
-    idx = r * half + i;
+    const int64_t idx = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;     // up to 2^24 rows x 128 pairs
+    if (idx >= (int64_t)(R - row0) * half) return;
+    const int r = row0 + (int)(idx / half), i = (int)(idx % half);
     double ang = (double)tree_position(r, P, Tn) * exp(-(double)i * log_theta_over_half);
     double s, c;
     sincos(ang, &s, &c);
-    cs[idx] = make_float2((float)c, (float)s);
+    cs[(int64_t)r * half + i] = make_float2((float)c, (float)s);
 }
 
 // ---- S2 epilogue (unfused): rotate q and k in place -------------------------------------------

@@ -245,3 +245,46 @@ def test_out_of_cache_size_sampled():
     for l in range(2):
         kth = n + 1 - int(r[l])
         assert q[l] == np.partition(host, kth - 1)[kth - 1]
+
+
+def test_export_import_round_trip():
+    """Checkpoint / resume of the online calibration state: a handle restored from an export gives the same ranks,
+    classes and thresholds bit for bit, before and after further appends to both."""
+    import paper_2509_15148_amd as A
+    announce("calib export/import")
+    for n0, n1 in ((16, 5), (1000, 37), (70000, 9000), (300000, 70001)):
+        cal = lognormal_scores(n0, 901).astype(np.float32)
+        cal[:: max(n0 // 7, 1)] = cal[0]
+        if n0 > 100:
+            cal[3], cal[5], cal[9], cal[11] = np.nan, -0.0, 0.0, np.inf
+        more = lognormal_scores(n1, 902).astype(np.float32)
+        test = np.concatenate([lognormal_scores(3000, 903).astype(np.float32), cal[:50],
+                               np.array([np.nan, 0.0, -0.0, np.inf, -np.inf], dtype=np.float32)])
+        alphas = [0.05, 0.2]
+        a = A.Calib(n0 + n1)
+        A.atts_calibrate_online(a, dev(cal[: n0 // 2]))
+        A.atts_calibrate_online(a, dev(cal[n0 // 2:]))
+        saved = torch.empty(n0, dtype=torch.float32, device="cuda")
+        A.atts_calib_export(a, saved)
+        b = A.Calib(n0 + n1)
+        A.atts_calibrate_online(b, dev(more))                     # old contents are replaced by the import
+        A.atts_calib_import(b, saved)
+        assert A.atts_calib_size(b) == n0
+        ra = _classify(A, a, test, alphas)
+        rb = _classify(A, b, test, alphas)
+        for x, y in zip(ra, rb):
+            assert np.array_equal(x, y, equal_nan=True)
+        _check_against_oracle(A, b, cal.astype(np.float64), test, alphas, brute=n0 <= 1000)
+        A.atts_calibrate_online(a, dev(more))
+        A.atts_calibrate_online(b, dev(more))
+        ra = _classify(A, a, test, alphas)
+        rb = _classify(A, b, test, alphas)
+        for x, y in zip(ra, rb):
+            assert np.array_equal(x, y, equal_nan=True)
+        with pytest.raises(A.AttsError) as e:
+            A.atts_calib_import(b, torch.zeros(n0 + n1 + 1, dtype=torch.float32, device="cuda"))
+        assert e.value.code == A.ERR_CAPACITY
+        A.atts_calib_import(b, torch.zeros(0, dtype=torch.float32, device="cuda"))
+        assert A.atts_calib_size(b) == 0
+        a.close()
+        b.close()

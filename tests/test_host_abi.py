@@ -89,3 +89,23 @@ def test_stage_entry_points_validate_arguments():
     assert lib.atts_attention_workspace_bytes(0, 100, 2, 32, ctypes.byref(out)) == 0 and out.value == 0
     assert lib.atts_attention_shared_prefix(1, null, null, 4, 1, 4, 2, 1, 128, null, ctypes.c_size_t(0), null) \
         == A.ERR_INVALID_ARG
+
+
+def test_classic_pipeline_and_import_validate_arguments():
+    lib = B._lib
+    null = ctypes.c_void_p(0)
+    out = ctypes.c_size_t()
+    i64, f64 = ctypes.c_int64, ctypes.c_double
+    assert lib.atts_classic_workspace_bytes(i64(0), ctypes.byref(out)) == A.ERR_INVALID_ARG
+    assert lib.atts_classic_workspace_bytes(i64(1000), ctypes.byref(out)) == 0 and out.value >= 2 * 1000 * 4
+    assert out.value % 256 == 0
+    assert lib.atts_classic_normalize(null, i64(3), 0, null, null) == A.ERR_INVALID_ARG          # m < 1
+    assert lib.atts_classic_normalize(null, i64(3), 4, null, null) == A.ERR_INVALID_ARG          # NULL arrays
+    assert lib.atts_classic_normalize(null, i64(0), 4, null, null) == 0                          # nothing to do
+    one = ctypes.c_void_p(256)                                                                   # non-NULL, never dereferenced
+    assert lib.atts_classic_threshold(one, i64(10), f64(1.5), one, one, ctypes.c_size_t(1 << 20), null) == A.ERR_INVALID_ARG
+    assert lib.atts_classic_threshold(one, i64(10), f64(0.1), one, null, ctypes.c_size_t(0), null) == A.ERR_WORKSPACE
+    assert lib.atts_classic_threshold(one, i64(10), f64(0.1), one, one, ctypes.c_size_t(16), null) == A.ERR_WORKSPACE
+    assert lib.atts_classic_prediction_sets(null, i64(5), null, null, null) == A.ERR_INVALID_ARG
+    assert lib.atts_classic_prediction_sets(null, i64(0), null, null, null) == 0
+    assert lib.atts_calib_import(null, null, i64(0), null) == A.ERR_INVALID_ARG
