@@ -454,6 +454,9 @@ def main():
                     help="also run one plain 1 GiB device-to-device copy (reference for scaling HBM counters)")
     ap.add_argument("--skip-extras", action="store_true",
                     help="leave out the calibration-only, out-of-cache and decode-shaped measurements (profiling runs)")
+    ap.add_argument("--legs", default="all",
+                    help="comma-separated extra legs to run after the headline measurement: calib, calib_scaled, warm_prefix, "
+                         "decode_shaped, conditional, continuation, sync_vs_async (default: all of them)")
     ap.add_argument("--calib-batches", type=int, default=-1,
                     help="scoring passes used to pre-sample the calibration set (-1: all ceil(n_cal / K) for tiny/7b, "
                          "2 for the larger models); the rest is drawn from a normal fitted to those scores")
@@ -603,13 +606,27 @@ def main():
         "async_arithmetic_intensity": {"T_c_ms": t_c, "T_m_ms": t_m, "T_s_ms": t_s, "r": t_c / (t_m + t_s) if t_m + t_s > 0 else None},
     }
     if args.workload != "tiny" and not args.skip_extras:
-        out["calibration_stage"] = bench_calibration(A, torch, np, cpu=not args.no_cpu_baseline)
-        out["calibration_stage_scaled"] = bench_calibration(A, torch, np, steps=4, scaled=True, cpu=not args.no_cpu_baseline)
-        out["warm_prefix"] = bench_warm_prefix(A, torch, model, cfg, wl, L)
-        out["decode_shaped"] = bench_decode_shaped(A, torch, model, cfg, wl, L)
-        out["conditional_stage"] = bench_conditional(A, torch, np)
-        out["continuation"] = bench_continuation(A, torch, model, cfg, wl, L)
-        out["sync_vs_async"] = bench_sync_vs_async(A, torch, np, model, cfg, wl, seen, t_m)
+        legs = {"calib", "calib_scaled", "warm_prefix", "decode_shaped", "conditional", "continuation", "sync_vs_async"}
+        if args.legs != "all":
+            want = set(x for x in args.legs.split(",") if x)
+            if not want <= legs:
+                print(f"bench.py: unknown leg(s) {sorted(want - legs)}; known: {sorted(legs)}", file=sys.stderr)
+                sys.exit(2)
+            legs = want
+        if "calib" in legs:
+            out["calibration_stage"] = bench_calibration(A, torch, np, cpu=not args.no_cpu_baseline)
+        if "calib_scaled" in legs:
+            out["calibration_stage_scaled"] = bench_calibration(A, torch, np, steps=4, scaled=True, cpu=not args.no_cpu_baseline)
+        if "warm_prefix" in legs:
+            out["warm_prefix"] = bench_warm_prefix(A, torch, model, cfg, wl, L)
+        if "decode_shaped" in legs:
+            out["decode_shaped"] = bench_decode_shaped(A, torch, model, cfg, wl, L)
+        if "conditional" in legs:
+            out["conditional_stage"] = bench_conditional(A, torch, np)
+        if "continuation" in legs:
+            out["continuation"] = bench_continuation(A, torch, model, cfg, wl, L)
+        if "sync_vs_async" in legs:
+            out["sync_vs_async"] = bench_sync_vs_async(A, torch, np, model, cfg, wl, seen, t_m)
     if not args.no_cpu_baseline:
         p0, d0 = ids[0]
         out["decision_flips"] = bench_decision_flips(A, torch, np)

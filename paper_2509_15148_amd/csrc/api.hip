@@ -3,6 +3,8 @@
 // gemm.hip / attention.hip / elementwise.hip / calib.hip.
 #include "common.h"
 
+#include <algorithm>
+
 #include <stdarg.h>
 #include <stdio.h>
 #include <mutex>
@@ -82,7 +84,7 @@ void prof_clear() {
 
 // Sub-buffers of the scoring workspace, each 256-byte aligned.
 struct Workspace {
-    size_t h, xn, qkv, qkv32, vt, ao, act, rope, xs, targets, valid, partials, zt, lp, total;
+    size_t h, xn, qkv, kpart, vt, ao, act, rope, xs, targets, valid, partials, zt, lp, total;
     int64_t ldv;
     int32_t n_part;
 };
@@ -91,6 +93,25 @@ struct Workspace {
 // aligned kernel then serves every row count (it reads the pad rows, whatever they hold, and drops their results).
 bool pads_rows(const atts_model_desc& d) { return d.dtype == ATTS_DTYPE_BF16; }
 constexpr int kSplitQkvRows = 128;
+
+// K-split projections (few rows, narrow output) store one partial result per K slice; the three of a layer (QKV, O,
+// down) use the same buffer one after the other.  Slices per projection for M rows through the model:
+struct SplitPlan {
+    int32_t qkv, o, down;        // 1 = not split (direct epilogue)
+    size_t bytes;                // of the shared partial buffer
+};
+SplitPlan split_plan(const atts_model_desc& d, int64_t M) {
+    SplitPlan p{1, 1, 1, 0};
+    if (M < 1 || M > (1 << 24)) return p;
+    const int32_t qd = d.n_q_heads * d.head_dim, qkv_out = (d.n_q_heads + 2 * d.n_kv_heads) * d.head_dim;
+    const bool padded = pads_rows(d);
+    if (M <= kSplitQkvRows) p.qkv = gemm_partial_slices(d.dtype, (int32_t)M, qkv_out, d.d_model, padded);
+    p.o = gemm_partial_slices(d.dtype, (int32_t)M, d.d_model, qd, padded);
+    p.down = gemm_partial_slices(d.dtype, (int32_t)M, d.d_model, d.d_ffn, padded);
+    auto need = [&](int32_t slices, int64_t n) { return slices > 1 ? (size_t)slices * (size_t)M * (size_t)n * sizeof(float) : (size_t)0; };
+    p.bytes = std::max(need(p.qkv, qkv_out), std::max(need(p.o, d.d_model), need(p.down, d.d_model)));
+    return p;
+}
 
 Workspace carve(const atts_model_desc& d, ScoreShape s) {
     const size_t es = dtype_size(d.dtype);
@@ -107,8 +128,8 @@ Workspace carve(const atts_model_desc& d, ScoreShape s) {
     w.h = take(R * d.d_model * sizeof(float));
     w.xn = take(Ra * d.d_model * es);
     w.qkv = take(R * (size_t)(d.n_q_heads + 2 * d.n_kv_heads) * d.head_dim * es);
-    // fp32 sums of a K-split QKV projection (calls with at most kSplitQkvRows computed rows)
-    w.qkv32 = take(pads_rows(d) ? (size_t)kSplitQkvRows * (d.n_q_heads + 2 * d.n_kv_heads) * d.head_dim * sizeof(float) : 0);
+    // partial sums of the K-split projections: the call computes all R rows, or the K T draft rows after a cached prefix
+    w.kpart = take(std::max(split_plan(d, (int64_t)R).bytes, split_plan(d, (int64_t)B).bytes));
     w.ldv = (int64_t)align_up(R, 64);
     w.vt = take(attention_uses_vt(d.dtype, d.head_dim) ? (size_t)d.n_kv_heads * d.head_dim * w.ldv * es : 0);
     w.ao = take(Ra * (size_t)d.n_q_heads * d.head_dim * es);
@@ -265,10 +286,13 @@ int32_t forward_tree(const atts_model* m, ScoreShape s, int32_t row0, atts_prefi
     // (a continuation call wants the value rows in the qkv buffer: the unfused path leaves them there)
     const bool fuse_rope = vt != nullptr && !tree && row0 % 4 == 0 && qkv_rope_fusable(d.dtype, M, qkv_out, d.d_model, d.head_dim, padded);
     float* h0 = h + (size_t)row0 * d.d_model;
-    // few rows: the QKV projection splits its K range like the residual projections do; the workgroups add into an
-    // fp32 buffer and a small kernel applies RoPE / the V transpose afterwards
-    float* qkv32 = reinterpret_cast<float*>(base + ws.qkv32);
-    const bool split_qkv = fuse_rope && M <= kSplitQkvRows && gemm_splits_k(d.dtype, M, qkv_out, d.d_model, padded);
+    // few rows: projections with a narrow output cut their K range over the chip (one partial result per slice in
+    // kpart); the consumers add the slices in order: the QKV finish (RoPE / V transpose), and the residual update, which
+    // also applies the RMSNorm that follows it
+    float* kpart = reinterpret_cast<float*>(base + ws.kpart);
+    SplitPlan plan = split_plan(d, M);
+    if (!fuse_rope) plan.qkv = 1;
+    const bool split_qkv = plan.qkv > 1;
 
     {
         StageTimer t_(ATTS_STAGE_EMBED, st);
@@ -276,23 +300,25 @@ int32_t forward_tree(const atts_model* m, ScoreShape s, int32_t row0, atts_prefi
         ATTS_TRY(launch_rope_table(rope, s, row0, d.head_dim, d.rope_theta, st));
         // the fused QKV epilogue writes only the R real columns of V^T
         if (fuse_rope) ATTS_TRY(launch_zero_vt_tail(d.dtype, vt, (int64_t)kvd, R, ws.ldv, st));
-        if (split_qkv) ATTS_TRY(launch_zero_f32(qkv32, (int64_t)M * qkv_out, st));
     }
+    char* xn0 = xn + (size_t)row0 * d.d_model * es;
+    bool xn_ready = false;      // xn already holds the attention norm of this layer (written with the previous residual update)
     for (int l = 0; l < d.n_layers; ++l) {
-        {
+        if (!xn_ready) {
             StageTimer t_(ATTS_STAGE_NORM, st);
-            ATTS_TRY(launch_rmsnorm(d.dtype, h0, m->attn_norm[l], d.rms_eps, M, d.d_model, xn + (size_t)row0 * d.d_model * es, st));
+            ATTS_TRY(launch_rmsnorm(d.dtype, h0, m->attn_norm[l], d.rms_eps, M, d.d_model, xn0, st));
         }
         GemmArgs g{};
         g.a = xn + (size_t)row0 * d.d_model * es; g.w = m->wqkv[l]; g.out = qkv + (size_t)row0 * qkv_out * es;
         g.M = M; g.N = qkv_out; g.Kd = d.d_model;
         g.lda = d.d_model; g.ldw = d.d_model; g.ldc = qkv_out; g.a_rows_padded = padded;
         if (split_qkv) {
-            g.out = qkv32;
+            g.out = kpart; g.n_slices = plan.qkv;
             StageTimer t_(ATTS_STAGE_GEMM_QKV, st);
-            ATTS_TRY(launch_gemm(d.dtype, EPI_RESID_F32, g, st));
-            ATTS_TRY(launch_qkv_finish(d.dtype, qkv32, rope + (size_t)row0 * (d.head_dim / 2), M, d.n_q_heads, d.n_kv_heads,
-                                       d.head_dim, qkv + (size_t)row0 * qkv_out * es, vt + (size_t)row0 * es, ws.ldv, st));
+            ATTS_TRY(launch_gemm(d.dtype, EPI_PARTIAL_F32, g, st));
+            ATTS_TRY(launch_qkv_finish(d.dtype, kpart, plan.qkv, (int64_t)M * qkv_out, rope + (size_t)row0 * (d.head_dim / 2), M,
+                                       d.n_q_heads, d.n_kv_heads, d.head_dim, qkv + (size_t)row0 * qkv_out * es,
+                                       vt + (size_t)row0 * es, ws.ldv, st));
         } else if (fuse_rope) {
             // QKV projection with RoPE and the V transpose applied to the accumulators
             g.rope = rope + (size_t)row0 * (d.head_dim / 2); g.vt = vt + (size_t)row0 * es; g.ldv = ws.ldv;
@@ -344,16 +370,24 @@ int32_t forward_tree(const atts_model* m, ScoreShape s, int32_t row0, atts_prefi
         g = GemmArgs{};
         g.a = ao + (size_t)row0 * qd * es; g.w = m->wo[l]; g.out = h0; g.M = M; g.N = d.d_model; g.Kd = qd;
         g.lda = qd; g.ldw = qd; g.ldc = d.d_model; g.a_rows_padded = padded;
-        {
-            StageTimer t_(ATTS_STAGE_GEMM_O, st);
-            ATTS_TRY(launch_gemm(d.dtype, EPI_RESID_F32, g, st));
-        }
-        {
+        if (plan.o > 1) {
+            g.out = kpart; g.n_slices = plan.o;
+            {
+                StageTimer t_(ATTS_STAGE_GEMM_O, st);
+                ATTS_TRY(launch_gemm(d.dtype, EPI_PARTIAL_F32, g, st));
+            }
             StageTimer t_(ATTS_STAGE_NORM, st);
-            ATTS_TRY(launch_rmsnorm(d.dtype, h0, m->ffn_norm[l], d.rms_eps, M, d.d_model, xn + (size_t)row0 * d.d_model * es, st));
+            ATTS_TRY(launch_resid_norm(d.dtype, h0, kpart, plan.o, (int64_t)M * d.d_model, m->ffn_norm[l], d.rms_eps, M, d.d_model, xn0, st));
+        } else {
+            {
+                StageTimer t_(ATTS_STAGE_GEMM_O, st);
+                ATTS_TRY(launch_gemm(d.dtype, EPI_RESID_F32, g, st));
+            }
+            StageTimer t_(ATTS_STAGE_NORM, st);
+            ATTS_TRY(launch_rmsnorm(d.dtype, h0, m->ffn_norm[l], d.rms_eps, M, d.d_model, xn0, st));
         }
         g = GemmArgs{};
-        g.a = xn + (size_t)row0 * d.d_model * es; g.w = m->w_gate_up[l]; g.out = act + (size_t)row0 * d.d_ffn * es;
+        g.a = xn0; g.w = m->w_gate_up[l]; g.out = act + (size_t)row0 * d.d_ffn * es;
         g.M = M; g.N = d.d_ffn; g.Kd = d.d_model;
         g.lda = d.d_model; g.ldw = d.d_model; g.ldc = d.d_ffn; g.a_rows_padded = padded;
         {
@@ -363,7 +397,18 @@ int32_t forward_tree(const atts_model* m, ScoreShape s, int32_t row0, atts_prefi
         g = GemmArgs{};
         g.a = act + (size_t)row0 * d.d_ffn * es; g.w = m->w_down[l]; g.out = h0; g.M = M; g.N = d.d_model; g.Kd = d.d_ffn;
         g.lda = d.d_ffn; g.ldw = d.d_ffn; g.ldc = d.d_model; g.a_rows_padded = padded;
-        {
+        if (plan.down > 1) {
+            g.out = kpart; g.n_slices = plan.down;
+            {
+                StageTimer t_(ATTS_STAGE_GEMM_DOWN, st);
+                ATTS_TRY(launch_gemm(d.dtype, EPI_PARTIAL_F32, g, st));
+            }
+            // with the next layer's attention norm (none after the last layer: the final norm runs on the scoring rows only)
+            xn_ready = l + 1 < d.n_layers;
+            StageTimer t_(ATTS_STAGE_NORM, st);
+            ATTS_TRY(launch_resid_norm(d.dtype, h0, kpart, plan.down, (int64_t)M * d.d_model, xn_ready ? m->attn_norm[l + 1] : nullptr,
+                                       d.rms_eps, M, d.d_model, xn0, st));
+        } else {
             StageTimer t_(ATTS_STAGE_GEMM_DOWN, st);
             ATTS_TRY(launch_gemm(d.dtype, EPI_RESID_F32, g, st));
         }
@@ -519,7 +564,7 @@ int32_t atts_score_drafts_cached(const atts_prefix* p, const int32_t* draft_ids,
 
 namespace {
 struct ContinueSpace {
-    size_t scoring, kc, vc, h, xn, ao, act, xs, qkv32, q, logits, argmax, rope, total;
+    size_t scoring, kc, vc, h, xn, ao, act, xs, kpart, q, logits, argmax, rope, total;
     int32_t Tc;
     size_t layer_bytes;
 };
@@ -547,7 +592,12 @@ ContinueSpace carve_continue(const atts_model_desc& d, int32_t P, int32_t Kr, in
     c.ao = take(rows_a * qd * es);
     c.act = take(rows_a * (size_t)d.d_ffn * es);
     c.xs = take(rows_a * d.d_model * es);
-    c.qkv32 = take((size_t)Kr * qkv_out * sizeof(float));
+    // a decoding step's projections with a narrow output: one partial result per K slice (or the one full result)
+    {
+        SplitPlan sp = split_plan(d, Kr);
+        sp.qkv = gemm_partial_slices(d.dtype, Kr, (int32_t)qkv_out, d.d_model, pads_rows(d));
+        c.kpart = take(std::max(sp.bytes, (size_t)sp.qkv * Kr * qkv_out * sizeof(float)));
+    }
     c.q = take((size_t)Kr * qd * es);
     c.logits = take((size_t)Kr * d.vocab * sizeof(float));
     c.argmax = take(argmax_scratch_bytes(Kr));
@@ -604,16 +654,15 @@ int32_t continue_tokens(const char* fn, const atts_prefix* p, const int32_t* dra
     char* ao = base + cs.ao;
     char* act = base + cs.act;
     char* xs = base + cs.xs;
-    float* qkv32 = reinterpret_cast<float*>(base + cs.qkv32);
+    float* kpart = reinterpret_cast<float*>(base + cs.kpart);
     char* q = base + cs.q;
     float* logits = reinterpret_cast<float*>(base + cs.logits);
     float2* rope = reinterpret_cast<float2*>(base + cs.rope);
     // (cos, sin) rows of the positions new tokens can take: P + 1 ... P + T + n_new - 1 (indexed by absolute position)
     ATTS_TRY(launch_rope_table(rope, ScoreShape{P, 1, cs.Tc}, P, d.head_dim, d.rope_theta, st));
-    // the QKV projection of a step has few tiles: where the aligned kernel would split its K range, the workgroups
-    // add into the (cleared) fp32 buffer; otherwise they store
-    const bool split_qkv = gemm_splits_k(d.dtype, K, qkv_out, d.d_model, padded);
-    if (split_qkv) ATTS_TRY(launch_zero_f32(qkv32, (int64_t)K * qkv_out, st));
+    // the projections of a step that have a narrow output cut their K range over the chip, one partial result per slice
+    SplitPlan plan = split_plan(d, K);
+    plan.qkv = gemm_partial_slices(d.dtype, K, qkv_out, d.d_model, padded);     // the QKV sums always pass through fp32 here
 
     auto next_token = [&](int t) -> int32_t {     // xs holds the normalised last hidden states: logits, arg max -> out_ids[:, t]
         GemmArgs g{};
@@ -635,22 +684,30 @@ int32_t continue_tokens(const char* fn, const atts_prefix* p, const int32_t* dra
     for (int t = 1; t < n_new; ++t) {
         const BranchPos pos{draft_lens, T, t - 1};
         ATTS_TRY(launch_embed_rows(d.dtype, m->tok_embed, d.vocab, d.d_model, out_ids + (t - 1), n_new, K, h, m->err_flag, st));
+        bool xn_ready = false;
         for (int l = 0; l < d.n_layers; ++l) {
             char* kc = tree.kc + (size_t)l * tree.layer_bytes;
             char* vc = tree.vc + (size_t)l * tree.layer_bytes;
-            ATTS_TRY(launch_rmsnorm(d.dtype, h, m->attn_norm[l], d.rms_eps, K, d.d_model, xn, st));
+            if (!xn_ready) ATTS_TRY(launch_rmsnorm(d.dtype, h, m->attn_norm[l], d.rms_eps, K, d.d_model, xn, st));
             GemmArgs g{};
-            g.a = xn; g.w = m->wqkv[l]; g.out = qkv32; g.M = K; g.N = qkv_out; g.Kd = d.d_model;
+            g.a = xn; g.w = m->wqkv[l]; g.out = kpart; g.M = K; g.N = qkv_out; g.Kd = d.d_model;
             g.lda = d.d_model; g.ldw = d.d_model; g.ldc = qkv_out; g.a_rows_padded = padded;
-            ATTS_TRY(launch_gemm(d.dtype, split_qkv ? EPI_RESID_F32 : EPI_STORE_F32, g, st));
-            ATTS_TRY(launch_decode_qkv_finish(d.dtype, qkv32, rope, K, d.n_q_heads, d.n_kv_heads, d.head_dim, P, cs.Tc, pos, q, kc, vc,
-                                              st));
+            g.n_slices = plan.qkv;
+            ATTS_TRY(launch_gemm(d.dtype, plan.qkv > 1 ? EPI_PARTIAL_F32 : EPI_STORE_F32, g, st));
+            ATTS_TRY(launch_decode_qkv_finish(d.dtype, kpart, plan.qkv, (int64_t)K * qkv_out, rope, K, d.n_q_heads, d.n_kv_heads,
+                                              d.head_dim, P, cs.Tc, pos, q, kc, vc, st));
             ATTS_TRY(launch_attn_decode(d.dtype, q, kc, vc, ao, K, P, cs.Tc, pos, d.n_q_heads, d.n_kv_heads, d.head_dim, st));
             g = GemmArgs{};
             g.a = ao; g.w = m->wo[l]; g.out = h; g.M = K; g.N = d.d_model; g.Kd = qd;
             g.lda = qd; g.ldw = qd; g.ldc = d.d_model; g.a_rows_padded = padded;
-            ATTS_TRY(launch_gemm(d.dtype, EPI_RESID_F32, g, st));
-            ATTS_TRY(launch_rmsnorm(d.dtype, h, m->ffn_norm[l], d.rms_eps, K, d.d_model, xn, st));
+            if (plan.o > 1) {
+                g.out = kpart; g.n_slices = plan.o;
+                ATTS_TRY(launch_gemm(d.dtype, EPI_PARTIAL_F32, g, st));
+                ATTS_TRY(launch_resid_norm(d.dtype, h, kpart, plan.o, (int64_t)K * d.d_model, m->ffn_norm[l], d.rms_eps, K, d.d_model, xn, st));
+            } else {
+                ATTS_TRY(launch_gemm(d.dtype, EPI_RESID_F32, g, st));
+                ATTS_TRY(launch_rmsnorm(d.dtype, h, m->ffn_norm[l], d.rms_eps, K, d.d_model, xn, st));
+            }
             g = GemmArgs{};
             g.a = xn; g.w = m->w_gate_up[l]; g.out = act; g.M = K; g.N = d.d_ffn; g.Kd = d.d_model;
             g.lda = d.d_model; g.ldw = d.d_model; g.ldc = d.d_ffn; g.a_rows_padded = padded;
@@ -658,7 +715,16 @@ int32_t continue_tokens(const char* fn, const atts_prefix* p, const int32_t* dra
             g = GemmArgs{};
             g.a = act; g.w = m->w_down[l]; g.out = h; g.M = K; g.N = d.d_model; g.Kd = d.d_ffn;
             g.lda = d.d_ffn; g.ldw = d.d_ffn; g.ldc = d.d_model; g.a_rows_padded = padded;
-            ATTS_TRY(launch_gemm(d.dtype, EPI_RESID_F32, g, st));
+            if (plan.down > 1) {
+                g.out = kpart; g.n_slices = plan.down;
+                ATTS_TRY(launch_gemm(d.dtype, EPI_PARTIAL_F32, g, st));
+                xn_ready = l + 1 < d.n_layers;
+                ATTS_TRY(launch_resid_norm(d.dtype, h, kpart, plan.down, (int64_t)K * d.d_model, xn_ready ? m->attn_norm[l + 1] : nullptr,
+                                           d.rms_eps, K, d.d_model, xn, st));
+            } else {
+                ATTS_TRY(launch_gemm(d.dtype, EPI_RESID_F32, g, st));
+                xn_ready = false;
+            }
         }
         ATTS_TRY(launch_norm_strided_rows(d.dtype, h, m->final_norm, d.rms_eps, d.d_model, 0, 1, BranchPos{nullptr, 0, 0}, K, xs, st));
         ATTS_TRY(next_token(t));

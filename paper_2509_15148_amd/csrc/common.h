@@ -108,6 +108,11 @@ enum GemmEpilogue : int32_t {
     EPI_LMHEAD = 4,      // per-row online-softmax partials over this tile's columns + target logit
     EPI_QKV_ROPE = 5,    // QKV projection: q/k heads rotated (rotate-half RoPE) and stored to out (T) [M, ldc];
                          // v heads stored transposed to vt [n_kv, 128, ldv].  head_dim 128, aligned bf16 shapes only.
+    EPI_PARTIAL_F32 = 6, // out (float) [n_slices][M, ldc]: the K range is cut into n_slices = gemm_partial_slices(...)
+                         // slices whose partial sums are stored one after the other (pitch M ldc floats); the consumer
+                         // adds them in slice order.  For projections with few rows and a narrow output, whose tiles
+                         // alone would leave most of the chip idle while the weights stream by.  No atomics: the
+                         // result does not depend on the order in which the workgroups finish.
 };
 
 struct GemmArgs {
@@ -127,6 +132,8 @@ struct GemmArgs {
     void* vt;                // [n_kv, 128, ldv] transposed V
     int64_t ldv;
     int32_t n_rot_heads;     // n_q + n_kv: heads (of 128 columns) that are rotated; the rest are V heads
+    // EPI_PARTIAL_F32 only:
+    int32_t n_slices;        // must equal gemm_partial_slices(dtype, M, N, Kd, a_rows_padded)
 };
 
 // Column slabs (partials per row) the LM-head epilogue of this call writes; lmhead_max_partials bounds it for any
@@ -168,14 +175,19 @@ int32_t launch_rope_split(int32_t dtype, void* qkv, const float2* cs, ScoreShape
                           int32_t hd, void* vt, int64_t ldv, hipStream_t stream);
 int32_t launch_transpose_v(int32_t dtype, const void* qkv, int32_t row0, int32_t R, int32_t nq, int32_t nkv, int32_t hd,
                            void* vt, int64_t ldv, hipStream_t stream);
-int32_t launch_zero_f32(float* p, int64_t n, hipStream_t stream);
-// acc [rows, (nq + 2 nkv) hd] fp32 (sums of a K-split QKV projection; cleared on return) -> RoPE on the q / k heads
-// (cs, qkv, vt already point at the first of the `rows` rows / columns), stored to qkv; v heads to vt [nkv hd, ldv]
-int32_t launch_qkv_finish(int32_t dtype, float* acc, const float2* cs, int32_t rows, int32_t nq, int32_t nkv, int32_t hd,
-                          void* qkv, void* vt, int64_t ldv, hipStream_t stream);
-// true if a residual-epilogue GEMM of this shape may split its K range (few tiles or few rows: weight-streaming
-// regime): partial sums are then added with atomics
-bool gemm_splits_k(int32_t dtype, int32_t M, int32_t N, int32_t Kd, bool a_rows_padded);
+// acc [n_slices][rows, (nq + 2 nkv) hd] fp32 (partial sums of a K-split QKV projection, added here in slice order) -> RoPE
+// on the q / k heads (cs, qkv, vt already point at the first of the `rows` rows / columns), stored to qkv; v heads to
+// vt [nkv hd, ldv]
+int32_t launch_qkv_finish(int32_t dtype, const float* acc, int32_t n_slices, int64_t slice_pitch, const float2* cs, int32_t rows,
+                          int32_t nq, int32_t nkv, int32_t hd, void* qkv, void* vt, int64_t ldv, hipStream_t stream);
+// K slices an EPI_PARTIAL_F32 projection of this shape is cut into (1: cutting would not help, the caller takes the
+// direct epilogue instead).  Depends on the shape only.
+int32_t gemm_partial_slices(int32_t dtype, int32_t M, int32_t N, int32_t Kd, bool a_rows_padded);
+int32_t skinny_partial_slices(int32_t N, int32_t Kd);     // the same for the kernel that serves at most 16 rows
+// h[r] += sum over the slices (in slice order) of partials[s][r]  for `rows` rows of d floats (slice pitch in floats);
+// gain != NULL: then xn[r] = rmsnorm(h[r]; gain) in the model dtype (residual update and the next norm in one pass)
+int32_t launch_resid_norm(int32_t dtype, float* h, const float* partials, int32_t n_slices, int64_t slice_pitch, const float* gain,
+                          float eps, int32_t rows, int32_t d, void* xn, hipStream_t stream);
 // dst[r][c] = src[r][c], rows x cols elements of the model dtype, pitches in elements
 int32_t launch_copy2d(int32_t dtype, const void* src, int64_t src_ld, void* dst, int64_t dst_ld, int64_t rows, int64_t cols,
                       hipStream_t stream);
@@ -201,9 +213,10 @@ struct BranchPos {
     __device__ int at(int j) const { return (lens ? min(max(lens[j], 1), T) : T) + done; }
 };
 // cs: (cos, sin) rows indexed by absolute position (prefix length + position in the branch)
-int32_t launch_decode_qkv_finish(int32_t dtype, float* acc, const float2* cs, int32_t Kr, int32_t nq, int32_t nkv, int32_t hd,
-                                 int32_t P, int32_t Tc, BranchPos pos, void* q_out, void* k_cache, void* v_cache,
-                                 hipStream_t stream);
+// acc [n_slices][Kr, (nq + 2 nkv) hd]: partial sums, added in slice order
+int32_t launch_decode_qkv_finish(int32_t dtype, const float* acc, int32_t n_slices, int64_t slice_pitch, const float2* cs, int32_t Kr,
+                                 int32_t nq, int32_t nkv, int32_t hd, int32_t P, int32_t Tc, BranchPos pos, void* q_out,
+                                 void* k_cache, void* v_cache, hipStream_t stream);
 int32_t launch_attn_decode(int32_t dtype, const void* q, const void* k_cache, const void* v_cache, void* out, int32_t Kr, int32_t P,
                            int32_t Tc, BranchPos pos, int32_t nq, int32_t nkv, int32_t hd, hipStream_t stream);
 // eos_id >= 0 and has_prev: a row whose previous token (ids[j stride - 1]) is eos_id gets eos_id again

@@ -56,23 +56,35 @@ __global__ __launch_bounds__(256) void embed_rows_kernel(const T* __restrict__ e
     for (int c = threadIdx.x; c < d; c += 256) h[(int64_t)j * d + c] = to_f32<T>(src[c]);
 }
 
-// One decode row per branch: acc [Kr, (nq + 2 nkv) hd] fp32 (cleared on return) -> q (rotated) to q_out [Kr, nq hd]; k (rotated) and v
-// to row `P + j Tc + pos.at(j)` of the layer's key / value cache.  cs: (cos, sin) rows indexed by absolute position.
+// One decode row per branch: acc [n_slices][Kr, (nq + 2 nkv) hd] fp32 partial sums (added in slice order) -> q (rotated) to
+// q_out [Kr, nq hd]; k (rotated) and v to row `P + j Tc + pos.at(j)` of the layer's key / value cache.  cs: (cos, sin)
+// rows indexed by absolute position.
 template <typename T>
-__global__ __launch_bounds__(256) void decode_qkv_finish_kernel(float* __restrict__ acc, const float2* __restrict__ cs, int Kr,
-                                                                int nq, int nkv, int hd, int P, int Tc, BranchPos pos,
-                                                                T* __restrict__ q_out, T* __restrict__ k_cache,
-                                                                T* __restrict__ v_cache) {
+__global__ __launch_bounds__(256) void decode_qkv_finish_kernel(const float* __restrict__ acc, int n_slices, int64_t pitch,
+                                                                const float2* __restrict__ cs, int Kr, int nq, int nkv, int hd,
+                                                                int P, int Tc, BranchPos pos, T* __restrict__ q_out,
+                                                                T* __restrict__ k_cache, T* __restrict__ v_cache) {
     const int half = hd >> 1, heads = nq + 2 * nkv;
     const int64_t idx = (int64_t)blockIdx.x * 256 + threadIdx.x;
     if (idx >= (int64_t)Kr * heads * half) return;
     const int i = (int)(idx % half);
     const int head = (int)((idx / half) % heads);
     const int j = (int)(idx / ((int64_t)half * heads));
-    float* a = acc + (int64_t)j * heads * hd + head * hd + i;
-    const float x1 = a[0], x2 = a[half];
-    a[0] = 0.f;                                  // left clear for a K-split projection that adds into it
-    a[half] = 0.f;
+    const float* a = acc + (int64_t)j * heads * hd + head * hd + i;
+    float x1 = 0.f, x2 = 0.f;
+    for (int s0 = 0; s0 < n_slices; s0 += 4) {          // four slices' loads in flight, added in slice order
+        float t1[4], t2[4];
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+            t1[u] = s0 + u < n_slices ? a[(s0 + u) * pitch] : 0.f;
+            t2[u] = s0 + u < n_slices ? a[(s0 + u) * pitch + half] : 0.f;
+        }
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+            x1 += t1[u];
+            x2 += t2[u];
+        }
+    }
     const int t_new = pos.at(j);
     const int64_t crow = P + (int64_t)j * Tc + t_new;
     if (head < nq + nkv) {
@@ -606,12 +618,12 @@ int32_t launch_embed_rows(int32_t dtype, const void* tok_embed, int32_t vocab, i
     return ATTS_OK;
 }
 
-int32_t launch_decode_qkv_finish(int32_t dtype, float* acc, const float2* cs, int32_t Kr, int32_t nq, int32_t nkv, int32_t hd,
-                                 int32_t P, int32_t Tc, BranchPos pos, void* q_out, void* k_cache, void* v_cache,
-                                 hipStream_t stream) {
+int32_t launch_decode_qkv_finish(int32_t dtype, const float* acc, int32_t n_slices, int64_t slice_pitch, const float2* cs, int32_t Kr,
+                                 int32_t nq, int32_t nkv, int32_t hd, int32_t P, int32_t Tc, BranchPos pos, void* q_out,
+                                 void* k_cache, void* v_cache, hipStream_t stream) {
     const int64_t total = (int64_t)Kr * (nq + 2 * nkv) * (hd / 2);
     DISPATCH_T(dtype, hipLaunchKernelGGL(decode_qkv_finish_kernel<T>, dim3((unsigned)ceil_div(total, 256)), dim3(256), 0, stream, acc,
-                                         cs, Kr, nq, nkv, hd, P, Tc, pos, (T*)q_out, (T*)k_cache, (T*)v_cache);)
+                                         n_slices, slice_pitch, cs, Kr, nq, nkv, hd, P, Tc, pos, (T*)q_out, (T*)k_cache, (T*)v_cache);)
     ATTS_LAUNCH_CHECK("decode_qkv_finish_kernel");
     return ATTS_OK;
 }

@@ -115,6 +115,85 @@ __global__ __launch_bounds__(256) void rmsnorm_kernel(const float* __restrict__ 
     rmsnorm_row<T>(h + (int64_t)blockIdx.x * d, gain, eps, d, out + (int64_t)blockIdx.x * d, red);
 }
 
+// ---- residual update from K-slice partial sums, fused with the next RMSNorm ------------------------------
+// One row per workgroup: h[r] += part[0][r] + part[1][r] + ... (slice order, so the sum does not depend on which
+// workgroup of the projection finished first), then, with a gain vector, out[r] = rmsnorm(h[r]).  Up to 4 float4 per
+// thread stay in registers between the passes; longer rows are read back (each thread re-reads what it wrote itself).
+template <typename T>
+__global__ __launch_bounds__(256) void resid_norm_kernel(float* __restrict__ h, const float* __restrict__ part, int n_slices,
+                                                         int64_t pitch, const float* __restrict__ gain, float eps, int d,
+                                                         T* __restrict__ out) {
+    __shared__ float red[4];
+    constexpr int kKeep = 4;
+    const int n4 = d >> 2;
+    float4* x4 = reinterpret_cast<float4*>(h + (int64_t)blockIdx.x * d);
+    const float4* p4 = reinterpret_cast<const float4*>(part + (int64_t)blockIdx.x * d);
+    const int64_t pitch4 = pitch >> 2;
+    // the slices are requested four at a time for all of the thread's chunks (16 independent loads in flight: with few
+    // rows this kernel is a handful of workgroups whose time is the latency of their loads), then added in slice order;
+    // a slice past the last one contributes +0
+    float4 keep[kKeep];
+    constexpr int kBatch = 4;
+#pragma unroll
+    for (int q = 0; q < kKeep; ++q) {
+        const int c = threadIdx.x + 256 * q;
+        keep[q] = c < n4 ? x4[c] : make_float4(0.f, 0.f, 0.f, 0.f);
+    }
+    for (int s0 = 0; s0 < n_slices; s0 += kBatch) {
+        float4 t[kBatch][kKeep];
+#pragma unroll
+        for (int u = 0; u < kBatch; ++u)
+#pragma unroll
+            for (int q = 0; q < kKeep; ++q) {
+                const int c = threadIdx.x + 256 * q;
+                t[u][q] = (s0 + u < n_slices && c < n4) ? p4[(s0 + u) * pitch4 + c] : make_float4(0.f, 0.f, 0.f, 0.f);
+            }
+#pragma unroll
+        for (int u = 0; u < kBatch; ++u)
+#pragma unroll
+            for (int q = 0; q < kKeep; ++q) {
+                keep[q].x += t[u][q].x; keep[q].y += t[u][q].y; keep[q].z += t[u][q].z; keep[q].w += t[u][q].w;
+            }
+    }
+    float ss = 0.f;
+#pragma unroll
+    for (int q = 0; q < kKeep; ++q) {
+        const int c = threadIdx.x + 256 * q;
+        if (c < n4) x4[c] = keep[q];
+        ss += keep[q].x * keep[q].x + keep[q].y * keep[q].y + keep[q].z * keep[q].z + keep[q].w * keep[q].w;
+    }
+    for (int c = threadIdx.x + 256 * kKeep; c < n4; c += 256) {
+        float4 v = x4[c];
+        for (int s0 = 0; s0 < n_slices; s0 += kBatch) {
+            float4 t[kBatch];
+#pragma unroll
+            for (int u = 0; u < kBatch; ++u) t[u] = s0 + u < n_slices ? p4[(s0 + u) * pitch4 + c] : make_float4(0.f, 0.f, 0.f, 0.f);
+#pragma unroll
+            for (int u = 0; u < kBatch; ++u) { v.x += t[u].x; v.y += t[u].y; v.z += t[u].z; v.w += t[u].w; }
+        }
+        x4[c] = v;
+        ss += v.x * v.x + v.y * v.y + v.z * v.z + v.w * v.w;
+    }
+    if (!gain) return;                                          // block-uniform
+    ss = block_sum<256>(ss, red);
+    const float inv = rsqrtf(ss / (float)d + eps);
+    const float4* g4 = reinterpret_cast<const float4*>(gain);
+    T* o = out + (int64_t)blockIdx.x * d;
+#pragma unroll
+    for (int q = 0; q < kKeep; ++q) {
+        const int c = threadIdx.x + 256 * q;
+        if (c < n4) {
+            const float4 g = g4[c];
+            store4<T>(o + 4 * c, make_float4(keep[q].x * inv * g.x, keep[q].y * inv * g.y, keep[q].z * inv * g.z,
+                                             keep[q].w * inv * g.w));
+        }
+    }
+    for (int c = threadIdx.x + 256 * kKeep; c < n4; c += 256) {
+        const float4 v = x4[c], g = g4[c];
+        store4<T>(o + 4 * c, make_float4(v.x * inv * g.x, v.y * inv * g.y, v.z * inv * g.z, v.w * inv * g.w));
+    }
+}
+
 // ---- rotary table per row: (cos, sin)(pos(r) * theta^(-2 i / hd)) in fp64, rounded once ----------
 __global__ void rope_table_kernel(float2* __restrict__ cs, int row0, int R, int P, int Tn, int half,
                                   double log_theta_over_half) {
@@ -177,14 +256,14 @@ __global__ __launch_bounds__(256) void copy2d_kernel(const T* __restrict__ src, 
     dst[r * dst_ld + c] = src[r * src_ld + c];
 }
 
-// Finish of a K-split QKV projection: acc [rows, (nq + 2 nkv) hd] holds the fp32 sums of the split workgroups.
-// One thread per (row, head, rotation pair i < hd / 2): q and k heads are rotated (rotate-half RoPE, table row
-// cs[r]) and stored to the qkv row, v heads are stored to the transposed copy vt [nkv hd, ldv] at column r.
-// The accumulator entries are cleared for the next projection.
+// Finish of a K-split QKV projection: acc [n_slices][rows, (nq + 2 nkv) hd] holds the fp32 partial sums of the K slices,
+// added here in slice order.  One thread per (row, head, rotation pair i < hd / 2): q and k heads are rotated
+// (rotate-half RoPE, table row cs[r]) and stored to the qkv row, v heads are stored to the transposed copy
+// vt [nkv hd, ldv] at column r.
 template <typename T>
-__global__ __launch_bounds__(256) void qkv_finish_kernel(float* __restrict__ acc, const float2* __restrict__ cs, int rows,
-                                                         int nq, int nkv, int hd, T* __restrict__ qkv,
-                                                         T* __restrict__ vt, int64_t ldv) {
+__global__ __launch_bounds__(256) void qkv_finish_kernel(const float* __restrict__ acc, int n_slices, int64_t pitch,
+                                                         const float2* __restrict__ cs, int rows, int nq, int nkv, int hd,
+                                                         T* __restrict__ qkv, T* __restrict__ vt, int64_t ldv) {
     const int half = hd >> 1, heads = nq + 2 * nkv;
     const int64_t idx = (int64_t)blockIdx.x * 256 + threadIdx.x;
     if (idx >= (int64_t)rows * heads * half) return;
@@ -192,10 +271,21 @@ __global__ __launch_bounds__(256) void qkv_finish_kernel(float* __restrict__ acc
     const int head = (int)((idx / half) % heads);
     const int r = (int)(idx / ((int64_t)half * heads));
     const int64_t ld = (int64_t)heads * hd;
-    float* a = acc + (int64_t)r * ld + head * hd + i;
-    const float x1 = a[0], x2 = a[half];
-    a[0] = 0.f;
-    a[half] = 0.f;
+    const float* a = acc + (int64_t)r * ld + head * hd + i;
+    float x1 = 0.f, x2 = 0.f;
+    for (int s0 = 0; s0 < n_slices; s0 += 4) {          // four slices' loads in flight, added in slice order
+        float t1[4], t2[4];
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+            t1[u] = s0 + u < n_slices ? a[(s0 + u) * pitch] : 0.f;
+            t2[u] = s0 + u < n_slices ? a[(s0 + u) * pitch + half] : 0.f;
+        }
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+            x1 += t1[u];
+            x2 += t2[u];
+        }
+    }
     if (head < nq + nkv) {
         const float2 c_s = cs[(int64_t)r * half + i];
         T* p = qkv + (int64_t)r * ld + head * hd + i;
@@ -206,11 +296,6 @@ __global__ __launch_bounds__(256) void qkv_finish_kernel(float* __restrict__ acc
         p[0] = from_f32<T>(x1);
         p[(int64_t)half * ldv] = from_f32<T>(x2);
     }
-}
-
-__global__ __launch_bounds__(256) void zero_f32_kernel(float* __restrict__ p, int64_t n) {
-    const int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x;
-    if (i < n) p[i] = 0.f;
 }
 
 // Zero columns [R, ldv) of every row of V^T (for a producer that writes only the R real columns).
@@ -331,19 +416,22 @@ int32_t launch_rope_split(int32_t dtype, void* qkv, const float2* cs, ScoreShape
     return ATTS_OK;
 }
 
-int32_t launch_zero_f32(float* p, int64_t n, hipStream_t stream) {
-    if (n <= 0) return ATTS_OK;
-    hipLaunchKernelGGL(zero_f32_kernel, dim3((unsigned)ceil_div(n, 256)), dim3(256), 0, stream, p, n);
-    ATTS_LAUNCH_CHECK("zero_f32_kernel");
+int32_t launch_qkv_finish(int32_t dtype, const float* acc, int32_t n_slices, int64_t slice_pitch, const float2* cs, int32_t rows,
+                          int32_t nq, int32_t nkv, int32_t hd, void* qkv, void* vt, int64_t ldv, hipStream_t stream) {
+    const int64_t total = (int64_t)rows * (nq + 2 * nkv) * (hd / 2);
+    DISPATCH_T(dtype, hipLaunchKernelGGL(qkv_finish_kernel<T>, dim3((unsigned)ceil_div(total, 256)), dim3(256), 0, stream, acc,
+                                         n_slices, slice_pitch, cs, rows, nq, nkv, hd, (T*)qkv, (T*)vt, ldv);)
+    ATTS_LAUNCH_CHECK("qkv_finish_kernel");
     return ATTS_OK;
 }
 
-int32_t launch_qkv_finish(int32_t dtype, float* acc, const float2* cs, int32_t rows, int32_t nq, int32_t nkv, int32_t hd,
-                          void* qkv, void* vt, int64_t ldv, hipStream_t stream) {
-    const int64_t total = (int64_t)rows * (nq + 2 * nkv) * (hd / 2);
-    DISPATCH_T(dtype, hipLaunchKernelGGL(qkv_finish_kernel<T>, dim3((unsigned)ceil_div(total, 256)), dim3(256), 0, stream, acc, cs,
-                                         rows, nq, nkv, hd, (T*)qkv, (T*)vt, ldv);)
-    ATTS_LAUNCH_CHECK("qkv_finish_kernel");
+int32_t launch_resid_norm(int32_t dtype, float* h, const float* partials, int32_t n_slices, int64_t slice_pitch, const float* gain,
+                          float eps, int32_t rows, int32_t d, void* xn, hipStream_t stream) {
+    if (rows <= 0) return ATTS_OK;
+    if (d % 4 || slice_pitch % 4) return fail(ATTS_ERR_SHAPE, "residual update: row length and slice pitch must be multiples of 4");
+    DISPATCH_T(dtype, hipLaunchKernelGGL(resid_norm_kernel<T>, dim3(rows), dim3(256), 0, stream, h, partials, n_slices, slice_pitch,
+                                         gain, eps, d, (T*)xn);)
+    ATTS_LAUNCH_CHECK("resid_norm_kernel");
     return ATTS_OK;
 }
 

@@ -82,8 +82,8 @@ struct GemmDims {
     int32_t n_part, nt_m, nt_n;
     int64_t ldv;            // EPI_QKV_ROPE: row pitch of the transposed V
     int32_t n_rot_heads;    // EPI_QKV_ROPE: heads (128 columns each) that get rotated; later heads are V
-    int32_t k_slices;       // fast path, EPI_RESID_F32: > 1 = the K range is split over this many workgroups per tile,
-                            // which add their partial sums to the output with atomics
+    int32_t k_slices;       // EPI_PARTIAL_F32: the K range is split over this many workgroups per tile, slice s stores
+    int64_t slice_pitch;    // its partial sums at out + s slice_pitch (floats); 1 for every other epilogue
 };
 
 constexpr int kResidAheadCols = 2;   // column blocks of block row 0 whose old values a kernel may hand to the residual epilogue
@@ -100,7 +100,7 @@ __device__ __forceinline__ void gemm_epilogue_impl(f32x16 (&acc)[MI][NI], int m0
     constexpr int WM = 32 * MI, WN = 32 * NI;
     const int row_base = m0 + wm * WM + 4 * half;
 
-    if constexpr (EPI == EPI_STORE_ACT || EPI == EPI_STORE_F32 || EPI == EPI_RESID_F32) {
+    if constexpr (EPI == EPI_STORE_ACT || EPI == EPI_STORE_F32 || EPI == EPI_RESID_F32 || EPI == EPI_PARTIAL_F32) {
         const int col_base = n0 + wn * WN + l32;
 #pragma unroll
         for (int i = 0; i < MI; ++i)
@@ -114,10 +114,9 @@ __device__ __forceinline__ void gemm_epilogue_impl(f32x16 (&acc)[MI][NI], int m0
                     if (col >= g.N) continue;
                     int64_t idx = (int64_t)row * g.ldc + col;
                     if (EPI == EPI_STORE_ACT) reinterpret_cast<T*>(g_out)[idx] = from_f32<T>(acc[i][j][v]);
-                    if (EPI == EPI_STORE_F32) reinterpret_cast<float*>(g_out)[idx] = acc[i][j][v];
+                    if (EPI == EPI_STORE_F32 || EPI == EPI_PARTIAL_F32) reinterpret_cast<float*>(g_out)[idx] = acc[i][j][v];   // (slice base in g_out)
                     if (EPI == EPI_RESID_F32) {
-                        if (g.k_slices > 1) unsafeAtomicAdd(reinterpret_cast<float*>(g_out) + idx, acc[i][j][v]);
-                        else if (i == 0 && j < kResidAheadCols && have_resid0) reinterpret_cast<float*>(g_out)[idx] = resid0[j][v] + acc[i][j][v];
+                        if (i == 0 && j < kResidAheadCols && have_resid0) reinterpret_cast<float*>(g_out)[idx] = resid0[j][v] + acc[i][j][v];
                         else reinterpret_cast<float*>(g_out)[idx] += acc[i][j][v];
                     }
                 }
@@ -570,7 +569,7 @@ __global__ __launch_bounds__(128 * kWavesM) void gemm_bf16_wide_kernel(const cha
     // a dozen slabs before the end, so that half of the epilogue's read latency and traffic lies under the main loop.
     constexpr bool kResidAhead = EPI == EPI_RESID_F32 && MI == 2;
     float resid0[NI][16];
-    const bool resid_ahead = kResidAhead && g.k_slices == 1 && nk > 16;
+    const bool resid_ahead = kResidAhead && nk > 16;
     auto prefetch_resid = [&]() __attribute__((always_inline)) {
         const float* o = reinterpret_cast<const float*>(g_out);
         const int row_base = m0 + wm * WM + 4 * half, col_base = n0 + wn * WN + l32;
@@ -598,7 +597,9 @@ __global__ __launch_bounds__(128 * kWavesM) void gemm_bf16_wide_kernel(const cha
         slab(k, No{}, No{}, No{}, No{});
     }
 
-    gemm_epilogue_impl<bf16, MI, NI, EPI>(acc, m0, n0, wm, wn, l32, half, tc.tn, g_out, g_targets, g_partials, g_target_logit, g_rope,
+    void* out = g_out;
+    if (EPI == EPI_PARTIAL_F32) out = reinterpret_cast<float*>(g_out) + (int64_t)slice * g.slice_pitch;
+    gemm_epilogue_impl<bf16, MI, NI, EPI>(acc, m0, n0, wm, wn, l32, half, tc.tn, out, g_targets, g_partials, g_target_logit, g_rope,
                                           g_vt, g, resid0, resid_ahead);
 }
 
@@ -631,10 +632,10 @@ int fast_tile_rows(int epi, const GemmArgs& g) {
     return cost384 * 9 <= cost256 * 10 ? 384 : 256;   // a 384-row tile runs ~10 % closer to the MFMA peak
 }
 
-// K slices per tile for the residual epilogue: when the tiles alone leave most of the chip idle (few rows and a
+// K slices per tile for the partial-sum epilogue: when the tiles alone leave most of the chip idle (few rows and a
 // narrow output: the weight-streaming regime), the K range is cut so that about one workgroup per CU runs.
 int fast_k_slices(int epi, int n_tiles, int nk) {
-    if (epi != EPI_RESID_F32 || n_tiles >= 128) return 1;
+    if (epi != EPI_PARTIAL_F32 || n_tiles >= 128) return 1;
     int s = 256 / n_tiles;                                   // never more workgroups than CUs: no second round
     const int max_s = nk / 6;                                // every slice still walks several slabs
     if (s > max_s) s = max_s;
@@ -654,6 +655,7 @@ int32_t launch_wide_tile(const GemmArgs& g, hipStream_t stream) {
     d.nt_m = (int)ceil_div(g.M, BM);
     d.nt_n = g.N / n_out;
     d.k_slices = fast_k_slices(EPI, d.nt_m * d.nt_n, g.Kd / 64);
+    d.slice_pitch = (int64_t)g.M * g.ldc;
     const size_t lds = 160 * 1024;
     ATTS_TRY_RC((allow_dynamic_lds<gemm_bf16_wide_kernel<EPI, kWavesM, MI, NI>>(lds)));
     hipLaunchKernelGGL((gemm_bf16_wide_kernel<EPI, kWavesM, MI, NI>), dim3(d.nt_m * d.nt_n * d.k_slices), dim3(128 * kWavesM), lds, stream,
@@ -667,8 +669,8 @@ template <int EPI>
 int32_t launch_fast(const GemmArgs& g, hipStream_t stream) {
     const int rows = fast_tile_rows(EPI, g);
     if (rows == 128) {
-        // narrow outputs that split K: 128-column tiles double the tiles, so half as many K slices (and atomics) fill the chip
-        if constexpr (EPI == EPI_RESID_F32) return launch_wide_tile<EPI, 1, 2>(g, stream);
+        // narrow outputs that split K: 128-column tiles double the tiles, so half as many K slices fill the chip
+        if constexpr (EPI == EPI_PARTIAL_F32) return launch_wide_tile<EPI, 1, 2>(g, stream);
         return launch_wide_tile<EPI, 1>(g, stream);
     }
     if (rows == 384) return launch_wide_tile<EPI, 3>(g, stream);
@@ -685,6 +687,7 @@ int32_t launch_cfg(const GemmArgs& g, hipStream_t stream) {
     d.ldv = g.ldv;
     d.n_rot_heads = g.n_rot_heads;
     d.k_slices = 1;
+    d.slice_pitch = 0;
     d.nt_m = (int)ceil_div(g.M, BM);
     d.nt_n = (int)ceil_div(g.N, n_out);
     const size_t lds = 2 * (size_t)(BM + BN) * kRowBytes;
@@ -718,6 +721,7 @@ int32_t launch_t(GemmEpilogue epi, const GemmArgs& g, hipStream_t stream) {
         case EPI_RESID_F32: return launch_epi<T, EPI_RESID_F32>(g, stream);
         case EPI_SWIGLU: return launch_epi<T, EPI_SWIGLU>(g, stream);
         case EPI_LMHEAD: return launch_epi<T, EPI_LMHEAD>(g, stream);
+        case EPI_PARTIAL_F32: return launch_epi<T, EPI_PARTIAL_F32>(g, stream);
         case EPI_QKV_ROPE: break;   // fast path only, dispatched by launch_gemm
     }
     return fail(ATTS_ERR_INVALID_ARG, "unknown GEMM epilogue %d", (int)epi);
@@ -764,14 +768,14 @@ bool qkv_rope_fusable(int32_t dtype, int32_t M, int32_t N, int32_t Kd, int32_t h
     return head_dim == 128 && fast_path_ok(dtype, EPI_QKV_ROPE, g);
 }
 
-bool gemm_splits_k(int32_t dtype, int32_t M, int32_t N, int32_t Kd, bool a_rows_padded) {
+int32_t gemm_partial_slices(int32_t dtype, int32_t M, int32_t N, int32_t Kd, bool a_rows_padded) {
     GemmArgs g{};
     g.M = M; g.N = N; g.Kd = Kd; g.lda = Kd; g.ldw = Kd; g.a_rows_padded = a_rows_padded;
-    if (gemm_skinny_ok(dtype, EPI_RESID_F32, g)) return true;     // always the accumulating form
-    if (!fast_path_ok(dtype, EPI_RESID_F32, g)) return false;
-    const int bm = fast_tile_rows(EPI_RESID_F32, g);
+    if (gemm_skinny_ok(dtype, EPI_PARTIAL_F32, g)) return skinny_partial_slices(N, Kd);
+    if (!fast_path_ok(dtype, EPI_PARTIAL_F32, g)) return 1;
+    const int bm = fast_tile_rows(EPI_PARTIAL_F32, g);
     const int64_t tiles = ceil_div(M, bm) * (N / (bm == 128 ? 128 : 256));
-    return fast_k_slices(EPI_RESID_F32, (int)tiles, Kd / 64) > 1;
+    return fast_k_slices(EPI_PARTIAL_F32, (int)tiles, Kd / 64);
 }
 
 int32_t launch_gemm(int32_t dtype, GemmEpilogue epi, const GemmArgs& g, hipStream_t stream) {
@@ -782,16 +786,18 @@ int32_t launch_gemm(int32_t dtype, GemmEpilogue epi, const GemmArgs& g, hipStrea
     if (((uintptr_t)g.a | (uintptr_t)g.w) & 15) return fail(ATTS_ERR_INVALID_ARG, "gemm: operands must be 16-byte aligned");
     if (epi == EPI_LMHEAD && g.n_part != lmhead_num_partials(dtype, g.M, g.N, g.Kd, g.a_rows_padded))
         return fail(ATTS_ERR_INVALID_ARG, "gemm: wrong partial count for the LM-head epilogue");
+    if (epi == EPI_PARTIAL_F32 && g.n_slices != gemm_partial_slices(dtype, g.M, g.N, g.Kd, g.a_rows_padded))
+        return fail(ATTS_ERR_INVALID_ARG, "gemm: wrong slice count for the partial-sum epilogue");
     if (epi == EPI_QKV_ROPE) {
         if (!qkv_rope_fusable(dtype, g.M, g.N, g.Kd, 128, g.a_rows_padded) || !g.rope || !g.vt || g.ldv < g.M || g.ldv % 4 ||
             g.n_rot_heads < 1 || g.n_rot_heads * 128 >= g.N)
             return fail(ATTS_ERR_SHAPE, "gemm: the fused QKV epilogue does not apply to this call");
         return launch_fast<EPI_QKV_ROPE>(g, stream);
     }
-    // A decoding step (at most 16 rows) streams the weights once.  Narrow outputs with the residual epilogue go to
-    // the kernel that cuts K over single wavefronts; wide outputs (SwiGLU, logits) already give the aligned kernel
+    // A decoding step (at most 16 rows) streams the weights once.  Narrow outputs (partial-sum epilogue) go to the
+    // kernel that cuts K over single wavefronts; wide outputs (SwiGLU, logits) already give the aligned kernel
     // enough tiles, and it streams them as fast, so they only go there when it cannot serve the shape.
-    if (gemm_skinny_ok(dtype, epi, g) && (epi == EPI_RESID_F32 || !fast_path_ok(dtype, epi, g)))
+    if (gemm_skinny_ok(dtype, epi, g) && (epi == EPI_PARTIAL_F32 || !fast_path_ok(dtype, epi, g)))
         return launch_gemm_skinny(epi, g, stream);
     return dtype == ATTS_DTYPE_F32 ? launch_t<float>(epi, g, stream) : launch_t<bf16>(epi, g, stream);
 }

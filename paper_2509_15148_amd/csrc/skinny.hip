@@ -14,8 +14,9 @@
 //   * Weights go global -> registers with kSkinnyUnroll k-steps per buffer and two buffers (ping-pong), so
 //     up to 2 x 3 x kSkinnyUnroll 16-byte loads per lane are outstanding while the other buffer feeds the MFMAs.
 //     Deeper buffers did not stream faster; what counts is that every CU has about four such wavefronts.
-//   * EPI_RESID_F32 cuts the K range into slices (the output is narrow, so column groups alone would leave
-//     the chip idle); every slice adds its partial sums with fp32 atomics, whose order is not fixed.
+//   * EPI_PARTIAL_F32 cuts the K range into slices (the output is narrow, so column groups alone would leave
+//     the chip idle); every slice stores its partial sums in its own copy of the output, and the consumer adds the
+//     copies in slice order (no atomics: bit-reproducible).
 //     EPI_STORE_F32 and EPI_SWIGLU (gate block + up block of the same 16 features per wavefront) take the
 //     whole K range in one wavefront.
 #include "common.h"
@@ -25,19 +26,15 @@ namespace {
 
 constexpr int kSkinnyRows = 16;
 constexpr int kSkinnyWaves = 4;      // wavefronts (independent work items) per workgroup
-#ifndef ATTS_SKINNY_UNROLL
-#define ATTS_SKINNY_UNROLL 2
-#endif
-constexpr int kSkinnyUnroll = ATTS_SKINNY_UNROLL;
+constexpr int kSkinnyUnroll = 2;     // k-steps per register buffer
 constexpr int kStepElems = 32;       // K elements per MFMA
-#ifndef ATTS_SKINNY_WAVES_TARGET
-#define ATTS_SKINNY_WAVES_TARGET 1024
-#endif
+constexpr int kSkinnyWavesTarget = 1024;   // wavefronts a K-split launch aims for
 
 struct SkinnyDims {
     int32_t M, N, n_w_rows;
     int64_t lda, ldw, ldc;
     int32_t n_groups, k_slices, n_steps, steps_per_slice;
+    int64_t slice_pitch;
 };
 
 struct SkinnyFrags {
@@ -113,17 +110,23 @@ __global__ __launch_bounds__(64 * kSkinnyWaves) void gemm_skinny_kernel(const bf
                 reinterpret_cast<bf16*>(g_out)[(int64_t)row * d.ldc + col] = from_f32<bf16>(y);
             }
         } else {
-            float* out = reinterpret_cast<float*>(g_out) + (int64_t)row * d.ldc;
+            float* out = reinterpret_cast<float*>(g_out) + (int64_t)slice * d.slice_pitch + (int64_t)row * d.ldc;   // pitch 0 unless partial
             const int col0 = grp * 32 + r, col1 = col0 + 16;
-            if constexpr (EPI == EPI_RESID_F32) {
-                if (col0 < d.N) unsafeAtomicAdd(out + col0, acc0[v]);
-                if (col1 < d.N) unsafeAtomicAdd(out + col1, acc1[v]);
-            } else {
-                if (col0 < d.N) out[col0] = acc0[v];
-                if (col1 < d.N) out[col1] = acc1[v];
-            }
+            if (col0 < d.N) out[col0] = acc0[v];
+            if (col1 < d.N) out[col1] = acc1[v];
         }
     }
+}
+
+// K steps per slice of the partial-sum form: about four wavefronts per CU stream fastest (measured: fewer leave CUs
+// idle, many more shorten every wavefront's run), each with at least two buffers of k-steps
+int32_t skinny_steps_per_slice(int32_t N, int32_t Kd) {
+    const int64_t n_groups = ceil_div(N, 32), n_steps = Kd / kStepElems;
+    int64_t s = kSkinnyWavesTarget / n_groups;
+    const int64_t max_s = n_steps / (2 * kSkinnyUnroll);
+    if (s > max_s) s = max_s;
+    if (s < 1) s = 1;
+    return (int32_t)align_up((size_t)ceil_div(n_steps, s), 2 * kSkinnyUnroll);
 }
 
 template <int EPI>
@@ -136,15 +139,11 @@ int32_t launch_skinny_epi(const GemmArgs& g, hipStream_t stream) {
     d.n_steps = g.Kd / kStepElems;
     d.k_slices = 1;
     d.steps_per_slice = d.n_steps;
-    if (EPI == EPI_RESID_F32) {
-        // about four wavefronts per CU stream fastest (measured: fewer leave CUs idle, many more shorten every
-        // wavefront's run and multiply the atomics), each with at least two buffers of k-steps
-        int64_t s = ATTS_SKINNY_WAVES_TARGET / d.n_groups;
-        const int64_t max_s = d.n_steps / (2 * kSkinnyUnroll);
-        if (s > max_s) s = max_s;
-        if (s < 1) s = 1;
-        d.steps_per_slice = (int32_t)align_up((size_t)ceil_div(d.n_steps, s), 2 * kSkinnyUnroll);
+    d.slice_pitch = 0;
+    if (EPI == EPI_PARTIAL_F32) {
+        d.steps_per_slice = skinny_steps_per_slice(g.N, g.Kd);
         d.k_slices = (int32_t)ceil_div(d.n_steps, d.steps_per_slice);
+        d.slice_pitch = (int64_t)g.M * g.ldc;
     }
     const int64_t items = (int64_t)d.n_groups * d.k_slices;
     hipLaunchKernelGGL(gemm_skinny_kernel<EPI>, dim3((unsigned)ceil_div(items, kSkinnyWaves)), dim3(64 * kSkinnyWaves), 0, stream,
@@ -156,15 +155,19 @@ int32_t launch_skinny_epi(const GemmArgs& g, hipStream_t stream) {
 }  // namespace
 
 bool gemm_skinny_ok(int32_t dtype, GemmEpilogue epi, const GemmArgs& g) {
-    return dtype == ATTS_DTYPE_BF16 && (epi == EPI_STORE_F32 || epi == EPI_RESID_F32 || epi == EPI_SWIGLU) && g.M >= 1 &&
+    return dtype == ATTS_DTYPE_BF16 && (epi == EPI_STORE_F32 || epi == EPI_PARTIAL_F32 || epi == EPI_SWIGLU) && g.M >= 1 &&
            g.M <= kSkinnyRows && g.N >= 1 && g.Kd >= kStepElems && g.Kd % kStepElems == 0 && g.lda % 8 == 0 && g.ldw % 8 == 0 &&
            (int64_t)g.N * (epi == EPI_SWIGLU ? 2 : 1) < (1ll << 30);
+}
+
+int32_t skinny_partial_slices(int32_t N, int32_t Kd) {
+    return (int32_t)ceil_div(Kd / kStepElems, skinny_steps_per_slice(N, Kd));
 }
 
 int32_t launch_gemm_skinny(GemmEpilogue epi, const GemmArgs& g, hipStream_t stream) {
     switch (epi) {
         case EPI_STORE_F32: return launch_skinny_epi<EPI_STORE_F32>(g, stream);
-        case EPI_RESID_F32: return launch_skinny_epi<EPI_RESID_F32>(g, stream);
+        case EPI_PARTIAL_F32: return launch_skinny_epi<EPI_PARTIAL_F32>(g, stream);
         case EPI_SWIGLU: return launch_skinny_epi<EPI_SWIGLU>(g, stream);
         default: break;
     }

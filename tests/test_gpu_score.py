@@ -66,10 +66,10 @@ def test_small_models_ragged_shapes(cfg, P, K, T):
     assert flag == 0
     assert np.abs(lp - ref_lp).max() <= TOL[cfg.dtype], np.abs(lp - ref_lp).max()
     assert np.abs(sc - ref_s).max() <= TOL[cfg.dtype]
-    # scores only (token_logprobs = NULL) gives the same scores (calls with this few rows split the K range of
-    # some projections over workgroups that add their partial sums atomically: equal up to rounding order)
+    # scores only (token_logprobs = NULL) gives the same scores, bit for bit: calls with this few rows split the K range
+    # of some projections over workgroups, whose partial sums are added in a fixed order
     _, sc2, _ = _run_gpu(A, cfg, w_dev, prefix, drafts, want_lp=False)
-    assert np.abs(sc - sc2).max() <= TOL[cfg.dtype] / 20
+    assert np.array_equal(sc, sc2)
 
 
 def test_variable_draft_lengths_and_padding_ids():
@@ -134,6 +134,9 @@ def _full_width_case(name, n_layers, k_sample, shape=None):
     w_dev, prefix, drafts = _case(cfg, P, K, T, wl.seed, n_layers=n_layers)
     lp, sc, flag = _run_gpu(A, cfg, w_dev, prefix, drafts)
     assert flag == 0 and np.all(np.isfinite(lp)) and np.all(lp <= 0)
+    if shape is not None:      # run-to-run bit-stability, also where projections split their K range over workgroups
+        lp2, sc2, _ = _run_gpu(A, cfg, w_dev, prefix, drafts)
+        assert np.array_equal(lp, lp2) and np.array_equal(sc, sc2)
     w_np = weights_to_numpy(w_dev)
     del w_dev
     torch.cuda.empty_cache()
@@ -156,11 +159,12 @@ def test_7b_shape_two_layer_slice():
     _full_width_case("7b", n_layers=2, k_sample="all")
 
 
-@pytest.mark.parametrize("shape", [(16, 16, 8), (300, 5, 67), (1, 2, 3)])
+@pytest.mark.parametrize("shape", [(16, 16, 8), (300, 5, 67), (1, 2, 3), (700, 3, 100)])
 def test_7b_width_few_and_ragged_rows(shape):
     """Row counts that are not whole 256-row tiles, at full model width: the decode-like shape that bench.py
     times (144 rows: projections with few tiles split their K range over several workgroups), a ragged
-    multi-tile one, and a handful of rows.  All drafts are compared."""
+    multi-tile one, a handful of rows, and 1000 rows (four tile rows, still few enough tiles to split K).  All drafts
+    are compared, and a second run must reproduce the first bit for bit."""
     _full_width_case("7b", n_layers=2, k_sample="all", shape=shape)
 
 
