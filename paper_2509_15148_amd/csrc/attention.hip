@@ -80,9 +80,11 @@ __global__ __launch_bounds__(64) void attn_simple_kernel(const T* __restrict__ q
 constexpr int kHd = 128;
 constexpr int kKTile = 64;    // keys per LDS tile
 
-// kWaves wavefronts of 32 query rows each share the key / value tiles of one head; kStages tiles of LDS form a ring
-// (kStages - 1 tiles are in flight or in use: with three stages the loads run two tiles ahead of the MFMAs).
-template <int kWaves, int kStages>
+// kWaves wavefronts of 32 query rows each share the key / value tiles of one head; kStages tiles of LDS form a ring.
+// kPipe: the scores of tile t + 1 are issued to the matrix cores BEFORE the softmax of tile t, so that the exponentials
+// (vector ALU) of one tile run while the matrix pipe works on the next one; needs the key tile t + 1 next to the value
+// tile t in LDS, hence one more stage than the plain order for the same prefetch distance.
+template <int kWaves, int kStages, bool kPipe>
 __global__ __launch_bounds__(64 * kWaves, 512 / (64 * kWaves)) void attn_mfma_kernel(const bf16* __restrict__ qkv, const bf16* __restrict__ vt,
                                                            int64_t ldv, bf16* __restrict__ out, int row0, int R, int P, int Tn,
                                                            int nq, int nkv, float scale_log2e) {
@@ -91,7 +93,9 @@ __global__ __launch_bounds__(64 * kWaves, 512 / (64 * kWaves)) void attn_mfma_ke
     constexpr int kQTile = 32 * kWaves;                 // query rows per workgroup
     constexpr int kKBytes = kKTile * kHd * 2, kStage = 2 * kKBytes;
     constexpr int kDmaK = 16 / kWaves, kDmaV = 16 / kWaves;     // 1 KiB DMA instructions per wave and tile
+    constexpr int kDmaTile = kDmaK + kDmaV;
     static_assert(kWaves == 4 || kWaves == 8, "DMA addressing below");
+    static_assert(kStages >= (kPipe ? 3 : 2), "ring depth");
     extern __shared__ __attribute__((aligned(16))) char smem[];   // [kStages][kStage]
 
     const int tid = threadIdx.x, lane = tid & 63;
@@ -108,7 +112,8 @@ __global__ __launch_bounds__(64 * kWaves, 512 / (64 * kWaves)) void attn_mfma_ke
     const int r = rw0 + l32;
     const bool r_ok = r < R;
     const int ss = seg_start(r_ok ? r : r_last, P, Tn);
-    const int ss_w1 = seg_start(max(rw1, rw0 <= r_last ? rw0 : r_last), P, Tn);   // draft start of the wave's last row
+    const int ss_w0 = seg_start(min(rw0, r_last), P, Tn);            // draft start of the wave's first row
+    const int ss_w1 = seg_start(max(rw1, rw0 <= r_last ? rw0 : r_last), P, Tn);   // ... and of its last row
 
     // Q fragments (B operand of S^T = K Q^T): lane holds Q[r][16 s + 8 g + (0..7)], s = 0..7.
     bf16x8 qf[8];
@@ -168,29 +173,26 @@ __global__ __launch_bounds__(64 * kWaves, 512 / (64 * kWaves)) void attn_mfma_ke
     float m_run = -1e30f;   // reference max (scaled, log2 domain), shared by the lane pair (l, l ^ 32)
     float l_run = 0.f;      // this lane's share of the running denominator
 
-    // Ring of kStages tiles: tiles 0 .. kStages - 2 are requested up front; at the top of step t the tiles up to
-    // t + kStages - 2 have been requested, tile t must have landed (the younger ones may stay in flight), and after
-    // the barrier tile t + kStages - 1 is requested into the stage that tile t - 1 occupied.
-#pragma unroll
-    for (int t = 0; t < kStages - 1; ++t)
-        if (t < n_tiles) issue_tile(t);
-    for (int t = 0; t < n_tiles; ++t) {
+    // Wave-uniform visibility of tile t for the wave's rows rw0 .. rw1:
+    //   nothing visible: the tile starts after the last row, or lies in drafts before the wave's first row's
+    //   fully visible:   every key <= first row, and (a prefix tile or inside the draft of the last row)
+    auto tile_none = [&](int t) {
         const int j0 = tile_start(t);
-        if (t + kStages - 2 < n_tiles) wait_vmcnt<(kStages - 2) * (kDmaK + kDmaV)>(); else wait_vmcnt<0>();
-        block_barrier();            // tile t is in LDS for every wave; every wave is done with tile t - 1
-        if (t + kStages - 1 < n_tiles) issue_tile(t + kStages - 1);
+        return rw1 < rw0 || j0 > rw1 || (j0 >= P && j0 + kKTile <= ss_w0);
+    };
+    auto tile_full = [&](int t) {
+        const int j0 = tile_start(t);
+        return j0 + kKTile - 1 <= rw0 && (j0 + kKTile <= P || j0 >= ss_w1) && rw0 + 31 <= r_last;
+    };
 
-        // Wave-uniform visibility of this tile for the wave's rows rw0 .. rw1:
-        //   nothing visible: the tile starts after the last row, or lies in drafts before the wave's first row's
-        //   fully visible:   every key <= first row, and (a prefix tile or inside the draft of the last row)
-        const bool none = rw1 < rw0 || j0 > rw1 || (j0 >= P && j0 + kKTile <= seg_start(rw0, P, Tn));
-        if (none) continue;
-        const bool full = j0 + kKTile - 1 <= rw0 && (j0 + kKTile <= P || j0 >= ss_w1) && rw0 + 31 <= r_last;
+    // ---- S^T = K Q^T for the two 32-key blocks of tile t.  MFMA row i of a block is fed with key pi(i) of the block,
+    // pi = exchange of bits 2 and 3: accumulator entry v of lane half g is then the score of key
+    //     32 kb + 16 (v >> 3) + 8 g + (v & 7),
+    // eight consecutive keys per lane and 16-key step: exactly the k order of a 16-byte V^T fragment, so the
+    // probabilities feed the second product from registers and the value fragments are single 16-byte LDS reads.
+    const int kperm = (l32 & 0x13) | ((l32 & 8) >> 1) | ((l32 & 4) << 1);
+    auto score_tile = [&](int t, f32x16 (&acc_s)[2]) __attribute__((always_inline)) {
         const char* sK = smem + (t % kStages) * kStage;
-        const char* sV = sK + kKBytes;
-
-        // ---- S^T = K Q^T for two 32-key blocks
-        f32x16 acc_s[2];
 #pragma unroll
         for (int kb = 0; kb < 2; ++kb)
 #pragma unroll
@@ -199,18 +201,23 @@ __global__ __launch_bounds__(64 * kWaves, 512 / (64 * kWaves)) void attn_mfma_ke
         for (int s = 0; s < 8; ++s)
 #pragma unroll
             for (int kb = 0; kb < 2; ++kb) {
-                const int kr = kb * 32 + l32;
+                const int kr = kb * 32 + kperm;
                 bf16x8 kf = *reinterpret_cast<const bf16x8*>(sK + kr * 256 + (((2 * s + g) ^ (kr & 15)) << 4));
                 acc_s[kb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, qf[s], acc_s[kb], 0, 0, 0);
             }
-        // acc_s[kb][4 a + b] = raw score (q . k) of key j0 + 32 kb + 8 a + 4 g + b for this lane's query.  The softmax
-        // works on z = score * scale * log2(e): the scale is folded into the one fused multiply-add in front of exp2.
-        if (!full) {
+    };
+
+    // ---- softmax of tile t (raw scores in acc_s) and O^T += V^T P^T.  The softmax works on
+    // z = score * scale * log2(e): the scale is folded into the one fused multiply-add in front of exp2.
+    auto softmax_pv = [&](int t, f32x16 (&acc_s)[2]) __attribute__((always_inline)) {
+        const int j0 = tile_start(t);
+        const char* sV = smem + (t % kStages) * kStage + kKBytes;
+        if (!tile_full(t)) {
 #pragma unroll
             for (int kb = 0; kb < 2; ++kb)
 #pragma unroll
                 for (int v = 0; v < 16; ++v) {
-                    const int j = j0 + 32 * kb + 8 * (v >> 2) + 4 * g + (v & 3);
+                    const int j = j0 + 32 * kb + 16 * (v >> 3) + 8 * g + (v & 7);
                     const bool vis = r_ok && j <= r && (j < P || j >= ss);
                     acc_s[kb][v] = vis ? acc_s[kb][v] : -INFINITY;
                 }
@@ -244,22 +251,55 @@ __global__ __launch_bounds__(64 * kWaves, 512 / (64 * kWaves)) void attn_mfma_ke
                 pf[kb * 2 + (v >> 3)][v & 7] = (bf16)p;
             }
         l_run += psum;
-
-        // ---- O^T += V^T P^T
 #pragma unroll
         for (int s = 0; s < 4; ++s)
 #pragma unroll
             for (int nb = 0; nb < 4; ++nb) {
                 const int n = nb * 32 + l32;
-                const char* vp = sV + n * 128 + 8 * g;
-                union {
-                    uint2 u[2];
-                    bf16x8 f;
-                } vf;
-                vf.u[0] = *reinterpret_cast<const uint2*>(vp + (((2 * s) ^ ((n >> 1) & 7)) << 4));
-                vf.u[1] = *reinterpret_cast<const uint2*>(vp + (((2 * s + 1) ^ ((n >> 1) & 7)) << 4));
-                acc_o[nb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf.f, pf[s], acc_o[nb], 0, 0, 0);
+                bf16x8 vf = *reinterpret_cast<const bf16x8*>(sV + n * 128 + (((2 * s + g) ^ ((n >> 1) & 7)) << 4));
+                acc_o[nb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf, pf[s], acc_o[nb], 0, 0, 0);
             }
+    };
+
+    // Ring of kStages tiles, tiles 0 .. kStages - 2 requested up front.
+#pragma unroll
+    for (int t = 0; t < kStages - 1; ++t)
+        if (t < n_tiles) issue_tile(t);
+    if constexpr (!kPipe) {
+        // At the top of step t the tiles up to t + kStages - 2 have been requested, tile t must have landed (the
+        // younger ones may stay in flight); after the barrier tile t + kStages - 1 goes into the stage of tile t - 1.
+        for (int t = 0; t < n_tiles; ++t) {
+            if (t + kStages - 2 < n_tiles) wait_vmcnt<(kStages - 2) * kDmaTile>(); else wait_vmcnt<0>();
+            block_barrier();            // tile t is in LDS for every wave; every wave is done with tile t - 1
+            if (t + kStages - 1 < n_tiles) issue_tile(t + kStages - 1);
+            if (tile_none(t)) continue;
+            f32x16 acc_s[2];
+            score_tile(t, acc_s);
+            softmax_pv(t, acc_s);
+        }
+    } else {
+        // Step t: scores of tile t + 1, then softmax and value product of tile t.  At its top the tiles up to
+        // t + kStages - 2 have been requested and tile t + 1 must have landed; after the barrier (every wave is done
+        // with tile t - 1) tile t + kStages - 1 goes into that tile's stage.
+        f32x16 acc_a[2], acc_b[2];
+        if (n_tiles > 0) {
+            if (kStages - 2 < n_tiles) wait_vmcnt<(kStages - 2) * kDmaTile>(); else wait_vmcnt<0>();
+            block_barrier();
+            if (!tile_none(0)) score_tile(0, acc_a);
+        }
+        auto step = [&](int t, f32x16 (&cur)[2], f32x16 (&nxt)[2]) __attribute__((always_inline)) {
+            if (t + 1 < n_tiles) {
+                if (t + kStages - 2 < n_tiles) wait_vmcnt<(kStages - 3) * kDmaTile>(); else wait_vmcnt<0>();
+                block_barrier();
+                if (t + kStages - 1 < n_tiles) issue_tile(t + kStages - 1);
+                if (!tile_none(t + 1)) score_tile(t + 1, nxt);
+            }
+            if (!tile_none(t)) softmax_pv(t, cur);
+        };
+        for (int t = 0; t < n_tiles; t += 2) {
+            step(t, acc_a, acc_b);
+            if (t + 1 < n_tiles) step(t + 1, acc_b, acc_a);
+        }
     }
 
     // ---- normalise and store: acc_o[nb][4 a + b] = O[r][32 nb + 8 a + 4 g + b]
@@ -300,21 +340,22 @@ int32_t launch_attention(int32_t dtype, const void* qkv, const void* vt, int64_t
     if (attention_uses_vt(dtype, hd)) {
         if (!vt || ldv < (int64_t)align_up(R, kKTile) || ldv % 8)
             return fail(ATTS_ERR_WORKSPACE, "attention: transposed-V buffer missing or too narrow");
-        // 256 query rows per workgroup (8 wavefronts, one workgroup per CU, loads two tiles ahead) once the call has
-        // enough rows to fill the chip that way; 128 rows (4 wavefronts, two workgroups per CU) for smaller calls
+        // 256 query rows per workgroup (8 wavefronts, one workgroup per CU, four LDS stages, scores of the next tile issued
+        // ahead of the softmax) once the call has enough rows to fill the chip that way; 128 rows (4 wavefronts, two
+        // workgroups per CU) for smaller calls
         constexpr int kStage = 2 * kKTile * kHd * 2;
         const float sc2 = scale * 1.4426950408889634f;
         if ((int64_t)ceil_div(R - row0, 256) * nq >= 256) {
-            constexpr size_t lds = 3 * kStage;
-            int32_t rc = allow_dynamic_lds<attn_mfma_kernel<8, 3>>(lds);
+            constexpr size_t lds = 4 * kStage;
+            int32_t rc = allow_dynamic_lds<attn_mfma_kernel<8, 4, true>>(lds);
             if (rc != ATTS_OK) return rc;
-            hipLaunchKernelGGL((attn_mfma_kernel<8, 3>), dim3((unsigned)ceil_div(R - row0, 256), nq), dim3(512), lds, stream, (const bf16*)qkv,
+            hipLaunchKernelGGL((attn_mfma_kernel<8, 4, true>), dim3((unsigned)ceil_div(R - row0, 256), nq), dim3(512), lds, stream, (const bf16*)qkv,
                                (const bf16*)vt, ldv, (bf16*)out, row0, R, s.P, s.T, nq, nkv, sc2);
         } else {
             constexpr size_t lds = 2 * kStage;
-            int32_t rc = allow_dynamic_lds<attn_mfma_kernel<4, 2>>(lds);
+            int32_t rc = allow_dynamic_lds<attn_mfma_kernel<4, 2, false>>(lds);
             if (rc != ATTS_OK) return rc;
-            hipLaunchKernelGGL((attn_mfma_kernel<4, 2>), dim3((unsigned)ceil_div(R - row0, 128), nq), dim3(256), lds, stream, (const bf16*)qkv,
+            hipLaunchKernelGGL((attn_mfma_kernel<4, 2, false>), dim3((unsigned)ceil_div(R - row0, 128), nq), dim3(256), lds, stream, (const bf16*)qkv,
                                (const bf16*)vt, ldv, (bf16*)out, row0, R, s.P, s.T, nq, nkv, sc2);
         }
         ATTS_LAUNCH_CHECK("attn_mfma_kernel");
