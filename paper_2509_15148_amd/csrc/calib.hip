@@ -7,10 +7,11 @@
 //   append (Online Calibration):  keys of the new scores are sorted (sort.hip: block sort + one-pass
 //       multi-way placement for small batches, radix sort for large ones) and
 //       merged with the resident array by a merge-path kernel into the other half of a ping-pong
-//       buffer.  The same pass writes four sampled copies of its output (every 16th, 256th, 4096th,
-//       65536th key), the levels of a static 16-ary search index.
+//       buffer.  The same pass writes four sampled copies of its output (every 32nd, 1024th, 32768th,
+//       2^20-th key), the levels of a static 32-ary search index: a node is one 128-byte line, the unit the L2
+//       fills from memory.
 //   classify (Eq. "p-value", Eq. "prediction_set"):  ranks = #{cal >= s} by one search per test
-//       score: the coarsest index level sits in LDS, every further level costs one aligned 64-byte
+//       score: the coarsest index level sits in LDS, every further level costs one aligned 128-byte
 //       line.  The class is an integer comparison of ranks + 1 with r_l = floor(alpha_l (N + 1));
 //       the quantile thresholds of Eq. "quantile" are read straight from the sorted array.
 //   conditional coverage (Proposition 2):  no state; one wavefront ranks the candidates of one input against
@@ -22,10 +23,12 @@
 #include <new>
 
 constexpr int kIndexLevels = 4;
+constexpr int kFanBits = 5;                 // 32 keys per index node (one 128-byte line)
+constexpr int kFan = 1 << kFanBits;
 
 struct atts_calib {
     uint32_t* keys[2];                  // ping-pong sorted arrays, capacity each
-    uint32_t* index[2][kIndexLevels];   // index[side][k][j] = keys[side][j * 16^(k+1)]
+    uint32_t* index[2][kIndexLevels];   // index[side][k][j] = keys[side][j * 32^(k+1)]
     uint32_t* runs;                     // the batch being appended: two buffers the sort alternates between
     uint32_t* batch;
     uint32_t* sort_scratch;             // digit histograms of the radix sort
@@ -70,7 +73,7 @@ struct MergeJob {
     const uint32_t* b;   // the sorted batch
     int64_t nb;
     uint32_t* out;
-    uint32_t* index[kIndexLevels];   // EMIT only: index[k][j] = out[j * 16^(k+1)]
+    uint32_t* index[kIndexLevels];   // EMIT only: index[k][j] = out[j * 32^(k+1)]
 };
 
 // LDS position of element i: one pad word per 32, so that the accesses "thread t, element t * PER + e" fall
@@ -202,7 +205,7 @@ __global__ __launch_bounds__(kMergeThreads) void merge_kernel(MergeJob job, cons
     if constexpr (EMIT) {
 #pragma unroll
         for (int lvl = 0; lvl < kIndexLevels; ++lvl) {
-            const int shift = 4 * (lvl + 1);
+            const int shift = kFanBits * (lvl + 1);
             if (((int64_t)1 << shift) <= SEG) {
                 for (int t = threadIdx.x; (t << shift) < len; t += kMergeThreads)
                     job.index[lvl][(o0 >> shift) + t] = buf[lds_pad(t << shift)];
@@ -219,10 +222,10 @@ struct ClassifyLevels {
     int32_t n_alpha;
 };
 
-constexpr int kTopEntries = 4096;   // LDS copy of the coarsest level (or of every 2^top_shift-th entry of it)
+constexpr int kTopEntries = 8192;   // LDS copy of the coarsest level (or of every 2^top_shift-th entry of it): 32 KB
 
 struct SearchIndex {
-    const uint32_t* lvl[kIndexLevels + 1];   // lvl[0] = the sorted keys, lvl[k][j] = keys[j * 16^k]
+    const uint32_t* lvl[kIndexLevels + 1];   // lvl[0] = the sorted keys, lvl[k][j] = keys[j * 32^k]
     int64_t len[kIndexLevels + 1];
     int32_t top_level;                       // the level staged in LDS
     int32_t top_shift;
@@ -231,11 +234,12 @@ struct SearchIndex {
 
 // One level of the index for the four test keys of a quad of lanes (lane l of the quad owns key x_l and the count
 // t_l of entries of the next coarser level below it).  Result for each lane: the same count for level L, whose
-// candidates are the 16 entries of one aligned 64-byte line.  The quad takes its four keys in turn: in round r all
-// four lanes work on lane r's key, each loading and comparing a quarter (16 bytes) of its line, so that one load
-// instruction of the wavefront touches 16 lines instead of 64 (the vector cache looks up one line per cycle: a
-// lane-per-line load costs four times the tag look-ups).  Values move inside the quad by DPP, not through LDS.
-// Every lane of the quad must be active; a lane without work passes t = 0 (nothing is loaded for it).
+// candidates are the 32 entries of one aligned 128-byte line (the whole line the L2 fetches is used).  The quad takes
+// its four keys in turn: in round r all four lanes work on lane r's key, each loading and comparing a quarter
+// (32 bytes) of its line, so that one load instruction of the wavefront touches 16 lines instead of 64 (the vector
+// cache looks up one line per cycle: a lane-per-line load costs four times the tag look-ups).  Values move inside the
+// quad by DPP, not through LDS.  Every lane of the quad must be active; a lane without work passes t = 0 (nothing is
+// loaded for it).
 template <int CTRL>
 __device__ __forceinline__ int quad_perm(int v) { return __builtin_amdgcn_mov_dpp(v, CTRL, 0xF, 0xF, true); }
 
@@ -245,12 +249,14 @@ __device__ __forceinline__ int quad_descend(const uint32_t* __restrict__ L, int6
     auto round = [&](int xr_, int tr, int r) {
         const uint32_t xr = (uint32_t)xr_;
         int c = 0;
-        const int base = (tr - 1) << 4;
+        const int base = (tr - 1) << kFanBits;
         if (tr > 0) {
-            const uint4 v = *reinterpret_cast<const uint4*>(L + base + 4 * q);
-            const int valid = (int)min((int64_t)16, len - base) - 4 * q;     // entries of this quarter that exist
-            c = ((valid > 0 && v.x < xr) ? 1 : 0) + ((valid > 1 && v.y < xr) ? 1 : 0) + ((valid > 2 && v.z < xr) ? 1 : 0) +
-                ((valid > 3 && v.w < xr) ? 1 : 0);
+            const uint4 v0 = *reinterpret_cast<const uint4*>(L + base + 8 * q);
+            const uint4 v1 = *reinterpret_cast<const uint4*>(L + base + 8 * q + 4);
+            const int valid = (int)min((int64_t)kFan, len - base) - 8 * q;     // entries of this quarter that exist
+            c = ((valid > 0 && v0.x < xr) ? 1 : 0) + ((valid > 1 && v0.y < xr) ? 1 : 0) + ((valid > 2 && v0.z < xr) ? 1 : 0) +
+                ((valid > 3 && v0.w < xr) ? 1 : 0) + ((valid > 4 && v1.x < xr) ? 1 : 0) + ((valid > 5 && v1.y < xr) ? 1 : 0) +
+                ((valid > 6 && v1.z < xr) ? 1 : 0) + ((valid > 7 && v1.w < xr) ? 1 : 0);
         }
         c += quad_perm<0xB1>(c);      // lanes (1, 0, 3, 2)
         c += quad_perm<0x4E>(c);      // lanes (2, 3, 0, 1)
@@ -418,7 +424,7 @@ __global__ void import_kernel(const float* __restrict__ scores, int64_t n, Impor
     job.keys[i] = k;
 #pragma unroll
     for (int lvl = 0; lvl < kIndexLevels; ++lvl) {
-        const int shift = 4 * (lvl + 1);
+        const int shift = kFanBits * (lvl + 1);
         if ((i & (((int64_t)1 << shift) - 1)) == 0) job.index[lvl][i >> shift] = k;
     }
 }
@@ -461,7 +467,7 @@ int32_t atts_calib_create(int64_t capacity, atts_calib** out) {
     c->capacity = capacity;
     c->n = 0;
     c->cur = 0;
-    // Every array is rounded up to whole 64-byte lines plus one: the index search reads whole lines (entries
+    // Every array is rounded up to whole 128-byte lines plus one: the index search reads whole lines (entries
     // past the fill are masked, not avoided).  Sorted runs are padded to whole chunks only in LDS.
     uint32_t** bufs[5 + 2 * kIndexLevels] = {&c->keys[0], &c->keys[1], &c->runs, &c->batch, &c->sort_scratch};
     int64_t sizes[5 + 2 * kIndexLevels];
@@ -470,12 +476,12 @@ int32_t atts_calib_create(int64_t capacity, atts_calib** out) {
     for (int side = 0; side < 2; ++side)
         for (int k = 0; k < kIndexLevels; ++k) {
             bufs[5 + side * kIndexLevels + k] = &c->index[side][k];
-            sizes[5 + side * kIndexLevels + k] = ceil_div(capacity, (int64_t)1 << (4 * (k + 1)));
+            sizes[5 + side * kIndexLevels + k] = ceil_div(capacity, (int64_t)1 << (kFanBits * (k + 1)));
         }
     constexpr int n_bufs = 5 + 2 * kIndexLevels;
     for (int i = 0; i < n_bufs; ++i) *bufs[i] = nullptr;
     for (int i = 0; i < n_bufs; ++i) {
-        const size_t bytes = ((size_t)ceil_div(sizes[i], 16) * 16 + 16) * sizeof(uint32_t);
+        const size_t bytes = ((size_t)ceil_div(sizes[i], kFan) * kFan + kFan) * sizeof(uint32_t);
         hipError_t e = hipMalloc(reinterpret_cast<void**>(bufs[i]), bytes);
         if (e != hipSuccess) {
             for (int j = 0; j < n_bufs; ++j)
@@ -589,7 +595,7 @@ int32_t atts_classify_ordinal(const atts_calib* c, const float* test_scores, int
     ix.len[0] = c->n;
     for (int k = 1; k <= kIndexLevels; ++k) {
         ix.lvl[k] = c->index[c->cur][k - 1];
-        ix.len[k] = ceil_div(c->n, (int64_t)1 << (4 * k));
+        ix.len[k] = ceil_div(c->n, (int64_t)1 << (kFanBits * k));
     }
     ix.top_level = 0;
     while (ix.top_level < kIndexLevels && ix.len[ix.top_level] > kTopEntries) ++ix.top_level;

@@ -71,7 +71,9 @@ def test_small_with_ties_and_special_values():
 
 
 @pytest.mark.parametrize("sizes", [(1,), (7, 1, 300), (2047, 2048, 2049, 5), (8191, 8193, 5), (65536, 65537, 16, 65535),
-                                   (20000, 3, 70001), (200000, 131072 + 17)])
+                                   (20000, 3, 70001), (200000, 131072 + 17),
+                                   # set sizes at and around whole index nodes (32, 1024, 32768 keys)
+                                   (31, 1, 1, 991, 1, 31743, 1, 1)])
 def test_online_appends_span_sort_chunks_and_merge_paths(sizes):
     """Batches below / at / above one sort run (8192 keys), the one-pass multi-way placement (up to 8 runs =
     65,536 keys) and the radix sort (larger batches, ragged last tile); after every append the state must equal
