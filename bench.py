@@ -168,7 +168,7 @@ def bench_calibration(A, torch, np, steps=16, scaled=False, cpu=True):
     # scores, write ranks (4 B) and classes (1 B).  Keeping the set sorted adds one more pass: the merge reads
     # the old array and writes the new one.
     bytes_step = 4 * n_mid + 8 * n_new + 4 * n_test + 5 * n_test
-    merge_bytes = 4 * n_mid2 + 4 * n_new + 4 * (n_mid2 + n_new) * (1 + 1 / 16 + 1 / 256)   # old + batch in, array + index out
+    merge_bytes = 4 * n_mid2 + 4 * n_new + 4 * (n_mid2 + n_new) * (1 + 1 / 32 + 1 / 1024)   # old + batch in, array + index out
     out = {
         "workload": (f"calib{' (scaled, out of cache)' if scaled else ''}: {n_cal} lognormal scores + {n_new} appended and "
                      f"{n_test} classified per step, alphas {list(wl.alphas)}"),
