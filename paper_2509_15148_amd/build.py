@@ -20,7 +20,7 @@ FLAGS = [
     # packed fp32 instructions are switched off for all device code
     "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
     "-I", os.path.join(ROOT, "include"), "-I", CSRC,
-] + os.environ.get("ATTS_HIPCC_EXTRA", "").split()     # e.g. -DATTS_FAST_WAVES_M=2 when tuning
+] + os.environ.get("ATTS_HIPCC_EXTRA", "").split()     # extra hipcc flags (e.g. -save-temps when reading the ISA)
 
 
 def _compile(src: str) -> str:
