@@ -15,6 +15,7 @@
 // re-uses A and W slabs.
 #include "common.h"
 
+#include <atomic>
 #include <type_traits>
 
 namespace atts {
@@ -394,9 +395,12 @@ __global__ __launch_bounds__(128 * kWavesM) void gemm_bf16_wide_kernel(const cha
     const int nk_all = g.Kd / BK;
     const int k_first = (int)((int64_t)slice * nk_all / g.k_slices);
     const int nk = (int)((int64_t)(slice + 1) * nk_all / g.k_slices) - k_first;   // >= 3 (checked on the host)
-    const TileCoord tc = tile_of_block((int)blockIdx.x - slice * n_tiles, g.nt_m, g.nt_n);
-    const int m0 = tc.tm * BM;
-    const int n0 = tc.tn * N_OUT;
+    // Two-stage form without a K split: a workgroup walks tiles blockIdx.x, blockIdx.x + gridDim.x, ... and requests
+    // the first slab of the next tile under the last slab of the current one, so that the DMA ring never runs dry at a
+    // tile boundary and the epilogue's stores overlap that request.  (The host launches one workgroup per CU then;
+    // with a grid of n_tiles workgroups the loop body runs once.)
+    constexpr bool kTileLoop = !kDeep && kStages == 2;
+    int tile = (int)blockIdx.x - slice * n_tiles;
 
     // LDS offsets of the operands of slab k
     auto a_slot = [&](int k) { return kDeep ? ((2 * k) % 5) * UNIT_A : (k % kStages) * (UNIT_A + UNIT_B); };
@@ -407,27 +411,32 @@ __global__ __launch_bounds__(128 * kWavesM) void gemm_bf16_wide_kernel(const cha
     // r0 / 8 and j have the same parity, so two per-lane offsets per operand (even / odd j) serve every j.
     const int dq = lane / CHUNKS, dslot = lane % CHUNKS;
     uint32_t a_lane_off[2], b_lane_off[2];
+    const char* a_base[DMA_A];
+    const char* b_base[DMA_B];
 #pragma unroll
     for (int p = 0; p < 2; ++p) {
         const int sw = (4 * p + (dq >> 1)) & 7;
         a_lane_off[p] = (uint32_t)dq * (uint32_t)(g.lda * 2) + (uint32_t)((dslot ^ sw) * 16) + (uint32_t)k_first * BKB;
         b_lane_off[p] = (uint32_t)dq * (uint32_t)(g.ldw * 2) + (uint32_t)((dslot ^ sw) * 16) + (uint32_t)k_first * BKB;
     }
-    const char* a_base[DMA_A];
-    const char* b_base[DMA_B];
+    // DMA sources of a tile: the row pointers of this wave's instructions
+    auto aim_dma = [&](int m0, int n0) __attribute__((always_inline)) {
 #pragma unroll
-    for (int j = 0; j < DMA_A; ++j) a_base[j] = gA + (int64_t)(m0 + (wave * DMA_A + j) * ROWS_PER_DMA) * g.lda * 2;
+        for (int j = 0; j < DMA_A; ++j) a_base[j] = gA + (int64_t)(m0 + (wave * DMA_A + j) * ROWS_PER_DMA) * g.lda * 2;
 #pragma unroll
-    for (int j = 0; j < DMA_B; ++j) {
-        const int r0 = (wave * DMA_B + j) * ROWS_PER_DMA;
-        int64_t wrow = r0;
-        if (EPI == EPI_SWIGLU) {
-            constexpr int H = WN / 2;                             // wave slab = [gate H | up H]
-            const int jw = r0 / WN, jj = r0 % WN;
-            wrow = (int64_t)(jj / H) * g.N + jw * H + jj % H;
+        for (int j = 0; j < DMA_B; ++j) {
+            const int r0 = (wave * DMA_B + j) * ROWS_PER_DMA;
+            int64_t wrow = r0;
+            if (EPI == EPI_SWIGLU) {
+                constexpr int H = WN / 2;                             // wave slab = [gate H | up H]
+                const int jw = r0 / WN, jj = r0 % WN;
+                wrow = (int64_t)(jj / H) * g.N + jw * H + jj % H;
+            }
+            b_base[j] = gW + (n0 + wrow) * g.ldw * 2;
         }
-        b_base[j] = gW + (n0 + wrow) * g.ldw * 2;
-    }
+    };
+    TileCoord tc = tile_of_block(tile, g.nt_m, g.nt_n);
+    aim_dma(tc.tm * BM, tc.tn * N_OUT);
     auto issue_a = [&](int k) __attribute__((always_inline)) {
         char* dst = smem + a_slot(k);
 #pragma unroll
@@ -462,12 +471,6 @@ __global__ __launch_bounds__(128 * kWavesM) void gemm_bf16_wide_kernel(const cha
     };
 
     f32x16 acc[MI][NI];
-#pragma unroll
-    for (int i = 0; i < MI; ++i)
-#pragma unroll
-        for (int j = 0; j < NI; ++j)
-#pragma unroll
-            for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.f;
 
     // One k-step, column by column: the MI MFMAs of column j, then the W fragment of column j is replaced in place
     // by the one of the next k-step (it is free as soon as those MFMAs have issued, and not needed again before the
@@ -526,16 +529,12 @@ __global__ __launch_bounds__(128 * kWavesM) void gemm_bf16_wide_kernel(const cha
             issue_b(q);
         }
     }
-    wait_vmcnt<kSteadyWait>();
-    block_barrier();
-    load_a(0, 0, fa[0]);
-#pragma unroll
-    for (int j = 0; j < NI; ++j) fb[j] = load_b1(0, 0, j);
-
     // slab k.  first / second: the DMA halves issued under k-steps 0 and 1:
     //   deep ring:         W rows of slab k + 1 (into the unit slab k - 1 freed), then A rows of slab k + 2
     //   whole-slab stages: A rows, then W rows of slab k + kLook
     // steady: the loads issued under this slab may stay in flight across its end (else everything is awaited).
+    // prefetch_tile (two-stage form, last slab of a tile): the DMA issued under this slab is slab 0 of the next tile,
+    // whose sources aim_dma has already been pointed at; it lands in the stage slab k - 1 occupied.
     auto slab = [&](int k, auto has_next, auto first, auto second, auto steady) __attribute__((always_inline)) {
         // k-step 0
         if (first) { if (kDeep) issue_b(k + 1); else issue_a(k + kLook); }
@@ -570,37 +569,77 @@ __global__ __launch_bounds__(128 * kWavesM) void gemm_bf16_wide_kernel(const cha
     constexpr bool kResidAhead = EPI == EPI_RESID_F32 && MI == 2;
     float resid0[NI][16];
     const bool resid_ahead = kResidAhead && nk > 16;
-    auto prefetch_resid = [&]() __attribute__((always_inline)) {
-        const float* o = reinterpret_cast<const float*>(g_out);
-        const int row_base = m0 + wm * WM + 4 * half, col_base = n0 + wn * WN + l32;
-#pragma unroll
-        for (int v = 0; v < 16; ++v) {
-            const int row = row_base + 8 * (v >> 2) + (v & 3);
-#pragma unroll
-            for (int j = 0; j < kResidAheadCols; ++j) {
-                resid0[j][v] = 0.f;
-                if (row < g.M) resid0[j][v] = o[(int64_t)row * g.ldc + col_base + 32 * j];
-            }
-        }
-    };
-    int k = 0;
-    if (kDeep) {
-        for (; k + 2 < nk; ++k) {
-            if (kResidAhead && resid_ahead && k == nk - 14) prefetch_resid();
-            slab(k, Yes{}, Yes{}, Yes{}, Yes{});
-        }
-        slab(k, Yes{}, Yes{}, No{}, No{});    // k = nk - 2: only the W rows of the last slab are left to issue
-        slab(k + 1, No{}, No{}, No{}, No{});
-    } else {
-        for (; k + kLook < nk; ++k) slab(k, Yes{}, Yes{}, Yes{}, Yes{});
-        for (; k + 1 < nk; ++k) slab(k, Yes{}, No{}, No{}, No{});
-        slab(k, No{}, No{}, No{}, No{});
-    }
-
     void* out = g_out;
     if (EPI == EPI_PARTIAL_F32) out = reinterpret_cast<float*>(g_out) + (int64_t)slice * g.slice_pitch;
-    gemm_epilogue_impl<bf16, MI, NI, EPI>(acc, m0, n0, wm, wn, l32, half, tc.tn, out, g_targets, g_partials, g_target_logit, g_rope,
-                                          g_vt, g, resid0, resid_ahead);
+
+    // kb: slabs this workgroup has walked in earlier tiles (the ring positions go on across tiles)
+    for (int kb = 0;; kb += nk) {
+        const int m0 = tc.tm * BM, n0 = tc.tn * N_OUT, tn = tc.tn;
+        auto prefetch_resid = [&]() __attribute__((always_inline)) {
+            const float* o = reinterpret_cast<const float*>(g_out);
+            const int row_base = m0 + wm * WM + 4 * half, col_base = n0 + wn * WN + l32;
+#pragma unroll
+            for (int v = 0; v < 16; ++v) {
+                const int row = row_base + 8 * (v >> 2) + (v & 3);
+#pragma unroll
+                for (int j = 0; j < kResidAheadCols; ++j) {
+                    resid0[j][v] = 0.f;
+                    if (row < g.M) resid0[j][v] = o[(int64_t)row * g.ldc + col_base + 32 * j];
+                }
+            }
+        };
+        // slab 0 of this tile has landed for every wave (and every wave is through with the tile before)
+        if (kb == 0) wait_vmcnt<kSteadyWait>(); else wait_vmcnt<0>();
+        block_barrier();
+        load_a(kb, 0, fa[0]);
+#pragma unroll
+        for (int j = 0; j < NI; ++j) fb[j] = load_b1(kb, 0, j);
+#pragma unroll
+        for (int i = 0; i < MI; ++i)
+#pragma unroll
+            for (int j = 0; j < NI; ++j)
+#pragma unroll
+                for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.f;
+
+        bool more = false;
+        int k = 0;
+        if (kDeep) {
+            for (; k + 2 < nk; ++k) {
+                if (kResidAhead && resid_ahead && k == nk - 14) prefetch_resid();
+                slab(k, Yes{}, Yes{}, Yes{}, Yes{});
+            }
+            slab(k, Yes{}, Yes{}, No{}, No{});    // k = nk - 2: only the W rows of the last slab are left to issue
+            slab(k + 1, No{}, No{}, No{}, No{});
+        } else {
+            for (; k + kLook < nk; ++k) slab(kb + k, Yes{}, Yes{}, Yes{}, Yes{});
+            for (; k + 1 < nk; ++k) slab(kb + k, Yes{}, No{}, No{}, No{});
+            if (kTileLoop) {
+                // The last slab always carries a slab's worth of DMA, so that there is one code path: slab 0 of the next
+                // tile, or (no tile left) slab 0 of this tile once more, into the free stage, awaited before leaving.
+                tile += (int)gridDim.x;
+                more = g.k_slices == 1 && tile < n_tiles;
+                if (more) tc = tile_of_block(tile, g.nt_m, g.nt_n);
+                aim_dma(tc.tm * BM, tc.tn * N_OUT);
+#pragma unroll
+                for (int p = 0; p < 2; ++p) {          // every slab of the tile has been issued: back to its first slab
+                    a_lane_off[p] -= (uint32_t)nk * BKB;
+                    b_lane_off[p] -= (uint32_t)nk * BKB;
+                }
+                slab(kb + k, No{}, Yes{}, Yes{}, No{});
+            } else {
+                slab(kb + k, No{}, No{}, No{}, No{});
+            }
+        }
+
+        // the lane coordinates are handed over as values of this iteration, so that the epilogue's address arithmetic is
+        // not hoisted out of the tile loop (it would sit in registers all through the main loop)
+        int l32_e = l32, half_e = half;
+        if (kTileLoop) asm volatile("" : "+v"(l32_e), "+v"(half_e));
+        gemm_epilogue_impl<bf16, MI, NI, EPI>(acc, m0, n0, wm, wn, l32_e, half_e, tn, out, g_targets, g_partials, g_target_logit,
+                                              g_rope, g_vt, g, resid0, resid_ahead);
+        if (!(kTileLoop && more)) break;
+    }
+    if (kTileLoop) wait_vmcnt<0>();   // no DMA may still be writing this workgroup's LDS when it is given up
 }
 
 #define ATTS_TRY_RC(expr)                 \
@@ -642,6 +681,23 @@ int fast_k_slices(int epi, int n_tiles, int nk) {
     return s < 1 ? 1 : s;
 }
 
+// Compute units of the current device (asked once per device).
+int32_t device_cu_count(int* out) {
+    static std::atomic<int> cached[64];
+    int dev = 0;
+    ATTS_HIP_TRY(hipGetDevice(&dev));
+    if (dev >= 0 && dev < 64 && cached[dev].load(std::memory_order_relaxed) > 0) {
+        *out = cached[dev].load(std::memory_order_relaxed);
+        return ATTS_OK;
+    }
+    int n = 0;
+    ATTS_HIP_TRY(hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev));
+    if (n < 1) return fail(ATTS_ERR_HIP, "device %d reports %d compute units", dev, n);
+    if (dev >= 0 && dev < 64) cached[dev].store(n, std::memory_order_relaxed);
+    *out = n;
+    return ATTS_OK;
+}
+
 template <int EPI, int MI, int NI = 4>
 int32_t launch_wide_tile(const GemmArgs& g, hipStream_t stream) {
     constexpr int n_out = (EPI == EPI_SWIGLU) ? 32 * NI : 64 * NI;
@@ -658,7 +714,16 @@ int32_t launch_wide_tile(const GemmArgs& g, hipStream_t stream) {
     d.slice_pitch = (int64_t)g.M * g.ldc;
     const size_t lds = 160 * 1024;
     ATTS_TRY_RC((allow_dynamic_lds<gemm_bf16_wide_kernel<EPI, kWavesM, MI, NI>>(lds)));
-    hipLaunchKernelGGL((gemm_bf16_wide_kernel<EPI, kWavesM, MI, NI>), dim3(d.nt_m * d.nt_n * d.k_slices), dim3(128 * kWavesM), lds, stream,
+    // 384-row tiles without a K split: one workgroup per CU (a workgroup takes a CU's whole LDS), each walking
+    // every n_cu-th tile with the next tile's first slab requested under the current tile's last
+    int grid = d.nt_m * d.nt_n * d.k_slices;
+    if (MI == 3 && d.k_slices == 1) {
+        int n_cu = 0;
+        ATTS_TRY_RC(device_cu_count(&n_cu));
+        n_cu &= ~7;                                   // the tile order deals workgroup ids to the 8 XCDs in turn
+        if (n_cu >= 8 && grid > n_cu) grid = n_cu;
+    }
+    hipLaunchKernelGGL((gemm_bf16_wide_kernel<EPI, kWavesM, MI, NI>), dim3(grid), dim3(128 * kWavesM), lds, stream,
                        reinterpret_cast<const char*>(g.a), reinterpret_cast<const char*>(g.w), g.out, g.targets, g.partials,
                        g.target_logit, g.rope, g.vt, d);
     ATTS_LAUNCH_CHECK("gemm_bf16_wide_kernel");
