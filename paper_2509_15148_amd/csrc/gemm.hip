@@ -23,7 +23,6 @@ namespace {
 
 constexpr int kThreads = 256;
 constexpr int kRowBytes = 128;  // bytes of K per LDS row per slab
-constexpr int kGroupM = 8;      // tile rows per group of the XCD-aware order
 
 template <typename T> struct Mma;
 
@@ -59,6 +58,7 @@ struct TileCoord {
 };
 
 // XCD-aware, grouped tile order.
+template <int kGroupM = 8>
 __device__ __forceinline__ TileCoord tile_of_block(int pid, int nt_m, int nt_n) {
     int n = nt_m * nt_n;
     int n8 = n & ~7;
@@ -400,6 +400,10 @@ __global__ __launch_bounds__(128 * kWavesM) void gemm_bf16_wide_kernel(const cha
     // tile boundary and the epilogue's stores overlap that request.  (The host launches one workgroup per CU then;
     // with a grid of n_tiles workgroups the loop body runs once.)
     constexpr bool kTileLoop = !kDeep && kStages == 2;
+    // Tile rows per group of the XCD-aware order.  The one-round calls of the 256-row tile do better with taller groups
+    // (an XCD then touches fewer W columns, which come cold from HBM, at the price of more A rows, which the Infinity
+    // Cache holds): O projection at 7B 3.79 -> 3.66 ms per step with 12 against 8, the other shapes within 0.5 %.
+    constexpr int kGroup = kDeep ? 12 : 8;
     int tile = (int)blockIdx.x - slice * n_tiles;
 
     // LDS offsets of the operands of slab k
@@ -435,7 +439,7 @@ __global__ __launch_bounds__(128 * kWavesM) void gemm_bf16_wide_kernel(const cha
             b_base[j] = gW + (n0 + wrow) * g.ldw * 2;
         }
     };
-    TileCoord tc = tile_of_block(tile, g.nt_m, g.nt_n);
+    TileCoord tc = tile_of_block<kGroup>(tile, g.nt_m, g.nt_n);
     aim_dma(tc.tm * BM, tc.tn * N_OUT);
     auto issue_a = [&](int k) __attribute__((always_inline)) {
         char* dst = smem + a_slot(k);
@@ -625,7 +629,7 @@ __global__ __launch_bounds__(128 * kWavesM) void gemm_bf16_wide_kernel(const cha
                 // tile, or (no tile left) slab 0 of this tile once more, into the free stage, awaited before leaving.
                 tile += (int)gridDim.x;
                 more = g.k_slices == 1 && tile < n_tiles;
-                if (more) tc = tile_of_block(tile, g.nt_m, g.nt_n);
+                if (more) tc = tile_of_block<kGroup>(tile, g.nt_m, g.nt_n);
                 aim_dma(tc.tm * BM, tc.tn * N_OUT);
 #pragma unroll
                 for (int p = 0; p < 2; ++p) {          // every slab of the tile has been issued: back to its first slab
