@@ -28,8 +28,8 @@ HBM_PEAK_GBS = 8000.0
 # (FETCH_SIZE, then WRITE_SIZE), each scaled by what the same counter reads for a plain device copy of known
 # size (--traffic-probe); see profiles/traffic_gemm_gate_up_7b.txt.  Valid only for the kernel source it was
 # taken with: reported as null when the hash of csrc/gemm.hip differs.
-MEASURED_TRAFFIC = {"gemm_sha256": "94e8821d5bb913adfdb5b03be75a088808a7de26b7c7b1cc8d9334eca231af57",
-                    "workload": "7b", "bytes_per_launch": 2.056e9}
+MEASURED_TRAFFIC = {"gemm_sha256": "38cd736a73c44372d36b7d188fa14f9a9b28190309eb2f0e1990cb6df51e0f5b",
+                    "workload": "7b", "bytes_per_launch": 1.853e9}
 
 
 def measured_traffic(workload):
