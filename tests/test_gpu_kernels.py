@@ -23,6 +23,9 @@ def _rand(shape, seed, dtype, scale=1.0):
 @pytest.mark.parametrize("dtype", [torch.float32, torch.bfloat16])
 @pytest.mark.parametrize("shape", [(1, 1, 8), (33, 70, 72), (300, 200, 136), (257, 513, 1000), (128, 128, 64),
                                    (3584, 3600, 264),
+                                   # aligned bf16 shapes with more 384-row tiles than compute units: workgroups walk two or
+                                   # three tiles each, some one fewer than others (510 and 700 tiles)
+                                   (1152, 43520, 768), (768, 89600, 832),
                                    # at most 16 rows: the weight-streaming kernel (bf16), ragged columns and k-step counts
                                    (1, 1, 32), (4, 100, 96), (7, 4608, 256), (16, 33, 2080), (16, 530, 3584), (3, 48, 18944)])
 def test_gemm_nt_matches_float64_matmul(dtype, shape):
