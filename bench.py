@@ -28,7 +28,7 @@ HBM_PEAK_GBS = 8000.0
 # (FETCH_SIZE, then WRITE_SIZE), each scaled by what the same counter reads for a plain device copy of known
 # size (--traffic-probe); see profiles/traffic_gemm_gate_up_7b.txt.  Valid only for the kernel source it was
 # taken with: reported as null when the hash of csrc/gemm.hip differs.
-MEASURED_TRAFFIC = {"gemm_sha256": "38cd736a73c44372d36b7d188fa14f9a9b28190309eb2f0e1990cb6df51e0f5b",
+MEASURED_TRAFFIC = {"gemm_sha256": "c6946ca162f197d041b49923daccf5afad9fd1d6f9001f107763d3d6676438ec",
                     "workload": "7b", "bytes_per_launch": 1.853e9}
 
 

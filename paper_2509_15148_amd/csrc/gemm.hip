@@ -542,8 +542,9 @@ __global__ __launch_bounds__(128 * kWavesM) void gemm_bf16_wide_kernel(const cha
     //   deep ring:         W rows of slab k + 1 (into the unit slab k - 1 freed), then A rows of slab k + 2
     //   whole-slab stages: A rows, then W rows of slab k + kLook
     // steady: the loads issued under this slab may stay in flight across its end (else everything is awaited).
-    // prefetch_tile (two-stage form, last slab of a tile): the DMA issued under this slab is slab 0 of the next tile,
-    // whose sources aim_dma has already been pointed at; it lands in the stage slab k - 1 occupied.
+    // Two-stage form, last slab of a tile (has_next false, first and second true): the DMA issued under this slab is
+    // slab 0 of the next tile, whose sources aim_dma has already been pointed at; it lands in the stage slab k - 1
+    // occupied and is awaited at the top of the tile loop.
     auto slab = [&](int k, auto has_next, auto first, auto second, auto steady) __attribute__((always_inline)) {
         // k-step 0
         if (first) { if (kDeep) issue_b(k + 1); else issue_a(k + kLook); }
