@@ -580,6 +580,10 @@ def main():
     t_c = sum(stages[k]["ms_per_step"] for k in ("gemm_qkv", "attention", "gemm_o", "gemm_gate_up", "gemm_down", "lmhead"))
     t_m = sum(stages[k]["ms_per_step"] for k in ("embed", "norm", "rope", "gather_norm", "reduce"))
     t_s = sum(stages[k]["ms_per_step"] for k in ("calib_sort", "calib_merge", "classify"))
+    # the five GEMM stages taken together: their algorithmic flops over the sum of their device times
+    gemm_names = ("gemm_qkv", "gemm_o", "gemm_gate_up", "gemm_down", "lmhead")
+    gemm_ms = sum(stage_ms[k][0] for k in gemm_names)
+    gemm_frac = (sum(fl[k] for k in gemm_names) * args.steps / (gemm_ms * 1e-3) / 1e12 / peak) if gemm_ms > 0 else None
     out = {
         "metric": "scored draft tokens/sec (shared-prefix target scoring + online conformal calibration + ordinal "
                   "classification), 1 MI355X",
@@ -596,6 +600,7 @@ def main():
         "conformal_decisions_per_s": wl.K * args.steps / dt,
         "algorithmic_tflop_per_step": fl["total"] / 1e12,
         "whole_step_mfma_frac": fl["total"] / (dt / args.steps) / 1e12 / peak,
+        "scoring_gemms_mfma_frac": gemm_frac,
         "roofline": {"bound": "mfma", "kernel": f"aligned {cfg.dtype} GEMM, SwiGLU epilogue (gate/up projection)",
                      "achieved": achieved, "peak": peak, "unit": "TFLOP/s", "frac": achieved / peak,
                      "avg_launch_ms": dom_avg_ms, "flops_per_launch": dom_flops,
