@@ -58,11 +58,22 @@ struct TileCoord {
 };
 
 // XCD-aware, grouped tile order.
+// round > 0: the launch has `round` workgroups that walk the tiles in rounds (pid = workgroup + i round); the tiles of
+// one round are then `round` consecutive positions of the order, dealt to the XCDs in blocks, so that at any time the
+// whole chip works inside one group of tile rows and its A rows stay in the Infinity Cache whatever the size of A
+// (with the XCDs spread over the whole order instead, eight groups are live at once: 250 MB of A rows at the 32B
+// workload, which the streaming W rows then push out; measured there 1993 -> 1881 ms per step, nothing at 7B).
 template <int kGroupM = 8>
-__device__ __forceinline__ TileCoord tile_of_block(int pid, int nt_m, int nt_n) {
+__device__ __forceinline__ TileCoord tile_of_block(int pid, int nt_m, int nt_n, int round = 0) {
     int n = nt_m * nt_n;
+    int base = 0;
+    if (round > 0) {
+        base = pid / round * round;
+        pid -= base;
+        n = min(round, n - base);
+    }
     int n8 = n & ~7;
-    int lid = pid < n8 ? (pid & 7) * (n8 >> 3) + (pid >> 3) : pid;
+    int lid = base + (pid < n8 ? (pid & 7) * (n8 >> 3) + (pid >> 3) : pid);
     int per_group = kGroupM * nt_n;
     int g = lid / per_group;
     int first_m = g * kGroupM;
@@ -81,6 +92,7 @@ struct GemmDims {
     int32_t M, N, Kd;
     int64_t lda, ldw, ldc;
     int32_t n_part, nt_m, nt_n;
+    int32_t round;          // workgroups of a tile-walking launch (0: one workgroup per tile)
     int64_t ldv;            // EPI_QKV_ROPE: row pitch of the transposed V
     int32_t n_rot_heads;    // EPI_QKV_ROPE: heads (128 columns each) that get rotated; later heads are V
     int32_t k_slices;       // EPI_PARTIAL_F32: the K range is split over this many workgroups per tile, slice s stores
@@ -439,7 +451,7 @@ __global__ __launch_bounds__(128 * kWavesM) void gemm_bf16_wide_kernel(const cha
             b_base[j] = gW + (n0 + wrow) * g.ldw * 2;
         }
     };
-    TileCoord tc = tile_of_block<kGroup>(tile, g.nt_m, g.nt_n);
+    TileCoord tc = tile_of_block<kGroup>(tile, g.nt_m, g.nt_n, g.round);
     aim_dma(tc.tm * BM, tc.tn * N_OUT);
     auto issue_a = [&](int k) __attribute__((always_inline)) {
         char* dst = smem + a_slot(k);
@@ -630,7 +642,7 @@ __global__ __launch_bounds__(128 * kWavesM) void gemm_bf16_wide_kernel(const cha
                 // tile, or (no tile left) slab 0 of this tile once more, into the free stage, awaited before leaving.
                 tile += (int)gridDim.x;
                 more = g.k_slices == 1 && tile < n_tiles;
-                if (more) tc = tile_of_block<kGroup>(tile, g.nt_m, g.nt_n);
+                if (more) tc = tile_of_block<kGroup>(tile, g.nt_m, g.nt_n, g.round);
                 aim_dma(tc.tm * BM, tc.tn * N_OUT);
 #pragma unroll
                 for (int p = 0; p < 2; ++p) {          // every slab of the tile has been issued: back to its first slab
@@ -729,11 +741,13 @@ int32_t launch_wide_tile(const GemmArgs& g, hipStream_t stream) {
     // 384-row tiles without a K split: one workgroup per CU (a workgroup takes a CU's whole LDS), each walking
     // every n_cu-th tile with the next tile's first slab requested under the current tile's last
     int grid = d.nt_m * d.nt_n * d.k_slices;
+    d.round = 0;
     if (MI == 3 && d.k_slices == 1) {
         int n_cu = 0;
         ATTS_TRY_RC(device_cu_count(&n_cu));
         n_cu &= ~7;                                   // the tile order deals workgroup ids to the 8 XCDs in turn
         if (n_cu >= 8 && grid > n_cu) grid = n_cu;
+        d.round = grid;
     }
     hipLaunchKernelGGL((gemm_bf16_wide_kernel<EPI, kWavesM, MI, NI>), dim3(grid), dim3(128 * kWavesM), lds, stream,
                        reinterpret_cast<const char*>(g.a), reinterpret_cast<const char*>(g.w), g.out, g.targets, g.partials,
@@ -750,7 +764,43 @@ int32_t launch_fast(const GemmArgs& g, hipStream_t stream) {
         if constexpr (EPI == EPI_PARTIAL_F32) return launch_wide_tile<EPI, 1, 2>(g, stream);
         return launch_wide_tile<EPI, 1>(g, stream);
     }
-    if (rows == 384) return launch_wide_tile<EPI, 3>(g, stream);
+    if (rows == 384) {
+        // A last round of tiles that would leave most CUs idle (32B-class O and down projections: 1820 tiles = 7.1 rounds
+        // of 256) is avoided by giving the last tile rows to a second launch with 128-row tiles: 89 tile rows in 7 full
+        // rounds, then 640 rows as 100 small tiles, each a third of the work.  Taken when the round count of the cost
+        // model (rounds x tile height, small tiles priced 40 % dearer per row) drops by 4 % or more.
+        constexpr bool kRowsShift = EPI != EPI_QKV_ROPE && EPI != EPI_PARTIAL_F32;   // outputs addressed by row alone
+        constexpr int n_out = (EPI == EPI_SWIGLU) ? 128 : 256;
+        const int64_t nt_n = g.N / n_out, nt_m = ceil_div(g.M, 384);
+        int best_h = 0;
+        if (kRowsShift && nt_m > 4) {
+            const double single = (double)ceil_div(nt_m * nt_n, 256) * 3;
+            double best = single * 0.96;
+            for (int drop = 1; drop <= 3; ++drop) {
+                const int64_t h = nt_m - drop, rem = g.M - h * 384;
+                const double c = (double)ceil_div(h * nt_n, 256) * 3 + (double)ceil_div(ceil_div(rem, 128) * nt_n, 256) * 1.4 + 0.05;
+                if (c < best) { best = c; best_h = (int)h; }
+            }
+        }
+        if (best_h > 0) {
+            GemmArgs head = g;
+            head.M = best_h * 384;
+            ATTS_TRY_RC((launch_wide_tile<EPI, 3>(head, stream)));
+            GemmArgs tail = g;
+            const int64_t r0 = head.M;
+            constexpr int64_t out_bytes = (EPI == EPI_STORE_F32 || EPI == EPI_RESID_F32) ? 4 : 2;
+            tail.M = g.M - head.M;
+            tail.a = static_cast<const char*>(g.a) + r0 * g.lda * 2;
+            if (g.out) tail.out = static_cast<char*>(g.out) + r0 * g.ldc * out_bytes;
+            if (EPI == EPI_LMHEAD) {
+                tail.targets = g.targets + r0;
+                tail.partials = g.partials + r0 * g.n_part;
+                tail.target_logit = g.target_logit + r0;
+            }
+            return launch_wide_tile<EPI, 1>(tail, stream);
+        }
+        return launch_wide_tile<EPI, 3>(g, stream);
+    }
     return launch_wide_tile<EPI, 2>(g, stream);
 }
 

@@ -40,6 +40,21 @@ def test_gemm_nt_matches_float64_matmul(dtype, shape):
     assert np.allclose(c.cpu().numpy(), ref, rtol=1e-5, atol=2e-5 * math.sqrt(Kd))
 
 
+def test_gemm_aligned_last_tile_rows_in_a_second_launch():
+    """27 x 38 tiles of 384 x 256 = 1026 = four rounds of 256 and two tiles over: the aligned bf16 path gives the last
+    tile row to a launch of its own with 128-row tiles (26 x 38 = 988 tiles in four rounds, then 384 rows as 114 small
+    tiles).  Every element against the float64 product."""
+    import paper_2509_15148_amd as A
+    M, N, Kd = 10368, 9728, 768
+    announce("gemm tail launch", (M, N, Kd))
+    a, w = _rand((M, Kd), 21, torch.bfloat16), _rand((N, Kd), 22, torch.bfloat16)
+    c = torch.full((M, N), float("nan"), dtype=torch.float32, device="cuda")
+    A.atts_gemm_nt(a.cuda(), w.cuda(), c)
+    torch.cuda.synchronize()
+    ref = a.double().numpy() @ w.double().numpy().T
+    assert np.allclose(c.cpu().numpy(), ref, rtol=1e-5, atol=2e-5 * math.sqrt(Kd))
+
+
 def test_gemm_few_rows_random_shapes():
     """Seeded sweep over the shapes the weight-streaming kernel serves (1..16 rows, any column count, inner
     dimension a multiple of 32 up to several K slices), against the float64 product."""
