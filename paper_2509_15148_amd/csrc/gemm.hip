@@ -99,7 +99,6 @@ struct GemmDims {
     int64_t slice_pitch;    // its partial sums at out + s slice_pitch (floats); 1 for every other epilogue
 };
 
-constexpr int kResidAheadCols = 2;   // column blocks of block row 0 whose old values a kernel may hand to the residual epilogue
 
 // Epilogue shared by both kernels.  acc[i][j][v] is element (row, col) of the tile with
 //   row = wm WM + 32 i + 8 (v / 4) + 4 half + (v % 4),   col = wn WN + 32 j + l32   (WM = 32 MI, WN = 32 NI).
@@ -108,8 +107,7 @@ __device__ __forceinline__ void gemm_epilogue_impl(f32x16 (&acc)[MI][NI], int m0
                                                    int tn, void* __restrict__ g_out, const int32_t* __restrict__ g_targets,
                                                    float2* __restrict__ g_partials, float* __restrict__ g_target_logit,
                                                    const float2* __restrict__ g_rope, void* __restrict__ g_vt,
-                                                   const GemmDims& g, const float (&resid0)[NI][16], bool have_resid0) {
-    // resid0 (EPI_RESID_F32 with have_resid0): the output's old values for block row i = 0, loaded earlier by the caller
+                                                   const GemmDims& g) {
     constexpr int WM = 32 * MI, WN = 32 * NI;
     const int row_base = m0 + wm * WM + 4 * half;
 
@@ -128,10 +126,11 @@ __device__ __forceinline__ void gemm_epilogue_impl(f32x16 (&acc)[MI][NI], int m0
                     int64_t idx = (int64_t)row * g.ldc + col;
                     if (EPI == EPI_STORE_ACT) reinterpret_cast<T*>(g_out)[idx] = from_f32<T>(acc[i][j][v]);
                     if (EPI == EPI_STORE_F32 || EPI == EPI_PARTIAL_F32) reinterpret_cast<float*>(g_out)[idx] = acc[i][j][v];   // (slice base in g_out)
-                    if (EPI == EPI_RESID_F32) {
-                        if (i == 0 && j < kResidAheadCols && have_resid0) reinterpret_cast<float*>(g_out)[idx] = resid0[j][v] + acc[i][j][v];
-                        else reinterpret_cast<float*>(g_out)[idx] += acc[i][j][v];
-                    }
+                    // Residual update: one hardware fp32 add per element, carried out at the L2 and not awaited.  Every
+                    // element has exactly one writer (this epilogue is never combined with a K split), so the result is
+                    // the same single rounding of old + acc as a load / add / store, run to run; what it saves is the
+                    // wait for the old values at the end of a tile (7B step: O and down projections 0.8 ms).
+                    if (EPI == EPI_RESID_F32) unsafeAtomicAdd(reinterpret_cast<float*>(g_out) + idx, acc[i][j][v]);
                 }
             }
     } else if constexpr (EPI == EPI_SWIGLU) {
@@ -243,9 +242,8 @@ __device__ __forceinline__ void gemm_epilogue(f32x16 (&acc)[MI][NI], int m0, int
                                               float2* __restrict__ g_partials, float* __restrict__ g_target_logit,
                                               const float2* __restrict__ g_rope, void* __restrict__ g_vt,
                                               const GemmDims& g) {
-    float none[NI][16];   // never read
     gemm_epilogue_impl<T, MI, NI, EPI>(acc, m0, n0, wm, wn, l32, half, tn, g_out, g_targets, g_partials, g_target_logit, g_rope,
-                                       g_vt, g, none, false);
+                                       g_vt, g);
 }
 
 template <typename T, int BM, int BN, int EPI>
@@ -588,30 +586,12 @@ __global__ __launch_bounds__(128 * kWavesM) void gemm_bf16_wide_kernel(const cha
     };
     struct Yes { constexpr operator bool() const { return true; } };
     struct No { constexpr operator bool() const { return false; } };
-    // Residual epilogue of the 256-row tile (spare registers): the old output values of block row 0 are requested
-    // a dozen slabs before the end, so that half of the epilogue's read latency and traffic lies under the main loop.
-    constexpr bool kResidAhead = EPI == EPI_RESID_F32 && MI == 2;
-    float resid0[NI][16];
-    const bool resid_ahead = kResidAhead && nk > 16;
     void* out = g_out;
     if (EPI == EPI_PARTIAL_F32) out = reinterpret_cast<float*>(g_out) + (int64_t)slice * g.slice_pitch;
 
     // kb: slabs this workgroup has walked in earlier tiles (the ring positions go on across tiles)
     for (int kb = 0;; kb += nk) {
         const int m0 = tc.tm * BM, n0 = tc.tn * N_OUT, tn = tc.tn;
-        auto prefetch_resid = [&]() __attribute__((always_inline)) {
-            const float* o = reinterpret_cast<const float*>(g_out);
-            const int row_base = m0 + wm * WM + 4 * half, col_base = n0 + wn * WN + l32;
-#pragma unroll
-            for (int v = 0; v < 16; ++v) {
-                const int row = row_base + 8 * (v >> 2) + (v & 3);
-#pragma unroll
-                for (int j = 0; j < kResidAheadCols; ++j) {
-                    resid0[j][v] = 0.f;
-                    if (row < g.M) resid0[j][v] = o[(int64_t)row * g.ldc + col_base + 32 * j];
-                }
-            }
-        };
         // slab 0 of this tile has landed for every wave (and every wave is through with the tile before)
         if (kb == 0) wait_vmcnt<kSteadyWait>(); else wait_vmcnt<0>();
         block_barrier();
@@ -628,10 +608,7 @@ __global__ __launch_bounds__(128 * kWavesM) void gemm_bf16_wide_kernel(const cha
         bool more = false;
         int k = 0;
         if (kDeep) {
-            for (; k + 2 < nk; ++k) {
-                if (kResidAhead && resid_ahead && k == nk - 14) prefetch_resid();
-                slab(k, Yes{}, Yes{}, Yes{}, Yes{});
-            }
+            for (; k + 2 < nk; ++k) slab(k, Yes{}, Yes{}, Yes{}, Yes{});
             slab(k, Yes{}, Yes{}, No{}, No{});    // k = nk - 2: only the W rows of the last slab are left to issue
             slab(k + 1, No{}, No{}, No{}, No{});
         } else {
@@ -660,7 +637,7 @@ __global__ __launch_bounds__(128 * kWavesM) void gemm_bf16_wide_kernel(const cha
         int l32_e = l32, half_e = half;
         if (kTileLoop) asm volatile("" : "+v"(l32_e), "+v"(half_e));
         gemm_epilogue_impl<bf16, MI, NI, EPI>(acc, m0, n0, wm, wn, l32_e, half_e, tn, out, g_targets, g_partials, g_target_logit,
-                                              g_rope, g_vt, g, resid0, resid_ahead);
+                                              g_rope, g_vt, g);
         if (!(kTileLoop && more)) break;
     }
     if (kTileLoop) wait_vmcnt<0>();   // no DMA may still be writing this workgroup's LDS when it is given up
@@ -726,7 +703,7 @@ template <int EPI, int MI, int NI = 4>
 int32_t launch_wide_tile(const GemmArgs& g, hipStream_t stream) {
     constexpr int n_out = (EPI == EPI_SWIGLU) ? 32 * NI : 64 * NI;
     constexpr int BM = kWavesM * MI * 32;
-    GemmDims d;
+    GemmDims d{};
     d.M = g.M; d.N = g.N; d.Kd = g.Kd;
     d.lda = g.lda; d.ldw = g.ldw; d.ldc = g.ldc;
     d.n_part = g.n_part;
@@ -807,7 +784,7 @@ int32_t launch_fast(const GemmArgs& g, hipStream_t stream) {
 template <typename T, int BM, int BN, int EPI>
 int32_t launch_cfg(const GemmArgs& g, hipStream_t stream) {
     constexpr int n_out = (EPI == EPI_SWIGLU) ? BN / 2 : BN;
-    GemmDims d;
+    GemmDims d{};
     d.M = g.M; d.N = g.N; d.Kd = g.Kd;
     d.lda = g.lda; d.ldw = g.ldw; d.ldc = g.ldc;
     d.n_part = g.n_part;
