@@ -132,11 +132,8 @@ int32_t atts_workspace_bytes(const atts_model* model, int32_t P, int32_t K, int3
  *
  * A token id outside [0, vocab) (among the non-padding ids) does not fault: it is read as
  * id 0 and sets the model's sticky device error flag, see atts_model_check.
- * Results are bit-reproducible run to run: no value is ever the sum of floating-point atomics in an order that could
- * vary.  The residual update adds each projection output to its element of the residual stream with one hardware
- * fp32 add (one writer per element: the same single rounding as a load / add / store); calls with few rows through the
- * model, whose narrow projections split their inner dimension over workgroups, store the partial sums per slice and add
- * them in a fixed order.
+ * Results are bit-reproducible run to run: no floating-point atomics anywhere; calls with few rows through the model,
+ * whose narrow projections split their inner dimension over workgroups, add the partial sums in a fixed order.
  * Host-detectable errors: NULL model/ids/scores, P < 1, K < 1, T_max < 1, bad score_mode,
  * P + T_max > 1048576 -> ATTS_ERR_INVALID_ARG; workspace -> ATTS_ERR_WORKSPACE. */
 int32_t atts_score_drafts(const atts_model* model,

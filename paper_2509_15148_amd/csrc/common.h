@@ -111,8 +111,8 @@ enum GemmEpilogue : int32_t {
     EPI_PARTIAL_F32 = 6, // out (float) [n_slices][M, ldc]: the K range is cut into n_slices = gemm_partial_slices(...)
                          // slices whose partial sums are stored one after the other (pitch M ldc floats); the consumer
                          // adds them in slice order.  For projections with few rows and a narrow output, whose tiles
-                         // alone would leave most of the chip idle while the weights stream by.  The slices are never
-                         // added with atomics: the result does not depend on the order in which the workgroups finish.
+                         // alone would leave most of the chip idle while the weights stream by.  No atomics: the
+                         // result does not depend on the order in which the workgroups finish.
 };
 
 struct GemmArgs {
