@@ -55,6 +55,25 @@ def test_gemm_aligned_last_tile_rows_in_a_second_launch():
     assert np.allclose(c.cpu().numpy(), ref, rtol=1e-5, atol=2e-5 * math.sqrt(Kd))
 
 
+def test_gemm_aligned_shapes_sweep():
+    """Seeded sweep over shapes the aligned bf16 kernel takes (rows a multiple of 256 or 384, columns of 256, inner
+    dimension of 64 from 768 up): tile counts below and above the number of compute units, partly filled last rounds of
+    the tile walk, both tile heights.  Every element against the float64 product."""
+    import paper_2509_15148_amd as A
+    rng = np.random.default_rng(15148)
+    for case in range(12):
+        M = int(rng.choice([256, 384, 768, 1152, 1280, 1536, 2304, 3072, 4224]))
+        N = 256 * int(rng.integers(1, 90))
+        Kd = 64 * int(rng.choice([12, 13, 16, 24, 31]))
+        announce("gemm aligned", case, (M, N, Kd))
+        a, w = _rand((M, Kd), 300 + case, torch.bfloat16), _rand((N, Kd), 400 + case, torch.bfloat16)
+        c = torch.full((M, N), float("nan"), dtype=torch.float32, device="cuda")
+        A.atts_gemm_nt(a.cuda(), w.cuda(), c)
+        torch.cuda.synchronize()
+        ref = a.double().numpy() @ w.double().numpy().T
+        assert np.allclose(c.cpu().numpy(), ref, rtol=1e-5, atol=2e-5 * math.sqrt(Kd)), (M, N, Kd)
+
+
 def test_gemm_few_rows_random_shapes():
     """Seeded sweep over the shapes the weight-streaming kernel serves (1..16 rows, any column count, inner
     dimension a multiple of 32 up to several K slices), against the float64 product."""
