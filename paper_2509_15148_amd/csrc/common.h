@@ -108,6 +108,8 @@ enum GemmEpilogue : int32_t {
     EPI_LMHEAD = 4,      // per-row online-softmax partials over this tile's columns + target logit
     EPI_QKV_ROPE = 5,    // QKV projection: q/k heads rotated (rotate-half RoPE) and stored to out (T) [M, ldc];
                          // v heads stored transposed to vt [n_kv, 128, ldv].  head_dim 128, aligned bf16 shapes only.
+    EPI_LMHEAD_T = 7,    // EPI_LMHEAD with the operands exchanged (rows of the product = vocabulary entries, columns = scoring
+                         // rows): launch_gemm takes it by itself for EPI_LMHEAD calls whose shape allows it
     EPI_PARTIAL_F32 = 6, // out (float) [n_slices][M, ldc]: the K range is cut into n_slices = gemm_partial_slices(...)
                          // slices whose partial sums are stored one after the other (pitch M ldc floats); the consumer
                          // adds them in slice order.  For projections with few rows and a narrow output, whose tiles

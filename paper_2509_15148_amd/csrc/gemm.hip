@@ -256,6 +256,43 @@ __device__ __forceinline__ void gemm_epilogue_impl(f32x16 (&acc)[MI][NI], int m0
                 for (int o = 1; o < 32; o <<= 1) sum += __shfl_xor(sum, o);
                 if (row_ok && l32 == 0) g_partials[(int64_t)row * g.n_part + part] = make_float2(mx, sum);
             }
+    } else if constexpr (EPI == EPI_LMHEAD_T) {
+        // Operands exchanged: the rows of this product are vocabulary entries (g.M of them), its columns the scoring rows.
+        // A lane holds, for each of its NI scoring rows, the logits of the 16 MI vocabulary entries of its wave's row
+        // block: maximum and sum of exponentials are taken inside the lane (no cross-lane reduction per scoring row, where
+        // the other orientation needs ten), the two lane halves are merged with one exchange, and the wave's partial goes to
+        // slot (tile row, wave row).  The target logit is stored by the lane that holds the target's vocabulary entry.
+        const int part = (m0 / (4 * WM)) * 4 + wm;
+        const int vrow0 = m0 + wm * WM + 4 * half;
+#pragma unroll
+        for (int j = 0; j < NI; ++j) {
+            const int col = n0 + wn * WN + 32 * j + l32;              // scoring row; < g.N (whole tiles, checked on the host)
+            const int trel = g_targets[col] - vrow0;                    // the target entry relative to this lane's first one
+            float mx = -INFINITY;
+#pragma unroll
+            for (int i = 0; i < MI; ++i)
+#pragma unroll
+                for (int v = 0; v < 16; ++v) {
+                    const int rel = 32 * i + 8 * (v >> 2) + (v & 3);
+                    const float z = vrow0 + rel < g.M ? acc[i][j][v] : -INFINITY;
+                    mx = fmaxf(mx, z);
+                    if (trel == rel) g_target_logit[col] = z;
+                }
+            float sum = 0.f;
+            if (mx > -INFINITY) {
+#pragma unroll
+                for (int i = 0; i < MI; ++i)
+#pragma unroll
+                    for (int v = 0; v < 16; ++v)
+                        if (vrow0 + 32 * i + 8 * (v >> 2) + (v & 3) < g.M) sum += __expf(acc[i][j][v] - mx);
+            }
+            // merge with the other half of the lane pair (l, l ^ 32): same scoring row, the rows in between
+            const float mx_o = __shfl_xor(mx, 32), sum_o = __shfl_xor(sum, 32);
+            const float m = fmaxf(mx, mx_o);
+            float tot = 0.f;
+            if (m > -INFINITY) tot = sum * __expf(mx - m) + sum_o * __expf(mx_o - m);   // a half with no entry: 0 * exp(-inf) = 0
+            if (half == 0) g_partials[(int64_t)col * g.n_part + part] = make_float2(m, tot);
+        }
     }
 }
 
@@ -840,6 +877,7 @@ int32_t launch_t(GemmEpilogue epi, const GemmArgs& g, hipStream_t stream) {
         case EPI_LMHEAD: return launch_epi<T, EPI_LMHEAD>(g, stream);
         case EPI_PARTIAL_F32: return launch_epi<T, EPI_PARTIAL_F32>(g, stream);
         case EPI_QKV_ROPE: break;   // fast path only, dispatched by launch_gemm
+        case EPI_LMHEAD_T: break;   // taken by launch_gemm itself, never asked for
     }
     return fail(ATTS_ERR_INVALID_ARG, "unknown GEMM epilogue %d", (int)epi);
 }
@@ -871,7 +909,16 @@ __global__ void lmhead_combine_kernel(const float2* __restrict__ partials, const
 
 }  // namespace
 
+// The LM head with the operands exchanged: the vocabulary tiles exactly by 384 rows and the scoring rows by 256 columns.
+// No row of padding is computed (4096 scoring rows are 10.67 tiles of 384 in the other orientation), the tile count drops
+// (7B: 6336 instead of 6534, 25 rounds instead of 26) and the epilogue reduces inside the lanes.
+static bool lmhead_exchanged_ok(int32_t dtype, int32_t M, int32_t N, int32_t Kd, int64_t lda, int64_t ldw) {
+    return dtype == ATTS_DTYPE_BF16 && N % 384 == 0 && M % 256 == 0 && Kd % kWideBK == 0 && Kd >= kMinSlabs * kWideBK &&
+           lda * 2 * 17 < (1ll << 31) && ldw * 2 * 17 < (1ll << 31);
+}
+
 int32_t lmhead_num_partials(int32_t dtype, int32_t M, int32_t N, int32_t Kd, bool a_rows_padded) {
+    if (lmhead_exchanged_ok(dtype, M, N, Kd, Kd, Kd)) return N / 384 * 4;
     GemmArgs g{};
     g.M = M; g.N = N; g.Kd = Kd; g.lda = Kd; g.ldw = Kd; g.a_rows_padded = a_rows_padded;
     const int bn = (fast_path_ok(dtype, EPI_LMHEAD, g) || use_big_tile(M, N)) ? 256 : 128;
@@ -905,6 +952,14 @@ int32_t launch_gemm(int32_t dtype, GemmEpilogue epi, const GemmArgs& g, hipStrea
         return fail(ATTS_ERR_INVALID_ARG, "gemm: wrong partial count for the LM-head epilogue");
     if (epi == EPI_PARTIAL_F32 && g.n_slices != gemm_partial_slices(dtype, g.M, g.N, g.Kd, g.a_rows_padded))
         return fail(ATTS_ERR_INVALID_ARG, "gemm: wrong slice count for the partial-sum epilogue");
+    if (epi == EPI_LMHEAD && lmhead_exchanged_ok(dtype, g.M, g.N, g.Kd, g.lda, g.ldw)) {
+        if (!g.targets || !g.partials || !g.target_logit) return fail(ATTS_ERR_INVALID_ARG, "gemm: LM-head epilogue without its buffers");
+        GemmArgs x = g;
+        x.a = g.w; x.lda = g.ldw; x.M = g.N;
+        x.w = g.a; x.ldw = g.lda; x.N = g.M;
+        x.a_rows_padded = false;
+        return launch_wide_tile<EPI_LMHEAD_T, 3>(x, stream);
+    }
     if (epi == EPI_QKV_ROPE) {
         if (!qkv_rope_fusable(dtype, g.M, g.N, g.Kd, 128, g.a_rows_padded) || !g.rope || !g.vt || g.ldv < g.M || g.ldv % 4 ||
             g.n_rot_heads < 1 || g.n_rot_heads * 128 >= g.N)

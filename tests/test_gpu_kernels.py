@@ -102,7 +102,11 @@ def test_gemm_rejects_unaligned_k():
 
 # ------------------------------------------------------------------------------------ LM head
 @pytest.mark.parametrize("dtype,tol", [(torch.float32, 1e-4), (torch.bfloat16, 1e-3)])
-@pytest.mark.parametrize("shape", [(1, 16, 7), (37, 128, 1000), (256, 128, 1024), (130, 264, 5003), (4096, 256, 19008)])
+@pytest.mark.parametrize("shape", [(1, 16, 7), (37, 128, 1000), (256, 128, 1024), (130, 264, 5003), (4096, 256, 19008),
+                                   # scoring rows a multiple of 256, vocabulary of 384, inner dimension of 64 from 768 up: the
+                                   # bf16 product is taken with the operands exchanged (vocabulary entries as rows); 300 and 30
+                                   # tiles, the second with a single column of tiles
+                                   (1280, 768, 23040), (256, 1344, 11520)])
 def test_lmhead_logprobs_matches_log_softmax_gather(dtype, tol, shape):
     """lp = z[target] - logsumexp(z) without materialising z; logits scaled to a spread of several
     units so that the running-max logic matters."""
