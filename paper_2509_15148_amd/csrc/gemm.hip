@@ -170,7 +170,9 @@ __device__ __forceinline__ void gemm_epilogue_impl(f32x16 (&acc)[MI][NI], int m0
                     int col = col_base + 32 * j;
                     if (col >= g.N) continue;
                     float gate = acc[i][j][v], up = acc[i][j + NI / 2][v];
-                    float y = gate / (1.f + __expf(-gate)) * up;
+                    // silu(gate) up with the hardware reciprocal (1 ulp) instead of an IEEE division, whose ten-instruction
+                    // expansion per element made this epilogue cost about as much again as its exponentials
+                    float y = gate * __builtin_amdgcn_rcpf(1.f + __expf(-gate)) * up;
                     reinterpret_cast<T*>(g_out)[(int64_t)row * g.ldc + col] = from_f32<T>(y);
                 }
             }

@@ -106,7 +106,7 @@ __global__ __launch_bounds__(64 * kSkinnyWaves) void gemm_skinny_kernel(const bf
             const int col = grp * 16 + r;
             if (col < d.N) {
                 const float gate = acc0[v], up = acc1[v];
-                const float y = gate / (1.f + __expf(-gate)) * up;
+                const float y = gate * __builtin_amdgcn_rcpf(1.f + __expf(-gate)) * up;   // hardware reciprocal, as in the tiled kernels
                 reinterpret_cast<bf16*>(g_out)[(int64_t)row * d.ldc + col] = from_f32<bf16>(y);
             }
         } else {
