@@ -129,7 +129,12 @@ __device__ __forceinline__ void start_accumulators(f32x16 (&acc)[MI][NI], int m0
             }
 }
 
-template <typename T, int MI, int NI, int EPI>
+// kWide: called by the aligned kernel, whose tiles are whole in the column direction.  The plain stores and the SwiGLU
+// then go without per-element checks (one wave-uniform test tells whether the tile is whole in the row direction too) and
+// address each element as a wave-uniform base (scalar arithmetic) plus one 32-bit lane offset: the checked form costs
+// about 25 instructions and a branch or two per element, which at 96 - 192 elements per lane and tile was a tenth of the
+// gate/up tile's time with the matrix pipe idle.
+template <typename T, int MI, int NI, int EPI, bool kWide = false>
 __device__ __forceinline__ void gemm_epilogue_impl(f32x16 (&acc)[MI][NI], int m0, int n0, int wm, int wn, int l32, int half,
                                                    int tn, void* __restrict__ g_out, const int32_t* __restrict__ g_targets,
                                                    float2* __restrict__ g_partials, float* __restrict__ g_target_logit,
@@ -138,7 +143,43 @@ __device__ __forceinline__ void gemm_epilogue_impl(f32x16 (&acc)[MI][NI], int m0
     constexpr int WM = 32 * MI, WN = 32 * NI;
     const int row_base = m0 + wm * WM + 4 * half;
 
-    if constexpr (EPI == EPI_STORE_ACT || EPI == EPI_STORE_F32 || EPI == EPI_RESID_F32 || EPI == EPI_PARTIAL_F32) {
+    constexpr bool kPlain = EPI == EPI_STORE_ACT || EPI == EPI_STORE_F32 || EPI == EPI_RESID_F32 || EPI == EPI_PARTIAL_F32;
+    if constexpr (kWide && (kPlain || EPI == EPI_SWIGLU)) {
+        constexpr int kOutCols = EPI == EPI_SWIGLU ? WN / 2 : WN;      // output columns of this wave
+        constexpr int kJ = EPI == EPI_SWIGLU ? NI / 2 : NI;
+        constexpr int ES = (EPI == EPI_STORE_ACT || EPI == EPI_SWIGLU) ? (int)sizeof(T) : 4;
+        const int rows_left = g.M - (m0 + wm * WM);                     // wave-uniform; >= WM: every row of the wave exists
+        char* const wave_base = reinterpret_cast<char*>(g_out) + ((int64_t)(m0 + wm * WM) * g.ldc + n0 + wn * kOutCols) * ES;
+        const uint32_t lane_off = (uint32_t)((4 * half * g.ldc + l32) * ES);
+        auto value = [&](int i, int j, int v) __attribute__((always_inline)) {
+            if constexpr (EPI == EPI_SWIGLU) {
+                // blocks j < NI/2 hold gate, j + NI/2 the matching up columns; silu(gate) up with the hardware reciprocal
+                // (1 ulp) instead of an IEEE division and its ten-instruction expansion
+                const float gate = acc[i][j][v], up = acc[i][j + NI / 2][v];
+                return gate * __builtin_amdgcn_rcpf(1.f + __expf(-gate)) * up;
+            } else {
+                return acc[i][j][v];
+            }
+        };
+        auto rows = [&](auto checked) __attribute__((always_inline)) {
+            constexpr bool kChecked = decltype(checked)::value;
+#pragma unroll
+            for (int i = 0; i < MI; ++i)
+#pragma unroll
+                for (int v = 0; v < 16; ++v) {
+                    const int r = 32 * i + 8 * (v >> 2) + (v & 3);     // + 4 half: in lane_off
+                    if (kChecked && r + 4 * half >= rows_left) continue;
+                    char* const p = wave_base + (int64_t)r * g.ldc * ES + lane_off;
+#pragma unroll
+                    for (int j = 0; j < kJ; ++j) {
+                        const float y = value(i, j, v);
+                        if (ES == (int)sizeof(T) && ES != 4) *reinterpret_cast<T*>(p + 32 * j * ES) = from_f32<T>(y);
+                        else *reinterpret_cast<float*>(p + 32 * j * ES) = y;
+                    }
+                }
+        };
+        if (rows_left >= WM) rows(std::false_type{}); else rows(std::true_type{});
+    } else if constexpr (kPlain) {
         const int col_base = n0 + wn * WN + l32;
 #pragma unroll
         for (int i = 0; i < MI; ++i)
@@ -182,48 +223,78 @@ __device__ __forceinline__ void gemm_epilogue_impl(f32x16 (&acc)[MI][NI], int m0
         static_assert(NI == 4 && sizeof(T) == 2, "QKV epilogue needs 128-column bf16 wave tiles");
         const int col0 = n0 + wn * WN;
         const int head = col0 / 128;                                  // wave-uniform
+        // Addresses as a wave-uniform base plus one lane offset, and one wave-uniform test for "every row of the wave
+        // exists" instead of a test per element (as in the plain stores above).
+        const int wrow0 = m0 + wm * WM;                               // first row of the wave
+        const int rows_left = g.M - wrow0;
         if (head < g.n_rot_heads) {
+            char* const obase = reinterpret_cast<char*>(g_out) + ((int64_t)wrow0 * g.ldc + col0) * sizeof(T);
+            const char* const cbase = reinterpret_cast<const char*>(g_rope + (int64_t)wrow0 * 64);
+            const uint32_t o_lane = (uint32_t)((4 * half * g.ldc + l32) * sizeof(T));
+            const uint32_t c_lane = (uint32_t)((4 * half * 64 + l32) * sizeof(float2));
+            // The (cos, sin) pairs of eight rows are requested together and only then used: the compiler keeps every load
+            // behind the stores in front of it, so one row at a time means one exposed L2 round trip per row.
+            auto rows = [&](auto checked) __attribute__((always_inline)) {
+                constexpr bool kChecked = decltype(checked)::value;
 #pragma unroll
-            for (int i = 0; i < MI; ++i)
+                for (int i = 0; i < MI; ++i)
 #pragma unroll
-                for (int v = 0; v < 16; ++v) {
-                    const int row = row_base + 32 * i + 8 * (v >> 2) + (v & 3);
-                    if (row >= g.M) continue;
-                    T* orow = reinterpret_cast<T*>(g_out) + (int64_t)row * g.ldc + col0 + l32;
-                    const float2* crow = g_rope + (int64_t)row * 64 + l32;
+                    for (int a2 = 0; a2 < 2; ++a2) {
+                        float2 cs[8][2];
 #pragma unroll
-                    for (int j = 0; j < 2; ++j) {
-                        const float2 cs = crow[32 * j];
-                        const float x1 = acc[i][j][v], x2 = acc[i][j + 2][v];
-                        orow[32 * j] = from_f32<T>(x1 * cs.x - x2 * cs.y);
-                        orow[32 * j + 64] = from_f32<T>(x2 * cs.x + x1 * cs.y);
-                    }
-                }
-        } else {
-            // V head: lane holds 4 consecutive rows (v % 4) of one head dim -> one 8-byte store into V^T
-            T* vbase = reinterpret_cast<T*>(g_vt) + (int64_t)(head - g.n_rot_heads) * 128 * g.ldv;
+                        for (int q = 0; q < 8; ++q) {
+                            const int r = 32 * i + 8 * (2 * a2 + (q >> 2)) + (q & 3);
+                            const int rc = kChecked ? min(r, max(rows_left - 1 - 4 * half, 0)) : r;     // a row that exists
+                            const float2* crow = reinterpret_cast<const float2*>(cbase + (int64_t)rc * 64 * sizeof(float2) + c_lane);
+                            cs[q][0] = crow[0];
+                            cs[q][1] = crow[32];
+                        }
 #pragma unroll
-            for (int i = 0; i < MI; ++i)
+                        for (int q = 0; q < 8; ++q) {
+                            const int v = 4 * (2 * a2 + (q >> 2)) + (q & 3);
+                            const int r = 32 * i + 8 * (v >> 2) + (v & 3);
+                            if (kChecked && r + 4 * half >= rows_left) continue;
+                            T* orow = reinterpret_cast<T*>(obase + (int64_t)r * g.ldc * sizeof(T) + o_lane);
 #pragma unroll
-                for (int a = 0; a < 4; ++a) {
-                    const int row0 = row_base + 32 * i + 8 * a;
-                    if (row0 >= g.M) continue;
-#pragma unroll
-                    for (int j = 0; j < NI; ++j) {
-                        typedef T T4 __attribute__((ext_vector_type(4)));
-                        T4 o4;
-#pragma unroll
-                        for (int b = 0; b < 4; ++b) o4[b] = from_f32<T>(acc[i][j][4 * a + b]);
-                        T* dst = vbase + (int64_t)(32 * j + l32) * g.ldv + row0;
-                        if (row0 + 4 <= g.M) {
-                            *reinterpret_cast<T4*>(dst) = o4;
-                        } else {
-#pragma unroll
-                            for (int b = 0; b < 4; ++b)
-                                if (row0 + b < g.M) dst[b] = o4[b];
+                            for (int j = 0; j < 2; ++j) {
+                                const float x1 = acc[i][j][v], x2 = acc[i][j + 2][v];
+                                orow[32 * j] = from_f32<T>(x1 * cs[q][j].x - x2 * cs[q][j].y);
+                                orow[32 * j + 64] = from_f32<T>(x2 * cs[q][j].x + x1 * cs[q][j].y);
+                            }
                         }
                     }
-                }
+            };
+            if (rows_left >= WM) rows(std::false_type{}); else rows(std::true_type{});
+        } else {
+            // V head: lane holds 4 consecutive rows (v % 4) of one head dim -> one 8-byte store into V^T
+            typedef T T4 __attribute__((ext_vector_type(4)));
+            char* const vbase = reinterpret_cast<char*>(g_vt) + ((int64_t)(head - g.n_rot_heads) * 128 * g.ldv + wrow0) * sizeof(T);
+            const uint32_t v_lane = (uint32_t)(((int64_t)l32 * g.ldv + 4 * half) * sizeof(T));
+            auto rows = [&](auto checked) __attribute__((always_inline)) {
+                constexpr bool kChecked = decltype(checked)::value;
+#pragma unroll
+                for (int i = 0; i < MI; ++i)
+#pragma unroll
+                    for (int a = 0; a < 4; ++a) {
+                        const int r0 = 32 * i + 8 * a + 4 * half;     // first of the lane's 4 consecutive rows, relative to the wave
+                        if (kChecked && r0 >= rows_left) continue;
+#pragma unroll
+                        for (int j = 0; j < NI; ++j) {
+                            T4 o4;
+#pragma unroll
+                            for (int b = 0; b < 4; ++b) o4[b] = from_f32<T>(acc[i][j][4 * a + b]);
+                            T* dst = reinterpret_cast<T*>(vbase + ((int64_t)(32 * j) * g.ldv + 32 * i + 8 * a) * sizeof(T) + v_lane);
+                            if (!kChecked || r0 + 4 <= rows_left) {
+                                *reinterpret_cast<T4*>(dst) = o4;
+                            } else {
+#pragma unroll
+                                for (int b = 0; b < 4; ++b)
+                                    if (r0 + b < rows_left) dst[b] = o4[b];
+                            }
+                        }
+                    }
+            };
+            if (rows_left >= WM) rows(std::false_type{}); else rows(std::true_type{});
         }
     } else if constexpr (EPI == EPI_LMHEAD) {
         // One (max, sum exp) partial per row for this wave's WN columns, plus the target logit.
@@ -265,28 +336,32 @@ __device__ __forceinline__ void gemm_epilogue_impl(f32x16 (&acc)[MI][NI], int m0
         // the other orientation needs ten), the two lane halves are merged with one exchange, and the wave's partial goes to
         // slot (tile row, wave row).  The target logit is stored by the lane that holds the target's vocabulary entry.
         const int part = (m0 / (4 * WM)) * 4 + wm;
-        const int vrow0 = m0 + wm * WM + 4 * half;
+        const int vrow0 = m0 + wm * WM + 4 * half;     // every vocabulary row of the tile exists (whole tiles, checked on the host)
 #pragma unroll
         for (int j = 0; j < NI; ++j) {
-            const int col = n0 + wn * WN + 32 * j + l32;              // scoring row; < g.N (whole tiles, checked on the host)
-            const int trel = g_targets[col] - vrow0;                    // the target entry relative to this lane's first one
-            float mx = -INFINITY;
+            const int col = n0 + wn * WN + 32 * j + l32;              // scoring row; < g.N (whole tiles too)
+            float mx = acc[0][j][0];
 #pragma unroll
             for (int i = 0; i < MI; ++i)
 #pragma unroll
-                for (int v = 0; v < 16; ++v) {
-                    const int rel = 32 * i + 8 * (v >> 2) + (v & 3);
-                    const float z = vrow0 + rel < g.M ? acc[i][j][v] : -INFINITY;
-                    mx = fmaxf(mx, z);
-                    if (trel == rel) g_target_logit[col] = z;
-                }
+                for (int v = (i == 0 ? 1 : 0); v < 16; ++v) mx = fmaxf(mx, acc[i][j][v]);
             float sum = 0.f;
-            if (mx > -INFINITY) {
+#pragma unroll
+            for (int i = 0; i < MI; ++i)
+#pragma unroll
+                for (int v = 0; v < 16; ++v) sum += __expf(acc[i][j][v] - mx);
+            // The target's vocabulary entry relative to this lane's first one: the lane holds entries 32 i + 8 a + b
+            // (b < 4).  Only about one wave in twelve holds any of its 128 scoring rows' targets, so the selection of the
+            // accumulator entry sits behind a branch that is mostly not taken.
+            const int trel = g_targets[col] - vrow0;
+            if (trel >= 0 && trel < WM && (trel & 4) == 0) {
+                const int ti = trel >> 5, tv = ((trel >> 3) & 3) * 4 + (trel & 3);
+                float z = 0.f;
 #pragma unroll
                 for (int i = 0; i < MI; ++i)
 #pragma unroll
-                    for (int v = 0; v < 16; ++v)
-                        if (vrow0 + 32 * i + 8 * (v >> 2) + (v & 3) < g.M) sum += __expf(acc[i][j][v] - mx);
+                    for (int v = 0; v < 16; ++v) z = (ti == i && tv == v) ? acc[i][j][v] : z;
+                g_target_logit[col] = z;
             }
             // merge with the other half of the lane pair (l, l ^ 32): same scoring row, the rows in between
             const float mx_o = __shfl_xor(mx, 32), sum_o = __shfl_xor(sum, 32);
@@ -687,7 +762,7 @@ __global__ __launch_bounds__(128 * kWavesM) void gemm_bf16_wide_kernel(const cha
         // not hoisted out of the tile loop (it would sit in registers all through the main loop)
         int l32_e = l32, half_e = half;
         if (kTileLoop) asm volatile("" : "+v"(l32_e), "+v"(half_e));
-        gemm_epilogue_impl<bf16, MI, NI, EPI>(acc, m0, n0, wm, wn, l32_e, half_e, tn, out, g_targets, g_partials, g_target_logit,
+        gemm_epilogue_impl<bf16, MI, NI, EPI, true>(acc, m0, n0, wm, wn, l32_e, half_e, tn, out, g_targets, g_partials, g_target_logit,
                                               g_rope, g_vt, g);
         if (!(kTileLoop && more)) break;
         start_accumulators<MI, NI, EPI>(acc, tc.tm * BM, tc.tn * N_OUT, wm, wn, l32_e, half_e, g_out, g);
