@@ -107,10 +107,35 @@ struct GemmDims {
 // first slabs are still on their way, instead of at the end of the tile, where every workgroup of a one-round launch
 // would wait for them at once (7B step: O and down projections 1.9 ms faster than with a load / add / store epilogue);
 // no atomics, one writer per element.
-template <int MI, int NI, int EPI>
+template <int MI, int NI, int EPI, bool kWide = false>
 __device__ __forceinline__ void start_accumulators(f32x16 (&acc)[MI][NI], int m0, int n0, int wm, int wn, int l32, int half,
                                                    const void* __restrict__ g_out, const GemmDims& g) {
     constexpr int WM = 32 * MI, WN = 32 * NI;
+    if constexpr (kWide && EPI == EPI_RESID_F32) {
+        // aligned kernel: whole tiles in the column direction; addresses as wave-uniform base + lane offset, rows of a
+        // last, partial tile row clamped to the last existing one (only when the wave-uniform test says there are any)
+        const int rows_left = g.M - (m0 + wm * WM);
+        const char* const wave_base = reinterpret_cast<const char*>(g_out) + ((int64_t)(m0 + wm * WM) * g.ldc + n0 + wn * WN) * 4;
+        const uint32_t lane_off = (uint32_t)((4 * half * g.ldc + l32) * 4);
+        auto rows = [&](auto checked) __attribute__((always_inline)) {
+            constexpr bool kChecked = decltype(checked)::value;
+#pragma unroll
+            for (int i = 0; i < MI; ++i)
+#pragma unroll
+                for (int v = 0; v < 16; ++v) {
+                    const int r = 32 * i + 8 * (v >> 2) + (v & 3);
+                    const char* p = wave_base + (int64_t)r * g.ldc * 4 + lane_off;
+                    if (kChecked) {     // this lane's row, clamped to the last row of the output (what it starts from is never stored)
+                        const int row = min(m0 + wm * WM + r + 4 * half, g.M - 1);
+                        p = reinterpret_cast<const char*>(g_out) + ((int64_t)row * g.ldc + n0 + wn * WN + l32) * 4;
+                    }
+#pragma unroll
+                    for (int j = 0; j < NI; ++j) acc[i][j][v] = *reinterpret_cast<const float*>(p + 32 * j * 4);
+                }
+        };
+        if (rows_left >= WM) rows(std::false_type{}); else rows(std::true_type{});
+        return;
+    }
     const int row_base = m0 + wm * WM + 4 * half, col_base = n0 + wn * WN + l32;
 #pragma unroll
     for (int i = 0; i < MI; ++i)
@@ -667,7 +692,7 @@ __global__ __launch_bounds__(128 * kWavesM) void gemm_bf16_wide_kernel(const cha
     using F_ = std::false_type;
 
     // ---- prologue (the accumulators' start values are requested first, so that they are on their way with the first slabs)
-    start_accumulators<MI, NI, EPI>(acc, tc.tm * BM, tc.tn * N_OUT, wm, wn, l32, half, g_out, g);
+    start_accumulators<MI, NI, EPI, true>(acc, tc.tm * BM, tc.tn * N_OUT, wm, wn, l32, half, g_out, g);
     constexpr int kLook = kStages - 1;                 // whole-slab stages: slab k + kLook is issued during slab k
     constexpr int kSteadyWait = kDeep ? DMA_A : (kStages - 2) * (DMA_A + DMA_B);   // loads that may stay in flight
     issue_a(0);
@@ -765,7 +790,7 @@ __global__ __launch_bounds__(128 * kWavesM) void gemm_bf16_wide_kernel(const cha
         gemm_epilogue_impl<bf16, MI, NI, EPI, true>(acc, m0, n0, wm, wn, l32_e, half_e, tn, out, g_targets, g_partials, g_target_logit,
                                               g_rope, g_vt, g);
         if (!(kTileLoop && more)) break;
-        start_accumulators<MI, NI, EPI>(acc, tc.tm * BM, tc.tn * N_OUT, wm, wn, l32_e, half_e, g_out, g);
+        start_accumulators<MI, NI, EPI, true>(acc, tc.tm * BM, tc.tn * N_OUT, wm, wn, l32_e, half_e, g_out, g);
     }
     if (kTileLoop) wait_vmcnt<0>();   // no DMA may still be writing this workgroup's LDS when it is given up
 }
