@@ -28,7 +28,7 @@ HBM_PEAK_GBS = 8000.0
 # (FETCH_SIZE, then WRITE_SIZE), each scaled by what the same counter reads for a plain device copy of known
 # size (--traffic-probe); see profiles/traffic_gemm_gate_up_7b.txt.  Valid only for the kernel source it was
 # taken with: reported as null when the hash of csrc/gemm.hip differs.
-MEASURED_TRAFFIC = {"gemm_sha256": "f4aa1d679e5b284f132b39ead738fb02ceb0076324ff9ee69403e6f1539f185f",
+MEASURED_TRAFFIC = {"gemm_sha256": "be847675f147059c48d5d5cdf77993c07690a2abac66844243b7e210c8fb4ade",
                     "workload": "7b", "bytes_per_launch": 1.753e9}
 
 
