@@ -159,6 +159,8 @@ def _tree_attention_reference(qkv, P, K, T, nq, nkv, hd):
     (torch.bfloat16, (130, 5, 17, 8, 8, 128), 1.5e-2),     # several drafts inside one query tile
     (torch.bfloat16, (512, 4, 256, 7, 1, 128), 1.5e-2),    # aligned, GQA group 7
     (torch.bfloat16, (200, 0, 1, 2, 2, 128), 1.5e-2),      # prefix only
+    (torch.bfloat16, (512, 16, 256, 28, 4, 128), 1.5e-2),  # the 7B step's launch: 256-row query tiles, 504 workgroups
+    (torch.bfloat16, (200, 21, 200, 16, 2, 128), 1.5e-2),  # the same kernel (288 workgroups), drafts and prefix not aligned to its tiles
 ])
 def test_shared_prefix_attention(dtype, shape, tol):
     import paper_2509_15148_amd as A
