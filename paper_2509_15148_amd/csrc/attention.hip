@@ -197,14 +197,32 @@ __global__ __launch_bounds__(64 * kWaves, 512 / (64 * kWaves)) void attn_mfma_ke
         for (int kb = 0; kb < 2; ++kb)
 #pragma unroll
             for (int v = 0; v < 16; ++v) acc_s[kb][v] = 0.f;
+        // Fragments in groups of four (two 16-column slices of the head dimension x the two key blocks), double-buffered:
+        // the reads of group q + 1 are issued behind the first MFMA of group q, whose wait has just drained the LDS
+        // queue, and arrive under the other three.
+        auto load_k = [&](int s_, int kb) __attribute__((always_inline)) {
+            const int kr = kb * 32 + kperm;
+            return *reinterpret_cast<const bf16x8*>(sK + kr * 256 + (((2 * s_ + g) ^ (kr & 15)) << 4));
+        };
+        bf16x8 kf[2][4];
 #pragma unroll
-        for (int s = 0; s < 8; ++s)
+        for (int i = 0; i < 4; ++i) kf[0][i] = load_k(i >> 1, i & 1);
+        __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
-            for (int kb = 0; kb < 2; ++kb) {
-                const int kr = kb * 32 + kperm;
-                bf16x8 kf = *reinterpret_cast<const bf16x8*>(sK + kr * 256 + (((2 * s + g) ^ (kr & 15)) << 4));
-                acc_s[kb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, qf[s], acc_s[kb], 0, 0, 0);
+        for (int q = 0; q < 4; ++q) {
+            acc_s[0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[q & 1][0], qf[2 * q], acc_s[0], 0, 0, 0);
+            if (q < 3) {
+#pragma unroll
+                for (int i = 0; i < 4; ++i) kf[(q + 1) & 1][i] = load_k(2 * (q + 1) + (i >> 1), i & 1);
             }
+            acc_s[1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[q & 1][1], qf[2 * q], acc_s[1], 0, 0, 0);
+            acc_s[0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[q & 1][2], qf[2 * q + 1], acc_s[0], 0, 0, 0);
+            acc_s[1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[q & 1][3], qf[2 * q + 1], acc_s[1], 0, 0, 0);
+            __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+            if (q < 3) __builtin_amdgcn_sched_group_barrier(0x100, 4, 0);
+            __builtin_amdgcn_sched_group_barrier(0x008, 3, 0);
+        }
+        __builtin_amdgcn_sched_barrier(0);
     };
 
     // ---- softmax of tile t (raw scores in acc_s) and O^T += V^T P^T.  The softmax works on
@@ -251,14 +269,29 @@ __global__ __launch_bounds__(64 * kWaves, 512 / (64 * kWaves)) void attn_mfma_ke
                 pf[kb * 2 + (v >> 3)][v & 7] = (bf16)p;
             }
         l_run += psum;
+        // value fragments in groups of four (one 16-key slice x the four 32-dim blocks), double-buffered as the key fragments
+        auto load_v = [&](int s_, int nb) __attribute__((always_inline)) {
+            const int n = nb * 32 + l32;
+            return *reinterpret_cast<const bf16x8*>(sV + n * 128 + (((2 * s_ + g) ^ ((n >> 1) & 7)) << 4));
+        };
+        bf16x8 vf[2][4];
 #pragma unroll
-        for (int s = 0; s < 4; ++s)
+        for (int nb = 0; nb < 4; ++nb) vf[0][nb] = load_v(0, nb);
+        __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
-            for (int nb = 0; nb < 4; ++nb) {
-                const int n = nb * 32 + l32;
-                bf16x8 vf = *reinterpret_cast<const bf16x8*>(sV + n * 128 + (((2 * s + g) ^ ((n >> 1) & 7)) << 4));
-                acc_o[nb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf, pf[s], acc_o[nb], 0, 0, 0);
+        for (int s_ = 0; s_ < 4; ++s_) {
+            acc_o[0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf[s_ & 1][0], pf[s_], acc_o[0], 0, 0, 0);
+            if (s_ < 3) {
+#pragma unroll
+                for (int nb = 0; nb < 4; ++nb) vf[(s_ + 1) & 1][nb] = load_v(s_ + 1, nb);
             }
+#pragma unroll
+            for (int nb = 1; nb < 4; ++nb) acc_o[nb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf[s_ & 1][nb], pf[s_], acc_o[nb], 0, 0, 0);
+            __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+            if (s_ < 3) __builtin_amdgcn_sched_group_barrier(0x100, 4, 0);
+            __builtin_amdgcn_sched_group_barrier(0x008, 3, 0);
+        }
+        __builtin_amdgcn_sched_barrier(0);
     };
 
     // Ring of kStages tiles, tiles 0 .. kStages - 2 requested up front.
