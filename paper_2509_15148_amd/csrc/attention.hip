@@ -243,7 +243,13 @@ __global__ __launch_bounds__(64 * kWaves, 512 / (64 * kWaves)) void attn_mfma_ke
         float mx = fmaxf(acc_s[0][0], acc_s[1][0]);
 #pragma unroll
         for (int v = 1; v < 16; ++v) mx = fmaxf(fmaxf(mx, acc_s[0][v]), acc_s[1][v]);    // one three-operand maximum each
-        mx = fmaxf(mx, __shfl_xor(mx, 32)) * scale_log2e;                                 // scale > 0: the order is kept
+        {   // maximum over the lane pair (l, l ^ 32): the two 32-lane halves exchanged in registers (no LDS round trip
+            // in the middle of the softmax): afterwards one result holds the lower half's values in every lane, the other
+            // the upper half's
+            const unsigned u = __builtin_bit_cast(unsigned, mx);
+            const auto sw = __builtin_amdgcn_permlane32_swap(u, u, false, false);
+            mx = fmaxf(__builtin_bit_cast(float, sw[0]), __builtin_bit_cast(float, sw[1])) * scale_log2e;   // scale > 0: the order is kept
+        }
         // Lazy rescaling: any reference value works in exp2(z - m) as long as it is the same for numerator and
         // denominator, so the running reference only moves when the new maximum exceeds it by more than 2^6
         // (p stays <= 64, far inside bf16 / fp32 range); the 64 accumulator multiplies are skipped otherwise.
