@@ -263,6 +263,16 @@ __global__ __launch_bounds__(64 * kWaves, 512 / (64 * kWaves)) void attn_mfma_ke
 #pragma unroll
                 for (int v = 0; v < 16; ++v) acc_o[nb][v] *= alpha;
         }
+        // value fragments in groups of four (one 16-key slice x the four 32-dim blocks), double-buffered as the key
+        // fragments; the first group is requested here, ahead of the exponentials, and has arrived when they are through
+        auto load_v = [&](int s_, int nb) __attribute__((always_inline)) {
+            const int n = nb * 32 + l32;
+            return *reinterpret_cast<const bf16x8*>(sV + n * 128 + (((2 * s_ + g) ^ ((n >> 1) & 7)) << 4));
+        };
+        bf16x8 vf[2][4];
+#pragma unroll
+        for (int nb = 0; nb < 4; ++nb) vf[0][nb] = load_v(0, nb);
+        __builtin_amdgcn_sched_barrier(0);
         float psum = 0.f;
         bf16x8 pf[4];
         const float neg_m = -m_run;
@@ -275,14 +285,6 @@ __global__ __launch_bounds__(64 * kWaves, 512 / (64 * kWaves)) void attn_mfma_ke
                 pf[kb * 2 + (v >> 3)][v & 7] = (bf16)p;
             }
         l_run += psum;
-        // value fragments in groups of four (one 16-key slice x the four 32-dim blocks), double-buffered as the key fragments
-        auto load_v = [&](int s_, int nb) __attribute__((always_inline)) {
-            const int n = nb * 32 + l32;
-            return *reinterpret_cast<const bf16x8*>(sV + n * 128 + (((2 * s_ + g) ^ ((n >> 1) & 7)) << 4));
-        };
-        bf16x8 vf[2][4];
-#pragma unroll
-        for (int nb = 0; nb < 4; ++nb) vf[0][nb] = load_v(0, nb);
         __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
         for (int s_ = 0; s_ < 4; ++s_) {
